@@ -1,0 +1,503 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix.
+
+None of these tests needs a GPU.  Each pins a part of oracle/kf_oracle.c to
+something other than itself: closed forms (Eq. 12), limits the paper states for
+the temperature (Sec. 3.3.1), the constants it prints for the Gumbel pdf
+(Sec. 4.4.3), textbook properties of Eq. 7 (CDF, Gumbel-max), an independent
+numpy/scipy evaluation of Eq. 1 / Eq. 4 / Eq. 11 / Alg. 1, and brute force.
+"""
+import itertools
+import math
+import os
+
+import numpy as np
+import pytest
+import scipy.special
+import scipy.stats
+
+from oracle import kf_oracle as ko
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def paper_constants():
+    out = {}
+    for line in open(os.path.join(GOLDEN, "paper_constants.txt")):
+        line = line.split("#")[0].split()
+        if len(line) == 2:
+            out[line[0]] = float(line[1])
+    return out
+
+
+def bf16_round(a):
+    """float32 -> nearest-even bf16, returned as uint16 bits (input prep only)."""
+    b = a.astype(np.float32).view(np.uint32).astype(np.uint64)
+    b = (b + 0x7FFF + ((b >> 16) & 1)) >> 16
+    return b.astype(np.uint16)
+
+
+def as_f64(a):
+    if a.dtype == np.uint16:
+        return (a.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    return a.astype(np.float64)
+
+
+def make_cache(rng, L, B, H, d, cap, n, dtype=ko.F32, pos=None):
+    c = ko.OracleCache(L, B, H, d, cap, dtype)
+    K = rng.standard_normal((L, B, H, n, d)).astype(np.float32)
+    V = rng.standard_normal((L, B, H, n, d)).astype(np.float32)
+    if dtype == ko.BF16:
+        K, V = bf16_round(K), bf16_round(V)
+    c.K[..., :n, :] = K
+    c.V[..., :n, :] = V
+    c.pos[..., :n] = np.arange(n) if pos is None else pos
+    c.len[...] = n
+    return c
+
+
+def rand_vec(rng, shape, dtype):
+    a = rng.standard_normal(shape).astype(np.float32)
+    return bf16_round(a) if dtype == ko.BF16 else a
+
+
+def zeta_matrix(noise, seed, layer, head, q_positions, k_positions):
+    return np.array([[ko.zeta(noise, seed, layer, head, int(qp), int(kp)) for kp in k_positions]
+                     for qp in q_positions])
+
+
+# ----------------------------------------------------------------------------
+# P11  tau schedule, Eq. 12
+# ----------------------------------------------------------------------------
+def test_tau_closed_form():
+    pc = paper_constants()
+    for T in (1, 7, 32, 512, 2048):
+        taus = [ko.tau(t, T, pc["tau_init"], pc["tau_end"]) for t in range(T + 1)]
+        assert taus[0] == pc["tau_init"]                      # prompt iteration
+        assert abs(taus[T] - pc["tau_end"]) < 1e-6            # last decode step
+        assert all(b > a for a, b in zip(taus, taus[1:]))     # increments by dtau > 0
+        for t in (1, T // 2, T):
+            exact = pc["tau_init"] + t * (pc["tau_end"] - pc["tau_init"]) / T
+            assert abs(taus[t] - exact) < 1e-6
+    assert ko.tau(5, 10, 1.5, 1.5) == 1.5                     # fixed temperature
+
+
+# ----------------------------------------------------------------------------
+# P8  noise distribution: Eq. 7 and the constants printed in Sec. 4.4.3
+# ----------------------------------------------------------------------------
+def _noise_sample(n_q=600, n_k=600, seed=20240309, layer=3, head=5):
+    return np.array([[ko.noise_bits(seed, layer, head, qp, kp) for kp in range(n_k)]
+                     for qp in range(1000, 1000 + n_q)], dtype=np.uint64)
+
+
+def test_noise_uniform_bits_and_gumbel_moments():
+    pc = paper_constants()
+    bits = _noise_sample()
+    N = bits.size
+    # every output bit is fair
+    for b in range(32):
+        frac = ((bits >> np.uint64(b)) & np.uint64(1)).mean()
+        assert abs(frac - 0.5) < 4.5 * 0.5 / math.sqrt(N), (b, frac)
+    z = np.array([ko.gumbel(int(v)) for v in bits.ravel()[:200000]])
+    n = z.size
+    # mean and std printed in the paper; 4 sigma of the sampling error
+    assert abs(z.mean() - pc["gumbel_mean"]) < 4 * pc["gumbel_std"] / math.sqrt(n) + 5e-5
+    assert abs(z.std() - pc["gumbel_std"]) < 4 * 1.1 * pc["gumbel_std"] / math.sqrt(n) + 5e-5
+    # Kolmogorov-Smirnov against the CDF of Eq. 7's pdf, exp(-exp(-z))
+    ks = scipy.stats.kstest(z, lambda t: np.exp(-np.exp(-t)))
+    assert ks.pvalue > 1e-3, ks
+    assert np.isfinite(z).all() and z.min() > -2.9 and z.max() < 16.7
+
+
+def test_noise_gumbel_is_inverse_cdf_of_eq7():
+    # u = (2*(bits>>9)+1)/2^24, CDF(zeta) must give u back: pins sign and form
+    for bits in (0, 1 << 9, 0x7FFFFFFF, 0x80000000, 0xFFFFFFFF, 123456789):
+        u = (2 * (bits >> 9) + 1) / 2.0 ** 24
+        z = ko.gumbel(bits)
+        assert abs(math.exp(-math.exp(-z)) - u) < 1e-12
+
+
+def test_noise_independence_across_positions_heads_seeds():
+    bits = _noise_sample(300, 300)
+    u = (bits >> np.uint64(9)).astype(np.float64) / 2 ** 23
+    N = u.size
+    lim = 4.5 / math.sqrt(N)
+    c = lambda a, b: np.corrcoef(a.ravel(), b.ravel())[0, 1]
+    assert abs(c(u[:, :-1], u[:, 1:])) < lim          # adjacent key positions
+    assert abs(c(u[:-1, :], u[1:, :])) < lim          # adjacent query positions (steps)
+    assert abs(c(u[:-1, :-1], u[1:, 1:])) < lim       # diagonal
+    assert abs(c(u, u.T)) < lim                       # (q,k) vs (k,q)
+    other = np.array([[ko.noise_bits(20240309, 3, 6, qp, kp) for kp in range(300)]
+                      for qp in range(1000, 1300)], dtype=np.uint64)
+    assert abs(c(u, (other >> np.uint64(9)).astype(np.float64))) < lim   # neighbouring head
+    other = np.array([[ko.noise_bits(20240308, 3, 5, qp, kp) for kp in range(300)]
+                      for qp in range(1000, 1300)], dtype=np.uint64)
+    assert abs(c(u, (other >> np.uint64(9)).astype(np.float64))) < lim   # neighbouring seed
+    # no duplicated streams: all 32-bit words of one row distinct from the next row's
+    assert (bits[0] != bits[1]).mean() > 0.999
+
+
+def test_noise_golden_file_matches_oracle():
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "noise_bits.txt")) if not l.startswith("#")]
+    assert len(rows) > 100
+    for r in rows:
+        assert ko.noise_bits(*map(int, r[:5])) == int(r[5])
+
+
+def test_gaussian_and_constant_adjustments():
+    pc = paper_constants()
+    assert ko.zeta(ko.NOISE_CONSTANT, 1, 2, 3, 4, 5) == pc["constant_adjustment"]
+    assert ko.zeta(ko.NOISE_NONE, 1, 2, 3, 4, 5) == 0.0
+    g = np.array([ko.zeta(ko.NOISE_GAUSSIAN, 7, 1, 2, qp, kp) for qp in range(300) for kp in range(300)])
+    n = g.size
+    assert abs(g.mean() - pc["gumbel_mean"]) < 4 * pc["gumbel_std"] / math.sqrt(n)
+    assert abs(g.std() - pc["gumbel_std"]) < 4 * pc["gumbel_std"] / math.sqrt(2 * n)
+    ks = scipy.stats.kstest(g, "norm", args=(pc["gumbel_mean"], pc["gumbel_std"]))
+    assert ks.pvalue > 1e-3
+    assert abs(scipy.stats.skew(g)) < 0.03     # symmetric, unlike the Gumbel (skew 1.14)
+
+
+# ----------------------------------------------------------------------------
+# P7  Gumbel-max: argmax_j (x_j + zeta_j) is distributed as softmax(x)
+# ----------------------------------------------------------------------------
+def test_gumbel_max_frequencies_follow_softmax():
+    x = np.array([0.3, -1.0, 1.2, 0.0, 2.0, -0.5])
+    p = scipy.special.softmax(x)
+    trials = 40000
+    counts = np.zeros(len(x))
+    for t in range(trials):
+        z = np.array([ko.zeta(ko.NOISE_GUMBEL, 99, 0, 1, t, j) for j in range(len(x))])
+        counts[np.argmax(x + z)] += 1
+    chi2 = ((counts - trials * p) ** 2 / (trials * p)).sum()
+    assert chi2 < scipy.stats.chi2.ppf(0.9995, len(x) - 1), (chi2, counts / trials, p)
+
+
+# ----------------------------------------------------------------------------
+# Independent numpy/scipy evaluation of one decode step (Eq. 1, Eq. 4, Eq. 11)
+# ----------------------------------------------------------------------------
+def numpy_decode(c, u_idx, q, q_pos, tau, scale, noise, seed, slope):
+    l, b, h = u_idx
+    m = int(c.len[l, b, h])
+    K = as_f64(c.K[l, b, h, :m])
+    V = as_f64(c.V[l, b, h, :m])
+    pos = c.pos[l, b, h, :m].astype(np.int64)
+    x = np.float64(np.float32(scale)) * (K @ as_f64(q)) - slope * (q_pos - pos)
+    p = scipy.special.softmax(x)
+    z = np.array([ko.zeta(noise, seed, l, h, q_pos, int(kp)) for kp in pos])
+    df = scipy.special.softmax((x + z) / np.float64(np.float32(tau)))
+    return p @ V, p, df
+
+
+@pytest.mark.parametrize("dtype", [ko.F32, ko.BF16])
+@pytest.mark.parametrize("noise", [ko.NOISE_GUMBEL, ko.NOISE_NONE, ko.NOISE_GAUSSIAN, ko.NOISE_CONSTANT])
+def test_decode_step_matches_numpy(dtype, noise):
+    rng = np.random.default_rng(5)
+    L, B, H, d, cap, n = 2, 2, 3, 16, 40, 29
+    # non-trivial, strictly ascending original positions
+    pos = np.sort(rng.choice(200, size=(L, B, H, n), replace=True), axis=-1)
+    pos = pos + np.arange(n)  # make strictly ascending
+    c = make_cache(rng, L, B, H, d, cap, n, dtype, pos=pos)
+    c.score[..., :n] = rng.random((L, B, H, n)).astype(np.float32)
+    before = c.copy()
+    q, kn, vn = (rand_vec(rng, (L, B, H, d), dtype) for _ in range(3))
+    seeds = np.array([11, 2 ** 63 + 5], np.uint64)
+    slopes = np.array([0.5, 0.0, 0.02], np.float32)
+    q_pos, tau, scale = 777, 1.37, 0.25
+    out, dp, df = c.decode_step(q, kn, vn, q_pos, tau, scale, noise, seeds, slopes, debug=True)
+    assert (c.len == n + 1).all()
+    # append semantics: new row at slot n, pos = q_pos, old rows untouched
+    assert (c.K[..., n, :] == kn).all() and (c.V[..., n, :] == vn).all()
+    assert (c.pos[..., n] == q_pos).all()
+    assert (c.K[..., :n, :] == before.K[..., :n, :]).all()
+    for l, b, h in itertools.product(range(L), range(B), range(H)):
+        o_ref, p_ref, df_ref = numpy_decode(c, (l, b, h), q[l, b, h], q_pos, tau, scale, noise,
+                                            int(seeds[b]), float(slopes[h]))
+        m = n + 1
+        np.testing.assert_allclose(dp[l, b, h, :m], p_ref, rtol=1e-11, atol=1e-300)
+        np.testing.assert_allclose(df[l, b, h, :m], df_ref, rtol=1e-11, atol=1e-300)
+        np.testing.assert_allclose(out[l, b, h], o_ref.astype(np.float32), rtol=2e-7, atol=1e-30)
+        f_ref = (np.append(before.score[l, b, h, :n], 0.0).astype(np.float64) + df_ref).astype(np.float32)
+        np.testing.assert_array_equal(c.score[l, b, h, :m], f_ref)
+        # P1: both softmaxes are probability vectors
+        assert abs(dp[l, b, h, :m].sum() - 1) < 1e-12 and abs(df[l, b, h, :m].sum() - 1) < 1e-12
+        # P2: a convex combination of the value rows
+        Vm = as_f64(c.V[l, b, h, :m])
+        assert (out[l, b, h] <= Vm.max(0) + 1e-6).all() and (out[l, b, h] >= Vm.min(0) - 1e-6).all()
+    if noise in (ko.NOISE_NONE, ko.NOISE_CONSTANT):
+        pass
+
+
+def test_no_noise_tau_one_is_plain_attention_and_constant_shift_is_invisible():
+    # P4: without adjustment and at tau = 1 the score increment IS the attention
+    # probability (accumulated-attention / H2O-style score); a constant added to
+    # every logit cancels in the softmax.
+    rng = np.random.default_rng(6)
+    c = make_cache(rng, 1, 1, 2, 32, 50, 37)
+    c2 = c.copy()
+    q, kn, vn = (rand_vec(rng, (1, 1, 2, 32), ko.F32) for _ in range(3))
+    _, dp, df = c.decode_step(q, kn, vn, 37, 1.0, 0.3, ko.NOISE_NONE, debug=True)
+    assert (dp == df).all()
+    _, dp2, df2 = c2.decode_step(q, kn, vn, 37, 1.0, 0.3, ko.NOISE_CONSTANT, debug=True)
+    np.testing.assert_allclose(df2[..., :38], dp[..., :38], rtol=1e-12)
+
+
+def test_temperature_limits():
+    # Sec. 3.3.1: tau -> infinity gives uniform scores, tau -> 0 a sharp distribution
+    rng = np.random.default_rng(7)
+    n = 23
+    c = make_cache(rng, 1, 1, 2, 16, 30, n)
+    q, kn, vn = (rand_vec(rng, (1, 1, 2, 16), ko.F32) for _ in range(3))
+    seeds = np.array([5], np.uint64)
+    hot = c.copy()
+    _, _, df = c.decode_step(q, kn, vn, 100, 1e9, 0.25, ko.NOISE_GUMBEL, seeds, debug=True)
+    np.testing.assert_allclose(df[..., :n + 1], 1.0 / (n + 1), rtol=1e-6)
+    _, _, df = hot.decode_step(q, kn, vn, 100, 1e-3, 0.25, ko.NOISE_GUMBEL, seeds, debug=True)
+    for h in range(2):
+        K = as_f64(hot.K[0, 0, h, :n + 1])
+        x = 0.25 * (K @ as_f64(q[0, 0, h]))
+        z = np.array([ko.zeta(ko.NOISE_GUMBEL, 5, 0, h, 100, int(p)) for p in hot.pos[0, 0, h, :n + 1]])
+        j = int(np.argmax(x + z))
+        assert df[0, 0, h, j] > 1 - 1e-9 and abs(df[0, 0, h, :n + 1].sum() - 1) < 1e-12
+
+
+def test_single_token_and_equal_keys():
+    # P2 special case: one cached token -> out = its value, increment = 1
+    c = ko.OracleCache(1, 1, 1, 8, 4)
+    rng = np.random.default_rng(8)
+    q, kn, vn = (rand_vec(rng, (1, 1, 1, 8), ko.F32) for _ in range(3))
+    out, dp, df = c.decode_step(q, kn, vn, 0, 1.7, 0.35, ko.NOISE_GUMBEL, np.array([3], np.uint64), debug=True)
+    np.testing.assert_array_equal(out, vn)
+    assert dp[0, 0, 0, 0] == 1.0 and df[0, 0, 0, 0] == 1.0 and c.score[0, 0, 0, 0] == 1.0
+    # P12: all keys equal and no noise -> uniform attention, out = mean of values
+    n = 12
+    c = make_cache(rng, 1, 1, 1, 8, 20, n)
+    c.K[...] = 0
+    c.K[..., :n, :] = kn[0, 0, 0]
+    out, dp, df = c.decode_step(q, kn, vn, n, 1.3, 0.35, ko.NOISE_NONE, debug=True)
+    np.testing.assert_allclose(dp[0, 0, 0, :n + 1], 1 / (n + 1), rtol=1e-12)
+    np.testing.assert_allclose(df[0, 0, 0, :n + 1], 1 / (n + 1), rtol=1e-12)
+    np.testing.assert_allclose(out[0, 0, 0], as_f64(c.V[0, 0, 0, :n + 1]).mean(0), rtol=1e-6, atol=1e-7)
+
+
+def test_alibi_bias_favours_recent_tokens():
+    # MPT's ALiBi: the bias shrinks with distance, so with equal keys the
+    # attention decays geometrically with (q_pos - pos): p_j ~ exp(-slope*dist)
+    rng = np.random.default_rng(9)
+    n = 10
+    c = make_cache(rng, 1, 1, 1, 8, 16, n, pos=np.arange(n) * 3)
+    c.K[...] = 0
+    q = rand_vec(rng, (1, 1, 1, 8), ko.F32)
+    zero = np.zeros((1, 1, 1, 8), np.float32)
+    slope = 0.125
+    q_pos = 40
+    _, dp, _ = c.decode_step(q, zero, zero, q_pos, 1.0, 0.3, ko.NOISE_NONE, None,
+                             np.array([slope], np.float32), debug=True)
+    pos = np.append(np.arange(n) * 3, q_pos)
+    ref = np.exp(-slope * (q_pos - pos))
+    np.testing.assert_allclose(dp[0, 0, 0, :n + 1], ref / ref.sum(), rtol=1e-12)
+    assert (np.diff(dp[0, 0, 0, :n + 1]) > 0).all()
+
+
+def test_decode_is_invariant_under_slot_permutation():
+    # P12: the cache is a set of (pos, K, V, f) entries; permuting the slots
+    # (with their positions) changes neither out nor the increments per position
+    rng = np.random.default_rng(10)
+    n, d = 17, 16
+    c = make_cache(rng, 1, 1, 1, d, 24, n, pos=np.arange(n) * 2 + 1)
+    perm = rng.permutation(n)
+    c2 = c.copy()
+    c2.K[0, 0, 0, :n] = c.K[0, 0, 0, perm]
+    c2.V[0, 0, 0, :n] = c.V[0, 0, 0, perm]
+    c2.pos[0, 0, 0, :n] = c.pos[0, 0, 0, perm]
+    q, kn, vn = (rand_vec(rng, (1, 1, 1, d), ko.F32) for _ in range(3))
+    sd = np.array([77], np.uint64)
+    o1, _, df1 = c.decode_step(q, kn, vn, 99, 1.5, 0.25, ko.NOISE_GUMBEL, sd, debug=True)
+    o2, _, df2 = c2.decode_step(q, kn, vn, 99, 1.5, 0.25, ko.NOISE_GUMBEL, sd, debug=True)
+    np.testing.assert_allclose(o1, o2, rtol=1e-6, atol=1e-7)
+    np.testing.assert_allclose(df1[0, 0, 0, perm], df2[0, 0, 0, :n], rtol=1e-12)
+    np.testing.assert_allclose(df1[0, 0, 0, n], df2[0, 0, 0, n], rtol=1e-12)
+
+
+# ----------------------------------------------------------------------------
+# Prompt-phase scoring (Sec. 3.4, Alg. 1 prompt branch)
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", [ko.F32, ko.BF16])
+@pytest.mark.parametrize("noise", [ko.NOISE_GUMBEL, ko.NOISE_NONE])
+def test_prefill_matches_numpy(dtype, noise):
+    rng = np.random.default_rng(11)
+    L, B, H, d, n, cap = 1, 2, 2, 16, 33, 40
+    c = make_cache(rng, L, B, H, d, cap, n, dtype)
+    c.pos[...] = -7
+    c.len[...] = 0
+    Q = rand_vec(rng, (L, B, H, n, d), dtype)
+    seeds = np.array([1234, 99], np.uint64)
+    slopes = np.array([0.0, 0.0625], np.float32)
+    tau, scale = 1.25, 0.25
+    c.prefill_score(Q, n, tau, scale, noise, seeds, slopes)
+    assert (c.len == n).all() and (c.pos[..., :n] == np.arange(n)).all()
+    i, j = np.meshgrid(np.arange(n), np.arange(n), indexing="ij")
+    for b, h in itertools.product(range(B), range(H)):
+        x = np.float64(np.float32(scale)) * (as_f64(Q[0, b, h]) @ as_f64(c.K[0, b, h, :n]).T)
+        x = x - float(slopes[h]) * (i - j)
+        z = zeta_matrix(noise, int(seeds[b]), 0, h, range(n), range(n))
+        y = (x + z) / np.float64(np.float32(tau))
+        y = np.where(j <= i, y, -np.inf)                  # causal: token i sees keys 0..i
+        zmat = scipy.special.softmax(y, axis=1)
+        f_ref = zmat.sum(axis=0)                          # column sums
+        np.testing.assert_allclose(c.score[0, b, h, :n], f_ref, rtol=3e-7)
+        assert abs(c.score[0, b, h, :n].astype(np.float64).sum() - n) < 1e-4   # P1: n rows, each sums to 1
+        assert c.score[0, b, h, n - 1] <= 1.0            # the last key is seen by one row only
+
+
+def test_prefill_first_row_and_uniform_case():
+    # one prompt token: f = [1].  Equal keys, no noise: row i spreads 1/(i+1)
+    # over its i+1 keys, so f[j] = sum_{i>=j} 1/(i+1) = H_n - H_j (harmonic numbers)
+    rng = np.random.default_rng(12)
+    c = make_cache(rng, 1, 1, 1, 8, 4, 1)
+    Q = rand_vec(rng, (1, 1, 1, 1, 8), ko.F32)
+    c.prefill_score(Q, 1, 1.0, 0.3, ko.NOISE_GUMBEL, np.array([1], np.uint64))
+    assert c.score[0, 0, 0, 0] == 1.0
+    n = 20
+    c = make_cache(rng, 1, 1, 1, 8, n, n)
+    c.K[0, 0, 0, :, :] = c.K[0, 0, 0, 0, :]
+    Q = rand_vec(rng, (1, 1, 1, n, 8), ko.F32)
+    c.prefill_score(Q, n, 1.0, 0.3, ko.NOISE_NONE)
+    harm = np.cumsum(1.0 / np.arange(1, n + 1))
+    ref = harm[-1] - np.concatenate([[0.0], harm[:-1]])
+    np.testing.assert_allclose(c.score[0, 0, 0], ref, rtol=3e-7)
+
+
+# ----------------------------------------------------------------------------
+# Selection + compaction (Alg. 1: S_w, S_key = argmax_(k-w) f[:-w], S_k)
+# ----------------------------------------------------------------------------
+def brute_force_keep(f, n, k, w):
+    """All subsets of the candidates: maximal score sum, then lexicographically
+    smallest index tuple (= prefers lower slots among equal scores)."""
+    ncand, nkey = n - w, k - w
+    best, best_sum = None, None
+    for comb in itertools.combinations(range(ncand), nkey):
+        s = math.fsum(float(f[i]) for i in comb)
+        if best is None or s > best_sum or (s == best_sum and comb < best):
+            best, best_sum = comb, s
+    return list(best) + list(range(n - w, n))
+
+
+def test_select_matches_brute_force_with_ties():
+    rng = np.random.default_rng(13)
+    for trial in range(60):
+        n = int(rng.integers(5, 15))
+        k = int(rng.integers(1, n))
+        w = int(rng.integers(0, k + 1))
+        if n - w > 12:
+            continue
+        c = make_cache(rng, 1, 1, 1, 4, n, n)
+        # few distinct dyadic values -> many exact ties, exactly summable
+        c.score[0, 0, 0, :n] = rng.integers(0, 4, n).astype(np.float32) * 0.25
+        before = c.copy()
+        kept = c.select_evict(k, w)
+        ref = brute_force_keep(before.score[0, 0, 0], n, k, w)
+        assert kept[0, 0, 0].tolist() == ref, (n, k, w, before.score[0, 0, 0].tolist())
+        # P3: survivors are bit-identical copies, in order
+        assert c.len[0, 0, 0] == k
+        np.testing.assert_array_equal(c.K[0, 0, 0, :k], before.K[0, 0, 0, ref])
+        np.testing.assert_array_equal(c.V[0, 0, 0, :k], before.V[0, 0, 0, ref])
+        np.testing.assert_array_equal(c.score[0, 0, 0, :k], before.score[0, 0, 0, ref])
+        np.testing.assert_array_equal(c.pos[0, 0, 0, :k], before.pos[0, 0, 0, ref])
+
+
+def test_select_equals_stable_sort_topk_and_invariants():
+    rng = np.random.default_rng(14)
+    L, B, H, d, n, k, w = 2, 2, 2, 8, 300, 120, 24
+    c = make_cache(rng, L, B, H, d, n, n, ko.BF16)
+    c.score[...] = rng.random((L, B, H, n)).astype(np.float32)
+    c.score[..., 50:90] = 0.5                    # a block of ties straddling the threshold region
+    c.len[0, 0, 0] = 100                         # a unit below the budget is left alone
+    before = c.copy()
+    kept = c.select_evict(k, w)
+    for l, b, h in itertools.product(range(L), range(B), range(H)):
+        n_u = int(before.len[l, b, h])
+        if n_u <= k:
+            assert c.len[l, b, h] == n_u
+            assert kept[l, b, h, :n_u].tolist() == list(range(n_u)) and (kept[l, b, h, n_u:] == -1).all()
+            np.testing.assert_array_equal(c.K[l, b, h], before.K[l, b, h])
+            continue
+        f = before.score[l, b, h, :n_u - w]
+        order = np.argsort(-f.astype(np.float64), kind="stable")       # stable: lower slot first
+        ref = sorted(order[:k - w].tolist()) + list(range(n_u - w, n_u))
+        assert kept[l, b, h].tolist() == ref
+        assert c.len[l, b, h] == k
+        pos = c.pos[l, b, h, :k]
+        assert (np.diff(pos) > 0).all()                                 # order preserved
+        assert set(range(n_u - w, n_u)) <= set(pos.tolist())            # recent window kept
+        # nothing evicted outscores anything kept among the candidates
+        evicted = sorted(set(range(n_u - w)) - set(ref))
+        assert before.score[l, b, h, evicted].max() <= before.score[l, b, h, ref[:k - w]].min()
+
+
+def test_decode_shape_drops_the_single_minimum():
+    # P10: with len = k+1 exactly one token leaves: the candidate with the
+    # smallest score, the highest slot among equal minima
+    rng = np.random.default_rng(15)
+    k, w = 40, 8
+    n = k + 1
+    c = make_cache(rng, 1, 1, 4, 4, n, n)
+    c.score[...] = rng.random((1, 1, 4, n)).astype(np.float32) + 1
+    c.score[0, 0, 0, [3, 17, 30]] = 0.5         # three equal minima -> slot 30 goes
+    c.score[0, 0, 1, 36] = 0.0                  # minimum inside the window is protected
+    c.score[0, 0, 2, 0] = 0.25                  # oldest token
+    c.score[0, 0, 3, n - w - 1] = 0.25          # last candidate
+    before = c.copy()
+    kept = c.select_evict(k, w)
+    drop = [30, int(np.argmin(before.score[0, 0, 1, :n - w])), 0, n - w - 1]
+    for h in range(4):
+        assert kept[0, 0, h].tolist() == [i for i in range(n) if i != drop[h]]
+
+
+def test_select_boundaries():
+    rng = np.random.default_rng(16)
+    n, k = 20, 8
+    for w in (0, k):                             # pure top-k ; pure recent window
+        c = make_cache(rng, 1, 1, 1, 4, n, n)
+        c.score[...] = rng.random((1, 1, 1, n)).astype(np.float32)
+        f = c.score[0, 0, 0].copy()
+        kept = c.select_evict(k, w)[0, 0, 0].tolist()
+        if w == 0:
+            assert kept == sorted(np.argsort(-f, kind="stable")[:k].tolist())
+        else:
+            assert kept == list(range(n - k, n))
+    c = make_cache(rng, 1, 1, 1, 4, n, n)
+    with pytest.raises(ValueError):
+        c.select_evict(8, 9)                     # w > k
+    with pytest.raises(ValueError):
+        c.select_evict(0, 0)                     # k < 1
+
+
+# ----------------------------------------------------------------------------
+# Whole algorithm on the tiny configuration: invariants of every step
+# ----------------------------------------------------------------------------
+def test_tiny_config_end_to_end_invariants():
+    import kf_workloads as kw
+    wl = kw.CONFIGS["tiny"]
+    Q, K, V = kw.prompt_layer(wl, 0)
+    c = ko.OracleCache(wl.L, wl.B, wl.H, wl.d, wl.n, ko.F32)
+    c.K[0, :, :, :wl.n] = kw.to_oracle(K)
+    c.V[0, :, :, :wl.n] = kw.to_oracle(V)
+    seeds = kw.noise_seeds(wl)
+    c.prefill_score(kw.to_oracle(Q)[None], wl.n, ko.tau(0, wl.T), wl.scale, ko.NOISE_GUMBEL, seeds)
+    assert abs(c.score.astype(np.float64).sum() - wl.units * wl.n) < 1e-3
+    c.select_evict(wl.k, wl.w)
+    assert (c.len == wl.k).all()
+    assert (c.pos[..., wl.k - wl.w:wl.k] == np.arange(wl.n - wl.w, wl.n)).all()
+    total = c.score[..., :wl.k].astype(np.float64).sum()
+    for t in range(1, wl.T + 1):
+        q, kn, vn = (kw.to_oracle(a) for a in kw.decode_inputs(wl, t))
+        q_pos = wl.n + t - 1
+        out = c.decode_step(q, kn, vn, q_pos, ko.tau(t, wl.T), wl.scale, ko.NOISE_GUMBEL, seeds)
+        assert (c.len == wl.k + 1).all() and np.isfinite(out).all()
+        now = c.score[..., :wl.k + 1].astype(np.float64).sum()
+        assert abs(now - total - wl.units) < 1e-4                  # each unit gained exactly 1
+        c.select_evict(wl.k, wl.w)
+        assert (c.len == wl.k).all()                               # cache never exceeds k after eviction
+        pos = c.pos[..., :wl.k]
+        assert (np.diff(pos, axis=-1) > 0).all()
+        assert (pos[..., wl.k - wl.w:] == np.arange(q_pos - wl.w + 1, q_pos + 1)).all()   # w most recent
+        total = c.score[..., :wl.k].astype(np.float64).sum()
