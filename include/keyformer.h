@@ -1,0 +1,156 @@
+/*
+ * keyformer.h -- C ABI of the MI355X (gfx950) Keyformer decode hot path.
+ *
+ * Keyformer (arXiv 2403.09054) keeps, per layer and per head, a KV cache of k
+ * tokens: the w most recent ones plus the k-w "key tokens" with the largest
+ * accumulated score f.  The score of a step is a softmax of the attention
+ * logits perturbed by a logit adjustment zeta and divided by a temperature tau
+ * that grows over the generation (Eq. 4, Eq. 11, Eq. 12, Algorithm 1).
+ *
+ * Conventions
+ *  - A "unit" is one (layer, batch, head) triple: an independent cache with its
+ *    own scores.  Unit index u = (l*B + b)*H + h.  Every call handles all units.
+ *  - Every pointer marked DEVICE is GPU memory owned by the caller; the library
+ *    never allocates, frees or keeps it.  Pointers marked HOST are read during
+ *    the call only.
+ *  - The three hot calls only enqueue kernels on `stream` (a hipStream_t passed
+ *    as void*, NULL = the default stream) and return; they do not synchronise.
+ *  - Arguments are validated on the host before anything is launched; a call
+ *    that returns an error has launched nothing.  kf_last_error() describes the
+ *    last failure of the calling thread.
+ *  - The workspace is DEVICE memory of at least kf_workspace_bytes() bytes,
+ *    16-byte aligned, zero-filled once by the caller before its first use; the
+ *    library leaves it reusable after every call.  Calls that share a workspace
+ *    must be ordered on one stream.
+ *  - Supported element type / head dimension pairs: bf16 with d in {64,128,256},
+ *    fp32 with d in {64,128}.
+ */
+#ifndef KEYFORMER_H
+#define KEYFORMER_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    KF_OK = 0,
+    KF_EINVAL = -1,       /* null pointer, size out of range, non-finite tau ... */
+    KF_EUNSUPPORTED = -2, /* dtype / head-dimension pair not built */
+    KF_EWORKSPACE = -3,   /* workspace missing, misaligned or too small */
+    KF_EDEVICE = -4       /* the HIP runtime refused a launch */
+} kf_status;
+
+typedef enum { KF_F32 = 0, KF_BF16 = 1 } kf_dtype;
+
+/* Logit adjustment zeta of Eq. 4.  GUMBEL is the method (Eq. 7); NONE is the
+ * accumulated-attention score of prior work; GAUSSIAN (Eq. 5, mean 0.5772,
+ * std 1.2825) and CONSTANT (0.5772) are the paper's ablation variants. */
+typedef enum {
+    KF_NOISE_NONE = 0,
+    KF_NOISE_GUMBEL = 1,
+    KF_NOISE_GAUSSIAN = 2,
+    KF_NOISE_CONSTANT = 3
+} kf_noise;
+
+/* The per-layer, per-head caches (Fig. 5: scores accumulate "for each layer
+ * and head").  Row j of a unit is one cached token. */
+typedef struct {
+    void *K;        /* DEVICE [L][B][H][cap][d] keys,   element type `dtype`, 16-byte aligned */
+    void *V;        /* DEVICE [L][B][H][cap][d] values                                   */
+    float *score;   /* DEVICE [L][B][H][cap]    accumulated score f_theta (Sec. 3.3.2)    */
+    int32_t *pos;   /* DEVICE [L][B][H][cap]    original position of each token ("Org Pos",
+                       Sec. 4.4.2); ascending over slots [0,len)                          */
+    int32_t *len;   /* DEVICE [L][B][H]         live tokens per unit                      */
+    int32_t L, B, H, d, cap;
+    int32_t dtype;  /* kf_dtype */
+} kf_cache;
+
+/* Parameters of the score function (Eq. 11) for one call. */
+typedef struct {
+    float tau;                 /* temperature of this iteration, from kf_tau()            */
+    float scale;               /* logit scale, 1/sqrt(d) in Eq. 1                         */
+    int32_t noise;             /* kf_noise                                                */
+    const uint64_t *seeds;     /* DEVICE [B] one noise seed per sequence; may be NULL
+                                  when noise is NONE or CONSTANT                          */
+    const float *alibi_slopes; /* DEVICE [H] or NULL.  Adds -slope[h]*(q_pos - pos_j) to
+                                  the logits (MPT's position bias)                        */
+} kf_score_cfg;
+
+/* Library version, for the binding to check it loaded what it expects. */
+int32_t kf_version(void);
+
+/* Text of the calling thread's last error ("" if none). */
+const char *kf_last_error(void);
+
+/* Temperature schedule, Eq. 12: tau_init + t*(tau_end - tau_init)/T, evaluated
+ * in fp32.  t = 0 is the prompt iteration, t = 1..T the decode steps. */
+float kf_tau(int32_t t, int32_t T, float tau_init, float tau_end);
+
+/* Host mirror of the device noise hash: the 32 random bits behind zeta for
+ * (seed, layer, head, query position, key's original position).  The uniform is
+ * u = (2*(bits>>9)+1)/2^24 and the Gumbel variate of Eq. 7 is -ln(-ln u). */
+uint32_t kf_noise_bits(uint64_t seed, uint32_t layer, uint32_t head, uint32_t q_pos, uint32_t k_pos);
+
+/* Bytes of workspace that suffice for any of the three hot calls on this
+ * cache, with prompt length up to n_max (pass 0 if kf_prefill_score is not
+ * used).  Only the cache's dimensions are read. */
+size_t kf_workspace_bytes(const kf_cache *c, int32_t n_max);
+
+/* Device-side error counter: the first int32 of the workspace counts units a
+ * kernel had to skip (kf_decode_step on a unit with len >= cap).  Exposed as a
+ * constant so callers can read it back themselves. */
+#define KF_WS_ERROR_WORD 0
+
+/*
+ * Prompt-phase scoring (Sec. 3.4, Algorithm 1 prompt branch).  For every unit,
+ * with the n prompt keys already stored in rows 0..n-1 of K:
+ *     x_ij = scale*<Q_i, K_j> - slope_h*(i-j)          j <= i   (causal)
+ *     z_i  = softmax_j((x_ij + zeta_ij)/tau)                    (Eq. 4, Eq. 11)
+ *     score[j] = sum_{i>=j} z_ij ;  pos[j] = j ;  len = n
+ * Q is DEVICE [L][B][H][n][d] in the cache's dtype.  V is not touched.
+ * Errors: KF_EINVAL if n < 1 or n > cap, tau not finite or <= 0, null pointers,
+ * seeds missing for a random adjustment.
+ */
+kf_status kf_prefill_score(const kf_cache *c, const void *Q, int32_t n, const kf_score_cfg *cfg,
+                           void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * One generation step (Algorithm 1 else-branch) for every unit:
+ *   append   K[len] = k_new, V[len] = v_new, pos[len] = q_pos, score[len] = 0; m = len+1
+ *   logits   x_j = scale*<q, K_j> - slope_h*(q_pos - pos_j)              (Eq. 1)
+ *   attend   out = sum_j softmax(x)_j V_j                   (no noise, no tau)
+ *   score    score[j] += softmax((x + zeta)/tau)_j   for all j < m  (Eq. 11, Sec. 3.3.2)
+ *   len      = m
+ * q, k_new, v_new are DEVICE [L][B][H][d] in the cache's dtype; out is DEVICE
+ * [L][B][H][d] fp32.  q_pos is the absolute position of the new token (n+t-1
+ * at decode step t).  m_hint is an upper bound of len+1 over all units, used
+ * only to shape the launch; pass 0 (= cap) if unknown.
+ * A unit whose len is already cap is skipped: its `out` is zero-filled and the
+ * workspace error word is incremented.
+ * Errors: KF_EINVAL for null pointers, q_pos < 0, bad tau, m_hint > cap;
+ * KF_EWORKSPACE if the workspace is too small.
+ */
+kf_status kf_decode_step(kf_cache *c, const void *q, const void *k_new, const void *v_new,
+                         int32_t q_pos, int32_t m_hint, const kf_score_cfg *cfg, float *out,
+                         void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Key-token selection and KV compaction (Algorithm 1: S_w, S_key, S_k; Sec. 3.4).
+ * Units with len <= k are left untouched.  Otherwise the survivors are the last
+ * w slots plus the k-w slots of [0, len-w) with the largest score, equal scores
+ * resolved in favour of the lower slot; K, V, score and pos rows of the
+ * survivors move to slots [0,k) in their original order, in place; len = k.
+ * kept_idx, if not NULL, is DEVICE [L][B][H][k] and receives the pre-compaction
+ * slot of every survivor (identity, then -1 padding, for untouched units).
+ * Errors: KF_EINVAL if k < 1, w < 0, w > k or k > cap.
+ */
+kf_status kf_select_evict(kf_cache *c, int32_t k, int32_t w, int32_t *kept_idx, void *workspace,
+                          size_t workspace_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KEYFORMER_H */

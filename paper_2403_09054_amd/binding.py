@@ -1,0 +1,193 @@
+"""ctypes binding of libkeyformer.so: same names as the C ABI, marshalling only.
+
+torch is used for device memory and streams; no arithmetic of the method is
+done here.  If the shared library is missing the import of the symbols fails
+with an error that says how to build it -- there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(HERE, "libkeyformer.so")
+
+F32, BF16 = 0, 1
+NOISE_NONE, NOISE_GUMBEL, NOISE_GAUSSIAN, NOISE_CONSTANT = 0, 1, 2, 3
+KF_OK, KF_EINVAL, KF_EUNSUPPORTED, KF_EWORKSPACE, KF_EDEVICE = 0, -1, -2, -3, -4
+
+# every symbol include/keyformer.h declares
+SYMBOLS = ("kf_version", "kf_last_error", "kf_tau", "kf_noise_bits", "kf_workspace_bytes",
+           "kf_prefill_score", "kf_decode_step", "kf_select_evict")
+
+
+class KeyformerError(RuntimeError):
+    def __init__(self, status, text):
+        super().__init__("keyformer status %d: %s" % (status, text))
+        self.status = status
+
+
+class kf_cache(C.Structure):
+    _fields_ = [("K", C.c_void_p), ("V", C.c_void_p), ("score", C.c_void_p), ("pos", C.c_void_p),
+                ("len", C.c_void_p), ("L", C.c_int32), ("B", C.c_int32), ("H", C.c_int32),
+                ("d", C.c_int32), ("cap", C.c_int32), ("dtype", C.c_int32)]
+
+
+class kf_score_cfg(C.Structure):
+    _fields_ = [("tau", C.c_float), ("scale", C.c_float), ("noise", C.c_int32),
+                ("seeds", C.c_void_p), ("alibi_slopes", C.c_void_p)]
+
+
+_lib = None
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def lib():
+    """The loaded library.  Raises if it has not been built (no fallback)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise ImportError(
+                "libkeyformer.so is not built: run `python -m paper_2403_09054_amd.build` "
+                "(or __graft_entry__.build()) first; there is no CPU fallback")
+        L = C.CDLL(_LIB_PATH)
+        vp = C.c_void_p
+        L.kf_version.restype = C.c_int32
+        L.kf_version.argtypes = []
+        L.kf_last_error.restype = C.c_char_p
+        L.kf_last_error.argtypes = []
+        L.kf_tau.restype = C.c_float
+        L.kf_tau.argtypes = [C.c_int32, C.c_int32, C.c_float, C.c_float]
+        L.kf_noise_bits.restype = C.c_uint32
+        L.kf_noise_bits.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32]
+        L.kf_workspace_bytes.restype = C.c_size_t
+        L.kf_workspace_bytes.argtypes = [C.POINTER(kf_cache), C.c_int32]
+        L.kf_prefill_score.restype = C.c_int
+        L.kf_prefill_score.argtypes = [C.POINTER(kf_cache), vp, C.c_int32, C.POINTER(kf_score_cfg), vp,
+                                       C.c_size_t, vp]
+        L.kf_decode_step.restype = C.c_int
+        L.kf_decode_step.argtypes = [C.POINTER(kf_cache), vp, vp, vp, C.c_int32, C.c_int32,
+                                     C.POINTER(kf_score_cfg), vp, vp, C.c_size_t, vp]
+        L.kf_select_evict.restype = C.c_int
+        L.kf_select_evict.argtypes = [C.POINTER(kf_cache), C.c_int32, C.c_int32, vp, vp, C.c_size_t, vp]
+        _lib = L
+    return _lib
+
+
+def _check(rc):
+    if rc != KF_OK:
+        raise KeyformerError(rc, lib().kf_last_error().decode())
+
+
+def kf_version() -> int:
+    return int(lib().kf_version())
+
+
+def kf_tau(t: int, T: int, tau_init: float = 1.0, tau_end: float = 2.0) -> float:
+    return float(lib().kf_tau(t, T, tau_init, tau_end))
+
+
+def kf_noise_bits(seed: int, layer: int, head: int, q_pos: int, k_pos: int) -> int:
+    return int(lib().kf_noise_bits(seed, layer, head, q_pos, k_pos))
+
+
+def _ptr(t):
+    """Device (or fake, for host-only validation tests) address of a tensor / int / None."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+@dataclass
+class Cache:
+    """Torch tensors that back a kf_cache.  K, V: [L,B,H,cap,d] (float32 or
+    bfloat16); score [L,B,H,cap] float32; pos [L,B,H,cap] int32; len [L,B,H] int32."""
+    K: object
+    V: object
+    score: object
+    pos: object
+    len: object
+    L: int
+    B: int
+    H: int
+    d: int
+    cap: int
+    dtype: int
+
+    @staticmethod
+    def allocate(L, B, H, d, cap, dtype=BF16, device="cuda"):
+        import torch
+        et = torch.float32 if dtype == F32 else torch.bfloat16
+        return Cache(K=torch.zeros((L, B, H, cap, d), dtype=et, device=device),
+                     V=torch.zeros((L, B, H, cap, d), dtype=et, device=device),
+                     score=torch.zeros((L, B, H, cap), dtype=torch.float32, device=device),
+                     pos=torch.zeros((L, B, H, cap), dtype=torch.int32, device=device),
+                     len=torch.zeros((L, B, H), dtype=torch.int32, device=device),
+                     L=L, B=B, H=H, d=d, cap=cap, dtype=dtype)
+
+    def c_struct(self) -> kf_cache:
+        return kf_cache(_ptr(self.K), _ptr(self.V), _ptr(self.score), _ptr(self.pos), _ptr(self.len),
+                        self.L, self.B, self.H, self.d, self.cap, self.dtype)
+
+
+def kf_workspace_bytes(cache: Cache, n_max: int = 0) -> int:
+    cs = cache.c_struct()
+    return int(lib().kf_workspace_bytes(C.byref(cs), n_max))
+
+
+def new_workspace(cache: Cache, n_max: int = 0, device="cuda"):
+    """A zero-filled workspace tensor large enough for every call on `cache`."""
+    import torch
+    nbytes = kf_workspace_bytes(cache, n_max)
+    if nbytes == 0:
+        raise KeyformerError(KF_EUNSUPPORTED, "unsupported cache shape")
+    return torch.zeros((nbytes + 15) // 16 * 16, dtype=torch.uint8, device=device)
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream if torch.cuda.is_available() else None
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def _ws(workspace):
+    if workspace is None:
+        return None, 0
+    if isinstance(workspace, tuple):  # (address, bytes), for host-only tests
+        return workspace
+    return workspace.data_ptr(), workspace.numel() * workspace.element_size()
+
+
+def _cfg(tau, scale, noise, seeds, slopes) -> kf_score_cfg:
+    return kf_score_cfg(tau, scale, noise, _ptr(seeds), _ptr(slopes))
+
+
+def kf_prefill_score(cache: Cache, Q, n: int, tau: float, scale: float, noise: int = NOISE_GUMBEL,
+                     seeds=None, slopes=None, workspace=None, stream=None) -> None:
+    cs, cfg = cache.c_struct(), _cfg(tau, scale, noise, seeds, slopes)
+    wp, wb = _ws(workspace)
+    _check(lib().kf_prefill_score(C.byref(cs), _ptr(Q), n, C.byref(cfg), wp, wb, _stream(stream)))
+
+
+def kf_decode_step(cache: Cache, q, k_new, v_new, q_pos: int, m_hint: int, tau: float, scale: float,
+                   noise: int = NOISE_GUMBEL, seeds=None, slopes=None, out=None, workspace=None,
+                   stream=None) -> None:
+    cs, cfg = cache.c_struct(), _cfg(tau, scale, noise, seeds, slopes)
+    wp, wb = _ws(workspace)
+    _check(lib().kf_decode_step(C.byref(cs), _ptr(q), _ptr(k_new), _ptr(v_new), q_pos, m_hint,
+                                C.byref(cfg), _ptr(out), wp, wb, _stream(stream)))
+
+
+def kf_select_evict(cache: Cache, k: int, w: int, kept_idx=None, workspace=None, stream=None) -> None:
+    cs = cache.c_struct()
+    wp, wb = _ws(workspace)
+    _check(lib().kf_select_evict(C.byref(cs), k, w, _ptr(kept_idx), wp, wb, _stream(stream)))

@@ -1,0 +1,240 @@
+// C ABI of the Keyformer library: argument validation on the host, workspace
+// carving, kernel launches.  Nothing here allocates device memory.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "kf_device.h"
+#include "kf_internal.h"
+
+namespace {
+
+thread_local char g_err[256] = "";
+
+kf_status fail(kf_status st, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+bool supported(int32_t dtype, int32_t d) {
+    if (dtype == KF_BF16) return d == 64 || d == 128 || d == 256;
+    if (dtype == KF_F32) return d == 64 || d == 128;
+    return false;
+}
+
+kf_status check_cache(const kf_cache* c) {
+    if (!c) return fail(KF_EINVAL, "cache is NULL");
+    if (!c->K || !c->V || !c->score || !c->pos || !c->len) return fail(KF_EINVAL, "cache has a NULL buffer");
+    if (c->L < 1 || c->B < 1 || c->H < 1 || c->cap < 1 || c->d < 1)
+        return fail(KF_EINVAL, "cache dimensions must be positive (L=%d B=%d H=%d d=%d cap=%d)", c->L, c->B, c->H,
+                    c->d, c->cap);
+    if ((int64_t)c->L * c->B * c->H > (int64_t)1 << 24) return fail(KF_EINVAL, "too many units");
+    if (c->dtype != KF_F32 && c->dtype != KF_BF16) return fail(KF_EINVAL, "unknown dtype %d", c->dtype);
+    if (!supported(c->dtype, c->d))
+        return fail(KF_EUNSUPPORTED, "dtype %d with head dimension %d is not built", c->dtype, c->d);
+    if (((uintptr_t)c->K | (uintptr_t)c->V) & 15) return fail(KF_EINVAL, "K and V must be 16-byte aligned");
+    return KF_OK;
+}
+
+kf_status check_cfg(const kf_score_cfg* cfg) {
+    if (!cfg) return fail(KF_EINVAL, "score configuration is NULL");
+    if (!(cfg->tau > 0.0f) || !isfinite(cfg->tau)) return fail(KF_EINVAL, "tau must be finite and positive");
+    if (!isfinite(cfg->scale)) return fail(KF_EINVAL, "scale must be finite");
+    if (cfg->noise < KF_NOISE_NONE || cfg->noise > KF_NOISE_CONSTANT)
+        return fail(KF_EINVAL, "unknown noise mode %d", cfg->noise);
+    if ((cfg->noise == KF_NOISE_GUMBEL || cfg->noise == KF_NOISE_GAUSSIAN) && !cfg->seeds)
+        return fail(KF_EINVAL, "a random logit adjustment needs seeds");
+    return KF_OK;
+}
+
+// Workspace layout (all regions 256-byte aligned):
+//   [0]        error word + padding
+//   counters   U int32            decode arrival counters (zero between calls)
+//   region X   the largest of
+//                decode : partial records U*S*(d+4) floats, then increments U*cap floats
+//                select : survivor index list U*cap int32
+//                prefill: row normalisers U*n_pad floats, then row keys U*n_pad uint32
+struct WsLayout {
+    size_t counters, region, total;
+};
+
+size_t decode_region(int64_t U, const kf_cache* c) {
+    const kf::DecodePlan p = kf::plan_decode(U, c->cap, c->d, c->dtype);
+    return align_up((size_t)U * p.S * (c->d + 4) * sizeof(float), 256) +
+           align_up((size_t)U * c->cap * sizeof(float), 256);
+}
+
+WsLayout ws_layout(const kf_cache* c, int32_t n_max) {
+    const int64_t U = (int64_t)c->L * c->B * c->H;
+    WsLayout w;
+    w.counters = 256;
+    w.region = w.counters + align_up((size_t)U * sizeof(int32_t), 256);
+    size_t x = decode_region(U, c);
+    const size_t sel = align_up((size_t)U * c->cap * sizeof(int32_t), 256);
+    if (sel > x) x = sel;
+    if (n_max > 0) {
+        const size_t n_pad = align_up((size_t)n_max, kf::kPrefillRowPad);
+        const size_t pre = 2 * align_up((size_t)U * n_pad * sizeof(float), 256);
+        if (pre > x) x = pre;
+    }
+    w.total = w.region + x;
+    return w;
+}
+
+kf_status check_ws(const void* ws, size_t have, size_t need) {
+    if (!ws) return fail(KF_EWORKSPACE, "workspace is NULL");
+    if ((uintptr_t)ws & 15) return fail(KF_EWORKSPACE, "workspace must be 16-byte aligned");
+    if (have < need) return fail(KF_EWORKSPACE, "workspace has %zu bytes, %zu needed", have, need);
+    return KF_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t kf_version(void) { return 1; }
+
+const char* kf_last_error(void) { return g_err; }
+
+float kf_tau(int32_t t, int32_t T, float tau_init, float tau_end) {
+    const float dtau = (tau_end - tau_init) / (float)T;
+    return tau_init + (float)t * dtau;
+}
+
+uint32_t kf_noise_bits(uint64_t seed, uint32_t layer, uint32_t head, uint32_t q_pos, uint32_t k_pos) {
+    return kf::logit_bits(kf::row_key(kf::unit_key(seed, layer, head), q_pos), k_pos);
+}
+
+size_t kf_workspace_bytes(const kf_cache* c, int32_t n_max) {
+    if (!c || c->L < 1 || c->B < 1 || c->H < 1 || c->cap < 1 || !supported(c->dtype, c->d)) return 0;
+    if (n_max < 0) n_max = 0;
+    return ws_layout(c, n_max).total;
+}
+
+kf_status kf_prefill_score(const kf_cache* c, const void* Q, int32_t n, const kf_score_cfg* cfg, void* workspace,
+                           size_t workspace_bytes, void* stream) {
+    kf_status st = check_cache(c);
+    if (st != KF_OK) return st;
+    st = check_cfg(cfg);
+    if (st != KF_OK) return st;
+    if (!Q) return fail(KF_EINVAL, "Q is NULL");
+    if ((uintptr_t)Q & 15) return fail(KF_EINVAL, "Q must be 16-byte aligned");
+    if (n < 1 || n > c->cap) return fail(KF_EINVAL, "prompt length %d outside [1, cap=%d]", n, c->cap);
+    const WsLayout w = ws_layout(c, n);
+    st = check_ws(workspace, workspace_bytes, w.total);
+    if (st != KF_OK) return st;
+
+    const int64_t U = (int64_t)c->L * c->B * c->H;
+    const size_t n_pad = align_up((size_t)n, kf::kPrefillRowPad);
+    kf::PrefillArgs a;
+    a.Q = Q;
+    a.K = c->K;
+    a.score = c->score;
+    a.pos = c->pos;
+    a.len = c->len;
+    a.seeds = cfg->seeds;
+    a.slopes = cfg->alibi_slopes;
+    a.ws_c = (float*)((char*)workspace + w.region);
+    a.ws_r = (uint32_t*)((char*)workspace + w.region + align_up((size_t)U * n_pad * sizeof(float), 256));
+    a.B = c->B;
+    a.H = c->H;
+    a.cap = c->cap;
+    a.n = n;
+    a.n_pad = (int32_t)n_pad;
+    a.noise = cfg->noise;
+    a.inv_tau = 1.0f / cfg->tau;
+    a.scale = cfg->scale;
+    const hipError_t e = kf::launch_prefill(a, U, c->d, c->dtype, (hipStream_t)stream);
+    if (e != hipSuccess) return fail(KF_EDEVICE, "prefill launch: %s", hipGetErrorString(e));
+    g_err[0] = 0;
+    return KF_OK;
+}
+
+kf_status kf_decode_step(kf_cache* c, const void* q, const void* k_new, const void* v_new, int32_t q_pos,
+                         int32_t m_hint, const kf_score_cfg* cfg, float* out, void* workspace,
+                         size_t workspace_bytes, void* stream) {
+    kf_status st = check_cache(c);
+    if (st != KF_OK) return st;
+    st = check_cfg(cfg);
+    if (st != KF_OK) return st;
+    if (!q || !k_new || !v_new || !out) return fail(KF_EINVAL, "q, k_new, v_new and out must not be NULL");
+    if (((uintptr_t)q | (uintptr_t)k_new | (uintptr_t)v_new) & 15)
+        return fail(KF_EINVAL, "q, k_new and v_new must be 16-byte aligned");
+    if (q_pos < 0) return fail(KF_EINVAL, "q_pos must be non-negative");
+    if (m_hint < 0 || m_hint > c->cap) return fail(KF_EINVAL, "m_hint %d outside [0, cap=%d]", m_hint, c->cap);
+    if (m_hint == 0) m_hint = c->cap;
+    const WsLayout w = ws_layout(c, 0);
+    st = check_ws(workspace, workspace_bytes, w.total);
+    if (st != KF_OK) return st;
+
+    const int64_t U = (int64_t)c->L * c->B * c->H;
+    const kf::DecodePlan p = kf::plan_decode(U, m_hint, c->d, c->dtype);
+    // the partial-record region is sized for the plan at m = cap, the largest
+    const kf::DecodePlan pmax = kf::plan_decode(U, c->cap, c->d, c->dtype);
+    if (p.S > pmax.S) return fail(KF_EWORKSPACE, "internal: split count %d exceeds the sized %d", p.S, pmax.S);
+    kf::DecodeArgs a;
+    a.K = c->K;
+    a.V = c->V;
+    a.score = c->score;
+    a.pos = c->pos;
+    a.len = c->len;
+    a.q = q;
+    a.k_new = k_new;
+    a.v_new = v_new;
+    a.out = out;
+    a.seeds = cfg->seeds;
+    a.slopes = cfg->alibi_slopes;
+    a.ws_err = (int32_t*)workspace + KF_WS_ERROR_WORD;
+    a.ws_cnt = (int32_t*)((char*)workspace + w.counters);
+    a.ws_part = (float*)((char*)workspace + w.region);
+    a.ws_e = (float*)((char*)workspace + w.region + align_up((size_t)U * pmax.S * (c->d + 4) * sizeof(float), 256));
+    a.B = c->B;
+    a.H = c->H;
+    a.cap = c->cap;
+    a.S = p.S;
+    a.chunk = p.chunk;
+    a.q_pos = q_pos;
+    a.noise = cfg->noise;
+    a.inv_tau = 1.0f / cfg->tau;
+    a.scale = cfg->scale;
+    const hipError_t e = kf::launch_decode(a, U, c->d, c->dtype, p.lds_bytes, (hipStream_t)stream);
+    if (e != hipSuccess) return fail(KF_EDEVICE, "decode launch: %s", hipGetErrorString(e));
+    g_err[0] = 0;
+    return KF_OK;
+}
+
+kf_status kf_select_evict(kf_cache* c, int32_t k, int32_t w, int32_t* kept_idx, void* workspace,
+                          size_t workspace_bytes, void* stream) {
+    kf_status st = check_cache(c);
+    if (st != KF_OK) return st;
+    if (k < 1 || k > c->cap) return fail(KF_EINVAL, "budget k=%d outside [1, cap=%d]", k, c->cap);
+    if (w < 0 || w > k) return fail(KF_EINVAL, "window w=%d outside [0, k=%d]", w, k);
+    const WsLayout wl = ws_layout(c, 0);
+    st = check_ws(workspace, workspace_bytes, wl.total);
+    if (st != KF_OK) return st;
+
+    const int64_t U = (int64_t)c->L * c->B * c->H;
+    kf::SelectArgs a;
+    a.K = c->K;
+    a.V = c->V;
+    a.score = c->score;
+    a.pos = c->pos;
+    a.len = c->len;
+    a.idx = kept_idx ? kept_idx : (int32_t*)((char*)workspace + wl.region);
+    a.cap = c->cap;
+    a.k = k;
+    a.w = w;
+    a.row_bytes = c->d * (c->dtype == KF_F32 ? 4 : 2);
+    const hipError_t e = kf::launch_select(a, U, (hipStream_t)stream);
+    if (e != hipSuccess) return fail(KF_EDEVICE, "select launch: %s", hipGetErrorString(e));
+    g_err[0] = 0;
+    return KF_OK;
+}
+
+}  // extern "C"

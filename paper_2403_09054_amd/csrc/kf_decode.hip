@@ -1,0 +1,316 @@
+// Fused decode step of Keyformer for gfx950: append, logits, attention and
+// score accumulation in one kernel, K and V each streamed from HBM once.
+//
+// Per unit (one layer/batch/head cache) the step is (Algorithm 1 else-branch):
+//   append the new token;  x_j = scale*<q,K_j> - slope*(q_pos - pos_j)   (Eq. 1)
+//   out = sum_j softmax(x)_j V_j                                          (attention)
+//   f_j += softmax((x + zeta)/tau)_j                                      (Eq. 4, Eq. 11, Sec. 3.3.2)
+//
+// Work decomposition: a unit's m tokens are cut into S contiguous splits, one
+// workgroup each.  A workgroup streams its K rows (16 bytes per lane, a row
+// spread over D*sizeof(T)/16 adjacent lanes so that every wave-wide load is one
+// contiguous kilobyte), keeps the logits in LDS, forms the two softmaxes'
+// local statistics, then streams its V rows.  With S == 1 it finishes the unit
+// itself.  With S > 1 it leaves a partial record (un-normalised output, local
+// max and sum of both softmaxes) and the last workgroup of the unit to arrive
+// merges the records; "last to arrive" is decided by a per-unit counter that
+// the merging workgroup resets, so no second launch and no memset is needed.
+#include "kf_device.h"
+#include "kf_internal.h"
+
+namespace kf {
+
+constexpr int kDecodeThreads = 256;
+constexpr int kDecodeMaxChunk = 4096;   // tokens per split the LDS arrays are sized for
+constexpr int kDecodeMaxSplits = 256;   // <= kDecodeThreads: one thread per split in the merge
+constexpr int kDecodeTargetBlocks = 2048;
+constexpr int kDecodeMinChunk = 128;
+
+template <typename T, int D, int NT>
+__global__ void __launch_bounds__(NT) decode_kernel(const DecodeArgs a) {
+    constexpr int EPV = ElemTraits<T>::kPerVec;  // elements per 16-byte vector
+    constexpr int LPR = D / EPV;                 // lanes that share one row
+    constexpr int RPW = kWave / LPR;             // rows per wave-wide load
+    constexpr int NW = NT / kWave;
+    constexpr int RPB = RPW * NW;                // rows per block-wide load
+    constexpr int UNR = 4;                       // independent loads in flight per lane
+    constexpr int PW = D + 4;                    // floats in a partial record
+    static_assert(LPR <= kWave && D <= NT, "row must fit a wave, output a block");
+
+    extern __shared__ float smem[];
+    float* xs = smem;                // [chunk] logits, then attention weights
+    float* ys = smem + a.chunk;      // [chunk] perturbed logits / tau, then their exponentials
+    float* red_o = ys + a.chunk;     // [NW][D] per-wave output partials
+    __shared__ float red_s[NW];
+    __shared__ float w_p[kDecodeMaxSplits], w_e[kDecodeMaxSplits];
+    __shared__ int s_last;
+
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int sub = lane / LPR, cl = lane % LPR;
+    const int S = a.S;
+    const int64_t u = blockIdx.x / S;
+    const int s = blockIdx.x % S;
+    const int h = (int)(u % a.H), b = (int)((u / a.H) % a.B), l = (int)(u / ((int64_t)a.H * a.B));
+
+    const int len0 = a.len[u];
+    const int m = len0 + 1;
+    if (len0 < 0 || len0 >= a.cap || m > S * a.chunk) {
+        // no room for the new token (or a launch shaped for fewer tokens):
+        // leave the unit alone and report it
+        if (s == 0) {
+            if (tid < D) a.out[u * D + tid] = 0.0f;
+            if (tid == 0) atomicAdd(a.ws_err, 1);
+        }
+        return;
+    }
+    const int j0 = s * a.chunk;
+    const int j1 = min(m, j0 + a.chunk);
+    const int cnt = max(j1 - j0, 0);
+
+    const T* Ku = (const T*)a.K + (size_t)u * a.cap * D;
+    const T* Vu = (const T*)a.V + (size_t)u * a.cap * D;
+    const T* qu = (const T*)a.q + (size_t)u * D;
+    const T* knew = (const T*)a.k_new + (size_t)u * D;
+    const T* vnew = (const T*)a.v_new + (size_t)u * D;
+    float* fu = a.score + (size_t)u * a.cap;
+    int32_t* pu = a.pos + (size_t)u * a.cap;
+
+    // ---- append: the split that owns slot len0 stores the new row.  The row is
+    // not read back from the cache in this launch (the streams below take it
+    // from k_new / v_new), so no ordering is needed.
+    if (len0 >= j0 && len0 < j1) {
+        if (wv == 0 && lane < LPR)
+            ((uint4*)((T*)a.K + ((size_t)u * a.cap + len0) * D))[lane] = ((const uint4*)knew)[lane];
+        if (wv == 1 && lane < LPR)
+            ((uint4*)((T*)a.V + ((size_t)u * a.cap + len0) * D))[lane] = ((const uint4*)vnew)[lane];
+        if (tid == 2 * kWave) pu[len0] = a.q_pos;
+    }
+
+    // ---- query slice of this lane
+    float qv[EPV];
+    {
+        const uint4 r = ((const uint4*)qu)[cl];
+        unpack16<T>(r, qv);
+    }
+
+    // ---- phase 1: stream K, logits into LDS
+    for (int base = j0 + wv * RPW; base < j1; base += RPB * UNR) {
+        uint4 raw[UNR];
+#pragma unroll
+        for (int i = 0; i < UNR; ++i) {
+            const int j = base + i * RPB + sub;
+            if (j < j1) {
+                const T* row = (j == len0) ? knew : Ku + (size_t)j * D;
+                raw[i] = ((const uint4*)row)[cl];
+            } else {
+                raw[i] = make_uint4(0u, 0u, 0u, 0u);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < UNR; ++i) {
+            float kvals[EPV];
+            unpack16<T>(raw[i], kvals);
+            float p = 0.0f;
+#pragma unroll
+            for (int e = 0; e < EPV; ++e) p = fmaf(kvals[e], qv[e], p);
+#pragma unroll
+            for (int o = LPR / 2; o > 0; o >>= 1) p += __shfl_xor(p, o, kWave);
+            const int j = base + i * RPB + sub;
+            if (cl == 0 && j < j1) xs[j - j0] = p * a.scale;
+        }
+    }
+    __syncthreads();
+
+    // ---- phase 1.5: position bias, logit adjustment, the two softmaxes' statistics
+    const float slope = a.slopes ? a.slopes[h] : 0.0f;
+    uint32_t rkey = 0;
+    if (a.noise == kNoiseGumbel || a.noise == kNoiseGaussian)
+        rkey = row_key(unit_key(a.seeds[b], (uint32_t)l, (uint32_t)h), (uint32_t)a.q_pos);
+    float mx = -INFINITY, my = -INFINITY;
+    for (int t = tid; t < cnt; t += NT) {
+        const int j = j0 + t;
+        const int pj = (j == len0) ? a.q_pos : pu[j];
+        const float x = xs[t] - slope * (float)(a.q_pos - pj);
+        const float y = (x + zeta_of(a.noise, rkey, (uint32_t)pj)) * a.inv_tau;
+        xs[t] = x;
+        ys[t] = y;
+        mx = fmaxf(mx, x);
+        my = fmaxf(my, y);
+    }
+    mx = block_max<NT>(mx, red_s);
+    my = block_max<NT>(my, red_s);
+    float sp = 0.0f, se = 0.0f;
+    for (int t = tid; t < cnt; t += NT) {
+        const float p = expf(xs[t] - mx);
+        const float e = expf(ys[t] - my);
+        xs[t] = p;
+        ys[t] = e;
+        sp += p;
+        se += e;
+    }
+    sp = block_sum<NT>(sp, red_s);
+    se = block_sum<NT>(se, red_s);
+    if (S == 1) {
+        // the whole unit is here: accumulate the normalised score increment
+        const float inv = 1.0f / se;
+        for (int t = tid; t < cnt; t += NT) {
+            const float prev = (t == len0) ? 0.0f : fu[t];
+            fu[t] = prev + ys[t] * inv;
+        }
+    } else {
+        float* we = a.ws_e + (size_t)u * a.cap;
+        for (int t = tid; t < cnt; t += NT) we[j0 + t] = ys[t];
+    }
+    __syncthreads();  // attention weights of all threads are in xs
+
+    // ---- phase 2: stream V, weighted sum
+    float acc[EPV];
+#pragma unroll
+    for (int e = 0; e < EPV; ++e) acc[e] = 0.0f;
+    for (int base = j0 + wv * RPW; base < j1; base += RPB * UNR) {
+        uint4 raw[UNR];
+#pragma unroll
+        for (int i = 0; i < UNR; ++i) {
+            const int j = base + i * RPB + sub;
+            if (j < j1) {
+                const T* row = (j == len0) ? vnew : Vu + (size_t)j * D;
+                raw[i] = ((const uint4*)row)[cl];
+            } else {
+                raw[i] = make_uint4(0u, 0u, 0u, 0u);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < UNR; ++i) {
+            const int j = base + i * RPB + sub;
+            const float p = (j < j1) ? xs[j - j0] : 0.0f;
+            float vvals[EPV];
+            unpack16<T>(raw[i], vvals);
+#pragma unroll
+            for (int e = 0; e < EPV; ++e) acc[e] = fmaf(p, vvals[e], acc[e]);
+        }
+    }
+    // rows of one wave-wide load live in different lane groups: fold them
+#pragma unroll
+    for (int o = LPR; o < kWave; o <<= 1) {
+#pragma unroll
+        for (int e = 0; e < EPV; ++e) acc[e] += __shfl_xor(acc[e], o, kWave);
+    }
+    if (sub == 0) {
+#pragma unroll
+        for (int e = 0; e < EPV; ++e) red_o[wv * D + cl * EPV + e] = acc[e];
+    }
+    __syncthreads();
+    float o_c = 0.0f;
+    if (tid < D) {
+#pragma unroll
+        for (int w2 = 0; w2 < NW; ++w2) o_c += red_o[w2 * D + tid];
+    }
+
+    if (S == 1) {
+        if (tid < D) a.out[u * D + tid] = o_c / sp;
+        if (tid == 0) a.len[u] = m;
+        return;
+    }
+
+    // ---- S > 1: leave a partial record, the last split to arrive merges
+    float* part = a.ws_part + ((size_t)u * S + s) * PW;
+    if (tid < D) part[tid] = o_c;
+    if (tid == 0) {
+        part[D + 0] = mx;
+        part[D + 1] = sp;
+        part[D + 2] = my;
+        part[D + 3] = se;
+    }
+    __threadfence();  // this thread's record and score increments are visible device-wide
+    __syncthreads();
+    if (tid == 0) s_last = (atomicAdd(a.ws_cnt + u, 1) == S - 1);
+    __syncthreads();
+    if (!s_last) return;
+    __threadfence();  // see the other splits' records
+
+    const float* parts = a.ws_part + (size_t)u * S * PW;
+    float pmx = -INFINITY, psp = 0.0f, pmy = -INFINITY, pse = 0.0f;
+    if (tid < S) {
+        const float* r = parts + (size_t)tid * PW + D;
+        pmx = r[0];
+        psp = r[1];
+        pmy = r[2];
+        pse = r[3];
+    }
+    const float Mx = block_max<NT>(pmx, red_s);
+    const float My = block_max<NT>(pmy, red_s);
+    const float wp = (psp > 0.0f) ? expf(pmx - Mx) : 0.0f;   // empty splits weigh nothing
+    const float we_ = (pse > 0.0f) ? expf(pmy - My) : 0.0f;
+    const float sumP = block_sum<NT>(wp * psp, red_s);
+    const float sumE = block_sum<NT>(we_ * pse, red_s);
+    if (tid < S) {
+        w_p[tid] = wp;
+        w_e[tid] = we_;
+    }
+    __syncthreads();
+    if (tid < D) {
+        float o = 0.0f;
+        for (int ss = 0; ss < S; ++ss) o = fmaf(w_p[ss], parts[(size_t)ss * PW + tid], o);
+        a.out[u * D + tid] = o / sumP;
+    }
+    {
+        const float* we = a.ws_e + (size_t)u * a.cap;
+        const float inv = 1.0f / sumE;
+        for (int j = tid; j < m; j += NT) {
+            const float prev = (j == len0) ? 0.0f : fu[j];
+            fu[j] = prev + we[j] * (w_e[j / a.chunk] * inv);
+        }
+    }
+    if (tid == 0) {
+        a.len[u] = m;
+        a.ws_cnt[u] = 0;  // ready for the next call
+    }
+}
+
+// -------------------------------------------------------------------- host
+static int rows_per_block(int32_t d, int32_t dtype) {
+    const int epv = dtype == KF_F32 ? 4 : 8;
+    const int lpr = d / epv;
+    return (kWave / lpr) * (kDecodeThreads / kWave);
+}
+
+DecodePlan plan_decode(int64_t U, int32_t m, int32_t d, int32_t dtype) {
+    DecodePlan p;
+    const int rpb = rows_per_block(d, dtype);
+    int64_t S = (kDecodeTargetBlocks + U - 1) / U;
+    const int64_t s_hi = (m + kDecodeMinChunk - 1) / kDecodeMinChunk;
+    const int64_t s_lo = (m + kDecodeMaxChunk - 1) / kDecodeMaxChunk;
+    if (S > s_hi) S = s_hi;
+    if (S < s_lo) S = s_lo;
+    if (S < 1) S = 1;
+    if (S > kDecodeMaxSplits) S = kDecodeMaxSplits;
+    int64_t chunk = (m + S - 1) / S;
+    chunk = (chunk + rpb - 1) / rpb * rpb;
+    p.S = (int32_t)S;
+    p.chunk = (int32_t)chunk;
+    p.lds_bytes = (size_t)(2 * chunk + (kDecodeThreads / kWave) * d) * sizeof(float);
+    return p;
+}
+
+template <typename T, int D>
+static hipError_t launch_decode_t(const DecodeArgs& a, int64_t U, size_t lds, hipStream_t st) {
+    const dim3 grid((unsigned)(U * a.S)), block(kDecodeThreads);
+    hipLaunchKernelGGL((decode_kernel<T, D, kDecodeThreads>), grid, block, lds, st, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_decode(const DecodeArgs& a, int64_t U, int32_t d, int32_t dtype, size_t lds_bytes,
+                         hipStream_t stream) {
+    if (a.chunk > kDecodeMaxChunk) return hipErrorInvalidValue;
+    if (dtype == KF_BF16) {
+        if (d == 64) return launch_decode_t<bf16_t, 64>(a, U, lds_bytes, stream);
+        if (d == 128) return launch_decode_t<bf16_t, 128>(a, U, lds_bytes, stream);
+        if (d == 256) return launch_decode_t<bf16_t, 256>(a, U, lds_bytes, stream);
+    } else {
+        if (d == 64) return launch_decode_t<float, 64>(a, U, lds_bytes, stream);
+        if (d == 128) return launch_decode_t<float, 128>(a, U, lds_bytes, stream);
+    }
+    return hipErrorInvalidValue;
+}
+
+}  // namespace kf

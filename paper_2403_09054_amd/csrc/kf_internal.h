@@ -1,0 +1,79 @@
+// Host-side declarations shared by the API layer and the kernel files.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/keyformer.h"
+
+namespace kf {
+
+// ------------------------------------------------------------------ decode
+struct DecodeArgs {
+    void* K;
+    void* V;
+    float* score;
+    int32_t* pos;
+    int32_t* len;
+    const void* q;
+    const void* k_new;
+    const void* v_new;
+    float* out;
+    const uint64_t* seeds;
+    const float* slopes;
+    float* ws_part;    // [U][S][D+4] partial outputs and softmax statistics of each split
+    float* ws_e;       // [U][cap]    un-normalised score increments of each token
+    int32_t* ws_cnt;   // [U]         arrival counters, zero between calls
+    int32_t* ws_err;   // [1]         skipped-unit counter
+    int32_t B, H, cap;
+    int32_t S;         // splits of a unit's token range
+    int32_t chunk;     // tokens per split
+    int32_t q_pos;
+    int32_t noise;
+    float inv_tau;
+    float scale;
+};
+
+// Launch shape of the decode kernel for U units of up to m tokens.
+struct DecodePlan {
+    int32_t S, chunk;
+    size_t lds_bytes;
+};
+DecodePlan plan_decode(int64_t U, int32_t m, int32_t d, int32_t dtype);
+hipError_t launch_decode(const DecodeArgs& a, int64_t U, int32_t d, int32_t dtype, size_t lds_bytes,
+                         hipStream_t stream);
+
+// ------------------------------------------------------------------ select
+struct SelectArgs {
+    void* K;
+    void* V;
+    float* score;
+    int32_t* pos;
+    int32_t* len;
+    int32_t* idx;       // [U][k] source slot of every survivor (caller's kept_idx or workspace)
+    int32_t cap, k, w;
+    int32_t row_bytes;  // d * sizeof(element)
+};
+hipError_t launch_select(const SelectArgs& a, int64_t U, hipStream_t stream);
+
+// ------------------------------------------------------------------ prefill
+struct PrefillArgs {
+    const void* Q;
+    const void* K;
+    float* score;
+    int32_t* pos;
+    int32_t* len;
+    const uint64_t* seeds;
+    const float* slopes;
+    float* ws_c;        // [U][n_pad] per-row log2 normaliser
+    uint32_t* ws_r;     // [U][n_pad] per-row noise key
+    int32_t B, H, cap, n, n_pad;
+    int32_t noise;
+    float inv_tau;
+    float scale;
+};
+hipError_t launch_prefill(const PrefillArgs& a, int64_t U, int32_t d, int32_t dtype, hipStream_t stream);
+
+constexpr int32_t kPrefillRowPad = 128;  // n is padded to this for the row-statistics arrays
+
+}  // namespace kf

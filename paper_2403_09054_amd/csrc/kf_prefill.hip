@@ -1,0 +1,244 @@
+// Prompt-phase scoring of Keyformer for gfx950 (Sec. 3.4, Algorithm 1 prompt
+// branch): for every unit
+//     x_ij = scale*<Q_i,K_j> - slope*(i-j),  j <= i
+//     z_i  = softmax_j((x_ij + zeta_ij)/tau)                 (Eq. 4, Eq. 11)
+//     f[j] = sum_{i>=j} z_ij
+// The logits are a dense n x n contraction: they are produced 32x32 tiles at a
+// time on the matrix cores (MFMA).  The normaliser of row i must be known before
+// any z_ij can be summed down a column, so two passes are made, each
+// re-computing the logits instead of storing n^2 values:
+//   pass 1  (row statistics)  computes the transposed tile K_tile * Q_tile^T so
+//           that a lane owns ONE query and sees 16 of the tile's 32 keys: the
+//           running max / sum of the row stay in the lane's registers.  Result:
+//           c_i = log2(sum_j 2^(y2_ij)), y2 = log2(e)*(x+zeta)/tau, and the
+//           row's noise key.
+//   pass 2  (column sums)     computes Q_tile * K_tile^T so that a lane owns ONE
+//           key and sees 16 of the tile's 32 queries: z_ij = 2^(y2_ij - c_i) is
+//           added into the lane's column sum.
+// Per logit the work is one 32-bit hash, two logarithms and one exponential;
+// that, not the MFMA rate, bounds the kernel.
+#include "kf_device.h"
+#include "kf_internal.h"
+
+namespace kf {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kPrefillThreads = 256;  // 4 waves, 32 queries (pass 1) or keys (pass 2) each
+constexpr int kTile = 32;
+constexpr float kLog2e = 1.44269504088896340736f;
+
+// One "group" = the 16 bytes a lane loads from a row: it feeds one bf16 MFMA
+// (K = 16: 8 elements from each half of the wave) or four fp32 MFMAs (K = 2).
+// Both operands use the same assignment of k indices to (wave half, element),
+// so the contraction runs over every k exactly once.
+template <typename T>
+struct Mma;
+template <>
+struct Mma<bf16_t> {
+    static __device__ __forceinline__ f32x16 group(const uint4& a, const uint4& b, f32x16 c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
+                                                       __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    }
+};
+template <>
+struct Mma<float> {
+    static __device__ __forceinline__ f32x16 group(const uint4& a, const uint4& b, f32x16 c) {
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b.x), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b.y), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.z), __uint_as_float(b.z), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), c, 0, 0, 0);
+        return c;
+    }
+};
+
+// Row of the 32x32 accumulator tile that register r of this lane holds
+// (the column is lane % 32).
+__device__ __forceinline__ int acc_row(int r, int half) { return (r >> 2) * 8 + half * 4 + (r & 3); }
+
+// y2 = log2(e) * (x + zeta)/tau for one logit.
+__device__ __forceinline__ float tempered_logit2(int noise, float x, uint32_t rkey, uint32_t k_pos,
+                                                 float c1, float inv_tau) {
+    if (noise == kNoiseGumbel) {
+        // zeta = -ln(L), L = -ln(u):  log2(e)*zeta/tau = -log2(L)/tau
+        const float L = neg_log_uniform(logit_bits(rkey, k_pos));
+        return fmaf(x, c1, -inv_tau * log2f(L));
+    }
+    return (x + zeta_of(noise, rkey, k_pos)) * c1;
+}
+
+// ------------------------------------------------------------------ pass 1
+template <typename T, int D>
+__global__ void __launch_bounds__(kPrefillThreads) prefill_rowstats_kernel(const PrefillArgs a, int nblk) {
+    constexpr int EPV = ElemTraits<T>::kPerVec;
+    constexpr int NG = D / (2 * EPV);
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int n0 = lane & 31, half = lane >> 5;
+    const int64_t u = blockIdx.x / nblk;
+    const int rb = nblk - 1 - (int)(blockIdx.x % nblk);  // longest rows first
+    const int n = a.n;
+    const int i0 = rb * (4 * kTile) + wv * kTile;
+    if (i0 >= n) return;  // wave-uniform; this kernel has no workgroup barrier
+    const int h = (int)(u % a.H), b = (int)((u / a.H) % a.B), l = (int)(u / ((int64_t)a.H * a.B));
+    const int i = i0 + n0;
+    const T* Qu = (const T*)a.Q + (size_t)u * n * D;
+    const T* Ku = (const T*)a.K + (size_t)u * a.cap * D;
+
+    uint4 bq[NG];
+    {
+        const T* row = Qu + (size_t)min(i, n - 1) * D + half * EPV;
+#pragma unroll
+        for (int g = 0; g < NG; ++g) bq[g] = *(const uint4*)(row + g * 2 * EPV);
+    }
+    const float slope = a.slopes ? a.slopes[h] : 0.0f;
+    const bool rnd = (a.noise == kNoiseGumbel || a.noise == kNoiseGaussian);
+    const uint32_t rkey = rnd ? row_key(unit_key(a.seeds[b], (uint32_t)l, (uint32_t)h), (uint32_t)i) : 0u;
+    const float c1 = a.inv_tau * kLog2e;
+
+    float M = -INFINITY, Ssum = 0.0f;
+    const int jt_end = min(i0 + kTile - 1, n - 1) / kTile;
+    uint4 ak[NG];
+    {
+        const T* row = Ku + (size_t)min(n0, n - 1) * D + half * EPV;
+#pragma unroll
+        for (int g = 0; g < NG; ++g) ak[g] = *(const uint4*)(row + g * 2 * EPV);
+    }
+    for (int jt = 0; jt <= jt_end; ++jt) {
+        f32x16 acc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+#pragma unroll
+        for (int g = 0; g < NG; ++g) acc = Mma<T>::group(ak[g], bq[g], acc);
+        if (jt < jt_end) {  // next key tile's rows, in flight during the epilogue
+            const T* row = Ku + (size_t)min((jt + 1) * kTile + n0, n - 1) * D + half * EPV;
+#pragma unroll
+            for (int g = 0; g < NG; ++g) ak[g] = *(const uint4*)(row + g * 2 * EPV);
+        }
+        const int jb = jt * kTile;
+        float y2[16];
+        float tmax = -INFINITY;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int j = jb + acc_row(r, half);
+            const float x = acc[r] * a.scale - slope * (float)(i - j);
+            const float y = tempered_logit2(a.noise, x, rkey, (uint32_t)j, c1, a.inv_tau);
+            y2[r] = (j <= i) ? y : -INFINITY;  // causal
+            tmax = fmaxf(tmax, y2[r]);
+        }
+        const float Mn = fmaxf(M, tmax);
+        if (Mn > -INFINITY) {
+            float ssum = 0.0f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) ssum += exp2f(y2[r] - Mn);
+            Ssum = Ssum * exp2f(M - Mn) + ssum;
+            M = Mn;
+        }
+    }
+    // the two halves of the wave hold disjoint key subsets of the same query
+    const float M2 = __shfl_xor(M, 32, kWave), S2 = __shfl_xor(Ssum, 32, kWave);
+    const float Mt = fmaxf(M, M2);
+    const float St = (M > -INFINITY ? Ssum * exp2f(M - Mt) : 0.0f) + (M2 > -INFINITY ? S2 * exp2f(M2 - Mt) : 0.0f);
+    if (half == 0 && i < n) {
+        a.ws_c[(size_t)u * a.n_pad + i] = Mt + log2f(St);
+        a.ws_r[(size_t)u * a.n_pad + i] = rkey;
+    }
+}
+
+// ------------------------------------------------------------------ pass 2
+template <typename T, int D>
+__global__ void __launch_bounds__(kPrefillThreads) prefill_colsum_kernel(const PrefillArgs a, int nblk) {
+    constexpr int EPV = ElemTraits<T>::kPerVec;
+    constexpr int NG = D / (2 * EPV);
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int n0 = lane & 31, half = lane >> 5;
+    const int64_t u = blockIdx.x / nblk;
+    const int cb = (int)(blockIdx.x % nblk);  // longest columns (lowest keys) first
+    const int n = a.n;
+    const int j0 = cb * (4 * kTile) + wv * kTile;
+    if (cb == 0 && threadIdx.x == 0) a.len[u] = n;
+    if (j0 >= n) return;  // wave-uniform; no workgroup barrier in this kernel
+    const int h = (int)(u % a.H);
+    const int j = j0 + n0;
+    const T* Qu = (const T*)a.Q + (size_t)u * n * D;
+    const T* Ku = (const T*)a.K + (size_t)u * a.cap * D;
+
+    uint4 bk[NG];
+    {
+        const T* row = Ku + (size_t)min(j, n - 1) * D + half * EPV;
+#pragma unroll
+        for (int g = 0; g < NG; ++g) bk[g] = *(const uint4*)(row + g * 2 * EPV);
+    }
+    const float slope = a.slopes ? a.slopes[h] : 0.0f;
+    const float c1 = a.inv_tau * kLog2e;
+    const float* wc = a.ws_c + (size_t)u * a.n_pad;
+    const uint32_t* wr = a.ws_r + (size_t)u * a.n_pad;
+
+    float colsum = 0.0f;
+    const int it_begin = j0 / kTile, it_end = (n - 1) / kTile;
+    uint4 aq[NG];
+    {
+        const T* row = Qu + (size_t)min(it_begin * kTile + n0, n - 1) * D + half * EPV;
+#pragma unroll
+        for (int g = 0; g < NG; ++g) aq[g] = *(const uint4*)(row + g * 2 * EPV);
+    }
+    for (int it = it_begin; it <= it_end; ++it) {
+        f32x16 acc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+#pragma unroll
+        for (int g = 0; g < NG; ++g) acc = Mma<T>::group(aq[g], bk[g], acc);
+        if (it < it_end) {
+            const T* row = Qu + (size_t)min((it + 1) * kTile + n0, n - 1) * D + half * EPV;
+#pragma unroll
+            for (int g = 0; g < NG; ++g) aq[g] = *(const uint4*)(row + g * 2 * EPV);
+        }
+        const int ib = it * kTile;
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+            const int ir = ib + q4 * 8 + half * 4;  // 4 consecutive query rows, 16-byte aligned stats
+            const float4 c4 = *(const float4*)(wc + ir);
+            const uint4 r4 = *(const uint4*)(wr + ir);
+            const float cs[4] = {c4.x, c4.y, c4.z, c4.w};
+            const uint32_t rs[4] = {r4.x, r4.y, r4.z, r4.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int i = ir + e;
+                const float x = acc[q4 * 4 + e] * a.scale - slope * (float)(i - j);
+                const float y = tempered_logit2(a.noise, x, rs[e], (uint32_t)j, c1, a.inv_tau);
+                const float z = exp2f(y - cs[e]);
+                colsum += (i >= j && i < n) ? z : 0.0f;
+            }
+        }
+    }
+    colsum += __shfl_xor(colsum, 32, kWave);
+    if (half == 0 && j < n) {
+        a.score[(size_t)u * a.cap + j] = colsum;
+        a.pos[(size_t)u * a.cap + j] = j;
+    }
+}
+
+template <typename T, int D>
+static hipError_t launch_prefill_t(const PrefillArgs& a, int64_t U, hipStream_t st) {
+    const int nblk = (a.n + 4 * kTile - 1) / (4 * kTile);
+    const dim3 grid((unsigned)(U * nblk)), block(kPrefillThreads);
+    hipLaunchKernelGGL((prefill_rowstats_kernel<T, D>), grid, block, 0, st, a, nblk);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((prefill_colsum_kernel<T, D>), grid, block, 0, st, a, nblk);
+    return hipGetLastError();
+}
+
+hipError_t launch_prefill(const PrefillArgs& a, int64_t U, int32_t d, int32_t dtype, hipStream_t stream) {
+    if (dtype == KF_BF16) {
+        if (d == 64) return launch_prefill_t<bf16_t, 64>(a, U, stream);
+        if (d == 128) return launch_prefill_t<bf16_t, 128>(a, U, stream);
+        if (d == 256) return launch_prefill_t<bf16_t, 256>(a, U, stream);
+    } else {
+        if (d == 64) return launch_prefill_t<float, 64>(a, U, stream);
+        if (d == 128) return launch_prefill_t<float, 128>(a, U, stream);
+    }
+    return hipErrorInvalidValue;
+}
+
+}  // namespace kf

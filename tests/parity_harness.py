@@ -1,0 +1,204 @@
+"""Shared helpers of the GPU parity tests: move state between the oracle's numpy
+caches and the library's torch caches, compare with the tolerances the build
+target states, and run the lock-step protocol.
+
+Tolerances (from the build target): attention outputs and accumulated scores
+within 2e-3 relative (fp32 accumulation over bf16 K/V); retained index sets
+bit-exact except at tokens whose oracle score lies within 1e-5 relative of the
+(k-w)-th largest candidate score.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import kf_workloads as kw
+import paper_2403_09054_amd as kf
+from oracle import kf_oracle as ko
+
+RTOL = 2e-3
+TIE_BAND = 1e-5
+
+
+def dev(a):
+    """numpy (oracle format) -> cuda tensor in the library's format."""
+    if a is None:
+        return None
+    if a.dtype == np.uint64:
+        return torch.from_numpy(a.view(np.int64).copy()).cuda()
+    return kw.from_oracle(a).cuda()
+
+
+def upload(oc: ko.OracleCache) -> kf.Cache:
+    return kf.Cache(K=dev(oc.K), V=dev(oc.V), score=dev(oc.score), pos=dev(oc.pos), len=dev(oc.len),
+                    L=oc.L, B=oc.B, H=oc.H, d=oc.d, cap=oc.cap, dtype=oc.dtype)
+
+
+def upload_into(gc: kf.Cache, oc: ko.OracleCache, kv=True):
+    if kv:
+        gc.K.copy_(dev(oc.K))
+        gc.V.copy_(dev(oc.V))
+    gc.score.copy_(dev(oc.score))
+    gc.pos.copy_(dev(oc.pos))
+    gc.len.copy_(dev(oc.len))
+
+
+def host(t):
+    return kw.to_oracle(t)
+
+
+def assert_close_out(got, ref, what="out"):
+    """|got-ref| <= 2e-3*|ref| + 1e-5*max|ref| per unit (last axis = head dim)."""
+    got = got.astype(np.float64)
+    ref = ref.astype(np.float64)
+    atol = 1e-5 * np.abs(ref).max(axis=-1, keepdims=True) + 1e-30
+    bad = np.abs(got - ref) > RTOL * np.abs(ref) + atol
+    assert not bad.any(), "%s: %d elements off, worst abs err %g" % (
+        what, bad.sum(), np.abs(got - ref).max())
+    return float((np.abs(got - ref) / (np.abs(ref) + atol)).max())
+
+
+def assert_close_score(got, ref, lens, what="score"):
+    """Accumulated scores of the live slots, relative 2e-3 element by element."""
+    worst = 0.0
+    L, B, H = lens.shape
+    for l in range(L):
+        for b in range(B):
+            for h in range(H):
+                m = int(lens[l, b, h])
+                g = got[l, b, h, :m].astype(np.float64)
+                r = ref[l, b, h, :m].astype(np.float64)
+                err = np.abs(g - r) / (np.abs(r) + 1e-30)
+                assert (err <= RTOL).all(), "%s unit (%d,%d,%d): worst rel err %g at slot %d" % (
+                    what, l, b, h, err.max(), int(err.argmax()))
+                worst = max(worst, float(err.max()) if m else 0.0)
+    return worst
+
+
+def compare_kept(kept_gpu, kept_ref, score_before, len_before, k, w):
+    """Exact match of the survivor lists, or a difference confined to the tie band.
+    Returns the number of units that needed the tie-band rule."""
+    events = 0
+    L, B, H = len_before.shape
+    for l in range(L):
+        for b in range(B):
+            for h in range(H):
+                g, r = kept_gpu[l, b, h], kept_ref[l, b, h]
+                if (g == r).all():
+                    continue
+                n = int(len_before[l, b, h])
+                assert n > k, "untouched unit must report identity"
+                f = score_before[l, b, h, : n - w].astype(np.float64)
+                thr = np.sort(f)[::-1][k - w - 1]
+                gs, rs = set(g.tolist()), set(r.tolist())
+                assert len(gs) == k and (np.diff(g) > 0).all(), "GPU survivors not a sorted k-set"
+                assert set(range(n - w, n)) <= gs, "recent window not retained"
+                for slot in gs ^ rs:
+                    assert slot < n - w
+                    assert abs(f[slot] - thr) <= TIE_BAND * abs(thr), (
+                        "unit (%d,%d,%d) slot %d score %r differs outside the tie band of threshold %r"
+                        % (l, b, h, slot, f[slot], thr))
+                events += 1
+    return events
+
+
+def assert_state_equal(gc: kf.Cache, oc: ko.OracleCache, kv=True, score_exact=True):
+    """Bit-exact comparison of the live part of both caches."""
+    lens = host(gc.len)
+    np.testing.assert_array_equal(lens, oc.len)
+    pos, score = host(gc.pos), host(gc.score)
+    K = host(gc.K) if kv else None
+    V = host(gc.V) if kv else None
+    for l in range(oc.L):
+        for b in range(oc.B):
+            for h in range(oc.H):
+                m = int(lens[l, b, h])
+                np.testing.assert_array_equal(pos[l, b, h, :m], oc.pos[l, b, h, :m])
+                if score_exact:
+                    np.testing.assert_array_equal(score[l, b, h, :m], oc.score[l, b, h, :m])
+                if kv:
+                    np.testing.assert_array_equal(K[l, b, h, :m], oc.K[l, b, h, :m])
+                    np.testing.assert_array_equal(V[l, b, h, :m], oc.V[l, b, h, :m])
+
+
+def error_word(ws) -> int:
+    return int(ws[:4].view(torch.int32)[0].item())
+
+
+class LockStep:
+    """Oracle and GPU advance together over a workload; before every call both
+    hold the same state (scores are re-uploaded from the oracle after each
+    decode step, everything after a tie-band event)."""
+
+    def __init__(self, wl: kw.Workload, noise=ko.NOISE_GUMBEL, layers=None, cap=None):
+        self.wl, self.noise = wl, noise
+        self.cap = cap or wl.n
+        dt = ko.F32 if wl.dtype == "f32" else ko.BF16
+        self.oc = ko.OracleCache(wl.L, wl.B, wl.H, wl.d, self.cap, dt)
+        self.Q = np.zeros((wl.L, wl.B, wl.H, wl.n, wl.d), self.oc.K.dtype)
+        for l in range(wl.L):
+            Q, K, V = kw.prompt_layer(wl, l)
+            self.Q[l] = kw.to_oracle(Q)
+            self.oc.K[l, :, :, : wl.n] = kw.to_oracle(K)
+            self.oc.V[l, :, :, : wl.n] = kw.to_oracle(V)
+        self.seeds = kw.noise_seeds(wl)
+        self.slopes = kw.alibi_slopes(wl)
+        self.gc = upload(self.oc)
+        self.ws = kf.new_workspace(self.gc, wl.n)
+        self.d_seeds, self.d_slopes = dev(self.seeds), dev(self.slopes)
+        self.out = torch.zeros((wl.L, wl.B, wl.H, wl.d), dtype=torch.float32, device="cuda")
+        self.kept = torch.zeros((wl.L, wl.B, wl.H, wl.k), dtype=torch.int32, device="cuda")
+        self.stats = dict(out_err=0.0, score_err=0.0, tie_events=0, steps=0)
+
+    def prefill(self):
+        wl = self.wl
+        tau_o, tau_g = ko.tau(0, wl.T, wl.tau_init, wl.tau_end), kf.kf_tau(0, wl.T, wl.tau_init, wl.tau_end)
+        assert tau_o == tau_g
+        self.oc.prefill_score(self.Q, wl.n, tau_o, wl.scale, self.noise, self.seeds, self.slopes)
+        kf.kf_prefill_score(self.gc, dev(self.Q), wl.n, tau_g, wl.scale, self.noise, self.d_seeds,
+                            self.d_slopes, self.ws)
+        torch.cuda.synchronize()
+        lens = host(self.gc.len)
+        np.testing.assert_array_equal(lens, self.oc.len)
+        np.testing.assert_array_equal(host(self.gc.pos)[..., : wl.n], self.oc.pos[..., : wl.n])
+        e = assert_close_score(host(self.gc.score), self.oc.score, lens, "prefill score")
+        self.stats["prefill_err"] = e
+        self.gc.score.copy_(dev(self.oc.score))
+        self.select()
+
+    def select(self):
+        wl = self.wl
+        before_score, before_len = self.oc.score.copy(), self.oc.len.copy()
+        kept_ref = self.oc.select_evict(wl.k, wl.w)
+        kf.kf_select_evict(self.gc, wl.k, wl.w, self.kept, self.ws)
+        torch.cuda.synchronize()
+        ev = compare_kept(host(self.kept), kept_ref, before_score, before_len, wl.k, wl.w)
+        self.stats["tie_events"] += ev
+        if ev:
+            upload_into(self.gc, self.oc)       # adopt the oracle's choice and go on
+        return ev
+
+    def step(self, t, check_kv=False):
+        wl = self.wl
+        q, kn, vn = kw.decode_inputs(wl, t)
+        q_pos = wl.n + t - 1
+        tau_o, tau_g = ko.tau(t, wl.T, wl.tau_init, wl.tau_end), kf.kf_tau(t, wl.T, wl.tau_init, wl.tau_end)
+        assert tau_o == tau_g
+        out_ref = self.oc.decode_step(kw.to_oracle(q), kw.to_oracle(kn), kw.to_oracle(vn), q_pos, tau_o,
+                                      wl.scale, self.noise, self.seeds, self.slopes)
+        kf.kf_decode_step(self.gc, q.cuda(), kn.cuda(), vn.cuda(), q_pos, min(wl.k + 1, self.cap), tau_g,
+                          wl.scale, self.noise, self.d_seeds, self.d_slopes, self.out, self.ws)
+        torch.cuda.synchronize()
+        assert error_word(self.ws) == 0
+        lens = host(self.gc.len)
+        np.testing.assert_array_equal(lens, self.oc.len)
+        self.stats["out_err"] = max(self.stats["out_err"], assert_close_out(host(self.out), out_ref))
+        self.stats["score_err"] = max(self.stats["score_err"],
+                                      assert_close_score(host(self.gc.score), self.oc.score, lens))
+        self.gc.score.copy_(dev(self.oc.score))     # lock-step: same scores before selection
+        self.select()
+        if check_kv:
+            assert_state_equal(self.gc, self.oc)
+        else:
+            assert_state_equal(self.gc, self.oc, kv=False)
+        self.stats["steps"] += 1

@@ -1,0 +1,264 @@
+"""GPU-vs-oracle parity of the three hot calls, element by element, through the
+C ABI (python binding -> libkeyformer.so).  Needs a real MI355X: -m gpu."""
+import itertools
+
+import numpy as np
+import pytest
+import torch
+
+import kf_workloads as kw
+import paper_2403_09054_amd as kf
+from oracle import kf_oracle as ko
+from parity_harness import (LockStep, assert_close_out, assert_close_score, assert_state_equal,
+                            compare_kept, dev, error_word, host, upload)
+
+pytestmark = pytest.mark.gpu
+
+DTYPES = [(ko.BF16, 64), (ko.BF16, 128), (ko.BF16, 256), (ko.F32, 64), (ko.F32, 128)]
+
+
+def bf16_round(a):
+    b = a.astype(np.float32).view(np.uint32).astype(np.uint64)
+    return ((b + 0x7FFF + ((b >> 16) & 1)) >> 16).astype(np.uint16)
+
+
+def rnd(rng, shape, dtype):
+    a = rng.standard_normal(shape).astype(np.float32)
+    return bf16_round(a) if dtype == ko.BF16 else a
+
+
+def random_cache(rng, L, B, H, d, cap, dtype, lens):
+    oc = ko.OracleCache(L, B, H, d, cap, dtype)
+    oc.K[...] = rnd(rng, oc.K.shape, dtype)
+    oc.V[...] = rnd(rng, oc.V.shape, dtype)
+    oc.score[...] = (rng.random(oc.score.shape) * 3).astype(np.float32)
+    # strictly ascending original positions with gaps
+    oc.pos[...] = np.cumsum(rng.integers(1, 4, oc.pos.shape), axis=-1).astype(np.int32)
+    oc.len[...] = lens
+    return oc
+
+
+# ------------------------------------------------------------------ decode
+@pytest.mark.parametrize("dtype,d", DTYPES)
+@pytest.mark.parametrize("noise", [ko.NOISE_GUMBEL, ko.NOISE_NONE, ko.NOISE_GAUSSIAN, ko.NOISE_CONSTANT])
+@pytest.mark.parametrize("cap", [97, 700, 2100])   # one split; several splits; ragged last split
+def test_decode_step_matches_oracle(dtype, d, noise, cap):
+    rng = np.random.default_rng(1000 + d + cap + noise)
+    L, B, H = 2, 2, 3
+    lens = rng.integers(0, cap, (L, B, H)).astype(np.int32)
+    lens[0, 0, 0] = 0            # empty cache: the new token attends to itself only
+    lens[0, 0, 1] = cap - 1      # fills the cache exactly
+    lens[1, 1, 2] = cap          # no room: unit must be skipped and reported
+    oc = random_cache(rng, L, B, H, d, cap, dtype, lens)
+    gc = upload(oc)
+    ws = kf.new_workspace(gc)
+    q, kn, vn = (rnd(rng, (L, B, H, d), dtype) for _ in range(3))
+    seeds = np.array([20240309, 2 ** 64 - 3], np.uint64)
+    slopes = np.array([0.25, 0.0, 0.0039], np.float32)
+    q_pos = int(oc.pos.max()) + 5
+    tau, scale = 1.4375, float(1.0 / np.sqrt(np.float32(d)))
+    out = torch.full((L, B, H, d), 7.0, dtype=torch.float32, device="cuda")
+    kf.kf_decode_step(gc, dev(q), dev(kn), dev(vn), q_pos, 0, tau, scale, noise, dev(seeds), dev(slopes),
+                      out, ws)
+    torch.cuda.synchronize()
+    assert error_word(ws) == 1
+    # the oracle refuses a full unit; run it with that unit emptied, then compare the rest
+    full = oc.copy()
+    oc.len[1, 1, 2] = 0
+    out_ref = oc.decode_step(q, kn, vn, q_pos, tau, scale, noise, seeds, slopes)
+    got_out, got_len = host(out), host(gc.len)
+    assert (got_out[1, 1, 2] == 0).all() and got_len[1, 1, 2] == cap
+    ok = np.ones((L, B, H), bool)
+    ok[1, 1, 2] = False
+    assert (got_len[ok] == oc.len[ok]).all()
+    assert_close_out(got_out[ok], out_ref[ok])
+    lens_cmp = np.where(ok, oc.len, 0)
+    assert_close_score(host(gc.score), oc.score, lens_cmp)
+    # K, V, pos: the appended row landed, nothing else moved (bit-exact)
+    gK, gV, gpos = host(gc.K), host(gc.V), host(gc.pos)
+    for l, b, h in itertools.product(range(L), range(B), range(H)):
+        ref = oc if ok[l, b, h] else full
+        m = int(ref.len[l, b, h])
+        np.testing.assert_array_equal(gK[l, b, h, :m], ref.K[l, b, h, :m])
+        np.testing.assert_array_equal(gV[l, b, h, :m], ref.V[l, b, h, :m])
+        np.testing.assert_array_equal(gpos[l, b, h, :m], ref.pos[l, b, h, :m])
+    # the workspace is reusable: a second step on the same workspace still matches
+    q2 = rnd(rng, (L, B, H, d), dtype)
+    oc.len[1, 1, 2] = cap
+    full_units = oc.len >= cap
+    gc2 = upload(oc)
+    oc.len[full_units] = 0
+    out_ref2 = oc.decode_step(q2, kn, vn, q_pos + 1, tau, scale, noise, seeds, slopes)
+    kf.kf_decode_step(gc2, dev(q2), dev(kn), dev(vn), q_pos + 1, 0, tau, scale, noise, dev(seeds),
+                      dev(slopes), out, ws)
+    torch.cuda.synchronize()
+    assert_close_out(host(out)[~full_units], out_ref2[~full_units])
+
+
+def test_decode_m_hint_shapes_the_launch_only():
+    rng = np.random.default_rng(5)
+    L, B, H, d, cap = 1, 2, 2, 128, 1500
+    oc = random_cache(rng, L, B, H, d, cap, ko.BF16, 400)
+    q, kn, vn = (rnd(rng, (L, B, H, d), ko.BF16) for _ in range(3))
+    seeds = np.array([1, 2], np.uint64)
+    outs = []
+    for hint in (0, 401, 900):
+        gc = upload(oc)
+        ws = kf.new_workspace(gc)
+        out = torch.zeros((L, B, H, d), dtype=torch.float32, device="cuda")
+        kf.kf_decode_step(gc, dev(q), dev(kn), dev(vn), 5000, hint, 1.5, 0.09, ko.NOISE_GUMBEL, dev(seeds),
+                          None, out, ws)
+        torch.cuda.synchronize()
+        assert error_word(ws) == 0
+        outs.append((host(out), host(gc.score)))
+    ref = oc.copy()
+    out_ref = ref.decode_step(q, kn, vn, 5000, 1.5, 0.09, ko.NOISE_GUMBEL, seeds)
+    for o, s in outs:
+        assert_close_out(o, out_ref)
+        assert_close_score(s, ref.score, ref.len)
+    # a hint below the true length is reported, not silently truncated
+    gc = upload(oc)
+    ws = kf.new_workspace(gc)
+    out = torch.zeros((L, B, H, d), dtype=torch.float32, device="cuda")
+    kf.kf_decode_step(gc, dev(q), dev(kn), dev(vn), 5000, 200, 1.5, 0.09, ko.NOISE_GUMBEL, dev(seeds), None,
+                      out, ws)
+    torch.cuda.synchronize()
+    assert error_word(ws) == L * B * H
+    assert (host(gc.len) == 400).all()
+
+
+# ------------------------------------------------------------------ select + compact
+@pytest.mark.parametrize("dtype,d", DTYPES)
+@pytest.mark.parametrize("n,k,w", [(65, 64, 16), (1025, 1024, 205), (128, 64, 16), (2048, 1024, 205),
+                                   (300, 120, 0), (300, 120, 120), (3000, 1200, 240), (50, 1, 0), (50, 1, 1)])
+def test_select_evict_matches_oracle(dtype, d, n, k, w):
+    rng = np.random.default_rng(n * 7 + k + w + d)
+    L, B, H = 2, 1, 3
+    lens = np.full((L, B, H), n, np.int32)
+    lens[0, 0, 1] = max(1, k - 3)     # under budget: untouched
+    lens[1, 0, 0] = k                 # exactly at budget: untouched
+    lens[1, 0, 2] = min(n, k + 1)     # one over
+    oc = random_cache(rng, L, B, H, d, n, dtype, lens)
+    # exact ties: few distinct score values in one unit, a tie block around the threshold in another
+    oc.score[0, 0, 0] = rng.integers(0, 5, n).astype(np.float32) * 0.5
+    oc.score[0, 0, 2, n // 4: n // 2] = 1.5
+    oc.score[1, 0, 1, :] = 2.0        # everything equal: lowest slots win
+    before = oc.copy()
+    gc = upload(oc)
+    ws = kf.new_workspace(gc)
+    kept = torch.full((L, B, H, k), -5, dtype=torch.int32, device="cuda")
+    kept_ref = oc.select_evict(k, w)
+    kf.kf_select_evict(gc, k, w, kept, ws)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(host(kept), kept_ref)       # ties included: bit-exact
+    assert_state_equal(gc, oc)
+    # without kept_idx the result is the same
+    gc2 = upload(before)
+    kf.kf_select_evict(gc2, k, w, None, ws)
+    torch.cuda.synchronize()
+    assert_state_equal(gc2, oc)
+
+
+def test_select_adversarial_eviction_slots():
+    # decode shape, evicted slot at the very front, at the last candidate, and mid-way
+    rng = np.random.default_rng(3)
+    k, w, d = 256, 51, 128
+    n = k + 1
+    oc = random_cache(rng, 1, 1, 4, d, n, ko.BF16, n)
+    oc.score[...] += 1.0
+    oc.score[0, 0, 0, 0] = 0.0
+    oc.score[0, 0, 1, n - w - 1] = 0.0
+    oc.score[0, 0, 2, 100] = 0.0
+    oc.score[0, 0, 3, [7, 90, 150]] = 0.5      # equal minima: the highest slot leaves
+    gc = upload(oc)
+    ws = kf.new_workspace(gc)
+    kept = torch.zeros((1, 1, 4, k), dtype=torch.int32, device="cuda")
+    kept_ref = oc.select_evict(k, w)
+    kf.kf_select_evict(gc, k, w, kept, ws)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(host(kept), kept_ref)
+    assert_state_equal(gc, oc)
+    assert [sorted(set(range(n)) - set(kept_ref[0, 0, h].tolist()))[0] for h in range(4)] == [0, n - w - 1, 100, 150]
+
+
+# ------------------------------------------------------------------ prefill
+@pytest.mark.parametrize("dtype,d", DTYPES)
+@pytest.mark.parametrize("n", [1, 31, 33, 128, 129, 300])
+def test_prefill_score_matches_oracle(dtype, d, n):
+    rng = np.random.default_rng(n + d)
+    L, B, H, cap = 1, 2, 2, n + 3
+    for noise in (ko.NOISE_GUMBEL, ko.NOISE_NONE) if n not in (33, 300) else (
+            ko.NOISE_GUMBEL, ko.NOISE_NONE, ko.NOISE_GAUSSIAN, ko.NOISE_CONSTANT):
+        oc = random_cache(rng, L, B, H, d, cap, dtype, 0)
+        Q = rnd(rng, (L, B, H, n, d), dtype)
+        seeds = np.array([77, 2 ** 40 + 1], np.uint64)
+        slopes = np.array([0.0, 0.0625], np.float32)
+        tau, scale = 1.0 if noise == ko.NOISE_GUMBEL else 1.3, float(1.0 / np.sqrt(np.float32(d)))
+        gc = upload(oc)
+        ws = kf.new_workspace(gc, n)
+        oc.prefill_score(Q, n, tau, scale, noise, seeds, slopes)
+        kf.kf_prefill_score(gc, dev(Q), n, tau, scale, noise, dev(seeds), dev(slopes), ws)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(host(gc.len), oc.len)
+        np.testing.assert_array_equal(host(gc.pos)[..., :n], oc.pos[..., :n])
+        assert_close_score(host(gc.score), oc.score, oc.len, "prefill noise=%d" % noise)
+
+
+# ------------------------------------------------------------------ the five configurations
+def test_tiny_config_full_lockstep_and_free_running():
+    wl = kw.CONFIGS["tiny"]
+    ls = LockStep(wl)
+    ls.prefill()
+    for t in range(1, wl.T + 1):
+        ls.step(t, check_kv=True)
+    assert ls.stats["steps"] == wl.T
+    print("tiny lockstep", ls.stats)
+    # free-running: no resynchronisation at all; report where (if ever) the sets part
+    fr = LockStep(wl)
+    fr.oc.prefill_score(fr.Q, wl.n, ko.tau(0, wl.T), wl.scale, fr.noise, fr.seeds, fr.slopes)
+    kf.kf_prefill_score(fr.gc, dev(fr.Q), wl.n, kf.kf_tau(0, wl.T), wl.scale, fr.noise, fr.d_seeds, None, fr.ws)
+    fr.oc.select_evict(wl.k, wl.w)
+    kf.kf_select_evict(fr.gc, wl.k, wl.w, None, fr.ws)
+    first_div = None
+    for t in range(1, wl.T + 1):
+        q, kn, vn = kw.decode_inputs(wl, t)
+        fr.oc.decode_step(kw.to_oracle(q), kw.to_oracle(kn), kw.to_oracle(vn), wl.n + t - 1, ko.tau(t, wl.T),
+                          wl.scale, fr.noise, fr.seeds)
+        kf.kf_decode_step(fr.gc, q.cuda(), kn.cuda(), vn.cuda(), wl.n + t - 1, wl.k + 1, kf.kf_tau(t, wl.T),
+                          wl.scale, fr.noise, fr.d_seeds, None, fr.out, fr.ws)
+        fr.oc.select_evict(wl.k, wl.w)
+        kf.kf_select_evict(fr.gc, wl.k, wl.w, None, fr.ws)
+        torch.cuda.synchronize()
+        if first_div is None and not (host(fr.gc.pos)[..., : wl.k] == fr.oc.pos[..., : wl.k]).all():
+            first_div = t
+    print("tiny free-running first divergence step:", first_div)
+    assert first_div is None      # well-separated scores: the sets stay identical for all 32 steps
+
+
+SLICES = {
+    # name: (slice kwargs, decode steps checked)
+    "gptj": (dict(L=2, H=16, T=512), 48),
+    "mpt": (dict(L=1, B=2, H=8, T=1024), 24),
+    "batched": (dict(L=1, B=4, H=8, T=1024), 24),
+}
+
+
+@pytest.mark.parametrize("name", list(SLICES))
+def test_config_slice_lockstep(name):
+    kwargs, steps = SLICES[name]
+    wl = kw.CONFIGS[name].slice(**kwargs)
+    ls = LockStep(wl)
+    ls.prefill()
+    for t in range(1, steps + 1):
+        ls.step(t, check_kv=(t == steps))
+    print(name, "slice lockstep", ls.stats)
+
+
+def test_long_config_slice_lockstep():
+    # full per-unit shape of the long-context configuration (n = 32768, k = 9830)
+    wl = kw.CONFIGS["long"].slice(L=1, H=2, T=2048)
+    ls = LockStep(wl)
+    ls.prefill()
+    for t in range(1, 9):
+        ls.step(t, check_kv=(t == 8))
+    print("long slice lockstep", ls.stats)

@@ -1,0 +1,137 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports
+every symbol the header declares, mirrors the oracle's tau schedule and noise
+hash bit for bit, and rejects bad arguments before launching anything."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2403_09054_amd as kf
+from paper_2403_09054_amd import binding
+from oracle import kf_oracle as ko
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+GOLDEN = os.path.join(ROOT, "tests", "golden")
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "keyformer.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(kf_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert set(names) == set(binding.SYMBOLS)
+    raw = ctypes.CDLL(kf.lib_path())
+    for n in names:
+        assert getattr(raw, n) is not None
+    assert kf.kf_version() == 1
+
+
+def test_tau_matches_oracle_bits():
+    for T in (1, 32, 512, 1024, 2048):
+        for t in range(0, T + 1, max(1, T // 37)):
+            assert kf.kf_tau(t, T, 1.0, 2.0) == ko.tau(t, T, 1.0, 2.0)
+    assert kf.kf_tau(0, 512) == 1.0 and abs(kf.kf_tau(512, 512) - 2.0) < 1e-6
+
+
+def test_noise_bits_match_golden_and_oracle():
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "noise_bits.txt")) if not l.startswith("#")]
+    for r in rows:
+        args = list(map(int, r[:5]))
+        assert kf.kf_noise_bits(*args) == int(r[5])
+    rng = np.random.default_rng(0)
+    for _ in range(2000):
+        seed = int(rng.integers(0, 2 ** 63)) * 2 + int(rng.integers(0, 2))
+        a = [int(rng.integers(0, 64)), int(rng.integers(0, 64)), int(rng.integers(0, 2 ** 31)),
+             int(rng.integers(0, 2 ** 31))]
+        assert kf.kf_noise_bits(seed, *a) == ko.noise_bits(seed, *a)
+
+
+def fake_cache(**over):
+    # addresses are never dereferenced: validation fails (or is all that is tested) first
+    kw = dict(K=0x10000, V=0x20000, score=0x30000, pos=0x40000, len=0x50000, L=2, B=1, H=4, d=128,
+              cap=1025, dtype=kf.BF16)
+    kw.update(over)
+    return kf.Cache(**kw)
+
+
+WS = (0x100000, 1 << 40)
+
+
+def expect(status, fn, *a, **k):
+    with pytest.raises(kf.KeyformerError) as e:
+        fn(*a, **k)
+    assert e.value.status == status, e.value
+    assert len(str(e.value)) > 20
+
+
+def test_workspace_size_query():
+    c = fake_cache()
+    small = kf.kf_workspace_bytes(c, 0)
+    big = kf.kf_workspace_bytes(c, 1 << 20)
+    assert 0 < small <= big
+    assert kf.kf_workspace_bytes(fake_cache(d=96), 0) == 0
+    assert kf.kf_workspace_bytes(fake_cache(dtype=kf.F32, d=256), 0) == 0
+
+
+def test_select_argument_validation():
+    c = fake_cache()
+    expect(binding.KF_EINVAL, kf.kf_select_evict, c, 0, 0, None, WS, 0)
+    expect(binding.KF_EINVAL, kf.kf_select_evict, c, 8, 9, None, WS, 0)
+    expect(binding.KF_EINVAL, kf.kf_select_evict, c, 8, -1, None, WS, 0)
+    expect(binding.KF_EINVAL, kf.kf_select_evict, c, 1026, 3, None, WS, 0)
+    expect(binding.KF_EWORKSPACE, kf.kf_select_evict, c, 8, 2, None, (0x100000, 64), 0)
+    expect(binding.KF_EWORKSPACE, kf.kf_select_evict, c, 8, 2, None, None, 0)
+    expect(binding.KF_EWORKSPACE, kf.kf_select_evict, c, 8, 2, None, (0x100004, 1 << 40), 0)
+    expect(binding.KF_EINVAL, kf.kf_select_evict, fake_cache(K=None), 8, 2, None, WS, 0)
+    expect(binding.KF_EINVAL, kf.kf_select_evict, fake_cache(K=0x10004), 8, 2, None, WS, 0)
+    expect(binding.KF_EUNSUPPORTED, kf.kf_select_evict, fake_cache(d=96), 8, 2, None, WS, 0)
+    expect(binding.KF_EINVAL, kf.kf_select_evict, fake_cache(dtype=7), 8, 2, None, WS, 0)
+    expect(binding.KF_EINVAL, kf.kf_select_evict, fake_cache(L=0), 8, 2, None, WS, 0)
+
+
+def test_decode_argument_validation():
+    c = fake_cache()
+    good = dict(q=0x1000, k_new=0x2000, v_new=0x3000, q_pos=10, m_hint=0, tau=1.5, scale=0.1,
+                noise=kf.NOISE_GUMBEL, seeds=0x4000, slopes=None, out=0x5000, workspace=WS, stream=0)
+
+    def call(**over):
+        a = dict(good)
+        a.update(over)
+        kf.kf_decode_step(c, a["q"], a["k_new"], a["v_new"], a["q_pos"], a["m_hint"], a["tau"], a["scale"],
+                          a["noise"], a["seeds"], a["slopes"], a["out"], a["workspace"], a["stream"])
+
+    for bad in (dict(q=None), dict(k_new=None), dict(v_new=None), dict(out=None), dict(q=0x1008),
+                dict(q_pos=-1), dict(m_hint=-1), dict(m_hint=1026), dict(tau=0.0), dict(tau=-1.0),
+                dict(tau=float("inf")), dict(tau=float("nan")), dict(scale=float("nan")), dict(noise=9),
+                dict(seeds=None), dict(noise=kf.NOISE_GAUSSIAN, seeds=None)):
+        expect(binding.KF_EINVAL, call, **bad)
+    expect(binding.KF_EWORKSPACE, call, workspace=(0x100000, 1000))
+
+
+def test_prefill_argument_validation():
+    c = fake_cache(cap=4096)
+    cfg = dict(tau=1.0, scale=0.1, noise=kf.NOISE_GUMBEL, seeds=0x4000, slopes=None, workspace=WS, stream=0)
+    expect(binding.KF_EINVAL, kf.kf_prefill_score, c, None, 128, **cfg)
+    expect(binding.KF_EINVAL, kf.kf_prefill_score, c, 0x1000, 0, **cfg)
+    expect(binding.KF_EINVAL, kf.kf_prefill_score, c, 0x1000, 4097, **cfg)
+    expect(binding.KF_EINVAL, kf.kf_prefill_score, c, 0x1004, 128, **cfg)
+    expect(binding.KF_EINVAL, kf.kf_prefill_score, c, 0x1000, 128, **dict(cfg, tau=0.0))
+    expect(binding.KF_EINVAL, kf.kf_prefill_score, c, 0x1000, 128, **dict(cfg, seeds=None))
+    expect(binding.KF_EWORKSPACE, kf.kf_prefill_score, c, 0x1000, 128, **dict(cfg, workspace=(0x100000, 4096)))
+
+
+def test_decode_launch_plan_is_consistent_with_workspace():
+    # the workspace a cache asks for must cover the decode plan at every hint:
+    # probe through the public size query on a grid of shapes
+    for (L, B, H, d, cap, dt) in [(1, 1, 1, 64, 128, kf.F32), (28, 1, 16, 256, 1025, kf.BF16),
+                                  (32, 8, 32, 128, 2049, kf.BF16), (32, 1, 32, 128, 9831, kf.BF16),
+                                  (1, 1, 1, 128, 600000, kf.BF16)]:
+        c = fake_cache(L=L, B=B, H=H, d=d, cap=cap, dtype=dt)
+        nbytes = kf.kf_workspace_bytes(c, 0)
+        U = L * B * H
+        assert nbytes >= U * cap * 4 + U * 4          # at least the increments and the counters
