@@ -1,0 +1,239 @@
+#!/usr/bin/env python3
+"""Benchmark of the Keyformer decode hot path on one MI355X.
+
+A "step" is one generation step of the whole path over every (layer, batch,
+head) unit of the workload: kf_decode_step (append + logits + attention +
+score accumulation, one fused kernel) followed by kf_select_evict (top-(k-w)
+selection + window retention + in-place KV compaction).  The state the timed
+steps start from is produced by the path itself: kf_prefill_score over the
+synthetic prompt, then kf_select_evict from n to k tokens.
+
+Prints ONE JSON line (see the keys below).  `value` is decode steps/s with all
+inputs resident in HBM; `roofline` is the fused decode kernel's algorithmic
+HBM bytes per launch over its mean launch duration (HIP events on the launch
+stream, inside the timed region) against the 8 TB/s peak; `cpu_baseline` is
+the CPU oracle timed on a bounded sample of the same state.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E peak
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=256)
+    ap.add_argument("--warmup", type=int, default=16)
+    ap.add_argument("--config", default="gptj", help="workload name in kf_workloads.CONFIGS")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-events", action="store_true",
+                    help="time the steps without per-kernel events (roofline is then null)")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU work budget of the oracle leg")
+    return ap.parse_args()
+
+
+def decode_bytes(wl, m):
+    """Algorithmic HBM bytes of one fused decode launch: K and V rows read once,
+    score read + written, pos read, plus the per-unit q/k_new/v_new/out vectors."""
+    per_unit = m * (2 * wl.d * wl.elem_bytes + 12) + 3 * wl.d * wl.elem_bytes + 4 * wl.d
+    return wl.units * per_unit
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (units are independent; see DESIGN.md for how the "
+              "path would shard); --gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+
+    import kf_workloads as kw
+    import paper_2403_09054_amd as kf
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    wl = kw.CONFIGS[args.config]
+    K_steps, W_steps = args.steps, args.warmup
+    dt = kf.F32 if wl.dtype == "f32" else kf.BF16
+    seeds = torch.from_numpy(kw.noise_seeds(wl).view(np.int64).copy()).cuda()
+    slopes_np = kw.alibi_slopes(wl)
+    slopes = None if slopes_np is None else torch.from_numpy(slopes_np).cuda()
+    noise = kf.NOISE_GUMBEL
+
+    # ---------------- state: prompt scoring + first eviction, layer by layer ----------------
+    cache = kf.Cache.allocate(wl.L, wl.B, wl.H, wl.d, wl.k + 1, dt)
+    ws = kf.new_workspace(cache)
+    stage = kf.Cache.allocate(1, wl.B, wl.H, wl.d, wl.n, dt)     # one layer's prompt-sized cache
+    ws_stage = kf.new_workspace(stage, wl.n)
+    tau0 = kf.kf_tau(0, wl.T, wl.tau_init, wl.tau_end)
+    prefill_ms = 0.0
+    first_select_ms = 0.0
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    for l in range(wl.L):
+        Q, K, V = kw.prompt_layer(wl, l, device="cuda")
+        stage.K[0].copy_(K)
+        stage.V[0].copy_(V)
+        stage.layer0 = l   # the staging cache plays layer l (noise key)
+        ev[0].record()
+        kf.kf_prefill_score(stage, Q.contiguous(), wl.n, tau0, wl.scale, noise, seeds, slopes, ws_stage)
+        ev[1].record()
+        kf.kf_select_evict(stage, wl.k, wl.w, None, ws_stage)
+        ev[2].record()
+        torch.cuda.synchronize()
+        prefill_ms += ev[0].elapsed_time(ev[1])
+        first_select_ms += ev[1].elapsed_time(ev[2])
+        cache.K[l, :, :, : wl.k].copy_(stage.K[0, :, :, : wl.k])
+        cache.V[l, :, :, : wl.k].copy_(stage.V[0, :, :, : wl.k])
+        cache.score[l, :, :, : wl.k].copy_(stage.score[0, :, :, : wl.k])
+        cache.pos[l, :, :, : wl.k].copy_(stage.pos[0, :, :, : wl.k])
+        cache.len[l].copy_(stage.len[0])
+        del Q, K, V
+    del stage, ws_stage
+    torch.cuda.empty_cache()
+    assert int(cache.len.min()) == wl.k and int(cache.len.max()) == wl.k
+
+    # ---------------- decode inputs, resident in HBM ----------------
+    n_distinct = min(W_steps + K_steps, 64)
+    steps_in = [kw.decode_inputs(wl, t + 1, device="cuda") for t in range(n_distinct)]
+    out = torch.zeros((wl.L, wl.B, wl.H, wl.d), dtype=torch.float32, device="cuda")
+    m = wl.k + 1
+
+    def one_step(t, e0=None, e1=None, e2=None):
+        tt = min(t, wl.T)
+        q, kn, vn = steps_in[(t - 1) % n_distinct]
+        if e0 is not None:
+            e0.record()
+        kf.kf_decode_step(cache, q, kn, vn, wl.n + t - 1, m, kf.kf_tau(tt, wl.T, wl.tau_init, wl.tau_end),
+                          wl.scale, noise, seeds, slopes, out, ws)
+        if e1 is not None:
+            e1.record()
+        kf.kf_select_evict(cache, wl.k, wl.w, None, ws)
+        if e2 is not None:
+            e2.record()
+
+    for t in range(1, W_steps + 1):
+        one_step(t)
+    torch.cuda.synchronize()
+
+    # snapshot for the CPU baseline / spot check (layer 0), taken before the timed region
+    snap = None
+    if not args.no_cpu_baseline:
+        snap = dict(K=cache.K[0:1].clone(), V=cache.V[0:1].clone(), score=cache.score[0:1].clone(),
+                    pos=cache.pos[0:1].clone(), len=cache.len[0:1].clone())
+
+    use_events = not args.no_events
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(K_steps)] if use_events else None
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(K_steps):
+        t = W_steps + 1 + i
+        if use_events:
+            one_step(t, *evs[i])
+        else:
+            one_step(t)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    elapsed = t1 - t0
+    err_word = int(ws[:4].view(torch.int32)[0].item())
+    assert err_word == 0, "decode kernel skipped units"
+    assert int(cache.len.min()) == wl.k and int(cache.len.max()) == wl.k
+
+    ms_per_step = elapsed * 1e3 / K_steps
+    value = K_steps / elapsed
+
+    roofline = None
+    select_info = None
+    if use_events:
+        dec_ms = sum(e[0].elapsed_time(e[1]) for e in evs) / K_steps
+        sel_ms = sum(e[1].elapsed_time(e[2]) for e in evs) / K_steps
+        nbytes = decode_bytes(wl, m)
+        achieved = nbytes / (dec_ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "kernel": "decode_kernel", "achieved": round(achieved, 1),
+                    "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                    "traffic": None, "bytes_per_launch": nbytes, "avg_launch_us": round(dec_ms * 1e3, 2)}
+        # bytes the in-place, order-preserving compaction really moves: every row behind the
+        # evicted slot is read and written once (K and V), plus the score read of the selection
+        kept = torch.zeros((wl.L, wl.B, wl.H, wl.k), dtype=torch.int32, device="cuda")
+        moved = 0.0
+        probes = 4
+        for i in range(probes):
+            t = W_steps + K_steps + 1 + i
+            tt = min(t, wl.T)
+            q, kn, vn = steps_in[(t - 1) % n_distinct]
+            kf.kf_decode_step(cache, q, kn, vn, wl.n + t - 1, m, kf.kf_tau(tt, wl.T, wl.tau_init, wl.tau_end),
+                              wl.scale, noise, seeds, slopes, out, ws)
+            kf.kf_select_evict(cache, wl.k, wl.w, kept, ws)
+            ar = torch.arange(wl.k, device="cuda", dtype=torch.int32)
+            moved += float((kept != ar).sum().item())
+        moved_rows = moved / probes
+        sel_bytes = moved_rows * (2 * 2 * wl.d * wl.elem_bytes + 2 * 8) + wl.units * m * 4
+        sel_gbs = sel_bytes / (sel_ms * 1e-3) / 1e9
+        select_info = {"kernel": "select_kernel", "avg_launch_us": round(sel_ms * 1e3, 2),
+                       "moved_rows_per_step": round(moved_rows, 1), "bytes_per_launch": int(sel_bytes),
+                       "achieved": round(sel_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                       "frac": round(sel_gbs / HBM_PEAK_GBS, 4)}
+        traffic_file = os.path.join(ROOT, "profiles", "traffic_%s.json" % wl.name)
+        if os.path.exists(traffic_file):
+            roofline["traffic"] = json.load(open(traffic_file)).get("decode_kernel_bytes_per_launch")
+
+    # prompt-phase scoring: dense causal QK^T twice (row statistics, column sums)
+    prefill_flops = wl.units * 2 * (2.0 * wl.d * wl.n * (wl.n + 1) / 2)
+    prefill = {"ms_total": round(prefill_ms, 3), "tflops": round(prefill_flops / (prefill_ms * 1e-3) / 1e12, 2),
+               "logits_per_s": round(wl.units * wl.n * (wl.n + 1) / (prefill_ms * 1e-3), 0),
+               "first_select_ms_total": round(first_select_ms, 3)}
+
+    # ---------------- CPU oracle on a bounded sample of the same state ----------------
+    cpu = None
+    if snap is not None:
+        from oracle import kf_oracle as ko
+        oc = ko.OracleCache(1, wl.B, wl.H, wl.d, wl.k + 1, ko.F32 if wl.dtype == "f32" else ko.BF16)
+        oc.K[...] = kw.to_oracle(snap["K"])
+        oc.V[...] = kw.to_oracle(snap["V"])
+        oc.score[...] = kw.to_oracle(snap["score"])
+        oc.pos[...] = kw.to_oracle(snap["pos"])
+        oc.len[...] = kw.to_oracle(snap["len"])
+        sl_units = wl.B * wl.H
+        cpu_steps, cpu_time = 0, 0.0
+        t = W_steps + 1
+        while cpu_time < args.cpu_seconds and cpu_steps < 64:
+            q, kn, vn = (kw.to_oracle(a[0:1]) for a in steps_in[(t - 1) % n_distinct])
+            c0 = time.perf_counter()
+            oc.decode_step(q, kn, vn, wl.n + t - 1, ko.tau(min(t, wl.T), wl.T, wl.tau_init, wl.tau_end),
+                           wl.scale, ko.NOISE_GUMBEL, kw.noise_seeds(wl), slopes_np)
+            oc.select_evict(wl.k, wl.w, want_idx=False)
+            cpu_time += time.perf_counter() - c0
+            cpu_steps += 1
+            t += 1
+        cpu_value = (cpu_steps / cpu_time) * (sl_units / wl.units)
+        cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+        cpu = {"value": round(cpu_value, 4), "unit": "steps/s", "cores": min(cores, sl_units), "kind": "oracle",
+               "sample": "layer 0 of %d (%d of %d units), %d decode+evict steps, scaled by units" % (
+                   wl.L, sl_units, wl.units, cpu_steps),
+               "host_cpus": os.cpu_count()}
+
+    line = {
+        "metric": "decode steps/s (fused attn+score+evict) at %d%% KV budget" % round(100 * wl.k / wl.n),
+        "value": round(value, 2), "unit": "steps/s", "n_gpus": 1, "steps": K_steps, "warmup": W_steps,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": "%s: L=%d B=%d H=%d d=%d n=%d k=%d w=%d T=%d %s" % (
+            wl.name, wl.L, wl.B, wl.H, wl.d, wl.n, wl.k, wl.w, wl.T, wl.dtype),
+            "units": wl.units, "noise": "gumbel", "tau": [wl.tau_init, wl.tau_end],
+            "layout": "ordered (in-place order-preserving compaction)"},
+        "roofline": roofline, "select_compact": select_info, "prefill_score": prefill, "cpu_baseline": cpu,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -66,6 +66,8 @@ typedef struct {
     int32_t *len;   /* DEVICE [L][B][H]         live tokens per unit                      */
     int32_t L, B, H, d, cap;
     int32_t dtype;  /* kf_dtype */
+    int32_t layer0; /* model-wide index of the cache's first layer; enters the noise key only, so
+                       a cache that holds a subset of the layers draws the same noise */
 } kf_cache;
 
 /* Parameters of the score function (Eq. 11) for one call. */

@@ -36,6 +36,9 @@
  *   score  [U][cap]      fp32, accumulated f
  *   pos    [U][cap]      int32, original token position, ascending in [0,len)
  *   len    [U]           int32
+ * layer0 is the model-wide index of the cache's first layer (it only enters
+ * the noise key), so that a cache holding a subset of the layers draws the
+ * same noise as the full one.
  */
 #include <math.h>
 #include <stdint.h>
@@ -186,13 +189,13 @@ static void softmax_inplace(double *v, int m)
 /* ------------------------------------------------------------------ */
 int kfo_prefill_score(const void *Q, const void *K, float *score, int32_t *pos,
                       int32_t *len, int L, int B, int H, int d, int cap,
-                      int dtype, int n, float tau, float scale, int noise,
+                      int dtype, int layer0, int n, float tau, float scale, int noise,
                       const uint64_t *seeds, const float *slopes)
 {
     if (n < 1 || n > cap || !(tau > 0.0f)) return -1;
     int U = L * B * H;
     for (int u = 0; u < U; ++u) {
-        int h = u % H, b = (u / H) % B, l = u / (H * B);
+        int h = u % H, b = (u / H) % B, l = layer0 + u / (H * B);
         double slope = slopes ? (double)slopes[h] : 0.0;
         uint64_t seed = seeds ? seeds[b] : 0;
         double *q = (double *)malloc((size_t)n * d * sizeof(double));
@@ -261,7 +264,7 @@ int kfo_prefill_score(const void *Q, const void *K, float *score, int32_t *pos,
 /* Optional debug outputs (may be NULL): dbg_p, dbg_df [U][cap] doubles. */
 /* ------------------------------------------------------------------ */
 int kfo_decode_step(void *K, void *V, float *score, int32_t *pos, int32_t *len,
-                    int L, int B, int H, int d, int cap, int dtype,
+                    int L, int B, int H, int d, int cap, int dtype, int layer0,
                     const void *q, const void *k_new, const void *v_new,
                     int32_t q_pos, float tau, float scale, int noise,
                     const uint64_t *seeds, const float *slopes, float *out,
@@ -275,7 +278,7 @@ int kfo_decode_step(void *K, void *V, float *score, int32_t *pos, int32_t *len,
     int failed = 0;
 #pragma omp parallel for schedule(dynamic, 1)
     for (int u = 0; u < U; ++u) {
-        int h = u % H, b = (u / H) % B, l = u / (H * B);
+        int h = u % H, b = (u / H) % B, l = layer0 + u / (H * B);
         double slope = slopes ? (double)slopes[h] : 0.0;
         uint64_t seed = seeds ? seeds[b] : 0;
         char *Ku = (char *)K + (size_t)u * cap * d * es;

@@ -35,6 +35,7 @@ kf_status check_cache(const kf_cache* c) {
         return fail(KF_EINVAL, "cache dimensions must be positive (L=%d B=%d H=%d d=%d cap=%d)", c->L, c->B, c->H,
                     c->d, c->cap);
     if ((int64_t)c->L * c->B * c->H > (int64_t)1 << 24) return fail(KF_EINVAL, "too many units");
+    if (c->layer0 < 0) return fail(KF_EINVAL, "layer0 must be non-negative");
     if (c->dtype != KF_F32 && c->dtype != KF_BF16) return fail(KF_EINVAL, "unknown dtype %d", c->dtype);
     if (!supported(c->dtype, c->d))
         return fail(KF_EUNSUPPORTED, "dtype %d with head dimension %d is not built", c->dtype, c->d);
@@ -54,14 +55,13 @@ kf_status check_cfg(const kf_score_cfg* cfg) {
 }
 
 // Workspace layout (all regions 256-byte aligned):
-//   [0]        error word + padding
-//   counters   U int32            decode arrival counters (zero between calls)
+//   [0]        error word + padding (the only part that must start as zero)
 //   region X   the largest of
 //                decode : partial records U*S*(d+4) floats, then increments U*cap floats
 //                select : survivor index list U*cap int32
 //                prefill: row normalisers U*n_pad floats, then row keys U*n_pad uint32
 struct WsLayout {
-    size_t counters, region, total;
+    size_t region, total;
 };
 
 size_t decode_region(int64_t U, const kf_cache* c) {
@@ -73,8 +73,7 @@ size_t decode_region(int64_t U, const kf_cache* c) {
 WsLayout ws_layout(const kf_cache* c, int32_t n_max) {
     const int64_t U = (int64_t)c->L * c->B * c->H;
     WsLayout w;
-    w.counters = 256;
-    w.region = w.counters + align_up((size_t)U * sizeof(int32_t), 256);
+    w.region = 256;
     size_t x = decode_region(U, c);
     const size_t sel = align_up((size_t)U * c->cap * sizeof(int32_t), 256);
     if (sel > x) x = sel;
@@ -145,6 +144,7 @@ kf_status kf_prefill_score(const kf_cache* c, const void* Q, int32_t n, const kf
     a.B = c->B;
     a.H = c->H;
     a.cap = c->cap;
+    a.layer0 = c->layer0;
     a.n = n;
     a.n_pad = (int32_t)n_pad;
     a.noise = cfg->noise;
@@ -191,12 +191,12 @@ kf_status kf_decode_step(kf_cache* c, const void* q, const void* k_new, const vo
     a.seeds = cfg->seeds;
     a.slopes = cfg->alibi_slopes;
     a.ws_err = (int32_t*)workspace + KF_WS_ERROR_WORD;
-    a.ws_cnt = (int32_t*)((char*)workspace + w.counters);
     a.ws_part = (float*)((char*)workspace + w.region);
     a.ws_e = (float*)((char*)workspace + w.region + align_up((size_t)U * pmax.S * (c->d + 4) * sizeof(float), 256));
     a.B = c->B;
     a.H = c->H;
     a.cap = c->cap;
+    a.layer0 = c->layer0;
     a.S = p.S;
     a.chunk = p.chunk;
     a.q_pos = q_pos;

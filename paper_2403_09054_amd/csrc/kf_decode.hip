@@ -10,11 +10,13 @@
 // workgroup each.  A workgroup streams its K rows (16 bytes per lane, a row
 // spread over D*sizeof(T)/16 adjacent lanes so that every wave-wide load is one
 // contiguous kilobyte), keeps the logits in LDS, forms the two softmaxes'
-// local statistics, then streams its V rows.  With S == 1 it finishes the unit
-// itself.  With S > 1 it leaves a partial record (un-normalised output, local
-// max and sum of both softmaxes) and the last workgroup of the unit to arrive
-// merges the records; "last to arrive" is decided by a per-unit counter that
-// the merging workgroup resets, so no second launch and no memset is needed.
+// local statistics while its first V tile is already in flight, then streams
+// its V rows.  With S == 1 it finishes the unit itself.  With S > 1 it leaves a
+// partial record (un-normalised output, local max and sum of both softmaxes,
+// un-normalised score increments) and a second, tiny launch merges the records
+// of each unit.  (Merging inside the first launch, by the last split to arrive,
+// needs device-scope fences; on this multi-die part every such fence writes
+// back an L2 and the kernel ran 6x slower, so the merge is a launch of its own.)
 #include "kf_device.h"
 #include "kf_internal.h"
 
@@ -23,8 +25,60 @@ namespace kf {
 constexpr int kDecodeThreads = 256;
 constexpr int kDecodeMaxChunk = 4096;   // tokens per split the LDS arrays are sized for
 constexpr int kDecodeMaxSplits = 256;   // <= kDecodeThreads: one thread per split in the merge
-constexpr int kDecodeTargetBlocks = 2048;
+#ifndef KF_DECODE_MIN_BLOCKS
+#define KF_DECODE_MIN_BLOCKS 1024
+#endif
+constexpr int kDecodeMinBlocks = KF_DECODE_MIN_BLOCKS;  // workgroups wanted on the chip
+constexpr int kComputeUnits = 256;                      // MI355X
+constexpr int kDecodeBlockOverheadTokens = 48;          // fixed cost of a workgroup, in tokens' worth of time
 constexpr int kDecodeMinChunk = 128;
+
+#ifndef KF_DECODE_UNROLL
+#define KF_DECODE_UNROLL 4
+#endif
+
+// Merges the S partial records of unit u: rescales every split's un-normalised
+// output and score increments to the unit-wide maxima, normalises, accumulates
+// the scores and publishes the new length.  Called by a whole workgroup.
+template <int D, int NT>
+__device__ __forceinline__ void merge_unit(const DecodeArgs& a, int64_t u, int len0, float* red_s, float* w_p,
+                                           float* w_e) {
+    constexpr int PW = D + 4;
+    const int tid = threadIdx.x, S = a.S, m = len0 + 1;
+    const float* parts = a.ws_part + (size_t)u * S * PW;
+    float* fu = a.score + (size_t)u * a.cap;
+    float pmx = -INFINITY, psp = 0.0f, pmy = -INFINITY, pse = 0.0f;
+    if (tid < S) {
+        const float* r = parts + (size_t)tid * PW + D;
+        pmx = r[0];
+        psp = r[1];
+        pmy = r[2];
+        pse = r[3];
+    }
+    const float Mx = block_max<NT>(pmx, red_s);
+    const float My = block_max<NT>(pmy, red_s);
+    const float wp = (psp > 0.0f) ? expf(pmx - Mx) : 0.0f;  // empty splits weigh nothing
+    const float we_ = (pse > 0.0f) ? expf(pmy - My) : 0.0f;
+    const float sumP = block_sum<NT>(wp * psp, red_s);
+    const float sumE = block_sum<NT>(we_ * pse, red_s);
+    if (tid < S) {
+        w_p[tid] = wp;
+        w_e[tid] = we_;
+    }
+    __syncthreads();
+    if (tid < D) {
+        float o = 0.0f;
+        for (int ss = 0; ss < S; ++ss) o = fmaf(w_p[ss], parts[(size_t)ss * PW + tid], o);
+        a.out[u * D + tid] = o / sumP;
+    }
+    const float* we = a.ws_e + (size_t)u * a.cap;
+    const float inv = 1.0f / sumE;
+    for (int j = tid; j < m; j += NT) {
+        const float prev = (j == len0) ? 0.0f : fu[j];
+        fu[j] = prev + we[j] * (w_e[j / a.chunk] * inv);
+    }
+    if (tid == 0) a.len[u] = m;
+}
 
 template <typename T, int D, int NT>
 __global__ void __launch_bounds__(NT) decode_kernel(const DecodeArgs a) {
@@ -33,7 +87,7 @@ __global__ void __launch_bounds__(NT) decode_kernel(const DecodeArgs a) {
     constexpr int RPW = kWave / LPR;             // rows per wave-wide load
     constexpr int NW = NT / kWave;
     constexpr int RPB = RPW * NW;                // rows per block-wide load
-    constexpr int UNR = 4;                       // independent loads in flight per lane
+    constexpr int UNR = KF_DECODE_UNROLL;        // independent loads in flight per lane
     constexpr int PW = D + 4;                    // floats in a partial record
     static_assert(LPR <= kWave && D <= NT, "row must fit a wave, output a block");
 
@@ -42,15 +96,13 @@ __global__ void __launch_bounds__(NT) decode_kernel(const DecodeArgs a) {
     float* ys = smem + a.chunk;      // [chunk] perturbed logits / tau, then their exponentials
     float* red_o = ys + a.chunk;     // [NW][D] per-wave output partials
     __shared__ float red_s[NW];
-    __shared__ float w_p[kDecodeMaxSplits], w_e[kDecodeMaxSplits];
-    __shared__ int s_last;
 
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int sub = lane / LPR, cl = lane % LPR;
     const int S = a.S;
     const int64_t u = blockIdx.x / S;
     const int s = blockIdx.x % S;
-    const int h = (int)(u % a.H), b = (int)((u / a.H) % a.B), l = (int)(u / ((int64_t)a.H * a.B));
+    const int h = (int)(u % a.H), b = (int)((u / a.H) % a.B), l = a.layer0 + (int)(u / ((int64_t)a.H * a.B));
 
     const int len0 = a.len[u];
     const int m = len0 + 1;
@@ -93,23 +145,32 @@ __global__ void __launch_bounds__(NT) decode_kernel(const DecodeArgs a) {
         unpack16<T>(r, qv);
     }
 
-    // ---- phase 1: stream K, logits into LDS
-    for (int base = j0 + wv * RPW; base < j1; base += RPB * UNR) {
-        uint4 raw[UNR];
+    // Loads one tile (UNR block-wide loads) of this lane's 16-byte pieces; the
+    // slot of the new token is served from the call's own k_new / v_new row.
+    auto load_tile = [&](const T* rows, const T* fresh, int base, uint4(&raw)[UNR]) {
 #pragma unroll
         for (int i = 0; i < UNR; ++i) {
             const int j = base + i * RPB + sub;
             if (j < j1) {
-                const T* row = (j == len0) ? knew : Ku + (size_t)j * D;
+                const T* row = (j == len0) ? fresh : rows + (size_t)j * D;
                 raw[i] = ((const uint4*)row)[cl];
             } else {
                 raw[i] = make_uint4(0u, 0u, 0u, 0u);
             }
         }
+    };
+    constexpr int TILE = RPB * UNR;
+    const int base0 = j0 + wv * RPW;
+
+    // ---- phase 1: stream K (next tile in flight while this one is reduced), logits into LDS
+    uint4 cur[UNR], nxt[UNR];
+    if (base0 < j1) load_tile(Ku, knew, base0, cur);
+    for (int base = base0; base < j1; base += TILE) {
+        if (base + TILE < j1) load_tile(Ku, knew, base + TILE, nxt);
 #pragma unroll
         for (int i = 0; i < UNR; ++i) {
             float kvals[EPV];
-            unpack16<T>(raw[i], kvals);
+            unpack16<T>(cur[i], kvals);
             float p = 0.0f;
 #pragma unroll
             for (int e = 0; e < EPV; ++e) p = fmaf(kvals[e], qv[e], p);
@@ -118,7 +179,11 @@ __global__ void __launch_bounds__(NT) decode_kernel(const DecodeArgs a) {
             const int j = base + i * RPB + sub;
             if (cl == 0 && j < j1) xs[j - j0] = p * a.scale;
         }
+#pragma unroll
+        for (int i = 0; i < UNR; ++i) cur[i] = nxt[i];
     }
+    // first V tile: in flight while the softmax statistics are formed
+    if (base0 < j1) load_tile(Vu, vnew, base0, cur);
     __syncthreads();
 
     // ---- phase 1.5: position bias, logit adjustment, the two softmaxes' statistics
@@ -167,27 +232,19 @@ __global__ void __launch_bounds__(NT) decode_kernel(const DecodeArgs a) {
     float acc[EPV];
 #pragma unroll
     for (int e = 0; e < EPV; ++e) acc[e] = 0.0f;
-    for (int base = j0 + wv * RPW; base < j1; base += RPB * UNR) {
-        uint4 raw[UNR];
-#pragma unroll
-        for (int i = 0; i < UNR; ++i) {
-            const int j = base + i * RPB + sub;
-            if (j < j1) {
-                const T* row = (j == len0) ? vnew : Vu + (size_t)j * D;
-                raw[i] = ((const uint4*)row)[cl];
-            } else {
-                raw[i] = make_uint4(0u, 0u, 0u, 0u);
-            }
-        }
+    for (int base = base0; base < j1; base += TILE) {
+        if (base + TILE < j1) load_tile(Vu, vnew, base + TILE, nxt);
 #pragma unroll
         for (int i = 0; i < UNR; ++i) {
             const int j = base + i * RPB + sub;
             const float p = (j < j1) ? xs[j - j0] : 0.0f;
             float vvals[EPV];
-            unpack16<T>(raw[i], vvals);
+            unpack16<T>(cur[i], vvals);
 #pragma unroll
             for (int e = 0; e < EPV; ++e) acc[e] = fmaf(p, vvals[e], acc[e]);
         }
+#pragma unroll
+        for (int i = 0; i < UNR; ++i) cur[i] = nxt[i];
     }
     // rows of one wave-wide load live in different lane groups: fold them
 #pragma unroll
@@ -212,7 +269,7 @@ __global__ void __launch_bounds__(NT) decode_kernel(const DecodeArgs a) {
         return;
     }
 
-    // ---- S > 1: leave a partial record, the last split to arrive merges
+    // ---- S > 1: leave a partial record for the merge
     float* part = a.ws_part + ((size_t)u * S + s) * PW;
     if (tid < D) part[tid] = o_c;
     if (tid == 0) {
@@ -221,50 +278,17 @@ __global__ void __launch_bounds__(NT) decode_kernel(const DecodeArgs a) {
         part[D + 2] = my;
         part[D + 3] = se;
     }
-    __threadfence();  // this thread's record and score increments are visible device-wide
-    __syncthreads();
-    if (tid == 0) s_last = (atomicAdd(a.ws_cnt + u, 1) == S - 1);
-    __syncthreads();
-    if (!s_last) return;
-    __threadfence();  // see the other splits' records
+}
 
-    const float* parts = a.ws_part + (size_t)u * S * PW;
-    float pmx = -INFINITY, psp = 0.0f, pmy = -INFINITY, pse = 0.0f;
-    if (tid < S) {
-        const float* r = parts + (size_t)tid * PW + D;
-        pmx = r[0];
-        psp = r[1];
-        pmy = r[2];
-        pse = r[3];
-    }
-    const float Mx = block_max<NT>(pmx, red_s);
-    const float My = block_max<NT>(pmy, red_s);
-    const float wp = (psp > 0.0f) ? expf(pmx - Mx) : 0.0f;   // empty splits weigh nothing
-    const float we_ = (pse > 0.0f) ? expf(pmy - My) : 0.0f;
-    const float sumP = block_sum<NT>(wp * psp, red_s);
-    const float sumE = block_sum<NT>(we_ * pse, red_s);
-    if (tid < S) {
-        w_p[tid] = wp;
-        w_e[tid] = we_;
-    }
-    __syncthreads();
-    if (tid < D) {
-        float o = 0.0f;
-        for (int ss = 0; ss < S; ++ss) o = fmaf(w_p[ss], parts[(size_t)ss * PW + tid], o);
-        a.out[u * D + tid] = o / sumP;
-    }
-    {
-        const float* we = a.ws_e + (size_t)u * a.cap;
-        const float inv = 1.0f / sumE;
-        for (int j = tid; j < m; j += NT) {
-            const float prev = (j == len0) ? 0.0f : fu[j];
-            fu[j] = prev + we[j] * (w_e[j / a.chunk] * inv);
-        }
-    }
-    if (tid == 0) {
-        a.len[u] = m;
-        a.ws_cnt[u] = 0;  // ready for the next call
-    }
+// Merge kernel: one workgroup per unit, launched after the split kernel.
+template <int D, int NT>
+__global__ void __launch_bounds__(NT) decode_merge_kernel(const DecodeArgs a) {
+    __shared__ float red_s[NT / kWave];
+    __shared__ float w_p[kDecodeMaxSplits], w_e[kDecodeMaxSplits];
+    const int64_t u = blockIdx.x;
+    const int len0 = a.len[u];
+    if (len0 < 0 || len0 >= a.cap || len0 + 1 > a.S * a.chunk) return;  // skipped by the split kernel too
+    merge_unit<D, NT>(a, u, len0, red_s, w_p, w_e);
 }
 
 // -------------------------------------------------------------------- host
@@ -274,19 +298,40 @@ static int rows_per_block(int32_t d, int32_t dtype) {
     return (kWave / lpr) * (kDecodeThreads / kWave);
 }
 
+// Chooses the number of splits S.  The launch is bandwidth bound and every
+// workgroup does the same amount of work, so what matters is how evenly U*S
+// workgroups spread over the compute units: the cost of a candidate is the
+// number of workgroups the busiest unit gets times the tokens (plus a fixed
+// per-workgroup overhead) each of them streams.  Candidates that leave the chip
+// with too few workgroups to hide memory latency are skipped when a better
+// filled one exists.
 DecodePlan plan_decode(int64_t U, int32_t m, int32_t d, int32_t dtype) {
     DecodePlan p;
     const int rpb = rows_per_block(d, dtype);
-    int64_t S = (kDecodeTargetBlocks + U - 1) / U;
-    const int64_t s_hi = (m + kDecodeMinChunk - 1) / kDecodeMinChunk;
-    const int64_t s_lo = (m + kDecodeMaxChunk - 1) / kDecodeMaxChunk;
-    if (S > s_hi) S = s_hi;
-    if (S < s_lo) S = s_lo;
-    if (S < 1) S = 1;
-    if (S > kDecodeMaxSplits) S = kDecodeMaxSplits;
-    int64_t chunk = (m + S - 1) / S;
+    int64_t s_hi = (m + kDecodeMinChunk - 1) / kDecodeMinChunk;
+    int64_t s_lo = (m + kDecodeMaxChunk - 1) / kDecodeMaxChunk;
+    if (s_hi > kDecodeMaxSplits) s_hi = kDecodeMaxSplits;
+    if (s_lo < 1) s_lo = 1;
+    if (s_hi < s_lo) s_hi = s_lo;
+    int64_t best_S = s_lo;
+    double best_cost = 0.0;
+    bool best_filled = false;
+    for (int64_t S = s_lo; S <= s_hi && S <= s_lo + 63; ++S) {
+        int64_t chunk = (m + S - 1) / S;
+        chunk = (chunk + rpb - 1) / rpb * rpb;
+        const int64_t blocks = U * S;
+        const int64_t per_cu = (blocks + kComputeUnits - 1) / kComputeUnits;
+        const double cost = (double)per_cu * (double)(chunk + kDecodeBlockOverheadTokens);
+        const bool filled = blocks >= kDecodeMinBlocks;
+        if (S == s_lo || (filled && !best_filled) || (filled == best_filled && cost < best_cost)) {
+            best_S = S;
+            best_cost = cost;
+            best_filled = filled;
+        }
+    }
+    int64_t chunk = (m + best_S - 1) / best_S;
     chunk = (chunk + rpb - 1) / rpb * rpb;
-    p.S = (int32_t)S;
+    p.S = (int32_t)best_S;
     p.chunk = (int32_t)chunk;
     p.lds_bytes = (size_t)(2 * chunk + (kDecodeThreads / kWave) * d) * sizeof(float);
     return p;
@@ -296,7 +341,12 @@ template <typename T, int D>
 static hipError_t launch_decode_t(const DecodeArgs& a, int64_t U, size_t lds, hipStream_t st) {
     const dim3 grid((unsigned)(U * a.S)), block(kDecodeThreads);
     hipLaunchKernelGGL((decode_kernel<T, D, kDecodeThreads>), grid, block, lds, st, a);
-    return hipGetLastError();
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess && a.S > 1) {
+        hipLaunchKernelGGL((decode_merge_kernel<D, kDecodeThreads>), dim3((unsigned)U), block, 0, st, a);
+        e = hipGetLastError();
+    }
+    return e;
 }
 
 hipError_t launch_decode(const DecodeArgs& a, int64_t U, int32_t d, int32_t dtype, size_t lds_bytes,

@@ -23,9 +23,8 @@ struct DecodeArgs {
     const float* slopes;
     float* ws_part;    // [U][S][D+4] partial outputs and softmax statistics of each split
     float* ws_e;       // [U][cap]    un-normalised score increments of each token
-    int32_t* ws_cnt;   // [U]         arrival counters, zero between calls
     int32_t* ws_err;   // [1]         skipped-unit counter
-    int32_t B, H, cap;
+    int32_t B, H, cap, layer0;
     int32_t S;         // splits of a unit's token range
     int32_t chunk;     // tokens per split
     int32_t q_pos;
@@ -67,7 +66,7 @@ struct PrefillArgs {
     const float* slopes;
     float* ws_c;        // [U][n_pad] per-row log2 normaliser
     uint32_t* ws_r;     // [U][n_pad] per-row noise key
-    int32_t B, H, cap, n, n_pad;
+    int32_t B, H, cap, layer0, n, n_pad;
     int32_t noise;
     float inv_tau;
     float scale;

@@ -80,7 +80,7 @@ __global__ void __launch_bounds__(kPrefillThreads) prefill_rowstats_kernel(const
     const int n = a.n;
     const int i0 = rb * (4 * kTile) + wv * kTile;
     if (i0 >= n) return;  // wave-uniform; this kernel has no workgroup barrier
-    const int h = (int)(u % a.H), b = (int)((u / a.H) % a.B), l = (int)(u / ((int64_t)a.H * a.B));
+    const int h = (int)(u % a.H), b = (int)((u / a.H) % a.B), l = a.layer0 + (int)(u / ((int64_t)a.H * a.B));
     const int i = i0 + n0;
     const T* Qu = (const T*)a.Q + (size_t)u * n * D;
     const T* Ku = (const T*)a.K + (size_t)u * a.cap * D;

@@ -31,7 +31,7 @@ def dev(a):
 
 def upload(oc: ko.OracleCache) -> kf.Cache:
     return kf.Cache(K=dev(oc.K), V=dev(oc.V), score=dev(oc.score), pos=dev(oc.pos), len=dev(oc.len),
-                    L=oc.L, B=oc.B, H=oc.H, d=oc.d, cap=oc.cap, dtype=oc.dtype)
+                    L=oc.L, B=oc.B, H=oc.H, d=oc.d, cap=oc.cap, dtype=oc.dtype, layer0=oc.layer0)
 
 
 def upload_into(gc: kf.Cache, oc: ko.OracleCache, kv=True):
