@@ -231,6 +231,7 @@ kf_status kf_select_evict(kf_cache* c, int32_t k, int32_t w, int32_t* kept_idx, 
     a.k = k;
     a.w = w;
     a.row_bytes = c->d * (c->dtype == KF_F32 ? 4 : 2);
+    a.idx_is_output = kept_idx ? 1 : 0;
     const hipError_t e = kf::launch_select(a, U, (hipStream_t)stream);
     if (e != hipSuccess) return fail(KF_EDEVICE, "select launch: %s", hipGetErrorString(e));
     g_err[0] = 0;

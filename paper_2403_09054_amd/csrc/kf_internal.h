@@ -52,6 +52,7 @@ struct SelectArgs {
     int32_t* idx;       // [U][k] source slot of every survivor (caller's kept_idx or workspace)
     int32_t cap, k, w;
     int32_t row_bytes;  // d * sizeof(element)
+    int32_t idx_is_output;  // idx is the caller's kept_idx (must be complete), not scratch
 };
 hipError_t launch_select(const SelectArgs& a, int64_t U, hipStream_t stream);
 

@@ -14,6 +14,10 @@
 //            precede it (lower slot wins).  Ballot/popcount prefix counts give
 //            each survivor its destination; the source slots are written to a
 //            dense index list.
+//            (A unit that is exactly one token over budget -- every decode
+//            step -- skips both: the token to evict is the candidate with the
+//            smallest score, the highest slot among equals, found by one
+//            min-reduction; see evict_one.)
 //   compact  rows are gathered front to back in tiles: a tile's sources are
 //            read into registers, the workgroup synchronises, then the tile's
 //            destinations are written.  Every source lies at or after its
@@ -24,8 +28,108 @@
 
 namespace kf {
 
-constexpr int kSelectThreads = 512;
+constexpr int kSelectThreads = 1024;
 constexpr int kSelectGroups = 4;  // row groups a thread holds in registers per tile
+constexpr int kShiftDepth = 8;    // independent 16-byte loads a lane keeps in flight while shifting
+
+// One token over budget (len = k+1, the shape of every decode step): evict the
+// candidate with the smallest score, the highest slot among equal minima (so
+// that lower slots are kept), then close the gap: rows e+1..k move down by one.
+//
+// The shift needs no synchronisation beyond one barrier.  Waves 2.. split the
+// moving rows into contiguous ranges; a lane owns one 16-byte piece of a row,
+// the two halves of a wave take K and V.  A wave walks its range upwards,
+// several rows in flight: row i+1 is loaded before row i is stored, loads
+// return in order, and the wave is the only writer of its range, so it never
+// overwrites a row it still has to read.  The one row it reads from its
+// neighbour's range (the first row above its own) is loaded before the barrier;
+// the neighbour stores only after it.  Waves 0 and 1 shift score and pos the
+// same way, 64 elements per instruction.
+template <int NT>
+__device__ __forceinline__ void evict_one(const SelectArgs& a, int64_t u, int n, bool write_idx) {
+    constexpr int NW = NT / kWave;
+    constexpr int G = kShiftDepth;
+    __shared__ unsigned long long wmin[NW];
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int k = a.k, w = a.w;
+    const int ncand = n - w;
+    float* fu = a.score + (size_t)u * a.cap;
+    int32_t* pu = a.pos + (size_t)u * a.cap;
+
+    // smallest (key, -slot): the low word holds ~slot so that the highest slot wins a tie
+    unsigned long long best = ~0ull;
+    for (int j = tid; j < ncand; j += NT) {
+        const unsigned long long pack = ((unsigned long long)float_key(fu[j]) << 32) | (uint32_t)(~(uint32_t)j);
+        best = pack < best ? pack : best;
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const unsigned long long t = __shfl_xor(best, o, kWave);
+        best = t < best ? t : best;
+    }
+    if (lane == 0) wmin[wv] = best;
+    __syncthreads();
+    best = wmin[0];
+#pragma unroll
+    for (int i = 1; i < NW; ++i) best = wmin[i] < best ? wmin[i] : best;
+    const int e = (int)(~(uint32_t)(best & 0xFFFFFFFFull));  // evicted slot, in [0, ncand)
+
+    if (write_idx) {
+        int32_t* idx = a.idx + (size_t)u * k;
+        for (int i = tid; i < k; i += NT) idx[i] = i + (i >= e ? 1 : 0);
+    }
+
+    if (wv >= 2) {
+        // ---- K and V rows
+        const int PPR = a.row_bytes >> 4;  // 16-byte pieces per row: 8, 16 or 32
+        const int RPI = 32 / PPR;          // rows per wave instruction (each half of the wave one tensor)
+        const int half = lane >> 5, rsub = (lane & 31) / PPR, piece = lane % PPR;
+        uint4* base = (uint4*)((char*)(half ? a.V : a.K) + (size_t)u * a.cap * a.row_bytes);
+        const int R = k - e;               // rows that move
+        int per = (R + (NW - 2) - 1) / (NW - 2);
+        per = (per + RPI - 1) / RPI * RPI;
+        const int r0 = e + (wv - 2) * per, r1 = min(k, r0 + per);
+        const int NI = r0 < r1 ? (r1 - r0 + RPI - 1) / RPI : 0;  // wave instructions of this range
+        // last instruction's sources: the only rows read from beyond the own range
+        const int last_i = r0 + (NI - 1) * RPI + rsub;
+        const bool has_last = NI > 0 && last_i < r1;
+        uint4 last = make_uint4(0u, 0u, 0u, 0u);
+        if (has_last) last = base[(size_t)(last_i + 1) * PPR + piece];
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        for (int ii = 0; ii < NI - 1; ii += G) {
+            uint4 regs[G];
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                regs[g] = make_uint4(0u, 0u, 0u, 0u);
+                if (ii + g < NI - 1) regs[g] = base[(size_t)(r0 + (ii + g) * RPI + rsub + 1) * PPR + piece];
+            }
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+                if (ii + g < NI - 1) base[(size_t)(r0 + (ii + g) * RPI + rsub) * PPR + piece] = regs[g];
+        }
+        if (has_last) base[(size_t)last_i * PPR + piece] = last;
+    } else {
+        // ---- score (wave 0) and pos (wave 1): one wave owns the whole range
+        uint32_t* arr = wv == 0 ? (uint32_t*)fu : (uint32_t*)pu;
+        __syncthreads();
+        for (int i0 = e; i0 < k; i0 += kWave * G) {
+            uint32_t regs[G];
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                const int i = i0 + g * kWave + lane;
+                regs[g] = 0u;
+                if (i < k) regs[g] = arr[i + 1];
+            }
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                const int i = i0 + g * kWave + lane;
+                if (i < k) arr[i] = regs[g];
+            }
+        }
+    }
+    if (tid == 0) a.len[u] = k;
+}
 
 template <int NT>
 __global__ void __launch_bounds__(NT) select_kernel(const SelectArgs a) {
@@ -43,6 +147,10 @@ __global__ void __launch_bounds__(NT) select_kernel(const SelectArgs a) {
 
     if (n <= k) {  // under budget: nothing leaves
         for (int i = tid; i < k; i += NT) idx[i] = (i < n) ? i : -1;
+        return;
+    }
+    if (n == k + 1) {  // decode shape
+        evict_one<NT>(a, u, n, a.idx_is_output != 0);
         return;
     }
     const int ncand = n - w, nkey = k - w;
@@ -152,6 +260,8 @@ __global__ void __launch_bounds__(NT) select_kernel(const SelectArgs a) {
             const int i = t0 + g * rpp + rsub;
             src[g] = (i < k) ? idx[i] : -1;
             if (src[g] >= n) src[g] = -1;  // cannot happen; never read past the unit
+            rk[g] = make_uint4(0u, 0u, 0u, 0u);
+            rv[g] = make_uint4(0u, 0u, 0u, 0u);
             if (src[g] >= 0 && src[g] != i) {
                 rk[g] = Kb[(size_t)src[g] * PPR + piece];
                 rv[g] = Vb[(size_t)src[g] * PPR + piece];
