@@ -75,9 +75,98 @@ __device__ __forceinline__ void merge_unit(const DecodeArgs& a, int64_t u, int l
     const float inv = 1.0f / sumE;
     for (int j = tid; j < m; j += NT) {
         const float prev = (j == len0) ? 0.0f : fu[j];
-        fu[j] = prev + we[j] * (w_e[j / a.chunk] * inv);
+        fu[j] = prev + we[j] * (w_e[(j == len0) ? S - 1 : j / a.chunk] * inv);  // the new token belongs to the last split
     }
     if (tid == 0) a.len[u] = m;
+}
+
+// ---- lane-group sums without LDS traffic ---------------------------------
+// A row's partial dot products sit in LPR adjacent lanes.  The data-parallel
+// primitive moves (quad permutes, half-row and row mirrors) fold 16 lanes in
+// four single-cycle adds; a 32-lane row needs one more exchange across the two
+// 16-lane rows.  Every lane of the group ends up with the group's sum.
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
+}
+template <int LPR>
+__device__ __forceinline__ float group_sum(float p) {
+    static_assert(LPR == 8 || LPR == 16 || LPR == 32, "row spans 8, 16 or 32 lanes");
+    p += dpp_move<0xB1>(p);   // quad_perm [1,0,3,2]
+    p += dpp_move<0x4E>(p);   // quad_perm [2,3,0,1]
+    p += dpp_move<0x141>(p);  // row_half_mirror: the other quad of the 8 lanes
+    if (LPR >= 16) p += dpp_move<0x140>(p);  // row_mirror: the other 8 lanes of the row
+    if (LPR >= 32)
+        p += __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, p), 0x401F));  // lane ^ 16
+    return p;
+}
+
+// ---- <q, K_row piece> for the 16 bytes a lane holds ------------------------
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+template <typename T>
+struct QueryPiece;
+template <>
+struct QueryPiece<float> {
+    float q[4];
+    __device__ __forceinline__ void load(const uint4& r) { unpack16<float>(r, q); }
+    __device__ __forceinline__ float dot(const uint4& k) const {
+        float p = __uint_as_float(k.x) * q[0];
+        p = fmaf(__uint_as_float(k.y), q[1], p);
+        p = fmaf(__uint_as_float(k.z), q[2], p);
+        p = fmaf(__uint_as_float(k.w), q[3], p);
+        return p;
+    }
+};
+template <>
+struct QueryPiece<bf16_t> {
+    uint4 q;  // eight bf16, kept packed: products of bf16 pairs are accumulated in fp32
+    __device__ __forceinline__ void load(const uint4& r) { q = r; }
+    __device__ __forceinline__ float dot(const uint4& k) const {
+        float p = 0.0f;
+        p = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, k.x), __builtin_bit_cast(bf16x2_t, q.x), p, false);
+        p = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, k.y), __builtin_bit_cast(bf16x2_t, q.y), p, false);
+        p = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, k.z), __builtin_bit_cast(bf16x2_t, q.z), p, false);
+        p = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, k.w), __builtin_bit_cast(bf16x2_t, q.w), p, false);
+        return p;
+    }
+};
+
+// Block-wide max / sum of two values at once (one pair of barriers).
+template <int NT>
+__device__ __forceinline__ void block_max2(float& x, float& y, float* red /* [2*NT/64] */) {
+    x = wave_max(x);
+    y = wave_max(y);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) {
+        red[2 * (threadIdx.x >> 6)] = x;
+        red[2 * (threadIdx.x >> 6) + 1] = y;
+    }
+    __syncthreads();
+    x = red[0];
+    y = red[1];
+#pragma unroll
+    for (int i = 1; i < NT / 64; ++i) {
+        x = fmaxf(x, red[2 * i]);
+        y = fmaxf(y, red[2 * i + 1]);
+    }
+}
+template <int NT>
+__device__ __forceinline__ void block_sum2(float& x, float& y, float* red) {
+    x = wave_sum(x);
+    y = wave_sum(y);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) {
+        red[2 * (threadIdx.x >> 6)] = x;
+        red[2 * (threadIdx.x >> 6) + 1] = y;
+    }
+    __syncthreads();
+    x = red[0];
+    y = red[1];
+#pragma unroll
+    for (int i = 1; i < NT / 64; ++i) {
+        x += red[2 * i];
+        y += red[2 * i + 1];
+    }
 }
 
 template <typename T, int D, int NT>
@@ -88,14 +177,16 @@ __global__ void __launch_bounds__(NT) decode_kernel(const DecodeArgs a) {
     constexpr int NW = NT / kWave;
     constexpr int RPB = RPW * NW;                // rows per block-wide load
     constexpr int UNR = KF_DECODE_UNROLL;        // independent loads in flight per lane
+    constexpr int TILE = RPB * UNR;              // rows per tile of the workgroup
     constexpr int PW = D + 4;                    // floats in a partial record
-    static_assert(LPR <= kWave && D <= NT, "row must fit a wave, output a block");
+    constexpr size_t ROWB = (size_t)D * sizeof(T);
+    static_assert(LPR <= 32 && D <= NT, "row must fit half a wave, output a block");
 
     extern __shared__ float smem[];
-    float* xs = smem;                // [chunk] logits, then attention weights
-    float* ys = smem + a.chunk;      // [chunk] perturbed logits / tau, then their exponentials
-    float* red_o = ys + a.chunk;     // [NW][D] per-wave output partials
-    __shared__ float red_s[NW];
+    float* xs = smem;                // [chunk+1] logits, then attention weights (+1: the new token)
+    float* ys = smem + a.chunk + 1;  // [chunk+1] perturbed logits / tau, then their exponentials
+    float* red_o = ys + a.chunk + 1; // [NW][D] per-wave output partials
+    __shared__ float red_s[2 * NW];
 
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int sub = lane / LPR, cl = lane % LPR;
@@ -106,7 +197,7 @@ __global__ void __launch_bounds__(NT) decode_kernel(const DecodeArgs a) {
 
     const int len0 = a.len[u];
     const int m = len0 + 1;
-    if (len0 < 0 || len0 >= a.cap || m > S * a.chunk) {
+    if (len0 < 0 || len0 >= a.cap || len0 > S * a.chunk) {
         // no room for the new token (or a launch shaped for fewer tokens):
         // leave the unit alone and report it
         if (s == 0) {
@@ -115,75 +206,96 @@ __global__ void __launch_bounds__(NT) decode_kernel(const DecodeArgs a) {
         }
         return;
     }
+    // The split streams cache rows [j0, j1).  The new token never comes from the
+    // cache: the last split takes its key and value from k_new / v_new and keeps
+    // its logit in the LDS slot behind its own rows.
     const int j0 = s * a.chunk;
-    const int j1 = min(m, j0 + a.chunk);
-    const int cnt = max(j1 - j0, 0);
+    const int j1 = min(len0, j0 + a.chunk);
+    const int cnt_c = max(j1 - j0, 0);
+    const bool owner = (s == S - 1);
+    const int cnt = cnt_c + (owner ? 1 : 0);
 
-    const T* Ku = (const T*)a.K + (size_t)u * a.cap * D;
-    const T* Vu = (const T*)a.V + (size_t)u * a.cap * D;
+    const char* Ku = (const char*)a.K + (size_t)u * a.cap * ROWB;
+    const char* Vu = (const char*)a.V + (size_t)u * a.cap * ROWB;
     const T* qu = (const T*)a.q + (size_t)u * D;
-    const T* knew = (const T*)a.k_new + (size_t)u * D;
-    const T* vnew = (const T*)a.v_new + (size_t)u * D;
+    const char* knew = (const char*)a.k_new + (size_t)u * ROWB;
+    const char* vnew = (const char*)a.v_new + (size_t)u * ROWB;
     float* fu = a.score + (size_t)u * a.cap;
     int32_t* pu = a.pos + (size_t)u * a.cap;
 
-    // ---- append: the split that owns slot len0 stores the new row.  The row is
-    // not read back from the cache in this launch (the streams below take it
-    // from k_new / v_new), so no ordering is needed.
-    if (len0 >= j0 && len0 < j1) {
-        if (wv == 0 && lane < LPR)
-            ((uint4*)((T*)a.K + ((size_t)u * a.cap + len0) * D))[lane] = ((const uint4*)knew)[lane];
-        if (wv == 1 && lane < LPR)
-            ((uint4*)((T*)a.V + ((size_t)u * a.cap + len0) * D))[lane] = ((const uint4*)vnew)[lane];
+    // ---- append: the last split stores the new row (nobody reads it back in this launch)
+    if (owner) {
+        if (wv == 0 && lane < LPR) ((uint4*)(a.K))[((size_t)u * a.cap + len0) * LPR + lane] = ((const uint4*)knew)[lane];
+        if (wv == 1 && lane < LPR) ((uint4*)(a.V))[((size_t)u * a.cap + len0) * LPR + lane] = ((const uint4*)vnew)[lane];
         if (tid == 2 * kWave) pu[len0] = a.q_pos;
     }
 
-    // ---- query slice of this lane
-    float qv[EPV];
-    {
-        const uint4 r = ((const uint4*)qu)[cl];
-        unpack16<T>(r, qv);
-    }
+    QueryPiece<T> qp;
+    qp.load(((const uint4*)qu)[cl]);
 
-    // Loads one tile (UNR block-wide loads) of this lane's 16-byte pieces; the
-    // slot of the new token is served from the call's own k_new / v_new row.
-    auto load_tile = [&](const T* rows, const T* fresh, int base, uint4(&raw)[UNR]) {
+    // This lane's piece of row (base + i*RPB + sub) sits at lane_off + base*ROWB + i*RPB*ROWB.
+    const size_t lane_off = (size_t)sub * ROWB + (size_t)cl * 16;
+    const int base0 = j0 + wv * RPW;
+    // a tile starting at `base` is "plain" (no bounds checks) if all its rows are below j1
+    auto plain = [&](int base) { return base + (UNR - 1) * RPB + RPW <= j1; };
+    auto load_plain = [&](const char* rows, int base, uint4(&raw)[UNR]) {
+        const char* p = rows + (size_t)base * ROWB + lane_off;
+#pragma unroll
+        for (int i = 0; i < UNR; ++i) raw[i] = *(const uint4*)(p + (size_t)i * RPB * ROWB);
+    };
+    auto load_edge = [&](const char* rows, int base, uint4(&raw)[UNR]) {
 #pragma unroll
         for (int i = 0; i < UNR; ++i) {
             const int j = base + i * RPB + sub;
-            if (j < j1) {
-                const T* row = (j == len0) ? fresh : rows + (size_t)j * D;
-                raw[i] = ((const uint4*)row)[cl];
-            } else {
-                raw[i] = make_uint4(0u, 0u, 0u, 0u);
-            }
+            raw[i] = make_uint4(0u, 0u, 0u, 0u);
+            if (j < j1) raw[i] = *(const uint4*)(rows + (size_t)j * ROWB + (size_t)cl * 16);
         }
     };
-    constexpr int TILE = RPB * UNR;
-    const int base0 = j0 + wv * RPW;
+    auto load_tile = [&](const char* rows, int base, uint4(&raw)[UNR]) {
+        if (plain(base)) load_plain(rows, base, raw);
+        else load_edge(rows, base, raw);
+    };
 
     // ---- phase 1: stream K (next tile in flight while this one is reduced), logits into LDS
     uint4 cur[UNR], nxt[UNR];
-    if (base0 < j1) load_tile(Ku, knew, base0, cur);
-    for (int base = base0; base < j1; base += TILE) {
-        if (base + TILE < j1) load_tile(Ku, knew, base + TILE, nxt);
+    auto logits_of = [&](int base) {
+        float p[UNR];
+#pragma unroll
+        for (int i = 0; i < UNR; ++i) p[i] = qp.dot(cur[i]);
+#pragma unroll
+        for (int i = 0; i < UNR; ++i) p[i] = group_sum<LPR>(p[i]);
 #pragma unroll
         for (int i = 0; i < UNR; ++i) {
-            float kvals[EPV];
-            unpack16<T>(cur[i], kvals);
-            float p = 0.0f;
-#pragma unroll
-            for (int e = 0; e < EPV; ++e) p = fmaf(kvals[e], qv[e], p);
-#pragma unroll
-            for (int o = LPR / 2; o > 0; o >>= 1) p += __shfl_xor(p, o, kWave);
             const int j = base + i * RPB + sub;
-            if (cl == 0 && j < j1) xs[j - j0] = p * a.scale;
+            if (cl == 0 && j < j1) xs[j - j0] = p[i] * a.scale;
         }
+    };
+    {
+        int base = base0;
+        if (base < j1) load_tile(Ku, base, cur);
+        // steady state: the next tile needs no bounds checks, so the loop body is
+        // branch-free and only the older tile's loads are waited for
+        while (plain(base + TILE)) {
+            load_plain(Ku, base + TILE, nxt);
+            logits_of(base);
 #pragma unroll
-        for (int i = 0; i < UNR; ++i) cur[i] = nxt[i];
+            for (int i = 0; i < UNR; ++i) cur[i] = nxt[i];
+            base += TILE;
+        }
+        while (base < j1) {  // the last one or two tiles of the split
+            if (base + TILE < j1) load_edge(Ku, base + TILE, nxt);
+            logits_of(base);
+#pragma unroll
+            for (int i = 0; i < UNR; ++i) cur[i] = nxt[i];
+            base += TILE;
+        }
+    }
+    if (owner && wv == 0) {  // the new token's own logit (distance 0: no position bias)
+        const float p = group_sum<LPR>(qp.dot(((const uint4*)knew)[cl]));
+        if (lane == 0) xs[cnt_c] = p * a.scale;
     }
     // first V tile: in flight while the softmax statistics are formed
-    if (base0 < j1) load_tile(Vu, vnew, base0, cur);
+    if (base0 < j1) load_tile(Vu, base0, cur);
     __syncthreads();
 
     // ---- phase 1.5: position bias, logit adjustment, the two softmaxes' statistics
@@ -193,8 +305,7 @@ __global__ void __launch_bounds__(NT) decode_kernel(const DecodeArgs a) {
         rkey = row_key(unit_key(a.seeds[b], (uint32_t)l, (uint32_t)h), (uint32_t)a.q_pos);
     float mx = -INFINITY, my = -INFINITY;
     for (int t = tid; t < cnt; t += NT) {
-        const int j = j0 + t;
-        const int pj = (j == len0) ? a.q_pos : pu[j];
+        const int pj = (t == cnt_c) ? a.q_pos : pu[j0 + t];  // t == cnt_c: the new token
         const float x = xs[t] - slope * (float)(a.q_pos - pj);
         const float y = (x + zeta_of(a.noise, rkey, (uint32_t)pj)) * a.inv_tau;
         xs[t] = x;
@@ -202,8 +313,7 @@ __global__ void __launch_bounds__(NT) decode_kernel(const DecodeArgs a) {
         mx = fmaxf(mx, x);
         my = fmaxf(my, y);
     }
-    mx = block_max<NT>(mx, red_s);
-    my = block_max<NT>(my, red_s);
+    block_max2<NT>(mx, my, red_s);
     float sp = 0.0f, se = 0.0f;
     for (int t = tid; t < cnt; t += NT) {
         const float p = expf(xs[t] - mx);
@@ -213,38 +323,62 @@ __global__ void __launch_bounds__(NT) decode_kernel(const DecodeArgs a) {
         sp += p;
         se += e;
     }
-    sp = block_sum<NT>(sp, red_s);
-    se = block_sum<NT>(se, red_s);
+    block_sum2<NT>(sp, se, red_s);  // its barriers also publish the attention weights in xs
     if (S == 1) {
         // the whole unit is here: accumulate the normalised score increment
         const float inv = 1.0f / se;
         for (int t = tid; t < cnt; t += NT) {
-            const float prev = (t == len0) ? 0.0f : fu[t];
-            fu[t] = prev + ys[t] * inv;
+            const int slot = (t == cnt_c) ? len0 : j0 + t;
+            const float prev = (t == cnt_c) ? 0.0f : fu[slot];
+            fu[slot] = prev + ys[t] * inv;
         }
     } else {
         float* we = a.ws_e + (size_t)u * a.cap;
-        for (int t = tid; t < cnt; t += NT) we[j0 + t] = ys[t];
+        for (int t = tid; t < cnt; t += NT) we[(t == cnt_c) ? len0 : j0 + t] = ys[t];
     }
-    __syncthreads();  // attention weights of all threads are in xs
 
     // ---- phase 2: stream V, weighted sum
     float acc[EPV];
 #pragma unroll
     for (int e = 0; e < EPV; ++e) acc[e] = 0.0f;
-    for (int base = base0; base < j1; base += TILE) {
-        if (base + TILE < j1) load_tile(Vu, vnew, base + TILE, nxt);
+    auto weigh = [&](int base) {
+        float p[UNR];
 #pragma unroll
         for (int i = 0; i < UNR; ++i) {
             const int j = base + i * RPB + sub;
-            const float p = (j < j1) ? xs[j - j0] : 0.0f;
+            p[i] = (j < j1) ? xs[j - j0] : 0.0f;
+        }
+#pragma unroll
+        for (int i = 0; i < UNR; ++i) {
             float vvals[EPV];
             unpack16<T>(cur[i], vvals);
 #pragma unroll
-            for (int e = 0; e < EPV; ++e) acc[e] = fmaf(p, vvals[e], acc[e]);
+            for (int e = 0; e < EPV; ++e) acc[e] = fmaf(p[i], vvals[e], acc[e]);
         }
+    };
+    {
+        int base = base0;
+        while (plain(base + TILE)) {
+            load_plain(Vu, base + TILE, nxt);
+            weigh(base);
 #pragma unroll
-        for (int i = 0; i < UNR; ++i) cur[i] = nxt[i];
+            for (int i = 0; i < UNR; ++i) cur[i] = nxt[i];
+            base += TILE;
+        }
+        while (base < j1) {
+            if (base + TILE < j1) load_edge(Vu, base + TILE, nxt);
+            weigh(base);
+#pragma unroll
+            for (int i = 0; i < UNR; ++i) cur[i] = nxt[i];
+            base += TILE;
+        }
+    }
+    if (owner && wv == 0 && sub == 0) {  // the new token's value row
+        float vvals[EPV];
+        unpack16<T>(((const uint4*)vnew)[cl], vvals);
+        const float p = xs[cnt_c];
+#pragma unroll
+        for (int e = 0; e < EPV; ++e) acc[e] = fmaf(p, vvals[e], acc[e]);
     }
     // rows of one wave-wide load live in different lane groups: fold them
 #pragma unroll
@@ -287,7 +421,7 @@ __global__ void __launch_bounds__(NT) decode_merge_kernel(const DecodeArgs a) {
     __shared__ float w_p[kDecodeMaxSplits], w_e[kDecodeMaxSplits];
     const int64_t u = blockIdx.x;
     const int len0 = a.len[u];
-    if (len0 < 0 || len0 >= a.cap || len0 + 1 > a.S * a.chunk) return;  // skipped by the split kernel too
+    if (len0 < 0 || len0 >= a.cap || len0 > a.S * a.chunk) return;  // skipped by the split kernel too
     merge_unit<D, NT>(a, u, len0, red_s, w_p, w_e);
 }
 
@@ -308,6 +442,7 @@ static int rows_per_block(int32_t d, int32_t dtype) {
 DecodePlan plan_decode(int64_t U, int32_t m, int32_t d, int32_t dtype) {
     DecodePlan p;
     const int rpb = rows_per_block(d, dtype);
+    const int64_t rows = m > 1 ? m - 1 : 1;  // cache rows; the new token rides with the last split
     int64_t s_hi = (m + kDecodeMinChunk - 1) / kDecodeMinChunk;
     int64_t s_lo = (m + kDecodeMaxChunk - 1) / kDecodeMaxChunk;
     if (s_hi > kDecodeMaxSplits) s_hi = kDecodeMaxSplits;
@@ -317,7 +452,7 @@ DecodePlan plan_decode(int64_t U, int32_t m, int32_t d, int32_t dtype) {
     double best_cost = 0.0;
     bool best_filled = false;
     for (int64_t S = s_lo; S <= s_hi && S <= s_lo + 63; ++S) {
-        int64_t chunk = (m + S - 1) / S;
+        int64_t chunk = (rows + S - 1) / S;
         chunk = (chunk + rpb - 1) / rpb * rpb;
         const int64_t blocks = U * S;
         const int64_t per_cu = (blocks + kComputeUnits - 1) / kComputeUnits;
@@ -329,11 +464,11 @@ DecodePlan plan_decode(int64_t U, int32_t m, int32_t d, int32_t dtype) {
             best_filled = filled;
         }
     }
-    int64_t chunk = (m + best_S - 1) / best_S;
+    int64_t chunk = (rows + best_S - 1) / best_S;
     chunk = (chunk + rpb - 1) / rpb * rpb;
     p.S = (int32_t)best_S;
     p.chunk = (int32_t)chunk;
-    p.lds_bytes = (size_t)(2 * chunk + (kDecodeThreads / kWave) * d) * sizeof(float);
+    p.lds_bytes = (size_t)(2 * (chunk + 1) + (kDecodeThreads / kWave) * d) * sizeof(float);
     return p;
 }
 
