@@ -38,6 +38,9 @@ def parse():
     ap.add_argument("--no-events", action="store_true",
                     help="time the steps without per-kernel events (roofline is then null)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU work budget of the oracle leg")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a plain device copy of a known size (1 GiB, 10 times): the reference the "
+                         "FETCH_SIZE / WRITE_SIZE counters are scaled by")
     return ap.parse_args()
 
 
@@ -62,6 +65,14 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")   # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes": src.numel() * 4, "launches": 10}))
+        return
     wl = kw.CONFIGS[args.config]
     K_steps, W_steps = args.steps, args.warmup
     dt = kf.F32 if wl.dtype == "f32" else kf.BF16
@@ -158,7 +169,8 @@ def main():
         sel_ms = sum(e[1].elapsed_time(e[2]) for e in evs) / K_steps
         nbytes = decode_bytes(wl, m)
         achieved = nbytes / (dec_ms * 1e-3) / 1e9
-        roofline = {"bound": "hbm", "kernel": "decode_kernel", "achieved": round(achieved, 1),
+        roofline = {"bound": "hbm", "kernel": "kf_decode_step = decode_kernel + decode_merge_kernel",
+                    "achieved": round(achieved, 1),
                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                     "traffic": None, "bytes_per_launch": nbytes, "avg_launch_us": round(dec_ms * 1e3, 2)}
         # bytes the in-place, order-preserving compaction really moves: every row behind the
@@ -184,7 +196,9 @@ def main():
                        "frac": round(sel_gbs / HBM_PEAK_GBS, 4)}
         traffic_file = os.path.join(ROOT, "profiles", "traffic_%s.json" % wl.name)
         if os.path.exists(traffic_file):
-            roofline["traffic"] = json.load(open(traffic_file)).get("decode_kernel_bytes_per_launch")
+            tj = json.load(open(traffic_file))
+            roofline["traffic"] = tj.get("decode_kernel_bytes_per_launch", 0) + tj.get(
+                "decode_merge_kernel_bytes_per_launch", 0)
 
     # prompt-phase scoring: dense causal QK^T twice (row statistics, column sums)
     prefill_flops = wl.units * 2 * (2.0 * wl.d * wl.n * (wl.n + 1) / 2)
