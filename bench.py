@@ -84,31 +84,42 @@ def main():
     # ---------------- state: prompt scoring + first eviction, layer by layer ----------------
     cache = kf.Cache.allocate(wl.L, wl.B, wl.H, wl.d, wl.k + 1, dt)
     ws = kf.new_workspace(cache)
-    stage = kf.Cache.allocate(1, wl.B, wl.H, wl.d, wl.n, dt)     # one layer's prompt-sized cache
+    # prompt-sized staging cache: as many layers per call as fit in ~12 GB (Q + K + V)
+    layer_bytes = 3 * wl.B * wl.H * wl.n * wl.d * wl.elem_bytes
+    Ls = max(1, min(wl.L, int(12e9 // layer_bytes)))
+    stage = kf.Cache.allocate(Ls, wl.B, wl.H, wl.d, wl.n, dt)
+    Qs = torch.empty((Ls, wl.B, wl.H, wl.n, wl.d), dtype=wl.torch_dtype, device="cuda")
     ws_stage = kf.new_workspace(stage, wl.n)
     tau0 = kf.kf_tau(0, wl.T, wl.tau_init, wl.tau_end)
     prefill_ms = 0.0
     first_select_ms = 0.0
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
-    for l in range(wl.L):
-        Q, K, V = kw.prompt_layer(wl, l, device="cuda")
-        stage.K[0].copy_(K)
-        stage.V[0].copy_(V)
-        stage.layer0 = l   # the staging cache plays layer l (noise key)
+    for l0 in range(0, wl.L, Ls):
+        nl = min(Ls, wl.L - l0)
+        for i in range(nl):
+            Q, K, V = kw.prompt_layer(wl, l0 + i, device="cuda")
+            Qs[i].copy_(Q)
+            stage.K[i].copy_(K)
+            stage.V[i].copy_(V)
+            del Q, K, V
+        sub = stage if nl == Ls else kf.Cache(K=stage.K[:nl], V=stage.V[:nl], score=stage.score[:nl],
+                                              pos=stage.pos[:nl], len=stage.len[:nl], L=nl, B=wl.B, H=wl.H,
+                                              d=wl.d, cap=wl.n, dtype=dt)
+        sub.layer0 = l0   # the staging cache plays layers l0 .. l0+nl-1 (noise key)
         ev[0].record()
-        kf.kf_prefill_score(stage, Q.contiguous(), wl.n, tau0, wl.scale, noise, seeds, slopes, ws_stage)
+        kf.kf_prefill_score(sub, Qs[:nl], wl.n, tau0, wl.scale, noise, seeds, slopes, ws_stage)
         ev[1].record()
-        kf.kf_select_evict(stage, wl.k, wl.w, None, ws_stage)
+        kf.kf_select_evict(sub, wl.k, wl.w, None, ws_stage)
         ev[2].record()
         torch.cuda.synchronize()
         prefill_ms += ev[0].elapsed_time(ev[1])
         first_select_ms += ev[1].elapsed_time(ev[2])
-        cache.K[l, :, :, : wl.k].copy_(stage.K[0, :, :, : wl.k])
-        cache.V[l, :, :, : wl.k].copy_(stage.V[0, :, :, : wl.k])
-        cache.score[l, :, :, : wl.k].copy_(stage.score[0, :, :, : wl.k])
-        cache.pos[l, :, :, : wl.k].copy_(stage.pos[0, :, :, : wl.k])
-        cache.len[l].copy_(stage.len[0])
-        del Q, K, V
+        cache.K[l0:l0 + nl, :, :, : wl.k].copy_(stage.K[:nl, :, :, : wl.k])
+        cache.V[l0:l0 + nl, :, :, : wl.k].copy_(stage.V[:nl, :, :, : wl.k])
+        cache.score[l0:l0 + nl, :, :, : wl.k].copy_(stage.score[:nl, :, :, : wl.k])
+        cache.pos[l0:l0 + nl, :, :, : wl.k].copy_(stage.pos[:nl, :, :, : wl.k])
+        cache.len[l0:l0 + nl].copy_(stage.len[:nl])
+    del Qs
     del stage, ws_stage
     torch.cuda.empty_cache()
     assert int(cache.len.min()) == wl.k and int(cache.len.max()) == wl.k
@@ -202,7 +213,7 @@ def main():
 
     # prompt-phase scoring: dense causal QK^T twice (row statistics, column sums)
     prefill_flops = wl.units * 2 * (2.0 * wl.d * wl.n * (wl.n + 1) / 2)
-    prefill = {"ms_total": round(prefill_ms, 3), "tflops": round(prefill_flops / (prefill_ms * 1e-3) / 1e12, 2),
+    prefill = {"layers_per_call": Ls, "ms_total": round(prefill_ms, 3), "tflops": round(prefill_flops / (prefill_ms * 1e-3) / 1e12, 2),
                "logits_per_s": round(wl.units * wl.n * (wl.n + 1) / (prefill_ms * 1e-3), 0),
                "first_select_ms_total": round(first_select_ms, 3)}
 

@@ -57,8 +57,9 @@ __device__ __forceinline__ void merge_unit(const DecodeArgs& a, int64_t u, int l
     }
     const float Mx = block_max<NT>(pmx, red_s);
     const float My = block_max<NT>(pmy, red_s);
-    const float wp = (psp > 0.0f) ? expf(pmx - Mx) : 0.0f;  // empty splits weigh nothing
-    const float we_ = (pse > 0.0f) ? expf(pmy - My) : 0.0f;
+    // statistics are kept in the base-2 domain (logits times log2 e)
+    const float wp = (psp > 0.0f) ? hw_exp2(pmx - Mx) : 0.0f;  // empty splits weigh nothing
+    const float we_ = (pse > 0.0f) ? hw_exp2(pmy - My) : 0.0f;
     const float sumP = block_sum<NT>(wp * psp, red_s);
     const float sumE = block_sum<NT>(we_ * pse, red_s);
     if (tid < S) {
@@ -306,8 +307,9 @@ __global__ void __launch_bounds__(NT) decode_kernel(const DecodeArgs a) {
     float mx = -INFINITY, my = -INFINITY;
     for (int t = tid; t < cnt; t += NT) {
         const int pj = (t == cnt_c) ? a.q_pos : pu[j0 + t];  // t == cnt_c: the new token
-        const float x = xs[t] - slope * (float)(a.q_pos - pj);
-        const float y = (x + zeta_of(a.noise, rkey, (uint32_t)pj)) * a.inv_tau;
+        // base-2 domain: x2 = log2(e)*x, y2 = log2(e)*(x + zeta)/tau
+        const float x = (xs[t] - slope * (float)(a.q_pos - pj)) * kLog2e;
+        const float y = (x + zeta_log2e(a.noise, rkey, (uint32_t)pj)) * a.inv_tau;
         xs[t] = x;
         ys[t] = y;
         mx = fmaxf(mx, x);
@@ -316,8 +318,8 @@ __global__ void __launch_bounds__(NT) decode_kernel(const DecodeArgs a) {
     block_max2<NT>(mx, my, red_s);
     float sp = 0.0f, se = 0.0f;
     for (int t = tid; t < cnt; t += NT) {
-        const float p = expf(xs[t] - mx);
-        const float e = expf(ys[t] - my);
+        const float p = hw_exp2(xs[t] - mx);
+        const float e = hw_exp2(ys[t] - my);
         xs[t] = p;
         ys[t] = e;
         sp += p;

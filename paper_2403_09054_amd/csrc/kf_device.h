@@ -97,34 +97,41 @@ __host__ __device__ __forceinline__ uint32_t logit_bits(uint32_t rkey, uint32_t 
     return mix32(rkey ^ (k_pos * kKposMul));
 }
 
-// -ln(u) for u = (2*(bits>>9)+1)/2^24, accurate to a few ulp over the whole
-// range: near u = 1 the complement 1-u is formed exactly and fed to log1p.
-__device__ __forceinline__ float neg_log_uniform(uint32_t bits) {
-    const uint32_t m = bits >> 9;  // 23 bits
-    if (m >= (1u << 22)) {
-        const float v = (float)(0x1000000u - 2u * m - 1u) * 0x1p-24f;  // 1-u, exact
-        return -log1pf(-v);
-    }
-    const float u = (float)(2u * m + 1u) * 0x1p-24f;  // exact
-    return -logf(u);
-}
+// ---------------------------------------------------------------- base-2 transcendentals
+// The hardware log2 / exp2 (v_log_f32, v_exp_f32).  Measured on gfx950 over all
+// 2^23 uniforms the generator can produce: -log2(u) is within 1.2e-7 relative,
+// also where u is next to 1; exp2 is within 8.3e-8 relative on [-40, 20].
+__device__ __forceinline__ float hw_log2(float x) { return __builtin_amdgcn_logf(x); }
+__device__ __forceinline__ float hw_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+constexpr float kLog2e = 1.44269504088896340736f;
+constexpr float kLn2 = 0.69314718055994530942f;
+constexpr float kLog2Ln2 = -0.52876637294489779f;  // log2(ln 2)
 
 __device__ __forceinline__ float uniform_of(uint32_t bits) {
-    return (float)(2u * (bits >> 9) + 1u) * 0x1p-24f;
+    return (float)(2u * (bits >> 9) + 1u) * 0x1p-24f;  // exact: odd multiples of 2^-24 in (0,1)
 }
 
-// Logit adjustment zeta (Eq. 4) for one (query, key) pair.
-__device__ __forceinline__ float zeta_of(int noise, uint32_t rkey, uint32_t k_pos) {
+// t = -log2(u) > 0.
+__device__ __forceinline__ float neg_log2_uniform(uint32_t bits) { return -hw_log2(uniform_of(bits)); }
+
+// Standard Gumbel variate (inverse CDF of Eq. 7) times log2(e):
+//   zeta = -ln(-ln u), -ln u = t*ln2  =>  log2(e)*zeta = -(log2(t) + log2(ln 2)).
+__device__ __forceinline__ float gumbel_log2e(uint32_t bits) {
+    return -(hw_log2(neg_log2_uniform(bits)) + kLog2Ln2);
+}
+
+// Logit adjustment zeta (Eq. 4) for one (query, key) pair, times log2(e).
+__device__ __forceinline__ float zeta_log2e(int noise, uint32_t rkey, uint32_t k_pos) {
     switch (noise) {
-        case kNoiseGumbel:  // inverse CDF of Eq. 7
-            return -logf(neg_log_uniform(logit_bits(rkey, k_pos)));
+        case kNoiseGumbel:
+            return gumbel_log2e(logit_bits(rkey, k_pos));
         case kNoiseGaussian: {  // Eq. 5 via Box-Muller on two draws
-            const float l1 = neg_log_uniform(logit_bits(rkey, k_pos));
+            const float l1 = neg_log2_uniform(logit_bits(rkey, k_pos)) * kLn2;  // -ln u1
             const float u2 = uniform_of(logit_bits(rkey, k_pos ^ 0x80000000u));
-            return kAdjMean + kAdjStd * (sqrtf(2.0f * l1) * cospif(2.0f * u2));
+            return (kAdjMean + kAdjStd * (sqrtf(2.0f * l1) * cospif(2.0f * u2))) * kLog2e;
         }
         case kNoiseConstant:
-            return kAdjMean;
+            return kAdjMean * kLog2e;
         default:
             return 0.0f;
     }

@@ -27,7 +27,6 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int kPrefillThreads = 256;  // 4 waves, 32 queries (pass 1) or keys (pass 2) each
 constexpr int kTile = 32;
-constexpr float kLog2e = 1.44269504088896340736f;
 
 // One "group" = the 16 bytes a lane loads from a row: it feeds one bf16 MFMA
 // (K = 16: 8 elements from each half of the wave) or four fp32 MFMAs (K = 2).
@@ -57,15 +56,24 @@ struct Mma<float> {
 // (the column is lane % 32).
 __device__ __forceinline__ int acc_row(int r, int half) { return (r >> 2) * 8 + half * 4 + (r & 3); }
 
-// y2 = log2(e) * (x + zeta)/tau for one logit.
-__device__ __forceinline__ float tempered_logit2(int noise, float x, uint32_t rkey, uint32_t k_pos,
-                                                 float c1, float inv_tau) {
-    if (noise == kNoiseGumbel) {
-        // zeta = -ln(L), L = -ln(u):  log2(e)*zeta/tau = -log2(L)/tau
-        const float L = neg_log_uniform(logit_bits(rkey, k_pos));
-        return fmaf(x, c1, -inv_tau * log2f(L));
-    }
-    return (x + zeta_of(noise, rkey, k_pos)) * c1;
+// y2 = log2(e) * (x + zeta)/tau for one logit, x = scale*acc - slope*dist.
+// Gumbel (the method's adjustment) is the fast path: one hash, two hardware
+// logarithms; zeta*log2(e) = -(log2(t) + log2(ln 2)) with t = -log2(u).
+struct LogitParams {
+    float sc1;      // scale * log2(e) / tau
+    float slope1;   // slope * log2(e) / tau
+    float inv_tau;
+    float gz;       // -log2(ln 2) / tau : the constant part of the Gumbel term
+    float c1;       // log2(e) / tau
+    int noise;
+};
+__device__ __forceinline__ float logit2_gumbel(const LogitParams& lp, float acc, float dist, uint32_t hash_in) {
+    const float l2t = hw_log2(neg_log2_uniform(mix32(hash_in)));
+    return fmaf(acc, lp.sc1, fmaf(dist, -lp.slope1, fmaf(l2t, -lp.inv_tau, lp.gz)));
+}
+__device__ __forceinline__ float logit2_other(const LogitParams& lp, float acc, float dist, uint32_t rkey,
+                                              uint32_t k_pos) {
+    return fmaf(acc, lp.sc1, fmaf(dist, -lp.slope1, zeta_log2e(lp.noise, rkey, k_pos) * lp.inv_tau));
 }
 
 // ------------------------------------------------------------------ pass 1
@@ -91,10 +99,18 @@ __global__ void __launch_bounds__(kPrefillThreads) prefill_rowstats_kernel(const
 #pragma unroll
         for (int g = 0; g < NG; ++g) bq[g] = *(const uint4*)(row + g * 2 * EPV);
     }
-    const float slope = a.slopes ? a.slopes[h] : 0.0f;
     const bool rnd = (a.noise == kNoiseGumbel || a.noise == kNoiseGaussian);
     const uint32_t rkey = rnd ? row_key(unit_key(a.seeds[b], (uint32_t)l, (uint32_t)h), (uint32_t)i) : 0u;
-    const float c1 = a.inv_tau * kLog2e;
+    LogitParams lp;
+    lp.c1 = a.inv_tau * kLog2e;
+    lp.sc1 = a.scale * lp.c1;
+    lp.slope1 = (a.slopes ? a.slopes[h] : 0.0f) * lp.c1;
+    lp.inv_tau = a.inv_tau;
+    lp.gz = -kLog2Ln2 * a.inv_tau;
+    lp.noise = a.noise;
+    // key position of accumulator register r is jb + half*4 + (r>>2)*8 + (r&3); its hash input
+    // is rkey ^ (k_pos * kKposMul): the lane part of the product is formed once
+    const uint32_t kmul_lane = (uint32_t)(half * 4) * kKposMul;
 
     float M = -INFINITY, Ssum = 0.0f;
     const int jt_end = min(i0 + kTile - 1, n - 1) / kTile;
@@ -116,31 +132,48 @@ __global__ void __launch_bounds__(kPrefillThreads) prefill_rowstats_kernel(const
             for (int g = 0; g < NG; ++g) ak[g] = *(const uint4*)(row + g * 2 * EPV);
         }
         const int jb = jt * kTile;
+        const int jl = jb + half * 4;                       // first key of this lane in the tile
+        const uint32_t kmul = (uint32_t)jb * kKposMul + kmul_lane;
+        const float dist0 = (float)(i - jl);
         float y2[16];
-        float tmax = -INFINITY;
+        if (a.noise == kNoiseGumbel) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int j = jb + acc_row(r, half);
-            const float x = acc[r] * a.scale - slope * (float)(i - j);
-            const float y = tempered_logit2(a.noise, x, rkey, (uint32_t)j, c1, a.inv_tau);
-            y2[r] = (j <= i) ? y : -INFINITY;  // causal
-            tmax = fmaxf(tmax, y2[r]);
+            for (int r = 0; r < 16; ++r) {
+                const int ro = (r >> 2) * 8 + (r & 3);
+                y2[r] = logit2_gumbel(lp, acc[r], dist0 - (float)ro, rkey ^ (kmul + (uint32_t)ro * kKposMul));
+            }
+        } else {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int ro = (r >> 2) * 8 + (r & 3);
+                y2[r] = logit2_other(lp, acc[r], dist0 - (float)ro, rkey, (uint32_t)(jl + ro));
+            }
         }
+        if (jb + kTile - 1 > i0) {  // the tile crosses the diagonal for some lane: causal mask
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int ro = (r >> 2) * 8 + (r & 3);
+                y2[r] = (jl + ro <= i) ? y2[r] : -INFINITY;
+            }
+        }
+        float tmax = y2[0];
+#pragma unroll
+        for (int r = 1; r < 16; ++r) tmax = fmaxf(tmax, y2[r]);
         const float Mn = fmaxf(M, tmax);
         if (Mn > -INFINITY) {
             float ssum = 0.0f;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) ssum += exp2f(y2[r] - Mn);
-            Ssum = Ssum * exp2f(M - Mn) + ssum;
+            for (int r = 0; r < 16; ++r) ssum += hw_exp2(y2[r] - Mn);
+            Ssum = Ssum * hw_exp2(M - Mn) + ssum;
             M = Mn;
         }
     }
     // the two halves of the wave hold disjoint key subsets of the same query
     const float M2 = __shfl_xor(M, 32, kWave), S2 = __shfl_xor(Ssum, 32, kWave);
     const float Mt = fmaxf(M, M2);
-    const float St = (M > -INFINITY ? Ssum * exp2f(M - Mt) : 0.0f) + (M2 > -INFINITY ? S2 * exp2f(M2 - Mt) : 0.0f);
+    const float St = (M > -INFINITY ? Ssum * hw_exp2(M - Mt) : 0.0f) + (M2 > -INFINITY ? S2 * hw_exp2(M2 - Mt) : 0.0f);
     if (half == 0 && i < n) {
-        a.ws_c[(size_t)u * a.n_pad + i] = Mt + log2f(St);
+        a.ws_c[(size_t)u * a.n_pad + i] = Mt + hw_log2(St);
         a.ws_r[(size_t)u * a.n_pad + i] = rkey;
     }
 }
@@ -169,8 +202,14 @@ __global__ void __launch_bounds__(kPrefillThreads) prefill_colsum_kernel(const P
 #pragma unroll
         for (int g = 0; g < NG; ++g) bk[g] = *(const uint4*)(row + g * 2 * EPV);
     }
-    const float slope = a.slopes ? a.slopes[h] : 0.0f;
-    const float c1 = a.inv_tau * kLog2e;
+    LogitParams lp;
+    lp.c1 = a.inv_tau * kLog2e;
+    lp.sc1 = a.scale * lp.c1;
+    lp.slope1 = (a.slopes ? a.slopes[h] : 0.0f) * lp.c1;
+    lp.inv_tau = a.inv_tau;
+    lp.gz = -kLog2Ln2 * a.inv_tau;
+    lp.noise = a.noise;
+    const uint32_t kmul = (uint32_t)j * kKposMul;  // this lane's key in every hash
     const float* wc = a.ws_c + (size_t)u * a.n_pad;
     const uint32_t* wr = a.ws_r + (size_t)u * a.n_pad;
 
@@ -194,6 +233,8 @@ __global__ void __launch_bounds__(kPrefillThreads) prefill_colsum_kernel(const P
             for (int g = 0; g < NG; ++g) aq[g] = *(const uint4*)(row + g * 2 * EPV);
         }
         const int ib = it * kTile;
+        const bool edge = (ib < j0 + kTile) || (ib + kTile > n);  // crosses the diagonal or the end of the prompt
+        float z[16];
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
             const int ir = ib + q4 * 8 + half * 4;  // 4 consecutive query rows, 16-byte aligned stats
@@ -201,15 +242,24 @@ __global__ void __launch_bounds__(kPrefillThreads) prefill_colsum_kernel(const P
             const uint4 r4 = *(const uint4*)(wr + ir);
             const float cs[4] = {c4.x, c4.y, c4.z, c4.w};
             const uint32_t rs[4] = {r4.x, r4.y, r4.z, r4.w};
+            const float dist0 = (float)(ir - j);
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const int i = ir + e;
-                const float x = acc[q4 * 4 + e] * a.scale - slope * (float)(i - j);
-                const float y = tempered_logit2(a.noise, x, rs[e], (uint32_t)j, c1, a.inv_tau);
-                const float z = exp2f(y - cs[e]);
-                colsum += (i >= j && i < n) ? z : 0.0f;
+                const float y = (a.noise == kNoiseGumbel)
+                                    ? logit2_gumbel(lp, acc[q4 * 4 + e], dist0 + (float)e, rs[e] ^ kmul)
+                                    : logit2_other(lp, acc[q4 * 4 + e], dist0 + (float)e, rs[e], (uint32_t)j);
+                z[q4 * 4 + e] = hw_exp2(y - cs[e]);
             }
         }
+        if (edge) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int i = ib + (r >> 2) * 8 + half * 4 + (r & 3);
+                z[r] = (i >= j && i < n) ? z[r] : 0.0f;
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) colsum += z[r];
     }
     colsum += __shfl_xor(colsum, 32, kWave);
     if (half == 0 && j < n) {

@@ -262,3 +262,112 @@ def test_long_config_slice_lockstep():
     for t in range(1, 9):
         ls.step(t, check_kv=(t == 8))
     print("long slice lockstep", ls.stats)
+
+
+def test_gptj_full_size_in_bench_launch_shape_sampled_layers():
+    """The workload bench.py times (all 28 layers x 16 heads = 448 units in one
+    launch, cap = k+1 for decode), checked on three whole layers the oracle can
+    compute: prompt scoring, first eviction, then decode steps in lock-step."""
+    wl = kw.CONFIGS["gptj"]
+    sample = [0, 13, 27]
+    steps = 6
+    seeds, d_seeds = kw.noise_seeds(wl), dev(kw.noise_seeds(wl))
+    tau0 = kf.kf_tau(0, wl.T)
+    # --- prompt phase on the GPU: every layer in one call
+    stage = kf.Cache.allocate(wl.L, wl.B, wl.H, wl.d, wl.n, kf.BF16)
+    Qg = torch.empty((wl.L, wl.B, wl.H, wl.n, wl.d), dtype=torch.bfloat16, device="cuda")
+    ocs = {}
+    for l in range(wl.L):
+        Q, K, V = kw.prompt_layer(wl, l)              # CPU generator: the oracle sees the same bits
+        Qg[l].copy_(Q)
+        stage.K[l].copy_(K)
+        stage.V[l].copy_(V)
+        if l in sample:
+            oc = ko.OracleCache(1, wl.B, wl.H, wl.d, wl.n, ko.BF16, layer0=l)
+            oc.K[0], oc.V[0] = kw.to_oracle(K), kw.to_oracle(V)
+            oc.prefill_score(kw.to_oracle(Q)[None], wl.n, ko.tau(0, wl.T), wl.scale, ko.NOISE_GUMBEL, seeds)
+            ocs[l] = oc
+    ws = kf.new_workspace(stage, wl.n)
+    kf.kf_prefill_score(stage, Qg, wl.n, tau0, wl.scale, kf.NOISE_GUMBEL, d_seeds, None, ws)
+    torch.cuda.synchronize()
+    for l in sample:
+        assert_close_score(host(stage.score[l:l + 1]), ocs[l].score, ocs[l].len, "prefill layer %d" % l)
+        stage.score[l].copy_(dev(ocs[l].score)[0])    # lock-step: same scores before selection
+    kept = torch.zeros((wl.L, wl.B, wl.H, wl.k), dtype=torch.int32, device="cuda")
+    before = {l: (ocs[l].score.copy(), ocs[l].len.copy()) for l in sample}
+    kf.kf_select_evict(stage, wl.k, wl.w, kept, ws)
+    torch.cuda.synchronize()
+    ties = 0
+    for l in sample:
+        kept_ref = ocs[l].select_evict(wl.k, wl.w)
+        ties += compare_kept(host(kept[l:l + 1]), kept_ref, before[l][0], before[l][1], wl.k, wl.w)
+    assert ties == 0
+    # --- decode cache shaped as in bench.py: cap = k+1
+    cache = kf.Cache.allocate(wl.L, wl.B, wl.H, wl.d, wl.k + 1, kf.BF16)
+    cache.K[..., : wl.k, :].copy_(stage.K[..., : wl.k, :])
+    cache.V[..., : wl.k, :].copy_(stage.V[..., : wl.k, :])
+    cache.score[..., : wl.k].copy_(stage.score[..., : wl.k])
+    cache.pos[..., : wl.k].copy_(stage.pos[..., : wl.k])
+    cache.len.copy_(stage.len)
+    del stage, Qg
+    ws = kf.new_workspace(cache)
+    out = torch.zeros((wl.L, wl.B, wl.H, wl.d), dtype=torch.float32, device="cuda")
+    kept = torch.zeros((wl.L, wl.B, wl.H, wl.k), dtype=torch.int32, device="cuda")
+    dec = {}
+    for l in sample:                                   # the oracle continues in a cap = k+1 cache too
+        o = ko.OracleCache(1, wl.B, wl.H, wl.d, wl.k + 1, ko.BF16, layer0=l)
+        o.K[..., : wl.k, :], o.V[..., : wl.k, :] = ocs[l].K[..., : wl.k, :], ocs[l].V[..., : wl.k, :]
+        o.score[..., : wl.k], o.pos[..., : wl.k] = ocs[l].score[..., : wl.k], ocs[l].pos[..., : wl.k]
+        o.len[...] = ocs[l].len
+        dec[l] = o
+    for t in range(1, steps + 1):
+        q, kn, vn = kw.decode_inputs(wl, t)
+        q_pos = wl.n + t - 1
+        kf.kf_decode_step(cache, q.cuda(), kn.cuda(), vn.cuda(), q_pos, wl.k + 1, kf.kf_tau(t, wl.T), wl.scale,
+                          kf.NOISE_GUMBEL, d_seeds, None, out, ws)
+        torch.cuda.synchronize()
+        assert error_word(ws) == 0 and int(cache.len.min()) == wl.k + 1
+        for l in sample:
+            o = dec[l]
+            out_ref = o.decode_step(kw.to_oracle(q[l:l + 1]), kw.to_oracle(kn[l:l + 1]), kw.to_oracle(vn[l:l + 1]),
+                                    q_pos, ko.tau(t, wl.T), wl.scale, ko.NOISE_GUMBEL, seeds)
+            assert_close_out(host(out[l:l + 1]), out_ref)
+            assert_close_score(host(cache.score[l:l + 1]), o.score, o.len)
+            cache.score[l].copy_(dev(o.score)[0])
+            before[l] = (o.score.copy(), o.len.copy())
+        kf.kf_select_evict(cache, wl.k, wl.w, kept, ws)
+        torch.cuda.synchronize()
+        for l in sample:
+            kept_ref = dec[l].select_evict(wl.k, wl.w)
+            ev = compare_kept(host(kept[l:l + 1]), kept_ref, before[l][0], before[l][1], wl.k, wl.w)
+            assert ev == 0
+            sub = kf.Cache(K=cache.K[l:l + 1], V=cache.V[l:l + 1], score=cache.score[l:l + 1], pos=cache.pos[l:l + 1],
+                           len=cache.len[l:l + 1], L=1, B=wl.B, H=wl.H, d=wl.d, cap=wl.k + 1, dtype=kf.BF16)
+            assert_state_equal(sub, dec[l], kv=(t == steps))
+    assert int(cache.len.min()) == wl.k and int(cache.len.max()) == wl.k
+
+
+def test_layer_offset_draws_the_full_models_noise():
+    # a cache holding only layer 5 (layer0 = 5) must reproduce layer 5 of a six-layer cache
+    rng = np.random.default_rng(21)
+    L, B, H, d, cap, n = 6, 1, 2, 64, 80, 60
+    oc = random_cache(rng, L, B, H, d, cap, ko.BF16, n)
+    q, kn, vn = (rnd(rng, (L, B, H, d), ko.BF16) for _ in range(3))
+    seeds = np.array([99], np.uint64)
+    gc = upload(oc)
+    ws = kf.new_workspace(gc)
+    out = torch.zeros((L, B, H, d), dtype=torch.float32, device="cuda")
+    kf.kf_decode_step(gc, dev(q), dev(kn), dev(vn), 500, 0, 1.25, 0.125, kf.NOISE_GUMBEL, dev(seeds), None, out, ws)
+    one = ko.OracleCache(1, B, H, d, cap, ko.BF16, layer0=5)
+    for nm in ("K", "V", "score", "pos", "len"):
+        getattr(one, nm)[...] = getattr(oc, nm)[5:6]
+    g1 = upload(one)
+    ws1 = kf.new_workspace(g1)
+    out1 = torch.zeros((1, B, H, d), dtype=torch.float32, device="cuda")
+    kf.kf_decode_step(g1, dev(q[5:6]), dev(kn[5:6]), dev(vn[5:6]), 500, 0, 1.25, 0.125, kf.NOISE_GUMBEL, dev(seeds),
+                      None, out1, ws1)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(host(g1.score), host(gc.score)[5:6])
+    out_ref = one.decode_step(q[5:6], kn[5:6], vn[5:6], 500, 1.25, 0.125, ko.NOISE_GUMBEL, seeds)
+    assert_close_out(host(out1), out_ref)
+    assert_close_score(host(g1.score), one.score, one.len)
