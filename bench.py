@@ -211,6 +211,31 @@ def main():
             roofline["traffic"] = tj.get("decode_kernel_bytes_per_launch", 0) + tj.get(
                 "decode_merge_kernel_bytes_per_launch", 0)
 
+    # ---------------- variants of the same step (not the headline): one fused call per step, in the
+    # ordered layout and in the slot-replacement layout (one row moves per unit instead of ~0.2*k)
+    def timed_variant(layout):
+        base_t = W_steps + K_steps + 8
+        for i in range(4):
+            t = base_t + i
+            q, kn, vn = steps_in[(t - 1) % n_distinct]
+            kf.kf_decode_select_step(cache, q, kn, vn, wl.n + t - 1, m, kf.kf_tau(min(t, wl.T), wl.T), wl.scale,
+                                     noise, seeds, slopes, out, k=wl.k, w=wl.w, layout=layout, workspace=ws)
+        torch.cuda.synchronize()
+        c0 = time.perf_counter()
+        for i in range(K_steps):
+            t = base_t + 4 + i
+            q, kn, vn = steps_in[(t - 1) % n_distinct]
+            kf.kf_decode_select_step(cache, q, kn, vn, wl.n + t - 1, m, kf.kf_tau(min(t, wl.T), wl.T), wl.scale,
+                                     noise, seeds, slopes, out, k=wl.k, w=wl.w, layout=layout, workspace=ws)
+        torch.cuda.synchronize()
+        dt_ = time.perf_counter() - c0
+        assert int(ws[:4].view(torch.int32)[0].item()) == 0
+        assert int(cache.len.min()) == wl.k and int(cache.len.max()) == wl.k
+        return {"steps_per_s": round(K_steps / dt_, 2), "ms_per_step": round(dt_ * 1e3 / K_steps, 4)}
+
+    variants = {"fused_step_ordered_layout": timed_variant(kf.LAYOUT_ORDERED),
+                "fused_step_slot_layout": timed_variant(kf.LAYOUT_SLOT)}   # slot layout last: it unsorts the cache
+
     # prompt-phase scoring: dense causal QK^T twice (row statistics, column sums)
     prefill_flops = wl.units * 2 * (2.0 * wl.d * wl.n * (wl.n + 1) / 2)
     prefill = {"layers_per_call": Ls, "ms_total": round(prefill_ms, 3), "tflops": round(prefill_flops / (prefill_ms * 1e-3) / 1e12, 2),
@@ -255,7 +280,8 @@ def main():
             wl.name, wl.L, wl.B, wl.H, wl.d, wl.n, wl.k, wl.w, wl.T, wl.dtype),
             "units": wl.units, "noise": "gumbel", "tau": [wl.tau_init, wl.tau_end],
             "layout": "ordered (in-place order-preserving compaction)"},
-        "roofline": roofline, "select_compact": select_info, "prefill_score": prefill, "cpu_baseline": cpu,
+        "roofline": roofline, "select_compact": select_info, "prefill_score": prefill, "variants": variants,
+        "cpu_baseline": cpu,
     }
     print(json.dumps(line))
 

@@ -55,6 +55,15 @@ typedef enum {
     KF_NOISE_CONSTANT = 3
 } kf_noise;
 
+/* How kf_select_evict keeps the survivors.
+ *  ORDERED  slots stay sorted by original position: rows behind an evicted slot
+ *           move down (Algorithm 1 slices f[:-w], i.e. presumes positional order).
+ *  SLOT     the cache is an unordered set of (pos, K, V, score) entries: on a
+ *           decode step the newest entry takes the evicted entry's slot, one row
+ *           moves.  Window membership and tie-breaks are decided through pos, so
+ *           the retained SET is the same as in ORDERED.  Needs len <= k+1. */
+typedef enum { KF_LAYOUT_ORDERED = 0, KF_LAYOUT_SLOT = 1 } kf_layout;
+
 /* The per-layer, per-head caches (Fig. 5: scores accumulate "for each layer
  * and head").  Row j of a unit is one cached token. */
 typedef struct {
@@ -102,7 +111,8 @@ uint32_t kf_noise_bits(uint64_t seed, uint32_t layer, uint32_t head, uint32_t q_
 size_t kf_workspace_bytes(const kf_cache *c, int32_t n_max);
 
 /* Device-side error counter: the first int32 of the workspace counts units a
- * kernel had to skip (kf_decode_step on a unit with len >= cap).  Exposed as a
+ * kernel had to skip (kf_decode_step on a unit with len >= cap, kf_select_evict in
+ * the SLOT layout on a unit more than one token over budget).  Exposed as a
  * constant so callers can read it back themselves. */
 #define KF_WS_ERROR_WORD 0
 
@@ -147,10 +157,25 @@ kf_status kf_decode_step(kf_cache *c, const void *q, const void *k_new, const vo
  * survivors move to slots [0,k) in their original order, in place; len = k.
  * kept_idx, if not NULL, is DEVICE [L][B][H][k] and receives the pre-compaction
  * slot of every survivor (identity, then -1 padding, for untouched units).
- * Errors: KF_EINVAL if k < 1, w < 0, w > k or k > cap.
+ * layout is a kf_layout.  With KF_LAYOUT_SLOT a unit more than one token over
+ * budget is left untouched and the workspace error word is incremented; the
+ * recent window is then "the w largest pos", equal scores keep the lower pos.
+ * Errors: KF_EINVAL if k < 1, w < 0, w > k, k > cap or layout unknown.
  */
-kf_status kf_select_evict(kf_cache *c, int32_t k, int32_t w, int32_t *kept_idx, void *workspace,
-                          size_t workspace_bytes, void *stream);
+kf_status kf_select_evict(kf_cache *c, int32_t k, int32_t w, int32_t layout, int32_t *kept_idx,
+                          void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * One whole generation step: kf_decode_step followed by kf_select_evict, with
+ * the same arguments, results and error behaviour as the two calls in a row,
+ * in two kernel launches instead of three (the merge of the decode kernel's
+ * split-wise results rides in the selection kernel).  Algorithm 1, one
+ * iteration of the else-branch including the S_w / S_key / S_k lines.
+ */
+kf_status kf_decode_select_step(kf_cache *c, const void *q, const void *k_new, const void *v_new,
+                                int32_t q_pos, int32_t m_hint, const kf_score_cfg *cfg, float *out,
+                                int32_t k, int32_t w, int32_t layout, int32_t *kept_idx, void *workspace,
+                                size_t workspace_bytes, void *stream);
 
 #ifdef __cplusplus
 }

@@ -15,11 +15,12 @@ _LIB_PATH = os.path.join(HERE, "libkeyformer.so")
 
 F32, BF16 = 0, 1
 NOISE_NONE, NOISE_GUMBEL, NOISE_GAUSSIAN, NOISE_CONSTANT = 0, 1, 2, 3
+LAYOUT_ORDERED, LAYOUT_SLOT = 0, 1
 KF_OK, KF_EINVAL, KF_EUNSUPPORTED, KF_EWORKSPACE, KF_EDEVICE = 0, -1, -2, -3, -4
 
 # every symbol include/keyformer.h declares
 SYMBOLS = ("kf_version", "kf_last_error", "kf_tau", "kf_noise_bits", "kf_workspace_bytes",
-           "kf_prefill_score", "kf_decode_step", "kf_select_evict")
+           "kf_prefill_score", "kf_decode_step", "kf_select_evict", "kf_decode_select_step")
 
 
 class KeyformerError(RuntimeError):
@@ -73,7 +74,11 @@ def lib():
         L.kf_decode_step.argtypes = [C.POINTER(kf_cache), vp, vp, vp, C.c_int32, C.c_int32,
                                      C.POINTER(kf_score_cfg), vp, vp, C.c_size_t, vp]
         L.kf_select_evict.restype = C.c_int
-        L.kf_select_evict.argtypes = [C.POINTER(kf_cache), C.c_int32, C.c_int32, vp, vp, C.c_size_t, vp]
+        L.kf_select_evict.argtypes = [C.POINTER(kf_cache), C.c_int32, C.c_int32, C.c_int32, vp, vp, C.c_size_t, vp]
+        L.kf_decode_select_step.restype = C.c_int
+        L.kf_decode_select_step.argtypes = [C.POINTER(kf_cache), vp, vp, vp, C.c_int32, C.c_int32,
+                                            C.POINTER(kf_score_cfg), vp, C.c_int32, C.c_int32, C.c_int32, vp, vp,
+                                            C.c_size_t, vp]
         _lib = L
     return _lib
 
@@ -188,7 +193,18 @@ def kf_decode_step(cache: Cache, q, k_new, v_new, q_pos: int, m_hint: int, tau: 
                                 C.byref(cfg), _ptr(out), wp, wb, _stream(stream)))
 
 
-def kf_select_evict(cache: Cache, k: int, w: int, kept_idx=None, workspace=None, stream=None) -> None:
+def kf_select_evict(cache: Cache, k: int, w: int, kept_idx=None, workspace=None, stream=None,
+                    layout: int = LAYOUT_ORDERED) -> None:
     cs = cache.c_struct()
     wp, wb = _ws(workspace)
-    _check(lib().kf_select_evict(C.byref(cs), k, w, _ptr(kept_idx), wp, wb, _stream(stream)))
+    _check(lib().kf_select_evict(C.byref(cs), k, w, layout, _ptr(kept_idx), wp, wb, _stream(stream)))
+
+
+def kf_decode_select_step(cache: Cache, q, k_new, v_new, q_pos: int, m_hint: int, tau: float, scale: float,
+                          noise: int = NOISE_GUMBEL, seeds=None, slopes=None, out=None, k: int = 0, w: int = 0,
+                          layout: int = LAYOUT_ORDERED, kept_idx=None, workspace=None, stream=None) -> None:
+    cs, cfg = cache.c_struct(), _cfg(tau, scale, noise, seeds, slopes)
+    wp, wb = _ws(workspace)
+    _check(lib().kf_decode_select_step(C.byref(cs), _ptr(q), _ptr(k_new), _ptr(v_new), q_pos, m_hint,
+                                       C.byref(cfg), _ptr(out), k, w, layout, _ptr(kept_idx), wp, wb,
+                                       _stream(stream)))

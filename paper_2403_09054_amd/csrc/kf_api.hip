@@ -57,11 +57,12 @@ kf_status check_cfg(const kf_score_cfg* cfg) {
 // Workspace layout (all regions 256-byte aligned):
 //   [0]        error word + padding (the only part that must start as zero)
 //   region X   the largest of
-//                decode : partial records U*S*(d+4) floats, then increments U*cap floats
+//                decode : partial records U*S*(d+4) floats, then increments U*cap floats,
+//                         then (fused step) the survivor index list U*cap int32
 //                select : survivor index list U*cap int32
 //                prefill: row normalisers U*n_pad floats, then row keys U*n_pad uint32
 struct WsLayout {
-    size_t region, total;
+    size_t region, fused_idx, total;
 };
 
 size_t decode_region(int64_t U, const kf_cache* c) {
@@ -74,9 +75,10 @@ WsLayout ws_layout(const kf_cache* c, int32_t n_max) {
     const int64_t U = (int64_t)c->L * c->B * c->H;
     WsLayout w;
     w.region = 256;
-    size_t x = decode_region(U, c);
+    const size_t dec = decode_region(U, c);
     const size_t sel = align_up((size_t)U * c->cap * sizeof(int32_t), 256);
-    if (sel > x) x = sel;
+    w.fused_idx = w.region + dec;  // a fused step keeps the decode records while it selects
+    size_t x = dec + sel;
     if (n_max > 0) {
         const size_t n_pad = align_up((size_t)n_max, kf::kPrefillRowPad);
         const size_t pre = 2 * align_up((size_t)U * n_pad * sizeof(float), 256);
@@ -156,9 +158,10 @@ kf_status kf_prefill_score(const kf_cache* c, const void* Q, int32_t n, const kf
     return KF_OK;
 }
 
-kf_status kf_decode_step(kf_cache* c, const void* q, const void* k_new, const void* v_new, int32_t q_pos,
-                         int32_t m_hint, const kf_score_cfg* cfg, float* out, void* workspace,
-                         size_t workspace_bytes, void* stream) {
+// Validates the arguments of a decode step and fills the kernel arguments.
+static kf_status prepare_decode(kf_cache* c, const void* q, const void* k_new, const void* v_new, int32_t q_pos,
+                                int32_t m_hint, const kf_score_cfg* cfg, float* out, void* workspace,
+                                size_t workspace_bytes, kf::DecodeArgs* a, kf::DecodePlan* plan) {
     kf_status st = check_cache(c);
     if (st != KF_OK) return st;
     st = check_cfg(cfg);
@@ -178,62 +181,112 @@ kf_status kf_decode_step(kf_cache* c, const void* q, const void* k_new, const vo
     // the partial-record region is sized for the plan at m = cap, the largest
     const kf::DecodePlan pmax = kf::plan_decode(U, c->cap, c->d, c->dtype);
     if (p.S > pmax.S) return fail(KF_EWORKSPACE, "internal: split count %d exceeds the sized %d", p.S, pmax.S);
+    a->K = c->K;
+    a->V = c->V;
+    a->score = c->score;
+    a->pos = c->pos;
+    a->len = c->len;
+    a->q = q;
+    a->k_new = k_new;
+    a->v_new = v_new;
+    a->out = out;
+    a->seeds = cfg->seeds;
+    a->slopes = cfg->alibi_slopes;
+    a->ws_err = (int32_t*)workspace + KF_WS_ERROR_WORD;
+    a->ws_part = (float*)((char*)workspace + w.region);
+    a->ws_e = (float*)((char*)workspace + w.region + align_up((size_t)U * pmax.S * (c->d + 4) * sizeof(float), 256));
+    a->B = c->B;
+    a->H = c->H;
+    a->cap = c->cap;
+    a->layer0 = c->layer0;
+    a->S = p.S;
+    a->chunk = p.chunk;
+    a->q_pos = q_pos;
+    a->noise = cfg->noise;
+    a->inv_tau = 1.0f / cfg->tau;
+    a->scale = cfg->scale;
+    *plan = p;
+    return KF_OK;
+}
+
+// Same for a selection.  In a fused step the decode records occupy region X of
+// the workspace, so the survivor index list (needed only when the caller wants
+// no kept_idx) lives behind them.
+static kf_status prepare_select(kf_cache* c, int32_t k, int32_t w, int32_t layout, int32_t* kept_idx,
+                                void* workspace, size_t workspace_bytes, bool fused, kf::SelectArgs* a) {
+    kf_status st = check_cache(c);
+    if (st != KF_OK) return st;
+    if (k < 1 || k > c->cap) return fail(KF_EINVAL, "budget k=%d outside [1, cap=%d]", k, c->cap);
+    if (w < 0 || w > k) return fail(KF_EINVAL, "window w=%d outside [0, k=%d]", w, k);
+    if (layout != KF_LAYOUT_ORDERED && layout != KF_LAYOUT_SLOT) return fail(KF_EINVAL, "unknown layout %d", layout);
+    const WsLayout wl = ws_layout(c, 0);
+    st = check_ws(workspace, workspace_bytes, wl.total);
+    if (st != KF_OK) return st;
+    const int64_t U = (int64_t)c->L * c->B * c->H;
+    a->K = c->K;
+    a->V = c->V;
+    a->score = c->score;
+    a->pos = c->pos;
+    a->len = c->len;
+    a->idx = kept_idx ? kept_idx : (int32_t*)((char*)workspace + (fused ? wl.fused_idx : wl.region));
+    a->cap = c->cap;
+    a->k = k;
+    a->w = w;
+    a->row_bytes = c->d * (c->dtype == KF_F32 ? 4 : 2);
+    a->idx_is_output = kept_idx ? 1 : 0;
+    a->layout = layout;
+    a->ws_err = (int32_t*)workspace + KF_WS_ERROR_WORD;
+    (void)U;
+    return KF_OK;
+}
+
+kf_status kf_decode_step(kf_cache* c, const void* q, const void* k_new, const void* v_new, int32_t q_pos,
+                         int32_t m_hint, const kf_score_cfg* cfg, float* out, void* workspace,
+                         size_t workspace_bytes, void* stream) {
     kf::DecodeArgs a;
-    a.K = c->K;
-    a.V = c->V;
-    a.score = c->score;
-    a.pos = c->pos;
-    a.len = c->len;
-    a.q = q;
-    a.k_new = k_new;
-    a.v_new = v_new;
-    a.out = out;
-    a.seeds = cfg->seeds;
-    a.slopes = cfg->alibi_slopes;
-    a.ws_err = (int32_t*)workspace + KF_WS_ERROR_WORD;
-    a.ws_part = (float*)((char*)workspace + w.region);
-    a.ws_e = (float*)((char*)workspace + w.region + align_up((size_t)U * pmax.S * (c->d + 4) * sizeof(float), 256));
-    a.B = c->B;
-    a.H = c->H;
-    a.cap = c->cap;
-    a.layer0 = c->layer0;
-    a.S = p.S;
-    a.chunk = p.chunk;
-    a.q_pos = q_pos;
-    a.noise = cfg->noise;
-    a.inv_tau = 1.0f / cfg->tau;
-    a.scale = cfg->scale;
+    kf::DecodePlan p;
+    const kf_status st = prepare_decode(c, q, k_new, v_new, q_pos, m_hint, cfg, out, workspace, workspace_bytes, &a, &p);
+    if (st != KF_OK) return st;
+    const int64_t U = (int64_t)c->L * c->B * c->H;
     const hipError_t e = kf::launch_decode(a, U, c->d, c->dtype, p.lds_bytes, (hipStream_t)stream);
     if (e != hipSuccess) return fail(KF_EDEVICE, "decode launch: %s", hipGetErrorString(e));
     g_err[0] = 0;
     return KF_OK;
 }
 
-kf_status kf_select_evict(kf_cache* c, int32_t k, int32_t w, int32_t* kept_idx, void* workspace,
+kf_status kf_select_evict(kf_cache* c, int32_t k, int32_t w, int32_t layout, int32_t* kept_idx, void* workspace,
                           size_t workspace_bytes, void* stream) {
-    kf_status st = check_cache(c);
-    if (st != KF_OK) return st;
-    if (k < 1 || k > c->cap) return fail(KF_EINVAL, "budget k=%d outside [1, cap=%d]", k, c->cap);
-    if (w < 0 || w > k) return fail(KF_EINVAL, "window w=%d outside [0, k=%d]", w, k);
-    const WsLayout wl = ws_layout(c, 0);
-    st = check_ws(workspace, workspace_bytes, wl.total);
-    if (st != KF_OK) return st;
-
-    const int64_t U = (int64_t)c->L * c->B * c->H;
     kf::SelectArgs a;
-    a.K = c->K;
-    a.V = c->V;
-    a.score = c->score;
-    a.pos = c->pos;
-    a.len = c->len;
-    a.idx = kept_idx ? kept_idx : (int32_t*)((char*)workspace + wl.region);
-    a.cap = c->cap;
-    a.k = k;
-    a.w = w;
-    a.row_bytes = c->d * (c->dtype == KF_F32 ? 4 : 2);
-    a.idx_is_output = kept_idx ? 1 : 0;
+    const kf_status st = prepare_select(c, k, w, layout, kept_idx, workspace, workspace_bytes, false, &a);
+    if (st != KF_OK) return st;
+    const int64_t U = (int64_t)c->L * c->B * c->H;
     const hipError_t e = kf::launch_select(a, U, (hipStream_t)stream);
     if (e != hipSuccess) return fail(KF_EDEVICE, "select launch: %s", hipGetErrorString(e));
+    g_err[0] = 0;
+    return KF_OK;
+}
+
+kf_status kf_decode_select_step(kf_cache* c, const void* q, const void* k_new, const void* v_new, int32_t q_pos,
+                                int32_t m_hint, const kf_score_cfg* cfg, float* out, int32_t k, int32_t w,
+                                int32_t layout, int32_t* kept_idx, void* workspace, size_t workspace_bytes,
+                                void* stream) {
+    kf::DecodeArgs da;
+    kf::DecodePlan p;
+    kf_status st = prepare_decode(c, q, k_new, v_new, q_pos, m_hint, cfg, out, workspace, workspace_bytes, &da, &p);
+    if (st != KF_OK) return st;
+    kf::SelectArgs sa;
+    st = prepare_select(c, k, w, layout, kept_idx, workspace, workspace_bytes, true, &sa);
+    if (st != KF_OK) return st;
+    const int64_t U = (int64_t)c->L * c->B * c->H;
+    hipError_t e;
+    if (da.S > 1) {
+        e = kf::launch_decode_split(da, U, c->d, c->dtype, p.lds_bytes, (hipStream_t)stream);
+        if (e == hipSuccess) e = kf::launch_step_tail(da, sa, U, c->d, (hipStream_t)stream);
+    } else {  // the decode kernel finishes each unit itself: nothing to merge
+        e = kf::launch_decode(da, U, c->d, c->dtype, p.lds_bytes, (hipStream_t)stream);
+        if (e == hipSuccess) e = kf::launch_select(sa, U, (hipStream_t)stream);
+    }
+    if (e != hipSuccess) return fail(KF_EDEVICE, "step launch: %s", hipGetErrorString(e));
     g_err[0] = 0;
     return KF_OK;
 }

@@ -19,12 +19,12 @@
 // back an L2 and the kernel ran 6x slower, so the merge is a launch of its own.)
 #include "kf_device.h"
 #include "kf_internal.h"
+#include "kf_merge.h"
 
 namespace kf {
 
 constexpr int kDecodeThreads = 256;
 constexpr int kDecodeMaxChunk = 4096;   // tokens per split the LDS arrays are sized for
-constexpr int kDecodeMaxSplits = 256;   // <= kDecodeThreads: one thread per split in the merge
 #ifndef KF_DECODE_MIN_BLOCKS
 #define KF_DECODE_MIN_BLOCKS 1024
 #endif
@@ -36,50 +36,6 @@ constexpr int kDecodeMinChunk = 128;
 #ifndef KF_DECODE_UNROLL
 #define KF_DECODE_UNROLL 4
 #endif
-
-// Merges the S partial records of unit u: rescales every split's un-normalised
-// output and score increments to the unit-wide maxima, normalises, accumulates
-// the scores and publishes the new length.  Called by a whole workgroup.
-template <int D, int NT>
-__device__ __forceinline__ void merge_unit(const DecodeArgs& a, int64_t u, int len0, float* red_s, float* w_p,
-                                           float* w_e) {
-    constexpr int PW = D + 4;
-    const int tid = threadIdx.x, S = a.S, m = len0 + 1;
-    const float* parts = a.ws_part + (size_t)u * S * PW;
-    float* fu = a.score + (size_t)u * a.cap;
-    float pmx = -INFINITY, psp = 0.0f, pmy = -INFINITY, pse = 0.0f;
-    if (tid < S) {
-        const float* r = parts + (size_t)tid * PW + D;
-        pmx = r[0];
-        psp = r[1];
-        pmy = r[2];
-        pse = r[3];
-    }
-    const float Mx = block_max<NT>(pmx, red_s);
-    const float My = block_max<NT>(pmy, red_s);
-    // statistics are kept in the base-2 domain (logits times log2 e)
-    const float wp = (psp > 0.0f) ? hw_exp2(pmx - Mx) : 0.0f;  // empty splits weigh nothing
-    const float we_ = (pse > 0.0f) ? hw_exp2(pmy - My) : 0.0f;
-    const float sumP = block_sum<NT>(wp * psp, red_s);
-    const float sumE = block_sum<NT>(we_ * pse, red_s);
-    if (tid < S) {
-        w_p[tid] = wp;
-        w_e[tid] = we_;
-    }
-    __syncthreads();
-    if (tid < D) {
-        float o = 0.0f;
-        for (int ss = 0; ss < S; ++ss) o = fmaf(w_p[ss], parts[(size_t)ss * PW + tid], o);
-        a.out[u * D + tid] = o / sumP;
-    }
-    const float* we = a.ws_e + (size_t)u * a.cap;
-    const float inv = 1.0f / sumE;
-    for (int j = tid; j < m; j += NT) {
-        const float prev = (j == len0) ? 0.0f : fu[j];
-        fu[j] = prev + we[j] * (w_e[(j == len0) ? S - 1 : j / a.chunk] * inv);  // the new token belongs to the last split
-    }
-    if (tid == 0) a.len[u] = m;
-}
 
 // ---- lane-group sums without LDS traffic ---------------------------------
 // A row's partial dot products sit in LPR adjacent lanes.  The data-parallel
@@ -475,29 +431,39 @@ DecodePlan plan_decode(int64_t U, int32_t m, int32_t d, int32_t dtype) {
 }
 
 template <typename T, int D>
-static hipError_t launch_decode_t(const DecodeArgs& a, int64_t U, size_t lds, hipStream_t st) {
+static hipError_t launch_decode_t(const DecodeArgs& a, int64_t U, size_t lds, hipStream_t st, bool merge) {
     const dim3 grid((unsigned)(U * a.S)), block(kDecodeThreads);
     hipLaunchKernelGGL((decode_kernel<T, D, kDecodeThreads>), grid, block, lds, st, a);
     hipError_t e = hipGetLastError();
-    if (e == hipSuccess && a.S > 1) {
+    if (e == hipSuccess && a.S > 1 && merge) {
         hipLaunchKernelGGL((decode_merge_kernel<D, kDecodeThreads>), dim3((unsigned)U), block, 0, st, a);
         e = hipGetLastError();
     }
     return e;
 }
 
-hipError_t launch_decode(const DecodeArgs& a, int64_t U, int32_t d, int32_t dtype, size_t lds_bytes,
-                         hipStream_t stream) {
-    if (a.chunk > kDecodeMaxChunk) return hipErrorInvalidValue;
+static hipError_t launch_decode_any(const DecodeArgs& a, int64_t U, int32_t d, int32_t dtype, size_t lds_bytes,
+                                    hipStream_t stream, bool merge) {
+    if (a.chunk > kDecodeMaxChunk || a.S > kDecodeMaxSplits) return hipErrorInvalidValue;
     if (dtype == KF_BF16) {
-        if (d == 64) return launch_decode_t<bf16_t, 64>(a, U, lds_bytes, stream);
-        if (d == 128) return launch_decode_t<bf16_t, 128>(a, U, lds_bytes, stream);
-        if (d == 256) return launch_decode_t<bf16_t, 256>(a, U, lds_bytes, stream);
+        if (d == 64) return launch_decode_t<bf16_t, 64>(a, U, lds_bytes, stream, merge);
+        if (d == 128) return launch_decode_t<bf16_t, 128>(a, U, lds_bytes, stream, merge);
+        if (d == 256) return launch_decode_t<bf16_t, 256>(a, U, lds_bytes, stream, merge);
     } else {
-        if (d == 64) return launch_decode_t<float, 64>(a, U, lds_bytes, stream);
-        if (d == 128) return launch_decode_t<float, 128>(a, U, lds_bytes, stream);
+        if (d == 64) return launch_decode_t<float, 64>(a, U, lds_bytes, stream, merge);
+        if (d == 128) return launch_decode_t<float, 128>(a, U, lds_bytes, stream, merge);
     }
     return hipErrorInvalidValue;
+}
+
+hipError_t launch_decode(const DecodeArgs& a, int64_t U, int32_t d, int32_t dtype, size_t lds_bytes,
+                         hipStream_t stream) {
+    return launch_decode_any(a, U, d, dtype, lds_bytes, stream, true);
+}
+
+hipError_t launch_decode_split(const DecodeArgs& a, int64_t U, int32_t d, int32_t dtype, size_t lds_bytes,
+                               hipStream_t stream) {
+    return launch_decode_any(a, U, d, dtype, lds_bytes, stream, false);
 }
 
 }  // namespace kf

@@ -53,8 +53,15 @@ struct SelectArgs {
     int32_t cap, k, w;
     int32_t row_bytes;  // d * sizeof(element)
     int32_t idx_is_output;  // idx is the caller's kept_idx (must be complete), not scratch
+    int32_t layout;         // kf_layout
+    int32_t* ws_err;        // [1] skipped-unit counter
 };
 hipError_t launch_select(const SelectArgs& a, int64_t U, hipStream_t stream);
+// decode merge + select + compact of every unit in one launch (after the split kernel of a fused step)
+hipError_t launch_step_tail(const DecodeArgs& d, const SelectArgs& a, int64_t U, int32_t hd, hipStream_t stream);
+// the split kernel alone (no merge launch): first half of a fused step
+hipError_t launch_decode_split(const DecodeArgs& a, int64_t U, int32_t d, int32_t dtype, size_t lds_bytes,
+                               hipStream_t stream);
 
 // ------------------------------------------------------------------ prefill
 struct PrefillArgs {

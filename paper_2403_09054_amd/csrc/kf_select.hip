@@ -25,6 +25,7 @@
 //            has to read.  Rows that stay where they are are not touched.
 #include "kf_device.h"
 #include "kf_internal.h"
+#include "kf_merge.h"
 
 namespace kf {
 
@@ -131,8 +132,87 @@ __device__ __forceinline__ void evict_one(const SelectArgs& a, int64_t u, int n,
     if (tid == 0) a.len[u] = k;
 }
 
+// Slot-replacement variant of the same eviction (layout KF_LAYOUT_SLOT): the
+// cache is an unordered set of (pos, K, V, score) entries.  The recent window
+// is the w largest original positions -- positions are consecutive at the
+// recent end, so "pos > newest - w" -- the candidate with the smallest score
+// leaves (the highest position among equal minima, the same rule as above
+// expressed through pos), and the newest entry (slot k) takes its slot: one row
+// moves instead of every row behind the gap.
 template <int NT>
-__global__ void __launch_bounds__(NT) select_kernel(const SelectArgs a) {
+__device__ __forceinline__ void evict_one_slot(const SelectArgs& a, int64_t u, int n, bool write_idx) {
+    constexpr int NW = NT / kWave;
+    __shared__ unsigned long long wmin_s[NW];
+    __shared__ int s_slot;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int k = a.k, w = a.w;
+    float* fu = a.score + (size_t)u * a.cap;
+    int32_t* pu = a.pos + (size_t)u * a.cap;
+    const int newest = pu[n - 1];
+
+    unsigned long long best = ~0ull, mine[2] = {~0ull, ~0ull};
+    for (int j = tid, c = 0; j < n; j += NT, ++c) {
+        const int pj = pu[j];
+        unsigned long long pack = ~0ull;
+        if (pj <= newest - w)  // a candidate: outside the recent window
+            pack = ((unsigned long long)float_key(fu[j]) << 32) | (uint32_t)(~(uint32_t)pj);
+        best = pack < best ? pack : best;
+        if (c < 2) mine[c] = pack;
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const unsigned long long t = __shfl_xor(best, o, kWave);
+        best = t < best ? t : best;
+    }
+    if (lane == 0) wmin_s[wv] = best;
+    if (tid == 0) s_slot = -1;
+    __syncthreads();
+    best = wmin_s[0];
+#pragma unroll
+    for (int i = 1; i < NW; ++i) best = wmin_s[i] < best ? wmin_s[i] : best;
+    // positions are unique, so exactly one entry carries the winning pack
+    if (best != ~0ull) {
+        for (int j = tid, c = 0; j < n; j += NT, ++c) {
+            unsigned long long pack;
+            if (c < 2) {
+                pack = mine[c];
+            } else {
+                const int pj = pu[j];
+                pack = (pj <= newest - w)
+                           ? (((unsigned long long)float_key(fu[j]) << 32) | (uint32_t)(~(uint32_t)pj))
+                           : ~0ull;
+            }
+            if (pack == best) s_slot = j;
+        }
+    }
+    __syncthreads();
+    const int e = s_slot;
+    if (e < 0) {  // no entry lies outside the window (positions not consecutive at the recent end): report
+        if (tid == 0) atomicAdd(a.ws_err, 1);
+        return;
+    }
+    if (write_idx) {
+        int32_t* idx = a.idx + (size_t)u * k;
+        for (int i = tid; i < k; i += NT) idx[i] = (i == e) ? k : i;
+    }
+    if (e != k) {  // the newest entry moves into the freed slot
+        const int PPR = a.row_bytes >> 4;
+        if (tid < 2 * PPR) {
+            uint4* base = (uint4*)((char*)(tid < PPR ? a.K : a.V) + (size_t)u * a.cap * a.row_bytes);
+            const int piece = tid % PPR;
+            base[(size_t)e * PPR + piece] = base[(size_t)k * PPR + piece];
+        } else if (tid == 2 * PPR) {
+            fu[e] = fu[k];
+        } else if (tid == 2 * PPR + 1) {
+            pu[e] = newest;
+        }
+    }
+    if (tid == 0) a.len[u] = k;
+}
+
+// Selection and compaction of one unit by one workgroup.
+template <int NT>
+__device__ __forceinline__ void select_unit(const SelectArgs& a, int64_t u) {
     constexpr int NW = NT / kWave;
     __shared__ uint32_t hist[256];
     __shared__ uint32_t s_bin, s_rem;
@@ -140,13 +220,21 @@ __global__ void __launch_bounds__(NT) select_kernel(const SelectArgs a) {
     __shared__ int s_first;
 
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    const int64_t u = blockIdx.x;
     const int n = a.len[u];
     const int k = a.k, w = a.w;
     int32_t* idx = a.idx + (size_t)u * k;
 
     if (n <= k) {  // under budget: nothing leaves
-        for (int i = tid; i < k; i += NT) idx[i] = (i < n) ? i : -1;
+        if (a.idx_is_output)
+            for (int i = tid; i < k; i += NT) idx[i] = (i < n) ? i : -1;
+        return;
+    }
+    if (a.layout == KF_LAYOUT_SLOT) {
+        if (n == k + 1) {
+            evict_one_slot<NT>(a, u, n, a.idx_is_output != 0);
+        } else if (tid == 0) {
+            atomicAdd(a.ws_err, 1);  // more than one token over budget: not handled in this layout
+        }
         return;
     }
     if (n == k + 1) {  // decode shape
@@ -295,6 +383,36 @@ __global__ void __launch_bounds__(NT) select_kernel(const SelectArgs a) {
         }
     }
     if (tid == 0) a.len[u] = k;
+}
+
+template <int NT>
+__global__ void __launch_bounds__(NT) select_kernel(const SelectArgs a) {
+    select_unit<NT>(a, (int64_t)blockIdx.x);
+}
+
+// Tail of a fused generation step: merge the decode kernel's split records of
+// the unit (attention output, score accumulation, new length), then select and
+// compact -- one launch instead of two.
+template <int D, int NT>
+__global__ void __launch_bounds__(NT) step_tail_kernel(const DecodeArgs d, const SelectArgs a) {
+    __shared__ float red_s[NT / kWave];
+    __shared__ float w_p[kDecodeMaxSplits], w_e[kDecodeMaxSplits];
+    const int64_t u = blockIdx.x;
+    const int len0 = d.len[u];
+    if (len0 >= 0 && len0 < d.cap && len0 <= d.S * d.chunk) {  // else: skipped by the split kernel too
+        merge_unit<D, NT>(d, u, len0, red_s, w_p, w_e);
+        __syncthreads();  // the merged scores and the new length are visible to the whole workgroup
+    }
+    select_unit<NT>(a, u);
+}
+
+hipError_t launch_step_tail(const DecodeArgs& d, const SelectArgs& a, int64_t U, int32_t hd, hipStream_t stream) {
+    const dim3 grid((unsigned)U), block(kSelectThreads);
+    if (hd == 64) hipLaunchKernelGGL((step_tail_kernel<64, kSelectThreads>), grid, block, 0, stream, d, a);
+    else if (hd == 128) hipLaunchKernelGGL((step_tail_kernel<128, kSelectThreads>), grid, block, 0, stream, d, a);
+    else if (hd == 256) hipLaunchKernelGGL((step_tail_kernel<256, kSelectThreads>), grid, block, 0, stream, d, a);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
 }
 
 hipError_t launch_select(const SelectArgs& a, int64_t U, hipStream_t stream) {

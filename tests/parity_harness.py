@@ -121,6 +121,43 @@ def assert_state_equal(gc: kf.Cache, oc: ko.OracleCache, kv=True, score_exact=Tr
                     np.testing.assert_array_equal(V[l, b, h, :m], oc.V[l, b, h, :m])
 
 
+def sort_by_pos(gc: kf.Cache):
+    """Host copy of a cache with every unit's live entries sorted by original
+    position (what an unordered, slot-replacement cache means as a set).
+    Returns (K, V, score, pos, len, order) numpy arrays; order[l,b,h,:m] is the
+    slot of the i-th entry in position order."""
+    K, V, score, pos, lens = host(gc.K).copy(), host(gc.V).copy(), host(gc.score).copy(), host(gc.pos).copy(), host(gc.len)
+    order = np.zeros(pos.shape, np.int64)
+    L, B, H = lens.shape
+    for l in range(L):
+        for b in range(B):
+            for h in range(H):
+                m = int(lens[l, b, h])
+                o = np.argsort(pos[l, b, h, :m], kind="stable")
+                order[l, b, h, :m] = o
+                K[l, b, h, :m] = K[l, b, h, o]
+                V[l, b, h, :m] = V[l, b, h, o]
+                score[l, b, h, :m] = score[l, b, h, o]
+                pos[l, b, h, :m] = pos[l, b, h, o]
+    return K, V, score, pos, lens, order
+
+
+def assert_set_equal(gc: kf.Cache, oc: ko.OracleCache, kv=True, score_exact=True):
+    """The unordered GPU cache holds exactly the oracle's entries (keyed by pos), bit for bit."""
+    K, V, score, pos, lens, _ = sort_by_pos(gc)
+    np.testing.assert_array_equal(lens, oc.len)
+    for l in range(oc.L):
+        for b in range(oc.B):
+            for h in range(oc.H):
+                m = int(lens[l, b, h])
+                np.testing.assert_array_equal(pos[l, b, h, :m], oc.pos[l, b, h, :m])
+                if score_exact:
+                    np.testing.assert_array_equal(score[l, b, h, :m], oc.score[l, b, h, :m])
+                if kv:
+                    np.testing.assert_array_equal(K[l, b, h, :m], oc.K[l, b, h, :m])
+                    np.testing.assert_array_equal(V[l, b, h, :m], oc.V[l, b, h, :m])
+
+
 def error_word(ws) -> int:
     return int(ws[:4].view(torch.int32)[0].item())
 
@@ -130,8 +167,8 @@ class LockStep:
     hold the same state (scores are re-uploaded from the oracle after each
     decode step, everything after a tie-band event)."""
 
-    def __init__(self, wl: kw.Workload, noise=ko.NOISE_GUMBEL, layers=None, cap=None):
-        self.wl, self.noise = wl, noise
+    def __init__(self, wl: kw.Workload, noise=ko.NOISE_GUMBEL, layers=None, cap=None, layout=kf.LAYOUT_ORDERED):
+        self.wl, self.noise, self.layout = wl, noise, layout
         self.cap = cap or wl.n
         dt = ko.F32 if wl.dtype == "f32" else ko.BF16
         self.oc = ko.OracleCache(wl.L, wl.B, wl.H, wl.d, self.cap, dt)
@@ -170,9 +207,27 @@ class LockStep:
         wl = self.wl
         before_score, before_len = self.oc.score.copy(), self.oc.len.copy()
         kept_ref = self.oc.select_evict(wl.k, wl.w)
-        kf.kf_select_evict(self.gc, wl.k, wl.w, self.kept, self.ws)
+        slot = self.layout == kf.LAYOUT_SLOT and int(before_len.max()) <= wl.k + 1
+        if slot:
+            order_before = sort_by_pos(self.gc)[5]
+        kf.kf_select_evict(self.gc, wl.k, wl.w, self.kept, self.ws,
+                           layout=kf.LAYOUT_SLOT if slot else kf.LAYOUT_ORDERED)
         torch.cuda.synchronize()
-        ev = compare_kept(host(self.kept), kept_ref, before_score, before_len, wl.k, wl.w)
+        assert error_word(self.ws) == 0
+        if slot:
+            # survivors as ranks in position order = the ordered layout's slot numbers
+            kept_slots = host(self.kept)
+            kept_g = np.full_like(kept_ref, -1)
+            for l, b, h in np.ndindex(*before_len.shape):
+                n_u = int(before_len[l, b, h])
+                rank = np.empty(n_u, np.int64)
+                rank[order_before[l, b, h, :n_u]] = np.arange(n_u)
+                kk = kept_slots[l, b, h]
+                kk = kk[kk >= 0]
+                kept_g[l, b, h, : len(kk)] = np.sort(rank[kk])
+        else:
+            kept_g = host(self.kept)
+        ev = compare_kept(kept_g, kept_ref, before_score, before_len, wl.k, wl.w)
         self.stats["tie_events"] += ev
         if ev:
             upload_into(self.gc, self.oc)       # adopt the oracle's choice and go on
@@ -193,12 +248,25 @@ class LockStep:
         lens = host(self.gc.len)
         np.testing.assert_array_equal(lens, self.oc.len)
         self.stats["out_err"] = max(self.stats["out_err"], assert_close_out(host(self.out), out_ref))
-        self.stats["score_err"] = max(self.stats["score_err"],
-                                      assert_close_score(host(self.gc.score), self.oc.score, lens))
-        self.gc.score.copy_(dev(self.oc.score))     # lock-step: same scores before selection
-        self.select()
-        if check_kv:
-            assert_state_equal(self.gc, self.oc)
+        if self.layout == kf.LAYOUT_SLOT:
+            _, _, g_score, g_pos, _, order = sort_by_pos(self.gc)
+            for l, b, h in np.ndindex(*lens.shape):
+                np.testing.assert_array_equal(g_pos[l, b, h, : lens[l, b, h]], self.oc.pos[l, b, h, : lens[l, b, h]])
+            self.stats["score_err"] = max(self.stats["score_err"], assert_close_score(g_score, self.oc.score, lens))
+            new_score = host(self.gc.score).copy()       # oracle scores, scattered to the GPU's slots
+            for l, b, h in np.ndindex(*lens.shape):
+                m = int(lens[l, b, h])
+                new_score[l, b, h, order[l, b, h, :m]] = self.oc.score[l, b, h, :m]
+            self.gc.score.copy_(dev(new_score))
         else:
-            assert_state_equal(self.gc, self.oc, kv=False)
+            self.stats["score_err"] = max(self.stats["score_err"],
+                                          assert_close_score(host(self.gc.score), self.oc.score, lens))
+            self.gc.score.copy_(dev(self.oc.score))     # lock-step: same scores before selection
+        ev = self.select()
+        if self.layout == kf.LAYOUT_SLOT:
+            if ev:    # the oracle's (ordered) state was adopted: it is a valid unordered state as well
+                pass
+            assert_set_equal(self.gc, self.oc, kv=check_kv)
+        else:
+            assert_state_equal(self.gc, self.oc, kv=check_kv)
         self.stats["steps"] += 1

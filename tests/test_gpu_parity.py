@@ -9,7 +9,7 @@ import torch
 import kf_workloads as kw
 import paper_2403_09054_amd as kf
 from oracle import kf_oracle as ko
-from parity_harness import (LockStep, assert_close_out, assert_close_score, assert_state_equal,
+from parity_harness import (LockStep, assert_close_out, assert_close_score, assert_set_equal, assert_state_equal,
                             compare_kept, dev, error_word, host, upload)
 
 pytestmark = pytest.mark.gpu
@@ -371,3 +371,70 @@ def test_layer_offset_draws_the_full_models_noise():
     out_ref = one.decode_step(q[5:6], kn[5:6], vn[5:6], 500, 1.25, 0.125, ko.NOISE_GUMBEL, seeds)
     assert_close_out(host(out1), out_ref)
     assert_close_score(host(g1.score), one.score, one.len)
+
+
+# ------------------------------------------------------------------ slot-replacement layout, fused step
+@pytest.mark.parametrize("name,kwargs,steps", [("tiny", {}, 32), ("mpt", dict(L=1, B=2, H=4, T=1024), 16),
+                                               ("gptj", dict(L=1, H=4, T=512), 24)])
+def test_slot_layout_keeps_the_same_set_as_the_oracle(name, kwargs, steps):
+    wl = kw.CONFIGS[name].slice(**kwargs) if kwargs else kw.CONFIGS[name]
+    ls = LockStep(wl, layout=kf.LAYOUT_SLOT)
+    ls.prefill()                       # n -> k is more than one eviction: done in the ordered layout
+    unordered = False
+    for t in range(1, steps + 1):
+        ls.step(t, check_kv=(t % 8 == 0 or t == steps))
+        # the GPU cache really leaves positional order (it may pass through it again: when the
+        # evicted token is always the one that just left the window the slots behave as a ring)
+        unordered |= bool((np.diff(host(ls.gc.pos)[..., : wl.k], axis=-1) < 0).any())
+    assert unordered
+    print(name, "slot layout lockstep", ls.stats)
+
+
+def test_slot_layout_rejects_more_than_one_eviction():
+    rng = np.random.default_rng(31)
+    oc = random_cache(rng, 1, 1, 2, 64, 40, ko.BF16, 30)
+    oc.pos[...] = np.arange(40)
+    gc = upload(oc)
+    ws = kf.new_workspace(gc)
+    kf.kf_select_evict(gc, 20, 4, None, ws, layout=kf.LAYOUT_SLOT)
+    torch.cuda.synchronize()
+    assert error_word(ws) == 2 and (host(gc.len) == 30).all()
+    assert_state_equal(gc, oc)         # untouched
+
+
+@pytest.mark.parametrize("dtype,d,cap,layout", [(ko.BF16, 256, 1025, 0), (ko.BF16, 128, 300, 0), (ko.F32, 64, 65, 0),
+                                               (ko.BF16, 128, 2049, 1), (ko.BF16, 64, 131, 1)])
+def test_fused_step_equals_the_two_calls(dtype, d, cap, layout):
+    """kf_decode_select_step must leave exactly what kf_decode_step + kf_select_evict leave."""
+    rng = np.random.default_rng(cap + d)
+    L, B, H = 2, 2, 3            # 12 units: several splits at the larger caps, one split at the small ones
+    k = cap - 1
+    w = k // 5
+    lens = np.full((L, B, H), k, np.int32)
+    lens[0, 0, 0] = k // 2                       # under budget after the step: selection must not touch it
+    oc = random_cache(rng, L, B, H, d, cap, dtype, lens)
+    oc.pos[...] = np.arange(cap)                 # consecutive positions (the slot layout's window rule)
+    oc.score[0, 1, 0, 10:20] = 0.0               # tied minima
+    q, kn, vn = (rnd(rng, (L, B, H, d), dtype) for _ in range(3))
+    seeds = np.array([5, 6], np.uint64)
+    results = []
+    for fused in (False, True):
+        gc = upload(oc)
+        ws = kf.new_workspace(gc)
+        out = torch.zeros((L, B, H, d), dtype=torch.float32, device="cuda")
+        kept = torch.full((L, B, H, k), -7, dtype=torch.int32, device="cuda")
+        args = (dev(q), dev(kn), dev(vn), cap + 3, 0, 1.6, 0.11, kf.NOISE_GUMBEL, dev(seeds), None, out)
+        if fused:
+            kf.kf_decode_select_step(gc, *args, k=k, w=w, layout=layout, kept_idx=kept, workspace=ws)
+        else:
+            kf.kf_decode_step(gc, *args, ws)
+            kf.kf_select_evict(gc, k, w, kept, ws, layout=layout)
+        torch.cuda.synchronize()
+        assert error_word(ws) == 0
+        results.append([host(t).copy() for t in (out, kept, gc.K, gc.V, gc.score, gc.pos, gc.len)])
+    for a, b in zip(*results):
+        np.testing.assert_array_equal(a, b)
+    # and the two-call path is the one checked against the oracle
+    ref = oc.copy()
+    out_ref = ref.decode_step(q, kn, vn, cap + 3, 1.6, 0.11, ko.NOISE_GUMBEL, seeds)
+    assert_close_out(results[0][0], out_ref)
