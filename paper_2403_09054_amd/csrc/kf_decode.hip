@@ -198,14 +198,14 @@ __global__ void __launch_bounds__(NT) decode_kernel(const DecodeArgs a) {
     auto load_plain = [&](const char* rows, int base, uint4(&raw)[UNR]) {
         const char* p = rows + (size_t)base * ROWB + lane_off;
 #pragma unroll
-        for (int i = 0; i < UNR; ++i) raw[i] = *(const uint4*)(p + (size_t)i * RPB * ROWB);
+        for (int i = 0; i < UNR; ++i) raw[i] = stream_load((const uint4*)(p + (size_t)i * RPB * ROWB));
     };
     auto load_edge = [&](const char* rows, int base, uint4(&raw)[UNR]) {
 #pragma unroll
         for (int i = 0; i < UNR; ++i) {
             const int j = base + i * RPB + sub;
             raw[i] = make_uint4(0u, 0u, 0u, 0u);
-            if (j < j1) raw[i] = *(const uint4*)(rows + (size_t)j * ROWB + (size_t)cl * 16);
+            if (j < j1) raw[i] = stream_load((const uint4*)(rows + (size_t)j * ROWB + (size_t)cl * 16));
         }
     };
     auto load_tile = [&](const char* rows, int base, uint4(&raw)[UNR]) {
