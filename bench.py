@@ -38,6 +38,9 @@ def parse():
     ap.add_argument("--no-events", action="store_true",
                     help="time the steps without per-kernel events (roofline is then null)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU work budget of the oracle leg")
+    ap.add_argument("--no-variants", action="store_true",
+                    help="skip the fused-call / slot-layout variants after the timed region (used when profiling, "
+                         "so that per-kernel statistics cover the headline configuration only)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain device copy of a known size (1 GiB, 10 times): the reference the "
                          "FETCH_SIZE / WRITE_SIZE counters are scaled by")
@@ -233,8 +236,10 @@ def main():
         assert int(cache.len.min()) == wl.k and int(cache.len.max()) == wl.k
         return {"steps_per_s": round(K_steps / dt_, 2), "ms_per_step": round(dt_ * 1e3 / K_steps, 4)}
 
-    variants = {"fused_step_ordered_layout": timed_variant(kf.LAYOUT_ORDERED),
-                "fused_step_slot_layout": timed_variant(kf.LAYOUT_SLOT)}   # slot layout last: it unsorts the cache
+    variants = None
+    if not args.no_variants:
+        variants = {"fused_step_ordered_layout": timed_variant(kf.LAYOUT_ORDERED),
+                    "fused_step_slot_layout": timed_variant(kf.LAYOUT_SLOT)}   # slot layout last: it unsorts the cache
 
     # prompt-phase scoring: dense causal QK^T twice (row statistics, column sums)
     prefill_flops = wl.units * 2 * (2.0 * wl.d * wl.n * (wl.n + 1) / 2)

@@ -57,16 +57,24 @@ __device__ __forceinline__ void unpack16<bf16_t>(const uint4& r, float* f) {
 }
 
 // ---------------------------------------------------------------- streaming access
-// 16-byte loads of data that is read once per launch (K and V rows in the
-// decode kernel): marked non-temporal so that they stream through the caches
-// instead of displacing lines.  On MI355X the decode kernel reads 6.1-6.3 TB/s
-// this way against 5.7 TB/s with ordinary loads.  (The compaction's shift, which
-// reads and writes the same lines, measured no better with them.)
+// 16-byte loads / stores of data that is touched once per launch (K and V rows):
+// marked non-temporal so that they stream through the caches instead of
+// displacing lines.  On MI355X the decode kernel reads 6.1-6.3 TB/s this way
+// against 5.7 TB/s with ordinary loads.
 typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ uint4 stream_load(const uint4* p) {
     const u32x4_t v = __builtin_nontemporal_load((const u32x4_t*)p);
     return make_uint4(v.x, v.y, v.z, v.w);
 }
+__device__ __forceinline__ void stream_store(uint4* p, const uint4& v) {
+    u32x4_t t;
+    t.x = v.x;
+    t.y = v.y;
+    t.z = v.z;
+    t.w = v.w;
+    __builtin_nontemporal_store(t, (u32x4_t*)p);
+}
+
 // ---------------------------------------------------------------- noise hash
 // Counter-based generator keyed by (seed, layer, head, query position, key's
 // original position).  The paper only names the distribution of the logit
