@@ -221,6 +221,18 @@ __global__ void __launch_bounds__(kPrefillThreads) prefill_colsum_kernel(const P
 #pragma unroll
         for (int g = 0; g < NG; ++g) aq[g] = *(const uint4*)(row + g * 2 * EPV);
     }
+    // row statistics (normaliser, noise key) of the tile's 16 rows this lane sees: fetched one tile ahead
+    float4 c4[4];
+    uint4 r4[4];
+    auto load_stats = [&](int ib) {
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+            const int ir = ib + q4 * 8 + half * 4;  // 4 consecutive query rows, 16-byte aligned
+            c4[q4] = *(const float4*)(wc + ir);
+            r4[q4] = *(const uint4*)(wr + ir);
+        }
+    };
+    load_stats(it_begin * kTile);
     for (int it = it_begin; it <= it_end; ++it) {
         f32x16 acc;
 #pragma unroll
@@ -237,11 +249,9 @@ __global__ void __launch_bounds__(kPrefillThreads) prefill_colsum_kernel(const P
         float z[16];
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
-            const int ir = ib + q4 * 8 + half * 4;  // 4 consecutive query rows, 16-byte aligned stats
-            const float4 c4 = *(const float4*)(wc + ir);
-            const uint4 r4 = *(const uint4*)(wr + ir);
-            const float cs[4] = {c4.x, c4.y, c4.z, c4.w};
-            const uint32_t rs[4] = {r4.x, r4.y, r4.z, r4.w};
+            const int ir = ib + q4 * 8 + half * 4;
+            const float cs[4] = {c4[q4].x, c4[q4].y, c4[q4].z, c4[q4].w};
+            const uint32_t rs[4] = {r4[q4].x, r4[q4].y, r4[q4].z, r4[q4].w};
             const float dist0 = (float)(ir - j);
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
@@ -251,6 +261,7 @@ __global__ void __launch_bounds__(kPrefillThreads) prefill_colsum_kernel(const P
                 z[q4 * 4 + e] = hw_exp2(y - cs[e]);
             }
         }
+        if (it < it_end) load_stats(ib + kTile);  // in flight during the next tile's MFMAs
         if (edge) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
