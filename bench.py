@@ -236,10 +236,33 @@ def main():
         assert int(cache.len.min()) == wl.k and int(cache.len.max()) == wl.k
         return {"steps_per_s": round(K_steps / dt_, 2), "ms_per_step": round(dt_ * 1e3 / K_steps, 4)}
 
+    def graph_variant(layout):
+        """The same K fused steps captured once in a HIP graph and replayed: no launch gaps, no host work."""
+        base_t = W_steps + K_steps + 8
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for i in range(K_steps):
+                t = base_t + 4 + i
+                q, kn, vn = steps_in[(t - 1) % n_distinct]
+                kf.kf_decode_select_step(cache, q, kn, vn, wl.n + t - 1, m, kf.kf_tau(min(t, wl.T), wl.T), wl.scale,
+                                         noise, seeds, slopes, out, k=wl.k, w=wl.w, layout=layout, workspace=ws)
+        g.replay()                      # warm replay
+        torch.cuda.synchronize()
+        c0 = time.perf_counter()
+        g.replay()
+        torch.cuda.synchronize()
+        dt_ = time.perf_counter() - c0
+        assert int(ws[:4].view(torch.int32)[0].item()) == 0
+        assert int(cache.len.min()) == wl.k and int(cache.len.max()) == wl.k
+        return {"steps_per_s": round(K_steps / dt_, 2), "ms_per_step": round(dt_ * 1e3 / K_steps, 4)}
+
     variants = None
     if not args.no_variants:
         variants = {"fused_step_ordered_layout": timed_variant(kf.LAYOUT_ORDERED),
-                    "fused_step_slot_layout": timed_variant(kf.LAYOUT_SLOT)}   # slot layout last: it unsorts the cache
+                    "graph_fused_step_ordered_layout": graph_variant(kf.LAYOUT_ORDERED),
+                    # slot layout last: it unsorts the cache
+                    "fused_step_slot_layout": timed_variant(kf.LAYOUT_SLOT),
+                    "graph_fused_step_slot_layout": graph_variant(kf.LAYOUT_SLOT)}
 
     # prompt-phase scoring: dense causal QK^T twice (row statistics, column sums)
     prefill_flops = wl.units * 2 * (2.0 * wl.d * wl.n * (wl.n + 1) / 2)

@@ -438,3 +438,48 @@ def test_fused_step_equals_the_two_calls(dtype, d, cap, layout):
     ref = oc.copy()
     out_ref = ref.decode_step(q, kn, vn, cap + 3, 1.6, 0.11, ko.NOISE_GUMBEL, seeds)
     assert_close_out(results[0][0], out_ref)
+
+
+def test_steps_captured_in_a_hip_graph_replay_exactly():
+    """A run of fused steps captured in a HIP graph must reproduce the eager run bit for bit on every
+    replay (the library records no memset nodes; eager work and synchronisation sit between replays)."""
+    wl = kw.CONFIGS["gptj"].slice(L=2, H=16, T=512)      # 32 units: several splits, merge in the tail kernel
+    rng = np.random.default_rng(77)
+    k, cap = wl.k, wl.k + 1
+    oc = random_cache(rng, wl.L, wl.B, wl.H, wl.d, cap, ko.BF16, k)
+    oc.pos[...] = np.arange(cap)
+    state0 = upload(oc)
+    seeds = dev(kw.noise_seeds(wl))
+    steps = [tuple(t.cuda() for t in kw.decode_inputs(wl, t)) for t in range(1, 7)]
+    out = torch.zeros((wl.L, wl.B, wl.H, wl.d), dtype=torch.float32, device="cuda")
+    gc = upload(oc)
+    ws = kf.new_workspace(gc)
+
+    def restore():
+        for nm in ("K", "V", "score", "pos", "len"):
+            getattr(gc, nm).copy_(getattr(state0, nm))
+
+    def run():
+        for i, (q, kn, vn) in enumerate(steps):
+            kf.kf_decode_select_step(gc, q, kn, vn, cap + i, cap, kf.kf_tau(i + 1, wl.T), wl.scale, kf.NOISE_GUMBEL,
+                                     seeds, None, out, k=k, w=wl.w, layout=kf.LAYOUT_ORDERED, workspace=ws)
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return [host(t).copy() for t in (out, gc.K, gc.V, gc.score, gc.pos, gc.len)]
+
+    run()                               # eager reference (also loads the kernels before capture)
+    ref = snapshot()
+    restore()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        run()
+    for rep in range(4):
+        restore()
+        (out * 0).sum().item()          # unrelated eager work + a synchronisation between replays
+        g.replay()
+        got = snapshot()
+        for a, b in zip(got, ref):
+            np.testing.assert_array_equal(a, b)
+    assert error_word(ws) == 0
