@@ -110,6 +110,12 @@ uint32_t kf_noise_bits(uint64_t seed, uint32_t layer, uint32_t head, uint32_t q_
  * used).  Only the cache's dimensions are read. */
 size_t kf_workspace_bytes(const kf_cache *c, int32_t n_max);
 
+/* How kf_decode_step would shape its launch for this cache and m_hint (0 = cap):
+ * *splits = workgroups per unit, *chunk = cache rows per workgroup.  Host only;
+ * for callers that want to reason about occupancy.  Returns KF_EINVAL /
+ * KF_EUNSUPPORTED like the hot calls. */
+kf_status kf_decode_launch_shape(const kf_cache *c, int32_t m_hint, int32_t *splits, int32_t *chunk);
+
 /* Device-side error counter: the first int32 of the workspace counts units a
  * kernel had to skip (kf_decode_step on a unit with len >= cap, kf_select_evict in
  * the SLOT layout on a unit more than one token over budget).  Exposed as a

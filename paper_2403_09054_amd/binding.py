@@ -20,7 +20,8 @@ KF_OK, KF_EINVAL, KF_EUNSUPPORTED, KF_EWORKSPACE, KF_EDEVICE = 0, -1, -2, -3, -4
 
 # every symbol include/keyformer.h declares
 SYMBOLS = ("kf_version", "kf_last_error", "kf_tau", "kf_noise_bits", "kf_workspace_bytes",
-           "kf_prefill_score", "kf_decode_step", "kf_select_evict", "kf_decode_select_step")
+           "kf_prefill_score", "kf_decode_step", "kf_select_evict", "kf_decode_select_step",
+           "kf_decode_launch_shape")
 
 
 class KeyformerError(RuntimeError):
@@ -67,6 +68,9 @@ def lib():
         L.kf_noise_bits.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32]
         L.kf_workspace_bytes.restype = C.c_size_t
         L.kf_workspace_bytes.argtypes = [C.POINTER(kf_cache), C.c_int32]
+        L.kf_decode_launch_shape.restype = C.c_int
+        L.kf_decode_launch_shape.argtypes = [C.POINTER(kf_cache), C.c_int32, C.POINTER(C.c_int32),
+                                             C.POINTER(C.c_int32)]
         L.kf_prefill_score.restype = C.c_int
         L.kf_prefill_score.argtypes = [C.POINTER(kf_cache), vp, C.c_int32, C.POINTER(kf_score_cfg), vp,
                                        C.c_size_t, vp]
@@ -145,6 +149,14 @@ class Cache:
 def kf_workspace_bytes(cache: Cache, n_max: int = 0) -> int:
     cs = cache.c_struct()
     return int(lib().kf_workspace_bytes(C.byref(cs), n_max))
+
+
+def kf_decode_launch_shape(cache: Cache, m_hint: int = 0):
+    """(splits per unit, cache rows per split) of the decode launch for this cache."""
+    cs = cache.c_struct()
+    S, chunk = C.c_int32(0), C.c_int32(0)
+    _check(lib().kf_decode_launch_shape(C.byref(cs), m_hint, C.byref(S), C.byref(chunk)))
+    return S.value, chunk.value
 
 
 def new_workspace(cache: Cache, n_max: int = 0, device="cuda"):

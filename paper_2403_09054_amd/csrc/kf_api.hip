@@ -118,6 +118,18 @@ size_t kf_workspace_bytes(const kf_cache* c, int32_t n_max) {
     return ws_layout(c, n_max).total;
 }
 
+kf_status kf_decode_launch_shape(const kf_cache* c, int32_t m_hint, int32_t* splits, int32_t* chunk) {
+    if (!c || !splits || !chunk) return fail(KF_EINVAL, "NULL argument");
+    if (c->L < 1 || c->B < 1 || c->H < 1 || c->cap < 1) return fail(KF_EINVAL, "cache dimensions must be positive");
+    if (!supported(c->dtype, c->d))
+        return fail(KF_EUNSUPPORTED, "dtype %d with head dimension %d is not built", c->dtype, c->d);
+    if (m_hint < 0 || m_hint > c->cap) return fail(KF_EINVAL, "m_hint %d outside [0, cap=%d]", m_hint, c->cap);
+    const kf::DecodePlan p = kf::plan_decode((int64_t)c->L * c->B * c->H, m_hint ? m_hint : c->cap, c->d, c->dtype);
+    *splits = p.S;
+    *chunk = p.chunk;
+    return KF_OK;
+}
+
 kf_status kf_prefill_score(const kf_cache* c, const void* Q, int32_t n, const kf_score_cfg* cfg, void* workspace,
                            size_t workspace_bytes, void* stream) {
     kf_status st = check_cache(c);

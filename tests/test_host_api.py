@@ -125,6 +125,26 @@ def test_prefill_argument_validation():
     expect(binding.KF_EWORKSPACE, kf.kf_prefill_score, c, 0x1000, 128, **dict(cfg, workspace=(0x100000, 4096)))
 
 
+def test_decode_launch_shape_covers_the_rows_and_balances_the_chip():
+    # (L, B, H, d, cap, dtype, m_hint): the five workload shapes plus odd ones
+    shapes = [(1, 1, 2, 64, 65, kf.F32, 65), (28, 1, 16, 256, 1025, kf.BF16, 1025), (32, 8, 32, 128, 2049, kf.BF16, 2049),
+              (32, 1, 32, 128, 9831, kf.BF16, 9831), (32, 64, 32, 128, 1025, kf.BF16, 1025),
+              (1, 1, 1, 128, 600000, kf.BF16, 0), (3, 1, 5, 64, 777, kf.BF16, 500), (1, 1, 1, 64, 1, kf.F32, 1)]
+    for (L, B, H, d, cap, dt, hint) in shapes:
+        c = fake_cache(L=L, B=B, H=H, d=d, cap=cap, dtype=dt)
+        S, chunk = kf.kf_decode_launch_shape(c, hint)
+        rows = (hint or cap) - 1
+        assert 1 <= S <= 256 and 1 <= chunk <= 4096
+        assert S * chunk >= rows                      # every cache row belongs to a split
+        assert (S - 1) * chunk < max(rows, 1) or S == 1   # no split is entirely beyond the rows
+    # the GPT-J-shaped workload: 448 units -> 4 splits of 256 rows = 1792 workgroups = 7 per compute unit
+    assert kf.kf_decode_launch_shape(fake_cache(L=28, B=1, H=16, d=256, cap=1025), 1025) == (4, 256)
+    # plenty of units: one workgroup per unit, nothing to merge
+    assert kf.kf_decode_launch_shape(fake_cache(L=32, B=64, H=32, d=128, cap=1025), 1025)[0] == 1
+    expect(binding.KF_EINVAL, kf.kf_decode_launch_shape, fake_cache(), 2000)
+    expect(binding.KF_EUNSUPPORTED, kf.kf_decode_launch_shape, fake_cache(d=96), 0)
+
+
 def test_decode_launch_plan_is_consistent_with_workspace():
     # the workspace a cache asks for must cover the decode plan at every hint:
     # probe through the public size query on a grid of shapes
