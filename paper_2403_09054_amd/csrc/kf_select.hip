@@ -29,7 +29,8 @@
 
 namespace kf {
 
-constexpr int kSelectThreads = 1024;
+constexpr int kSelectThreads = 1024;     // ordered layout: many rows move, many waves stream them
+constexpr int kSelectThreadsSlot = 512;  // slot layout: one row moves, smaller workgroups finish sooner
 constexpr int kSelectGroups = 4;  // row groups a thread holds in registers per tile
 constexpr int kShiftDepth = 8;    // independent 16-byte loads a lane keeps in flight while shifting
 
@@ -409,18 +410,28 @@ __global__ void __launch_bounds__(NT) step_tail_kernel(const DecodeArgs d, const
     select_unit<NT>(a, u);
 }
 
-hipError_t launch_step_tail(const DecodeArgs& d, const SelectArgs& a, int64_t U, int32_t hd, hipStream_t stream) {
-    const dim3 grid((unsigned)U), block(kSelectThreads);
-    if (hd == 64) hipLaunchKernelGGL((step_tail_kernel<64, kSelectThreads>), grid, block, 0, stream, d, a);
-    else if (hd == 128) hipLaunchKernelGGL((step_tail_kernel<128, kSelectThreads>), grid, block, 0, stream, d, a);
-    else if (hd == 256) hipLaunchKernelGGL((step_tail_kernel<256, kSelectThreads>), grid, block, 0, stream, d, a);
+template <int NT>
+static hipError_t launch_step_tail_nt(const DecodeArgs& d, const SelectArgs& a, int64_t U, int32_t hd,
+                                      hipStream_t stream) {
+    const dim3 grid((unsigned)U), block(NT);
+    if (hd == 64) hipLaunchKernelGGL((step_tail_kernel<64, NT>), grid, block, 0, stream, d, a);
+    else if (hd == 128) hipLaunchKernelGGL((step_tail_kernel<128, NT>), grid, block, 0, stream, d, a);
+    else if (hd == 256) hipLaunchKernelGGL((step_tail_kernel<256, NT>), grid, block, 0, stream, d, a);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }
 
+hipError_t launch_step_tail(const DecodeArgs& d, const SelectArgs& a, int64_t U, int32_t hd, hipStream_t stream) {
+    if (a.layout == KF_LAYOUT_SLOT) return launch_step_tail_nt<kSelectThreadsSlot>(d, a, U, hd, stream);
+    return launch_step_tail_nt<kSelectThreads>(d, a, U, hd, stream);
+}
+
 hipError_t launch_select(const SelectArgs& a, int64_t U, hipStream_t stream) {
-    const dim3 grid((unsigned)U), block(kSelectThreads);
-    hipLaunchKernelGGL((select_kernel<kSelectThreads>), grid, block, 0, stream, a);
+    const dim3 grid((unsigned)U);
+    if (a.layout == KF_LAYOUT_SLOT)
+        hipLaunchKernelGGL((select_kernel<kSelectThreadsSlot>), grid, dim3(kSelectThreadsSlot), 0, stream, a);
+    else
+        hipLaunchKernelGGL((select_kernel<kSelectThreads>), grid, dim3(kSelectThreads), 0, stream, a);
     return hipGetLastError();
 }
 
