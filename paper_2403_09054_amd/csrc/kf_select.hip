@@ -38,21 +38,73 @@ constexpr int kShiftDepth = 8;    // independent 16-byte loads a lane keeps in f
 // candidate with the smallest score, the highest slot among equal minima (so
 // that lower slots are kept), then close the gap: rows e+1..k move down by one.
 //
-// The shift needs no synchronisation beyond one barrier.  Waves 2.. split the
-// moving rows into contiguous ranges; a lane owns one 16-byte piece of a row,
-// the two halves of a wave take K and V.  A wave walks its range upwards,
-// several rows in flight: row i+1 is loaded before row i is stored, loads
-// return in order, and the wave is the only writer of its range, so it never
-// overwrites a row it still has to read.  The one row it reads from its
-// neighbour's range (the first row above its own) is loaded before the barrier;
-// the neighbour stores only after it.  Waves 0 and 1 shift score and pos the
-// same way, 64 elements per instruction.  Row loads and stores are non-temporal:
-// the shifted rows are not needed again before the next step's full sweep, and
-// leaving them out of the caches shortens that sweep (the following decode launch
-// ran 93 -> 83 us on the GPT-J-shaped workload, this kernel 47 -> 51 us).
+// The rows that move are the candidates behind the evicted slot (usually a
+// handful) and the whole recent window (always, whatever slot is evicted).  The
+// window part therefore starts before the evicted slot is known: waves 2.. own
+// fixed contiguous ranges of it and have their first rows in flight while the
+// min-reduction runs.  A lane owns one 16-byte piece of a row, the two halves of
+// a wave take K and V.  A wave walks its range upwards, several rows in flight:
+// row i+1 is loaded before row i is stored, loads return in order, and the wave
+// is the only writer of its range, so it never overwrites a row it still has to
+// read.  The one row it reads from its neighbour's range (the first row above
+// its own) is loaded before the barrier; the neighbour stores only after it.
+// The candidate part is read completely before that same barrier -- into
+// registers when it is short, by a streaming pass of its own when it is long --
+// because its last source row is the window part's first destination.
+// Waves 0 and 1 shift score and pos the same way, 64 elements per instruction.
+// Row loads and stores are non-temporal: the shifted rows are not needed again
+// before the next step's full sweep, and leaving them out of the caches shortens
+// that sweep (the following decode launch ran 93 -> 83 us on the GPT-J-shaped
+// workload, this kernel 47 -> 51 us).
+struct RowLane {  // what a lane needs to address its piece of a row
+    uint4* base;
+    int PPR, RPI, rsub, piece;
+    __device__ __forceinline__ uint4* at(int row) const { return base + (size_t)row * PPR + piece; }
+};
+
+// Streams dst rows [r0, r1) <- src rows [r0+1, r1+1) of one wave's range.  `first`
+// holds the already loaded sources of the range's first G instructions, `last`
+// those of its last instruction (the only rows read from beyond the range).
+template <int G>
+__device__ __forceinline__ void shift_range(const RowLane& L, int r0, int NI, const uint4 (&first)[G], bool has_last,
+                                            int last_i, const uint4& last) {
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+        if (g < NI - 1) stream_store(L.at(r0 + g * L.RPI + L.rsub), first[g]);
+    for (int ii = G; ii < NI - 1; ii += G) {
+        uint4 regs[G];
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            regs[g] = make_uint4(0u, 0u, 0u, 0u);
+            if (ii + g < NI - 1) regs[g] = stream_load(L.at(r0 + (ii + g) * L.RPI + L.rsub + 1));
+        }
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+            if (ii + g < NI - 1) stream_store(L.at(r0 + (ii + g) * L.RPI + L.rsub), regs[g]);
+    }
+    if (has_last) stream_store(L.at(last_i), last);
+}
+
+// Loads what shift_range needs up front: the first G instructions' sources and the last one's.
+template <int G>
+__device__ __forceinline__ void preload_range(const RowLane& L, int r0, int r1, int& NI, uint4 (&first)[G],
+                                              bool& has_last, int& last_i, uint4& last) {
+    NI = r0 < r1 ? (r1 - r0 + L.RPI - 1) / L.RPI : 0;  // wave instructions of this range
+    last_i = r0 + (NI - 1) * L.RPI + L.rsub;
+    has_last = NI > 0 && last_i < r1;
+    last = make_uint4(0u, 0u, 0u, 0u);
+    if (has_last) last = stream_load(L.at(last_i + 1));
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        first[g] = make_uint4(0u, 0u, 0u, 0u);
+        if (g < NI - 1) first[g] = stream_load(L.at(r0 + g * L.RPI + L.rsub + 1));
+    }
+}
+
 template <int NT>
 __device__ __forceinline__ void evict_one(const SelectArgs& a, int64_t u, int n, bool write_idx) {
     constexpr int NW = NT / kWave;
+    constexpr int NRW = NW - 2;  // waves that move rows
     constexpr int G = kShiftDepth;
     __shared__ unsigned long long wmin[NW];
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
@@ -61,12 +113,37 @@ __device__ __forceinline__ void evict_one(const SelectArgs& a, int64_t u, int n,
     float* fu = a.score + (size_t)u * a.cap;
     int32_t* pu = a.pos + (size_t)u * a.cap;
 
+    RowLane L;
+    L.PPR = a.row_bytes >> 4;  // 16-byte pieces per row: 8, 16 or 32
+    L.RPI = 32 / L.PPR;        // rows per wave instruction (each half of the wave one tensor)
+    L.rsub = (lane & 31) / L.PPR;
+    L.piece = lane % L.PPR;
+    L.base = (uint4*)((char*)((lane >> 5) ? a.V : a.K) + (size_t)u * a.cap * a.row_bytes);
+    auto range_of = [&](int lo, int hi, int& r0, int& r1) {  // this wave's share of dst rows [lo, hi)
+        int per = (hi - lo + NRW - 1) / NRW;
+        per = (per + L.RPI - 1) / L.RPI * L.RPI;
+        r0 = min(hi, lo + (wv - 2) * per);
+        r1 = min(hi, r0 + per);
+    };
+
+    // candidate scores first, so that they return ahead of the row loads issued next
     // smallest (key, -slot): the low word holds ~slot so that the highest slot wins a tie
     unsigned long long best = ~0ull;
     for (int j = tid; j < ncand; j += NT) {
         const unsigned long long pack = ((unsigned long long)float_key(fu[j]) << 32) | (uint32_t)(~(uint32_t)j);
         best = pack < best ? pack : best;
     }
+
+    // ---- window part, dst rows [ncand-1, k): in flight before the evicted slot is known
+    const int w_lo = max(ncand - 1, 0);
+    int wr0 = 0, wr1 = 0, wNI = 0, wlast_i = 0;
+    bool whas_last = false;
+    uint4 wfirst[G], wlast = make_uint4(0u, 0u, 0u, 0u);
+    if (wv >= 2) {
+        range_of(w_lo, k, wr0, wr1);
+        preload_range<G>(L, wr0, wr1, wNI, wfirst, whas_last, wlast_i, wlast);
+    }
+
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) {
         const unsigned long long t = __shfl_xor(best, o, kWave);
@@ -84,40 +161,42 @@ __device__ __forceinline__ void evict_one(const SelectArgs& a, int64_t u, int n,
         for (int i = tid; i < k; i += NT) idx[i] = i + (i >= e ? 1 : 0);
     }
 
-    if (wv >= 2) {
-        // ---- K and V rows
-        const int PPR = a.row_bytes >> 4;  // 16-byte pieces per row: 8, 16 or 32
-        const int RPI = 32 / PPR;          // rows per wave instruction (each half of the wave one tensor)
-        const int half = lane >> 5, rsub = (lane & 31) / PPR, piece = lane % PPR;
-        uint4* base = (uint4*)((char*)(half ? a.V : a.K) + (size_t)u * a.cap * a.row_bytes);
-        const int R = k - e;               // rows that move
-        int per = (R + (NW - 2) - 1) / (NW - 2);
-        per = (per + RPI - 1) / RPI * RPI;
-        const int r0 = e + (wv - 2) * per, r1 = min(k, r0 + per);
-        const int NI = r0 < r1 ? (r1 - r0 + RPI - 1) / RPI : 0;  // wave instructions of this range
-        // last instruction's sources: the only rows read from beyond the own range
-        const int last_i = r0 + (NI - 1) * RPI + rsub;
-        const bool has_last = NI > 0 && last_i < r1;
-        uint4 last = make_uint4(0u, 0u, 0u, 0u);
-        if (has_last) last = stream_load(&base[(size_t)(last_i + 1) * PPR + piece]);
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-        for (int ii = 0; ii < NI - 1; ii += G) {
-            uint4 regs[G];
-#pragma unroll
-            for (int g = 0; g < G; ++g) {
-                regs[g] = make_uint4(0u, 0u, 0u, 0u);
-                if (ii + g < NI - 1) regs[g] = stream_load(&base[(size_t)(r0 + (ii + g) * RPI + rsub + 1) * PPR + piece]);
-            }
-#pragma unroll
-            for (int g = 0; g < G; ++g)
-                if (ii + g < NI - 1) stream_store(&base[(size_t)(r0 + (ii + g) * RPI + rsub) * PPR + piece], regs[g]);
+    // ---- candidate part, dst rows [e, ncand-1)
+    const int c = w_lo - e;                 // rows of it (>= 0)
+    const bool c_in_regs = c <= NRW * L.RPI;  // one instruction per wave covers it
+    uint4 creg = make_uint4(0u, 0u, 0u, 0u);
+    int crow = -1;
+    if (c > 0 && !c_in_regs) {
+        // long: a streaming pass of its own, finished (reads and writes) before the window part stores
+        if (wv >= 2) {
+            int r0, r1, NI, last_i;
+            bool has_last;
+            uint4 first[G], last;
+            range_of(e, w_lo, r0, r1);
+            preload_range<G>(L, r0, r1, NI, first, has_last, last_i, last);
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+            shift_range<G>(L, r0, NI, first, has_last, last_i, last);
+        } else {
+            __syncthreads();
         }
-        if (has_last) stream_store(&base[(size_t)last_i * PPR + piece], last);
+    } else if (c > 0 && wv >= 2) {
+        const int r = e + (wv - 2) * L.RPI + L.rsub;
+        if (r < w_lo) {
+            crow = r;
+            creg = stream_load(L.at(r + 1));
+        }
+    }
+    // every source row that another wave will overwrite has been read
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+
+    if (wv >= 2) {
+        if (crow >= 0) stream_store(L.at(crow), creg);
+        shift_range<G>(L, wr0, wNI, wfirst, whas_last, wlast_i, wlast);
     } else {
-        // ---- score (wave 0) and pos (wave 1): one wave owns the whole range
+        // ---- score (wave 0) and pos (wave 1): one wave owns the whole range [e, k)
         uint32_t* arr = wv == 0 ? (uint32_t*)fu : (uint32_t*)pu;
-        __syncthreads();
         for (int i0 = e; i0 < k; i0 += kWave * G) {
             uint32_t regs[G];
 #pragma unroll
