@@ -282,18 +282,8 @@ __global__ void __launch_bounds__(NT) decode_kernel(const DecodeArgs a) {
         se += e;
     }
     block_sum2<NT>(sp, se, red_s);  // its barriers also publish the attention weights in xs
-    if (S == 1) {
-        // the whole unit is here: accumulate the normalised score increment
-        const float inv = 1.0f / se;
-        for (int t = tid; t < cnt; t += NT) {
-            const int slot = (t == cnt_c) ? len0 : j0 + t;
-            const float prev = (t == cnt_c) ? 0.0f : fu[slot];
-            fu[slot] = prev + ys[t] * inv;
-        }
-    } else {
-        float* we = a.ws_e + (size_t)u * a.cap;
-        for (int t = tid; t < cnt; t += NT) we[(t == cnt_c) ? len0 : j0 + t] = ys[t];
-    }
+    // (The score increments in ys are written out after the V stream: stores issued here
+    // would have to drain before the first V tile could be consumed.)
 
     // ---- phase 2: stream V, weighted sum
     float acc[EPV];
@@ -356,9 +346,22 @@ __global__ void __launch_bounds__(NT) decode_kernel(const DecodeArgs a) {
     }
 
     if (S == 1) {
+        // the whole unit is here: accumulate the normalised score increment
+        const float inv = 1.0f / se;
+        for (int t = tid; t < cnt; t += NT) {
+            const int slot = (t == cnt_c) ? len0 : j0 + t;
+            // existing scores take the increment as a fire-and-forget atomic add at the L2: no load,
+            // no round trip (one add per address and launch, so the result is the plain fp32 sum)
+            if (t == cnt_c) fu[slot] = ys[t] * inv;
+            else unsafeAtomicAdd(&fu[slot], ys[t] * inv);
+        }
         if (tid < D) a.out[u * D + tid] = o_c / sp;
         if (tid == 0) a.len[u] = m;
         return;
+    }
+    {
+        float* we = a.ws_e + (size_t)u * a.cap;
+        for (int t = tid; t < cnt; t += NT) we[(t == cnt_c) ? len0 : j0 + t] = ys[t];
     }
 
     // ---- S > 1: leave a partial record for the merge

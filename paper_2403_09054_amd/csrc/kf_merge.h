@@ -46,8 +46,9 @@ __device__ __forceinline__ void merge_unit(const DecodeArgs& a, int64_t u, int l
     const float* we = a.ws_e + (size_t)u * a.cap;
     const float inv = 1.0f / sumE;
     for (int j = tid; j < m; j += NT) {
-        const float prev = (j == len0) ? 0.0f : fu[j];
-        fu[j] = prev + we[j] * (w_e[(j == len0) ? S - 1 : j / a.chunk] * inv);  // the new token belongs to the last split
+        const float df = we[j] * (w_e[(j == len0) ? S - 1 : j / a.chunk] * inv);  // the new token belongs to the last split
+        if (j == len0) fu[j] = df;
+        else unsafeAtomicAdd(&fu[j], df);  // fire-and-forget add at the L2 (one per address: the plain fp32 sum)
     }
     if (tid == 0) a.len[u] = m;
 }
