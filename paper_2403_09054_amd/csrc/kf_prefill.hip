@@ -52,6 +52,22 @@ struct Mma<float> {
     }
 };
 
+// Workgroup -> (unit, block of 128 rows).  Consecutive workgroup ids are dealt
+// round-robin to the chip's 8 XCDs, each with an L2 of its own; the blocks of
+// one unit re-read the same K / Q rows, so all blocks of a unit are given ids
+// that are equal modulo 8 and therefore share one L2.
+constexpr int kXcds = 8;
+__device__ __forceinline__ void unit_and_block(int nblk, int64_t& u, int& blk) {
+#ifdef KF_PREFILL_NO_XCD_MAP
+    u = blockIdx.x / nblk;
+    blk = (int)(blockIdx.x % nblk);
+#else
+    const unsigned xcd = blockIdx.x % kXcds, local = blockIdx.x / kXcds;
+    u = (int64_t)(local / nblk) * kXcds + xcd;
+    blk = (int)(local % nblk);
+#endif
+}
+
 // Row of the 32x32 accumulator tile that register r of this lane holds
 // (the column is lane % 32).
 __device__ __forceinline__ int acc_row(int r, int half) { return (r >> 2) * 8 + half * 4 + (r & 3); }
@@ -78,13 +94,16 @@ __device__ __forceinline__ float logit2_other(const LogitParams& lp, float acc, 
 
 // ------------------------------------------------------------------ pass 1
 template <typename T, int D>
-__global__ void __launch_bounds__(kPrefillThreads) prefill_rowstats_kernel(const PrefillArgs a, int nblk) {
+__global__ void __launch_bounds__(kPrefillThreads) prefill_rowstats_kernel(const PrefillArgs a, int nblk, int64_t units) {
     constexpr int EPV = ElemTraits<T>::kPerVec;
     constexpr int NG = D / (2 * EPV);
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int n0 = lane & 31, half = lane >> 5;
-    const int64_t u = blockIdx.x / nblk;
-    const int rb = nblk - 1 - (int)(blockIdx.x % nblk);  // longest rows first
+    int64_t u;
+    int blk;
+    unit_and_block(nblk, u, blk);
+    if (u >= units) return;
+    const int rb = nblk - 1 - blk;  // longest rows first
     const int n = a.n;
     const int i0 = rb * (4 * kTile) + wv * kTile;
     if (i0 >= n) return;  // wave-uniform; this kernel has no workgroup barrier
@@ -180,13 +199,15 @@ __global__ void __launch_bounds__(kPrefillThreads) prefill_rowstats_kernel(const
 
 // ------------------------------------------------------------------ pass 2
 template <typename T, int D>
-__global__ void __launch_bounds__(kPrefillThreads) prefill_colsum_kernel(const PrefillArgs a, int nblk) {
+__global__ void __launch_bounds__(kPrefillThreads) prefill_colsum_kernel(const PrefillArgs a, int nblk, int64_t units) {
     constexpr int EPV = ElemTraits<T>::kPerVec;
     constexpr int NG = D / (2 * EPV);
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int n0 = lane & 31, half = lane >> 5;
-    const int64_t u = blockIdx.x / nblk;
-    const int cb = (int)(blockIdx.x % nblk);  // longest columns (lowest keys) first
+    int64_t u;
+    int cb;  // longest columns (lowest keys) first
+    unit_and_block(nblk, u, cb);
+    if (u >= units) return;
     const int n = a.n;
     const int j0 = cb * (4 * kTile) + wv * kTile;
     if (cb == 0 && threadIdx.x == 0) a.len[u] = n;
@@ -282,11 +303,12 @@ __global__ void __launch_bounds__(kPrefillThreads) prefill_colsum_kernel(const P
 template <typename T, int D>
 static hipError_t launch_prefill_t(const PrefillArgs& a, int64_t U, hipStream_t st) {
     const int nblk = (a.n + 4 * kTile - 1) / (4 * kTile);
-    const dim3 grid((unsigned)(U * nblk)), block(kPrefillThreads);
-    hipLaunchKernelGGL((prefill_rowstats_kernel<T, D>), grid, block, 0, st, a, nblk);
+    const int64_t groups = (U + kXcds - 1) / kXcds;  // units are dealt to XCDs in groups of 8
+    const dim3 grid((unsigned)(groups * kXcds * nblk)), block(kPrefillThreads);
+    hipLaunchKernelGGL((prefill_rowstats_kernel<T, D>), grid, block, 0, st, a, nblk, U);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((prefill_colsum_kernel<T, D>), grid, block, 0, st, a, nblk);
+    hipLaunchKernelGGL((prefill_colsum_kernel<T, D>), grid, block, 0, st, a, nblk, U);
     return hipGetLastError();
 }
 
