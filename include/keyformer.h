@@ -79,6 +79,12 @@ typedef struct {
                        a cache that holds a subset of the layers draws the same noise */
 } kf_cache;
 
+/* Which positions the position bias sees (Sec. 4.4.2): the tokens' original
+ * positions ("Org Pos", the default and the better ablation), or their positions
+ * within the reduced cache ("New Pos": key j at slot j, the query at slot m-1).
+ * The noise key always uses original positions. */
+typedef enum { KF_POS_ORIGINAL = 0, KF_POS_NEW = 1 } kf_pos_mode;
+
 /* Parameters of the score function (Eq. 11) for one call. */
 typedef struct {
     float tau;                 /* temperature of this iteration, from kf_tau()            */
@@ -88,6 +94,7 @@ typedef struct {
                                   when noise is NONE or CONSTANT                          */
     const float *alibi_slopes; /* DEVICE [H] or NULL.  Adds -slope[h]*(q_pos - pos_j) to
                                   the logits (MPT's position bias)                        */
+    int32_t pos_mode;          /* kf_pos_mode; only matters with alibi_slopes, decode only */
 } kf_score_cfg;
 
 /* Library version, for the binding to check it loaded what it expects. */

@@ -267,7 +267,7 @@ int kfo_decode_step(void *K, void *V, float *score, int32_t *pos, int32_t *len,
                     int L, int B, int H, int d, int cap, int dtype, int layer0,
                     const void *q, const void *k_new, const void *v_new,
                     int32_t q_pos, float tau, float scale, int noise,
-                    const uint64_t *seeds, const float *slopes, float *out,
+                    const uint64_t *seeds, const float *slopes, int new_pos, float *out,
                     double *dbg_p, double *dbg_df)
 {
     if (!(tau > 0.0f)) return -1;
@@ -308,7 +308,11 @@ int kfo_decode_step(void *K, void *V, float *score, int32_t *pos, int32_t *len,
             for (int c = 0; c < d; ++c)
                 dot += load_elem(q, dtype, (size_t)u * d + c) *
                        load_elem(Ku, dtype, (size_t)j * d + c);
-            double x = (double)scale * dot - slope * (double)(q_pos - pu[j]);
+            /* distance behind the position bias: original positions ("Org Pos"), or -- the
+             * paper's "New Pos" ablation, Sec. 4.4.2 -- positions within the reduced cache,
+             * where the query sits at slot m-1 and key j at slot j */
+            double dist = new_pos ? (double)(m - 1 - j) : (double)(q_pos - pu[j]);
+            double x = (double)scale * dot - slope * dist;
             p[j] = x;
             y[j] = (x + zeta(noise, seed, (uint32_t)l, (uint32_t)h,
                              (uint32_t)q_pos, (uint32_t)pu[j])) / (double)tau;

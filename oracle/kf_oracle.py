@@ -56,7 +56,7 @@ def lib():
             C.c_float, C.c_float, C.c_int, vp, vp]
         L.kfo_decode_step.restype = C.c_int
         L.kfo_decode_step.argtypes = [vp, vp, vp, vp, vp] + [C.c_int] * 7 + [
-            vp, vp, vp, C.c_int32, C.c_float, C.c_float, C.c_int, vp, vp, vp, vp, vp]
+            vp, vp, vp, C.c_int32, C.c_float, C.c_float, C.c_int, vp, vp, C.c_int, vp, vp, vp]
         L.kfo_select_evict.restype = C.c_int
         L.kfo_select_evict.argtypes = [vp, vp, vp, vp, vp] + [C.c_int] * 8 + [vp]
         _lib = L
@@ -132,7 +132,7 @@ class OracleCache:
             raise ValueError("kfo_prefill_score rc=%d" % rc)
 
     def decode_step(self, q, k_new, v_new, q_pos, tau_, scale, noise=NOISE_GUMBEL,
-                    seeds=None, slopes=None, debug=False):
+                    seeds=None, slopes=None, debug=False, new_pos=False):
         """q, k_new, v_new: [L,B,H,d].  Returns out [L,B,H,d] float32
         (and, with debug, the attention probabilities and the score increment
         as float64 [L,B,H,cap])."""
@@ -147,7 +147,7 @@ class OracleCache:
         df = np.zeros(self.score.shape, np.float64) if debug else None
         rc = lib().kfo_decode_step(_p(self.K), _p(self.V), _p(self.score), _p(self.pos), _p(self.len),
                                    *self._dims(), self.layer0, _p(q), _p(k_new), _p(v_new), q_pos, tau_, scale,
-                                   noise, _p(seeds), _p(slopes), _p(out), _p(dp), _p(df))
+                                   noise, _p(seeds), _p(slopes), int(new_pos), _p(out), _p(dp), _p(df))
         if rc:
             raise ValueError("kfo_decode_step rc=%d" % rc)
         return (out, dp, df) if debug else out

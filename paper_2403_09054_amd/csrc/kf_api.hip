@@ -49,6 +49,8 @@ kf_status check_cfg(const kf_score_cfg* cfg) {
     if (!isfinite(cfg->scale)) return fail(KF_EINVAL, "scale must be finite");
     if (cfg->noise < KF_NOISE_NONE || cfg->noise > KF_NOISE_CONSTANT)
         return fail(KF_EINVAL, "unknown noise mode %d", cfg->noise);
+    if (cfg->pos_mode != KF_POS_ORIGINAL && cfg->pos_mode != KF_POS_NEW)
+        return fail(KF_EINVAL, "unknown pos_mode %d", cfg->pos_mode);
     if ((cfg->noise == KF_NOISE_GUMBEL || cfg->noise == KF_NOISE_GAUSSIAN) && !cfg->seeds)
         return fail(KF_EINVAL, "a random logit adjustment needs seeds");
     return KF_OK;
@@ -215,6 +217,7 @@ static kf_status prepare_decode(kf_cache* c, const void* q, const void* k_new, c
     a->chunk = p.chunk;
     a->q_pos = q_pos;
     a->noise = cfg->noise;
+    a->new_pos = cfg->pos_mode == KF_POS_NEW ? 1 : 0;
     a->inv_tau = 1.0f / cfg->tau;
     a->scale = cfg->scale;
     *plan = p;

@@ -264,7 +264,8 @@ __global__ void __launch_bounds__(NT) decode_kernel(const DecodeArgs a) {
     for (int t = tid; t < cnt; t += NT) {
         const int pj = (t == cnt_c) ? a.q_pos : pu[j0 + t];  // t == cnt_c: the new token
         // base-2 domain: x2 = log2(e)*x, y2 = log2(e)*(x + zeta)/tau
-        const float x = (xs[t] - slope * (float)(a.q_pos - pj)) * kLog2e;
+        const int dist = a.new_pos ? (len0 - (j0 + t)) : (a.q_pos - pj);  // the new token: 0 either way
+        const float x = (xs[t] - slope * (float)((t == cnt_c) ? 0 : dist)) * kLog2e;
         const float y = (x + zeta_log2e(a.noise, rkey, (uint32_t)pj)) * a.inv_tau;
         xs[t] = x;
         ys[t] = y;

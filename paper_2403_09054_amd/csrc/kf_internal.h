@@ -29,6 +29,7 @@ struct DecodeArgs {
     int32_t chunk;     // tokens per split
     int32_t q_pos;
     int32_t noise;
+    int32_t new_pos;   // position bias from slot indices instead of original positions
     float inv_tau;
     float scale;
 };

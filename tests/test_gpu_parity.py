@@ -483,3 +483,27 @@ def test_steps_captured_in_a_hip_graph_replay_exactly():
         for a, b in zip(got, ref):
             np.testing.assert_array_equal(a, b)
     assert error_word(ws) == 0
+
+
+@pytest.mark.parametrize("cap", [90, 900])
+def test_new_pos_mode_matches_oracle(cap):
+    rng = np.random.default_rng(cap)
+    L, B, H, d = 1, 2, 4, 128
+    lens = rng.integers(cap // 2, cap, (L, B, H)).astype(np.int32)
+    oc = random_cache(rng, L, B, H, d, cap, ko.BF16, lens)      # positions with gaps
+    q, kn, vn = (rnd(rng, (L, B, H, d), ko.BF16) for _ in range(3))
+    seeds = np.array([3, 4], np.uint64)
+    slopes = np.array([0.5, 0.125, 0.03125, 0.0], np.float32)
+    gc = upload(oc)
+    ws = kf.new_workspace(gc)
+    out = torch.zeros((L, B, H, d), dtype=torch.float32, device="cuda")
+    q_pos = int(oc.pos.max()) + 1
+    kf.kf_decode_step(gc, dev(q), dev(kn), dev(vn), q_pos, 0, 1.3, 0.09, kf.NOISE_GUMBEL, dev(seeds), dev(slopes),
+                      out, ws, pos_mode=kf.POS_NEW)
+    torch.cuda.synchronize()
+    org = oc.copy()
+    out_ref = oc.decode_step(q, kn, vn, q_pos, 1.3, 0.09, ko.NOISE_GUMBEL, seeds, slopes, new_pos=True)
+    assert_close_out(host(out), out_ref)
+    assert_close_score(host(gc.score), oc.score, oc.len)
+    out_org = org.decode_step(q, kn, vn, q_pos, 1.3, 0.09, ko.NOISE_GUMBEL, seeds, slopes)
+    assert np.abs(out_org - out_ref).max() > 1e-3        # the two modes really differ on this cache

@@ -297,6 +297,27 @@ def test_alibi_bias_favours_recent_tokens():
     assert (np.diff(dp[0, 0, 0, :n + 1]) > 0).all()
 
 
+def test_new_pos_mode_uses_slot_distances():
+    # Sec. 4.4.2 "New Pos": the position bias sees positions within the reduced cache.  With
+    # consecutive original positions ending at q_pos it coincides with "Org Pos"; with gaps
+    # (evicted tokens) it is the geometric decay in slot distance.
+    rng = np.random.default_rng(19)
+    n, slope = 9, 0.25
+    zero = np.zeros((1, 1, 1, 8), np.float32)
+    q = rand_vec(rng, (1, 1, 1, 8), ko.F32)
+    sl = np.array([slope], np.float32)
+    c = make_cache(rng, 1, 1, 1, 8, 16, n, pos=np.arange(n))
+    c2 = c.copy()
+    _, p_org, _ = c.decode_step(q, zero, zero, n, 1.0, 0.3, ko.NOISE_NONE, None, sl, debug=True)
+    _, p_new, _ = c2.decode_step(q, zero, zero, n, 1.0, 0.3, ko.NOISE_NONE, None, sl, debug=True, new_pos=True)
+    np.testing.assert_allclose(p_org, p_new, rtol=1e-13)
+    g = make_cache(rng, 1, 1, 1, 8, 16, n, pos=np.arange(n) * 5)
+    g.K[...] = 0
+    _, p_gap, _ = g.decode_step(q, zero, zero, 100, 1.0, 0.3, ko.NOISE_NONE, None, sl, debug=True, new_pos=True)
+    ref = np.exp(-slope * (n - np.arange(n + 1)))        # slot distances n, n-1, ..., 0
+    np.testing.assert_allclose(p_gap[0, 0, 0, :n + 1], ref / ref.sum(), rtol=1e-12)
+
+
 def test_decode_is_invariant_under_slot_permutation():
     # P12: the cache is a set of (pos, K, V, f) entries; permuting the slots
     # (with their positions) changes neither out nor the increments per position
