@@ -112,16 +112,12 @@ def main():
         ev[0].record()
         kf.kf_prefill_score(sub, Qs[:nl], wl.n, tau0, wl.scale, noise, seeds, slopes, ws_stage)
         ev[1].record()
-        kf.kf_select_evict(sub, wl.k, wl.w, None, ws_stage)
+        # first eviction n -> k, gathered straight into the generation cache (cap = k+1)
+        kf.kf_select_evict_into(sub, cache, l0, wl.k, wl.w, None, ws_stage)
         ev[2].record()
         torch.cuda.synchronize()
         prefill_ms += ev[0].elapsed_time(ev[1])
         first_select_ms += ev[1].elapsed_time(ev[2])
-        cache.K[l0:l0 + nl, :, :, : wl.k].copy_(stage.K[:nl, :, :, : wl.k])
-        cache.V[l0:l0 + nl, :, :, : wl.k].copy_(stage.V[:nl, :, :, : wl.k])
-        cache.score[l0:l0 + nl, :, :, : wl.k].copy_(stage.score[:nl, :, :, : wl.k])
-        cache.pos[l0:l0 + nl, :, :, : wl.k].copy_(stage.pos[:nl, :, :, : wl.k])
-        cache.len[l0:l0 + nl].copy_(stage.len[:nl])
     del Qs
     del stage, ws_stage
     torch.cuda.empty_cache()

@@ -179,6 +179,19 @@ kf_status kf_select_evict(kf_cache *c, int32_t k, int32_t w, int32_t layout, int
                           void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * The same selection (ordered layout), but the survivors are gathered into
+ * ANOTHER cache: layer l of `src` goes to layer dst_layer0 + l of `dst`, slots
+ * [0,k), in original order; dst len = min(src len, k).  `src` is not modified.
+ * This is the prompt-phase eviction (Sec. 3.4: n - k tokens are dropped right
+ * after the prompt) for callers that stage a layer's n-token prompt cache and
+ * keep only a (k+1)-token cache per layer for the generation.  B, H, d and
+ * dtype must agree, dst->cap >= k, and the two caches must not share buffers.
+ * The workspace is sized by the SOURCE cache (kf_workspace_bytes(src, ...)).
+ */
+kf_status kf_select_evict_into(const kf_cache *src, kf_cache *dst, int32_t dst_layer0, int32_t k, int32_t w,
+                               int32_t *kept_idx, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * One whole generation step: kf_decode_step followed by kf_select_evict, with
  * the same arguments, results and error behaviour as the two calls in a row,
  * in two kernel launches instead of three (the merge of the decode kernel's

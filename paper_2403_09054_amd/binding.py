@@ -21,7 +21,7 @@ KF_OK, KF_EINVAL, KF_EUNSUPPORTED, KF_EWORKSPACE, KF_EDEVICE = 0, -1, -2, -3, -4
 
 # every symbol include/keyformer.h declares
 SYMBOLS = ("kf_version", "kf_last_error", "kf_tau", "kf_noise_bits", "kf_workspace_bytes",
-           "kf_prefill_score", "kf_decode_step", "kf_select_evict", "kf_decode_select_step",
+           "kf_prefill_score", "kf_decode_step", "kf_select_evict", "kf_select_evict_into", "kf_decode_select_step",
            "kf_decode_launch_shape")
 
 
@@ -80,6 +80,9 @@ def lib():
                                      C.POINTER(kf_score_cfg), vp, vp, C.c_size_t, vp]
         L.kf_select_evict.restype = C.c_int
         L.kf_select_evict.argtypes = [C.POINTER(kf_cache), C.c_int32, C.c_int32, C.c_int32, vp, vp, C.c_size_t, vp]
+        L.kf_select_evict_into.restype = C.c_int
+        L.kf_select_evict_into.argtypes = [C.POINTER(kf_cache), C.POINTER(kf_cache), C.c_int32, C.c_int32, C.c_int32,
+                                           vp, vp, C.c_size_t, vp]
         L.kf_decode_select_step.restype = C.c_int
         L.kf_decode_select_step.argtypes = [C.POINTER(kf_cache), vp, vp, vp, C.c_int32, C.c_int32,
                                             C.POINTER(kf_score_cfg), vp, C.c_int32, C.c_int32, C.c_int32, vp, vp,
@@ -211,6 +214,14 @@ def kf_select_evict(cache: Cache, k: int, w: int, kept_idx=None, workspace=None,
     cs = cache.c_struct()
     wp, wb = _ws(workspace)
     _check(lib().kf_select_evict(C.byref(cs), k, w, layout, _ptr(kept_idx), wp, wb, _stream(stream)))
+
+
+def kf_select_evict_into(src: Cache, dst: Cache, dst_layer0: int, k: int, w: int, kept_idx=None, workspace=None,
+                         stream=None) -> None:
+    ss, ds = src.c_struct(), dst.c_struct()
+    wp, wb = _ws(workspace)
+    _check(lib().kf_select_evict_into(C.byref(ss), C.byref(ds), dst_layer0, k, w, _ptr(kept_idx), wp, wb,
+                                      _stream(stream)))
 
 
 def kf_decode_select_step(cache: Cache, q, k_new, v_new, q_pos: int, m_hint: int, tau: float, scale: float,

@@ -250,6 +250,7 @@ static kf_status prepare_select(kf_cache* c, int32_t k, int32_t w, int32_t layou
     a->row_bytes = c->d * (c->dtype == KF_F32 ? 4 : 2);
     a->idx_is_output = kept_idx ? 1 : 0;
     a->layout = layout;
+    a->move = 1;
     a->ws_err = (int32_t*)workspace + KF_WS_ERROR_WORD;
     (void)U;
     return KF_OK;
@@ -277,6 +278,52 @@ kf_status kf_select_evict(kf_cache* c, int32_t k, int32_t w, int32_t layout, int
     const int64_t U = (int64_t)c->L * c->B * c->H;
     const hipError_t e = kf::launch_select(a, U, (hipStream_t)stream);
     if (e != hipSuccess) return fail(KF_EDEVICE, "select launch: %s", hipGetErrorString(e));
+    g_err[0] = 0;
+    return KF_OK;
+}
+
+kf_status kf_select_evict_into(const kf_cache* src, kf_cache* dst, int32_t dst_layer0, int32_t k, int32_t w,
+                               int32_t* kept_idx, void* workspace, size_t workspace_bytes, void* stream) {
+    kf_status st = check_cache(dst);
+    if (st != KF_OK) return st;
+    if (!src) return fail(KF_EINVAL, "source cache is NULL");
+    if (src->B != dst->B || src->H != dst->H || src->d != dst->d || src->dtype != dst->dtype)
+        return fail(KF_EINVAL, "source and destination must agree in B, H, d and dtype");
+    if (dst_layer0 < 0 || dst_layer0 + src->L > dst->L)
+        return fail(KF_EINVAL, "layers [%d, %d) do not fit the destination's %d layers", dst_layer0,
+                    dst_layer0 + src->L, dst->L);
+    if (k > dst->cap) return fail(KF_EINVAL, "budget k=%d exceeds the destination capacity %d", k, dst->cap);
+    const char *s0 = (const char*)src->K, *d0 = (const char*)dst->K;
+    if (s0 == d0 || src->V == dst->V || src->score == dst->score)
+        return fail(KF_EINVAL, "source and destination must be different caches (use kf_select_evict in place)");
+    kf::SelectArgs a;
+    kf_cache src_mut = *src;  // the selection kernel only reads it in this mode
+    st = prepare_select(&src_mut, k, w, KF_LAYOUT_ORDERED, kept_idx, workspace, workspace_bytes, false, &a);
+    if (st != KF_OK) return st;
+    a.move = 0;
+    const int64_t U = (int64_t)src->L * src->B * src->H;
+    hipError_t e = kf::launch_select(a, U, (hipStream_t)stream);
+    if (e != hipSuccess) return fail(KF_EDEVICE, "select launch: %s", hipGetErrorString(e));
+    kf::GatherArgs g;
+    g.src_K = src->K;
+    g.src_V = src->V;
+    g.src_score = src->score;
+    g.src_pos = src->pos;
+    g.src_len = src->len;
+    g.dst_K = dst->K;
+    g.dst_V = dst->V;
+    g.dst_score = dst->score;
+    g.dst_pos = dst->pos;
+    g.dst_len = dst->len;
+    g.idx = a.idx;
+    g.units = U;
+    g.dst_unit0 = (int64_t)dst_layer0 * dst->B * dst->H;
+    g.src_cap = src->cap;
+    g.dst_cap = dst->cap;
+    g.k = k;
+    g.row_bytes = a.row_bytes;
+    e = kf::launch_gather(g, (hipStream_t)stream);
+    if (e != hipSuccess) return fail(KF_EDEVICE, "gather launch: %s", hipGetErrorString(e));
     g_err[0] = 0;
     return KF_OK;
 }

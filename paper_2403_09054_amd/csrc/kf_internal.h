@@ -55,9 +55,27 @@ struct SelectArgs {
     int32_t row_bytes;  // d * sizeof(element)
     int32_t idx_is_output;  // idx is the caller's kept_idx (must be complete), not scratch
     int32_t layout;         // kf_layout
+    int32_t move;           // 0: only write the survivor index list (rows are gathered elsewhere)
     int32_t* ws_err;        // [1] skipped-unit counter
 };
 hipError_t launch_select(const SelectArgs& a, int64_t U, hipStream_t stream);
+struct GatherArgs {
+    const void* src_K;
+    const void* src_V;
+    const float* src_score;
+    const int32_t* src_pos;
+    const int32_t* src_len;
+    void* dst_K;
+    void* dst_V;
+    float* dst_score;
+    int32_t* dst_pos;
+    int32_t* dst_len;
+    const int32_t* idx;  // [units][k] survivor slots in the source
+    int64_t units;       // units of the source cache
+    int64_t dst_unit0;   // first destination unit (dst_layer0 * B * H)
+    int32_t src_cap, dst_cap, k, row_bytes;
+};
+hipError_t launch_gather(const GatherArgs& g, hipStream_t stream);
 // decode merge + select + compact of every unit in one launch (after the split kernel of a fused step)
 hipError_t launch_step_tail(const DecodeArgs& d, const SelectArgs& a, int64_t U, int32_t hd, hipStream_t stream);
 // the split kernel alone (no merge launch): first half of a fused step

@@ -308,7 +308,7 @@ __device__ __forceinline__ void select_unit(const SelectArgs& a, int64_t u) {
     int32_t* idx = a.idx + (size_t)u * k;
 
     if (n <= k) {  // under budget: nothing leaves
-        if (a.idx_is_output)
+        if (a.idx_is_output || !a.move)
             for (int i = tid; i < k; i += NT) idx[i] = (i < n) ? i : -1;
         return;
     }
@@ -320,7 +320,7 @@ __device__ __forceinline__ void select_unit(const SelectArgs& a, int64_t u) {
         }
         return;
     }
-    if (n == k + 1) {  // decode shape
+    if (n == k + 1 && a.move) {  // decode shape
         evict_one<NT>(a, u, n, a.idx_is_output != 0);
         return;
     }
@@ -415,6 +415,7 @@ __device__ __forceinline__ void select_unit(const SelectArgs& a, int64_t u) {
     }
     for (int i = tid; i < w; i += NT) idx[nkey + i] = ncand + i;  // the recent window
     __syncthreads();  // idx and s_first are complete for the whole workgroup
+    if (!a.move) return;  // index list only: the rows are gathered into another cache by gather_kernel
 
     // ---- compact: front-to-back gather through registers
     const int PPR = a.row_bytes >> 4;  // 16-byte pieces per row
@@ -503,6 +504,59 @@ static hipError_t launch_step_tail_nt(const DecodeArgs& d, const SelectArgs& a, 
 hipError_t launch_step_tail(const DecodeArgs& d, const SelectArgs& a, int64_t U, int32_t hd, hipStream_t stream) {
     if (a.layout == KF_LAYOUT_SLOT) return launch_step_tail_nt<kSelectThreadsSlot>(d, a, U, hd, stream);
     return launch_step_tail_nt<kSelectThreads>(d, a, U, hd, stream);
+}
+
+// Out-of-place compaction: survivor i of unit u (slot idx[u][i] of the source
+// cache) goes to slot i of the destination cache.  Source and destination do
+// not overlap, so any number of workgroups can share a unit: a workgroup copies
+// kGatherRows rows, a lane one 16-byte piece of K or V.
+constexpr int kGatherThreads = 256;
+constexpr int kGatherRows = 64;
+
+__global__ void __launch_bounds__(kGatherThreads) gather_kernel(const GatherArgs g) {
+    const int64_t u = blockIdx.y + (int64_t)blockIdx.z * gridDim.y;
+    if (u >= g.units) return;
+    const int64_t ud = u + g.dst_unit0;
+    const int tid = threadIdx.x;
+    const int k = g.k;
+    const int32_t* idx = g.idx + (size_t)u * k;
+    const int row0 = blockIdx.x * kGatherRows;
+    const int PPR = g.row_bytes >> 4;
+    const uint4* Ks = (const uint4*)((const char*)g.src_K + (size_t)u * g.src_cap * g.row_bytes);
+    const uint4* Vs = (const uint4*)((const char*)g.src_V + (size_t)u * g.src_cap * g.row_bytes);
+    uint4* Kd = (uint4*)((char*)g.dst_K + (size_t)ud * g.dst_cap * g.row_bytes);
+    uint4* Vd = (uint4*)((char*)g.dst_V + (size_t)ud * g.dst_cap * g.row_bytes);
+    const int pieces = kGatherRows * PPR;  // per tensor
+    for (int p = tid; p < 2 * pieces; p += kGatherThreads) {
+        const int t = p >= pieces, q = t ? p - pieces : p;
+        const int i = row0 + q / PPR, piece = q % PPR;
+        if (i < k) {
+            const int s = idx[i];
+            if (s >= 0 && s < g.src_cap) {
+                const uint4 v = stream_load((t ? Vs : Ks) + (size_t)s * PPR + piece);
+                stream_store((t ? Vd : Kd) + (size_t)i * PPR + piece, v);
+            }
+        }
+    }
+    if (tid < kGatherRows) {
+        const int i = row0 + tid;
+        if (i < k) {
+            const int s = idx[i];
+            if (s >= 0 && s < g.src_cap) {
+                g.dst_score[(size_t)ud * g.dst_cap + i] = g.src_score[(size_t)u * g.src_cap + s];
+                g.dst_pos[(size_t)ud * g.dst_cap + i] = g.src_pos[(size_t)u * g.src_cap + s];
+            }
+        }
+    }
+    if (blockIdx.x == 0 && tid == 0) g.dst_len[ud] = min(g.src_len[u], k);
+}
+
+hipError_t launch_gather(const GatherArgs& g, hipStream_t stream) {
+    const unsigned gy = (unsigned)(g.units < 32768 ? g.units : 32768);
+    const unsigned gz = (unsigned)((g.units + gy - 1) / gy);
+    const dim3 grid((unsigned)((g.k + kGatherRows - 1) / kGatherRows), gy, gz);
+    hipLaunchKernelGGL(gather_kernel, grid, dim3(kGatherThreads), 0, stream, g);
+    return hipGetLastError();
 }
 
 hipError_t launch_select(const SelectArgs& a, int64_t U, hipStream_t stream) {

@@ -507,3 +507,49 @@ def test_new_pos_mode_matches_oracle(cap):
     assert_close_score(host(gc.score), oc.score, oc.len)
     out_org = org.decode_step(q, kn, vn, q_pos, 1.3, 0.09, ko.NOISE_GUMBEL, seeds, slopes)
     assert np.abs(out_org - out_ref).max() > 1e-3        # the two modes really differ on this cache
+
+
+@pytest.mark.parametrize("dtype,d", [(ko.BF16, 256), (ko.BF16, 64), (ko.F32, 128)])
+@pytest.mark.parametrize("n,k,w", [(600, 256, 51), (257, 256, 51), (100, 64, 0)])
+def test_select_evict_into_another_cache(dtype, d, n, k, w):
+    """Prompt-phase eviction gathered into the (smaller) generation cache: same survivors, same rows,
+    as the in-place call checked against the oracle; the source stays as it was."""
+    rng = np.random.default_rng(n + k + d)
+    Ls, Ld, B, H = 2, 5, 1, 3
+    lens = np.full((Ls, B, H), n, np.int32)
+    lens[0, 0, 1] = k - 7                      # under budget: copied whole
+    oc = random_cache(rng, Ls, B, H, d, n, dtype, lens)
+    oc.score[1, 0, 0, : n // 2] = 1.0          # ties
+    src = upload(oc)
+    dst = kf.Cache.allocate(Ld, B, H, d, k + 1, dtype)
+    dst.K.fill_(9.0)
+    dst.len.fill_(-3)
+    ws = kf.new_workspace(src, n)
+    kept = torch.full((Ls, B, H, k), -5, dtype=torch.int32, device="cuda")
+    kf.kf_select_evict_into(src, dst, 2, k, w, kept, ws)
+    torch.cuda.synchronize()
+    assert_state_equal(src, oc)                # the source is untouched
+    ref = oc.copy()
+    kept_ref = ref.select_evict(k, w)
+    np.testing.assert_array_equal(host(kept), kept_ref)
+    view = kf.Cache(K=dst.K[2:4], V=dst.V[2:4], score=dst.score[2:4], pos=dst.pos[2:4], len=dst.len[2:4],
+                    L=Ls, B=B, H=H, d=d, cap=k + 1, dtype=dtype)
+    got_len = host(view.len)
+    np.testing.assert_array_equal(got_len, ref.len)
+    gK, gV, gs, gp = host(view.K), host(view.V), host(view.score), host(view.pos)
+    for l, b, h in itertools.product(range(Ls), range(B), range(H)):
+        m = int(got_len[l, b, h])
+        np.testing.assert_array_equal(gK[l, b, h, :m], ref.K[l, b, h, :m])
+        np.testing.assert_array_equal(gV[l, b, h, :m], ref.V[l, b, h, :m])
+        np.testing.assert_array_equal(gs[l, b, h, :m], ref.score[l, b, h, :m])
+        np.testing.assert_array_equal(gp[l, b, h, :m], ref.pos[l, b, h, :m])
+    assert (host(dst.len)[[0, 1, 4]] == -3).all()      # other layers of the destination untouched
+    # without kept_idx
+    dst2 = kf.Cache.allocate(Ld, B, H, d, k + 1, dtype)
+    kf.kf_select_evict_into(src, dst2, 2, k, w, None, ws)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(host(dst2.pos[2:4])[..., : k - 7], gp[..., : k - 7])
+    with pytest.raises(kf.KeyformerError):
+        kf.kf_select_evict_into(src, dst, 4, k, w, None, ws)      # layers 4,5 do not fit
+    with pytest.raises(kf.KeyformerError):
+        kf.kf_select_evict_into(src, src, 0, k, w, None, ws)      # must be another cache
