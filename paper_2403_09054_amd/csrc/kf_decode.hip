@@ -25,17 +25,12 @@ namespace kf {
 
 constexpr int kDecodeThreads = 256;
 constexpr int kDecodeMaxChunk = 4096;   // tokens per split the LDS arrays are sized for
-#ifndef KF_DECODE_MIN_BLOCKS
-#define KF_DECODE_MIN_BLOCKS 1024
-#endif
-constexpr int kDecodeMinBlocks = KF_DECODE_MIN_BLOCKS;  // workgroups wanted on the chip
+constexpr int kDecodeMinBlocks = 1024;  // workgroups wanted on the chip
 constexpr int kComputeUnits = 256;                      // MI355X
 constexpr int kDecodeBlockOverheadTokens = 48;          // fixed cost of a workgroup, in tokens' worth of time
 constexpr int kDecodeMinChunk = 128;
 
-#ifndef KF_DECODE_UNROLL
-#define KF_DECODE_UNROLL 4
-#endif
+constexpr int kDecodeUnroll = 4;  // 16-byte loads a lane keeps in flight per tile (2 and 8 measured within 2 %)
 
 // ---- lane-group sums without LDS traffic ---------------------------------
 // A row's partial dot products sit in LPR adjacent lanes.  The data-parallel
@@ -133,7 +128,7 @@ __global__ void __launch_bounds__(NT) decode_kernel(const DecodeArgs a) {
     constexpr int RPW = kWave / LPR;             // rows per wave-wide load
     constexpr int NW = NT / kWave;
     constexpr int RPB = RPW * NW;                // rows per block-wide load
-    constexpr int UNR = KF_DECODE_UNROLL;        // independent loads in flight per lane
+    constexpr int UNR = kDecodeUnroll;             // independent loads in flight per lane
     constexpr int TILE = RPB * UNR;              // rows per tile of the workgroup
     constexpr int PW = D + 4;                    // floats in a partial record
     constexpr size_t ROWB = (size_t)D * sizeof(T);

@@ -58,14 +58,9 @@ struct Mma<float> {
 // that are equal modulo 8 and therefore share one L2.
 constexpr int kXcds = 8;
 __device__ __forceinline__ void unit_and_block(int nblk, int64_t& u, int& blk) {
-#ifdef KF_PREFILL_NO_XCD_MAP
-    u = blockIdx.x / nblk;
-    blk = (int)(blockIdx.x % nblk);
-#else
     const unsigned xcd = blockIdx.x % kXcds, local = blockIdx.x / kXcds;
     u = (int64_t)(local / nblk) * kXcds + xcd;
     blk = (int)(local % nblk);
-#endif
 }
 
 // Row of the 32x32 accumulator tile that register r of this lane holds
