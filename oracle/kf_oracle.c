@@ -20,6 +20,8 @@
  *                      reduced cache, score accumulation          [Eq. 1, Eq. 11, Sec. 3.3.2, Alg. 1 else-branch]
  *   kfo_select_evict   recent window + top-(k-w) key tokens,
  *                      order-preserving compaction                [Alg. 1 last three lines, Sec. 3.4]
+ *   (shared != 0 in the two scoring calls: the "Shared" score function of the
+ *    ablation -- one f for all layers, each layer's increments added to it)  [Sec. 4.4.1]
  *
  * All arithmetic is done in double on the exact input bits (fp32, or bf16
  * given as uint16).  State that persists between steps (the accumulated score
@@ -190,10 +192,17 @@ static void softmax_inplace(double *v, int m)
 int kfo_prefill_score(const void *Q, const void *K, float *score, int32_t *pos,
                       int32_t *len, int L, int B, int H, int d, int cap,
                       int dtype, int layer0, int n, float tau, float scale, int noise,
-                      const uint64_t *seeds, const float *slopes)
+                      const uint64_t *seeds, const float *slopes, int shared)
 {
     if (n < 1 || n > cap || !(tau > 0.0f)) return -1;
     int U = L * B * H;
+    /* "Shared" score function [Sec. 4.4.1]: every layer's column sums, kept in
+     * double until the layers have been added up */
+    double *fall = NULL;
+    if (shared) {
+        fall = (double *)calloc((size_t)U * n, sizeof(double));
+        if (!fall) return -2;
+    }
     for (int u = 0; u < U; ++u) {
         int h = u % H, b = (u / H) % B, l = layer0 + u / (H * B);
         double slope = slopes ? (double)slopes[h] : 0.0;
@@ -201,7 +210,7 @@ int kfo_prefill_score(const void *Q, const void *K, float *score, int32_t *pos,
         double *q = (double *)malloc((size_t)n * d * sizeof(double));
         double *kk = (double *)malloc((size_t)n * d * sizeof(double));
         double *f = (double *)calloc((size_t)n, sizeof(double));
-        if (!q || !kk || !f) { free(q); free(kk); free(f); return -2; }
+        if (!q || !kk || !f) { free(q); free(kk); free(f); free(fall); return -2; }
         for (size_t e = 0; e < (size_t)n * d; ++e) {
             q[e] = load_elem(Q, dtype, (size_t)u * n * d + e);
             kk[e] = load_elem(K, dtype, (size_t)u * cap * d + e);
@@ -241,15 +250,30 @@ int kfo_prefill_score(const void *Q, const void *K, float *score, int32_t *pos,
             free(fl);
             free(row);
         }
-        if (failed) { free(q); free(kk); free(f); return -2; }
+        if (failed) { free(q); free(kk); free(f); free(fall); return -2; }
         for (int j = 0; j < n; ++j) {
-            score[(size_t)u * cap + j] = (float)f[j];
+            if (shared) fall[(size_t)u * n + j] = f[j];
+            else score[(size_t)u * cap + j] = (float)f[j];
             pos[(size_t)u * cap + j] = j;
         }
         len[u] = n;
         free(q);
         free(kk);
         free(f);
+    }
+    if (shared) {
+        /* one score function for all layers: f[j] = sum over layers of that layer's
+         * column sum; every layer's cache carries the same copy */
+        int BH = B * H;
+        for (int bh = 0; bh < BH; ++bh)
+            for (int j = 0; j < n; ++j) {
+                double s = 0.0;
+                for (int l = 0; l < L; ++l)
+                    s += fall[((size_t)l * BH + bh) * n + j];
+                for (int l = 0; l < L; ++l)
+                    score[((size_t)l * BH + bh) * cap + j] = (float)s;
+            }
+        free(fall);
     }
     return 0;
 }
@@ -267,14 +291,28 @@ int kfo_decode_step(void *K, void *V, float *score, int32_t *pos, int32_t *len,
                     int L, int B, int H, int d, int cap, int dtype, int layer0,
                     const void *q, const void *k_new, const void *v_new,
                     int32_t q_pos, float tau, float scale, int noise,
-                    const uint64_t *seeds, const float *slopes, int new_pos, float *out,
-                    double *dbg_p, double *dbg_df)
+                    const uint64_t *seeds, const float *slopes, int new_pos, int shared,
+                    float *out, double *dbg_p, double *dbg_df)
 {
     if (!(tau > 0.0f)) return -1;
     int U = L * B * H;
     size_t es = elem_size(dtype);
     for (int u = 0; u < U; ++u)
         if (len[u] < 0 || len[u] >= cap) return -1;
+    /* "Shared" score function [Sec. 4.4.1]: all layers hold the same tokens (same
+     * scores, hence the same evictions), and every layer's increment of this step
+     * is added to the one score */
+    double *dfall = NULL;
+    if (shared) {
+        for (int u = 0; u < U; ++u) {
+            int u0 = u % (B * H);
+            if (len[u] != len[u0]) return -1;
+            for (int j = 0; j < len[u]; ++j)
+                if (pos[(size_t)u * cap + j] != pos[(size_t)u0 * cap + j]) return -1;
+        }
+        dfall = (double *)calloc((size_t)U * cap, sizeof(double));
+        if (!dfall) return -2;
+    }
     int failed = 0;
 #pragma omp parallel for schedule(dynamic, 1)
     for (int u = 0; u < U; ++u) {
@@ -326,13 +364,30 @@ int kfo_decode_step(void *K, void *V, float *score, int32_t *pos, int32_t *len,
             out[(size_t)u * d + c] = (float)o;
         }
         for (int j = 0; j < m; ++j) {
-            fu[j] = (float)((double)fu[j] + y[j]);
+            if (shared) dfall[(size_t)u * cap + j] = y[j];
+            else fu[j] = (float)((double)fu[j] + y[j]);
             if (dbg_p) dbg_p[(size_t)u * cap + j] = p[j];
             if (dbg_df) dbg_df[(size_t)u * cap + j] = y[j];
         }
         free(p);
         free(y);
     }
+    if (shared && !failed) {
+        int BH = B * H;
+        for (int bh = 0; bh < BH; ++bh) {
+            int m = len[bh];
+            for (int j = 0; j < m; ++j) {
+                double s = 0.0;
+                for (int l = 0; l < L; ++l)
+                    s += dfall[((size_t)l * BH + bh) * cap + j];
+                for (int l = 0; l < L; ++l) {
+                    float *f = score + ((size_t)l * BH + bh) * cap + j;
+                    *f = (float)((double)*f + s);
+                }
+            }
+        }
+    }
+    free(dfall);
     return failed ? -2 : 0;
 }
 

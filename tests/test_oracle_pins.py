@@ -388,6 +388,90 @@ def test_prefill_first_row_and_uniform_case():
 
 
 # ----------------------------------------------------------------------------
+# "Shared" score function (Sec. 4.4.1): one f for all layers, accumulated over
+# layers and decoding steps
+# ----------------------------------------------------------------------------
+def test_shared_score_is_the_sum_over_layers():
+    rng = np.random.default_rng(21)
+    L, B, H, d, n, cap = 3, 2, 2, 16, 21, 30
+    c = make_cache(rng, L, B, H, d, cap, n, ko.BF16)
+    Q = rand_vec(rng, (L, B, H, n, d), ko.BF16)
+    seeds = np.array([7, 8], np.uint64)
+    slopes = np.array([0.0, 0.125], np.float32)
+    tau, scale = 1.5, 0.25
+    c.prefill_score(Q, n, tau, scale, ko.NOISE_GUMBEL, seeds, slopes, shared=True)
+    # independent evaluation: each layer's causal column sums with numpy/scipy, added up
+    i, j = np.meshgrid(np.arange(n), np.arange(n), indexing="ij")
+    f_ref = np.zeros((B, H, n))
+    for l, b, h in itertools.product(range(L), range(B), range(H)):
+        x = np.float64(np.float32(scale)) * (as_f64(Q[l, b, h]) @ as_f64(c.K[l, b, h, :n]).T)
+        x = x - float(slopes[h]) * (i - j)
+        z = zeta_matrix(ko.NOISE_GUMBEL, int(seeds[b]), l, h, range(n), range(n))
+        y = np.where(j <= i, (x + z) / np.float64(np.float32(tau)), -np.inf)
+        f_ref[b, h] += scipy.special.softmax(y, axis=1).sum(axis=0)
+    for l in range(L):
+        np.testing.assert_allclose(c.score[l, ..., :n], f_ref, rtol=3e-7)
+        np.testing.assert_array_equal(c.score[l], c.score[0])          # one function: all copies equal
+    assert abs(c.score[0, ..., :n].astype(np.float64).sum() - L * B * H * n) < 1e-3
+
+    # a decode step adds every layer's increment to the one score
+    before = c.copy()
+    q, kn, vn = (rand_vec(rng, (L, B, H, d), ko.BF16) for _ in range(3))
+    q_pos, tau = n, 1.75
+    out, dp, df = c.decode_step(q, kn, vn, q_pos, tau, scale, ko.NOISE_GUMBEL, seeds, slopes, debug=True, shared=True)
+    m = n + 1
+    inc = np.zeros((B, H, m))
+    for l, b, h in itertools.product(range(L), range(B), range(H)):
+        o_ref, p_ref, df_ref = numpy_decode(c, (l, b, h), q[l, b, h], q_pos, tau, scale, ko.NOISE_GUMBEL,
+                                            int(seeds[b]), float(slopes[h]))
+        inc[b, h] += df_ref
+        np.testing.assert_allclose(out[l, b, h], o_ref.astype(np.float32), rtol=2e-7, atol=1e-30)  # attention unaffected
+    old = np.concatenate([before.score[0, ..., :n].astype(np.float64), np.zeros((B, H, 1))], axis=-1)
+    for l in range(L):
+        np.testing.assert_allclose(c.score[l, ..., :m], (old + inc), rtol=2e-7)
+        np.testing.assert_array_equal(c.score[l], c.score[0])
+    assert abs(c.score[0, ..., :m].astype(np.float64).sum() - before.score[0, ..., :n].astype(np.float64).sum()
+               - L * B * H) < 1e-4                                       # every layer added a probability vector
+    # the same scores everywhere => the same evictions everywhere
+    kept = c.select_evict(12, 4)
+    for l in range(L):
+        np.testing.assert_array_equal(kept[l], kept[0])
+        np.testing.assert_array_equal(c.pos[l], c.pos[0])
+
+
+def test_shared_score_special_cases():
+    rng = np.random.default_rng(22)
+    B, H, d, n, cap = 1, 2, 8, 12, 16
+    seeds = np.array([3], np.uint64)
+    # one layer: shared and per-layer are the same thing, bit for bit
+    a = make_cache(rng, 1, B, H, d, cap, n)
+    b_ = a.copy()
+    Q = rand_vec(rng, (1, B, H, n, d), ko.F32)
+    a.prefill_score(Q, n, 1.0, 0.3, ko.NOISE_GUMBEL, seeds)
+    b_.prefill_score(Q, n, 1.0, 0.3, ko.NOISE_GUMBEL, seeds, shared=True)
+    np.testing.assert_array_equal(a.score, b_.score)
+    q, kn, vn = (rand_vec(rng, (1, B, H, d), ko.F32) for _ in range(3))
+    a.decode_step(q, kn, vn, n, 1.2, 0.3, ko.NOISE_GUMBEL, seeds)
+    b_.decode_step(q, kn, vn, n, 1.2, 0.3, ko.NOISE_GUMBEL, seeds, shared=True)
+    np.testing.assert_array_equal(a.score, b_.score)
+    # L identical layers without noise: the shared score is L times the single layer's
+    L = 4
+    one = make_cache(rng, 1, B, H, d, cap, n)
+    many = ko.OracleCache(L, B, H, d, cap, ko.F32)
+    for l in range(L):
+        many.K[l], many.V[l] = one.K[0], one.V[0]
+    Q1 = rand_vec(rng, (1, B, H, n, d), ko.F32)
+    one.prefill_score(Q1, n, 1.0, 0.3, ko.NOISE_NONE)
+    many.prefill_score(np.repeat(Q1, L, axis=0), n, 1.0, 0.3, ko.NOISE_NONE, shared=True)
+    np.testing.assert_allclose(many.score[2, ..., :n], L * one.score[0, ..., :n].astype(np.float64), rtol=2e-7)
+    np.testing.assert_array_equal(many.select_evict(8, 3)[1], one.select_evict(8, 3)[0])
+    # layers that do not hold the same tokens cannot share a score
+    many.pos[1, 0, 0, 2] += 1
+    with pytest.raises(ValueError):
+        many.decode_step(*(np.repeat(x, L, axis=0) for x in (q, kn, vn)), n, 1.0, 0.3, ko.NOISE_NONE, shared=True)
+
+
+# ----------------------------------------------------------------------------
 # Selection + compaction (Alg. 1: S_w, S_key = argmax_(k-w) f[:-w], S_k)
 # ----------------------------------------------------------------------------
 def brute_force_keep(f, n, k, w):
