@@ -85,6 +85,16 @@ typedef struct {
  * The noise key always uses original positions. */
 typedef enum { KF_POS_ORIGINAL = 0, KF_POS_NEW = 1 } kf_pos_mode;
 
+/* Whether every layer accumulates its own score (the method, and the better
+ * ablation) or one score serves all layers (Sec. 4.4.1, "Shared"): then each
+ * scoring call adds the contributions of ALL layers of the cache, in layer
+ * order, to the score of every (batch, head), every layer's `score` rows hold
+ * the same copy of it, and so all layers retain the same tokens.  A shared score
+ * needs all layers in one cache, holding the same tokens (equal len and pos per
+ * (batch, head) over the layers); a call on layers that disagree in len leaves
+ * the scores of that (batch, head) alone and increments the workspace error word. */
+typedef enum { KF_SCORE_PER_LAYER = 0, KF_SCORE_SHARED = 1 } kf_score_mode;
+
 /* Parameters of the score function (Eq. 11) for one call. */
 typedef struct {
     float tau;                 /* temperature of this iteration, from kf_tau()            */
@@ -95,6 +105,7 @@ typedef struct {
     const float *alibi_slopes; /* DEVICE [H] or NULL.  Adds -slope[h]*(q_pos - pos_j) to
                                   the logits (MPT's position bias)                        */
     int32_t pos_mode;          /* kf_pos_mode; only matters with alibi_slopes, decode only */
+    int32_t score_mode;        /* kf_score_mode                                           */
 } kf_score_cfg;
 
 /* Library version, for the binding to check it loaded what it expects. */

@@ -17,6 +17,7 @@ F32, BF16 = 0, 1
 NOISE_NONE, NOISE_GUMBEL, NOISE_GAUSSIAN, NOISE_CONSTANT = 0, 1, 2, 3
 LAYOUT_ORDERED, LAYOUT_SLOT = 0, 1
 POS_ORIGINAL, POS_NEW = 0, 1
+SCORE_PER_LAYER, SCORE_SHARED = 0, 1
 KF_OK, KF_EINVAL, KF_EUNSUPPORTED, KF_EWORKSPACE, KF_EDEVICE = 0, -1, -2, -3, -4
 
 # every symbol include/keyformer.h declares
@@ -39,7 +40,8 @@ class kf_cache(C.Structure):
 
 class kf_score_cfg(C.Structure):
     _fields_ = [("tau", C.c_float), ("scale", C.c_float), ("noise", C.c_int32),
-                ("seeds", C.c_void_p), ("alibi_slopes", C.c_void_p), ("pos_mode", C.c_int32)]
+                ("seeds", C.c_void_p), ("alibi_slopes", C.c_void_p), ("pos_mode", C.c_int32),
+                ("score_mode", C.c_int32)]
 
 
 _lib = None
@@ -189,21 +191,22 @@ def _ws(workspace):
     return workspace.data_ptr(), workspace.numel() * workspace.element_size()
 
 
-def _cfg(tau, scale, noise, seeds, slopes, pos_mode=0) -> kf_score_cfg:
-    return kf_score_cfg(tau, scale, noise, _ptr(seeds), _ptr(slopes), pos_mode)
+def _cfg(tau, scale, noise, seeds, slopes, pos_mode=0, score_mode=0) -> kf_score_cfg:
+    return kf_score_cfg(tau, scale, noise, _ptr(seeds), _ptr(slopes), pos_mode, score_mode)
 
 
 def kf_prefill_score(cache: Cache, Q, n: int, tau: float, scale: float, noise: int = NOISE_GUMBEL,
-                     seeds=None, slopes=None, workspace=None, stream=None) -> None:
-    cs, cfg = cache.c_struct(), _cfg(tau, scale, noise, seeds, slopes)
+                     seeds=None, slopes=None, workspace=None, stream=None,
+                     score_mode: int = SCORE_PER_LAYER) -> None:
+    cs, cfg = cache.c_struct(), _cfg(tau, scale, noise, seeds, slopes, 0, score_mode)
     wp, wb = _ws(workspace)
     _check(lib().kf_prefill_score(C.byref(cs), _ptr(Q), n, C.byref(cfg), wp, wb, _stream(stream)))
 
 
 def kf_decode_step(cache: Cache, q, k_new, v_new, q_pos: int, m_hint: int, tau: float, scale: float,
                    noise: int = NOISE_GUMBEL, seeds=None, slopes=None, out=None, workspace=None,
-                   stream=None, pos_mode: int = POS_ORIGINAL) -> None:
-    cs, cfg = cache.c_struct(), _cfg(tau, scale, noise, seeds, slopes, pos_mode)
+                   stream=None, pos_mode: int = POS_ORIGINAL, score_mode: int = SCORE_PER_LAYER) -> None:
+    cs, cfg = cache.c_struct(), _cfg(tau, scale, noise, seeds, slopes, pos_mode, score_mode)
     wp, wb = _ws(workspace)
     _check(lib().kf_decode_step(C.byref(cs), _ptr(q), _ptr(k_new), _ptr(v_new), q_pos, m_hint,
                                 C.byref(cfg), _ptr(out), wp, wb, _stream(stream)))
@@ -227,8 +230,8 @@ def kf_select_evict_into(src: Cache, dst: Cache, dst_layer0: int, k: int, w: int
 def kf_decode_select_step(cache: Cache, q, k_new, v_new, q_pos: int, m_hint: int, tau: float, scale: float,
                           noise: int = NOISE_GUMBEL, seeds=None, slopes=None, out=None, k: int = 0, w: int = 0,
                           layout: int = LAYOUT_ORDERED, kept_idx=None, workspace=None, stream=None,
-                          pos_mode: int = POS_ORIGINAL) -> None:
-    cs, cfg = cache.c_struct(), _cfg(tau, scale, noise, seeds, slopes, pos_mode)
+                          pos_mode: int = POS_ORIGINAL, score_mode: int = SCORE_PER_LAYER) -> None:
+    cs, cfg = cache.c_struct(), _cfg(tau, scale, noise, seeds, slopes, pos_mode, score_mode)
     wp, wb = _ws(workspace)
     _check(lib().kf_decode_select_step(C.byref(cs), _ptr(q), _ptr(k_new), _ptr(v_new), q_pos, m_hint,
                                        C.byref(cfg), _ptr(out), k, w, layout, _ptr(kept_idx), wp, wb,

@@ -51,6 +51,8 @@ kf_status check_cfg(const kf_score_cfg* cfg) {
         return fail(KF_EINVAL, "unknown noise mode %d", cfg->noise);
     if (cfg->pos_mode != KF_POS_ORIGINAL && cfg->pos_mode != KF_POS_NEW)
         return fail(KF_EINVAL, "unknown pos_mode %d", cfg->pos_mode);
+    if (cfg->score_mode != KF_SCORE_PER_LAYER && cfg->score_mode != KF_SCORE_SHARED)
+        return fail(KF_EINVAL, "unknown score_mode %d", cfg->score_mode);
     if ((cfg->noise == KF_NOISE_GUMBEL || cfg->noise == KF_NOISE_GAUSSIAN) && !cfg->seeds)
         return fail(KF_EINVAL, "a random logit adjustment needs seeds");
     return KF_OK;
@@ -59,8 +61,9 @@ kf_status check_cfg(const kf_score_cfg* cfg) {
 // Workspace layout (all regions 256-byte aligned):
 //   [0]        error word + padding (the only part that must start as zero)
 //   region X   the largest of
-//                decode : partial records U*S*(d+4) floats, then increments U*cap floats,
-//                         then (fused step) the survivor index list U*cap int32
+//                decode : partial records U*S*(d+4) floats, then increments U*cap floats, then
+//                         per-unit token counts U int32 (shared score), then (fused step) the
+//                         survivor index list U*cap int32
 //                select : survivor index list U*cap int32
 //                prefill: row normalisers U*n_pad floats, then row keys U*n_pad uint32
 struct WsLayout {
@@ -70,7 +73,7 @@ struct WsLayout {
 size_t decode_region(int64_t U, const kf_cache* c) {
     const kf::DecodePlan p = kf::plan_decode(U, c->cap, c->d, c->dtype);
     return align_up((size_t)U * p.S * (c->d + 4) * sizeof(float), 256) +
-           align_up((size_t)U * c->cap * sizeof(float), 256);
+           align_up((size_t)U * c->cap * sizeof(float), 256) + align_up((size_t)U * sizeof(int32_t), 256);
 }
 
 WsLayout ws_layout(const kf_cache* c, int32_t n_max) {
@@ -166,7 +169,18 @@ kf_status kf_prefill_score(const kf_cache* c, const void* Q, int32_t n, const kf
     a.noise = cfg->noise;
     a.inv_tau = 1.0f / cfg->tau;
     a.scale = cfg->scale;
-    const hipError_t e = kf::launch_prefill(a, U, c->d, c->dtype, (hipStream_t)stream);
+    hipError_t e = kf::launch_prefill(a, U, c->d, c->dtype, (hipStream_t)stream);
+    if (e == hipSuccess && cfg->score_mode == KF_SCORE_SHARED) {
+        kf::ShareArgs sh;
+        sh.score = c->score;
+        sh.inc = nullptr;
+        sh.m = c->len;
+        sh.ws_err = (int32_t*)workspace + KF_WS_ERROR_WORD;
+        sh.L = c->L;
+        sh.BH = c->B * c->H;
+        sh.cap = c->cap;
+        e = kf::launch_share(sh, (hipStream_t)stream);
+    }
     if (e != hipSuccess) return fail(KF_EDEVICE, "prefill launch: %s", hipGetErrorString(e));
     g_err[0] = 0;
     return KF_OK;
@@ -209,6 +223,7 @@ static kf_status prepare_decode(kf_cache* c, const void* q, const void* k_new, c
     a->ws_err = (int32_t*)workspace + KF_WS_ERROR_WORD;
     a->ws_part = (float*)((char*)workspace + w.region);
     a->ws_e = (float*)((char*)workspace + w.region + align_up((size_t)U * pmax.S * (c->d + 4) * sizeof(float), 256));
+    a->ws_m = (int32_t*)((char*)a->ws_e + align_up((size_t)U * c->cap * sizeof(float), 256));
     a->B = c->B;
     a->H = c->H;
     a->cap = c->cap;
@@ -218,10 +233,24 @@ static kf_status prepare_decode(kf_cache* c, const void* q, const void* k_new, c
     a->q_pos = q_pos;
     a->noise = cfg->noise;
     a->new_pos = cfg->pos_mode == KF_POS_NEW ? 1 : 0;
+    a->shared = cfg->score_mode == KF_SCORE_SHARED ? 1 : 0;
     a->inv_tau = 1.0f / cfg->tau;
     a->scale = cfg->scale;
     *plan = p;
     return KF_OK;
+}
+
+// Second half of a scoring call with a shared score: the layers' contributions are added up.
+static hipError_t share_after_decode(const kf_cache* c, const kf::DecodeArgs& a, hipStream_t stream) {
+    kf::ShareArgs sh;
+    sh.score = c->score;
+    sh.inc = a.ws_e;
+    sh.m = a.ws_m;
+    sh.ws_err = a.ws_err;
+    sh.L = c->L;
+    sh.BH = c->B * c->H;
+    sh.cap = c->cap;
+    return kf::launch_share(sh, stream);
 }
 
 // Same for a selection.  In a fused step the decode records occupy region X of
@@ -264,7 +293,8 @@ kf_status kf_decode_step(kf_cache* c, const void* q, const void* k_new, const vo
     const kf_status st = prepare_decode(c, q, k_new, v_new, q_pos, m_hint, cfg, out, workspace, workspace_bytes, &a, &p);
     if (st != KF_OK) return st;
     const int64_t U = (int64_t)c->L * c->B * c->H;
-    const hipError_t e = kf::launch_decode(a, U, c->d, c->dtype, p.lds_bytes, (hipStream_t)stream);
+    hipError_t e = kf::launch_decode(a, U, c->d, c->dtype, p.lds_bytes, (hipStream_t)stream);
+    if (e == hipSuccess && a.shared) e = share_after_decode(c, a, (hipStream_t)stream);
     if (e != hipSuccess) return fail(KF_EDEVICE, "decode launch: %s", hipGetErrorString(e));
     g_err[0] = 0;
     return KF_OK;
@@ -341,7 +371,11 @@ kf_status kf_decode_select_step(kf_cache* c, const void* q, const void* k_new, c
     if (st != KF_OK) return st;
     const int64_t U = (int64_t)c->L * c->B * c->H;
     hipError_t e;
-    if (da.S > 1) {
+    if (da.shared) {  // the layers' increments must be added up between the merge and the selection
+        e = kf::launch_decode(da, U, c->d, c->dtype, p.lds_bytes, (hipStream_t)stream);
+        if (e == hipSuccess) e = share_after_decode(c, da, (hipStream_t)stream);
+        if (e == hipSuccess) e = kf::launch_select(sa, U, (hipStream_t)stream);
+    } else if (da.S > 1) {
         e = kf::launch_decode_split(da, U, c->d, c->dtype, p.lds_bytes, (hipStream_t)stream);
         if (e == hipSuccess) e = kf::launch_step_tail(da, sa, U, c->d, (hipStream_t)stream);
     } else {  // the decode kernel finishes each unit itself: nothing to merge

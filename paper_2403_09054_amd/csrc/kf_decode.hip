@@ -154,7 +154,10 @@ __global__ void __launch_bounds__(NT) decode_kernel(const DecodeArgs a) {
         // leave the unit alone and report it
         if (s == 0) {
             if (tid < D) a.out[u * D + tid] = 0.0f;
-            if (tid == 0) atomicAdd(a.ws_err, 1);
+            if (tid == 0) {
+                atomicAdd(a.ws_err, 1);
+                if (a.shared) a.ws_m[u] = 0;
+            }
         }
         return;
     }
@@ -344,15 +347,20 @@ __global__ void __launch_bounds__(NT) decode_kernel(const DecodeArgs a) {
     if (S == 1) {
         // the whole unit is here: accumulate the normalised score increment
         const float inv = 1.0f / se;
+        float* we = a.ws_e + (size_t)u * a.cap;
         for (int t = tid; t < cnt; t += NT) {
             const int slot = (t == cnt_c) ? len0 : j0 + t;
             // existing scores take the increment as a fire-and-forget atomic add at the L2: no load,
             // no round trip (one add per address and launch, so the result is the plain fp32 sum)
-            if (t == cnt_c) fu[slot] = ys[t] * inv;
+            if (a.shared) we[slot] = ys[t] * inv;  // summed over the layers by the launch that follows
+            else if (t == cnt_c) fu[slot] = ys[t] * inv;
             else unsafeAtomicAdd(&fu[slot], ys[t] * inv);
         }
         if (tid < D) a.out[u * D + tid] = o_c / sp;
-        if (tid == 0) a.len[u] = m;
+        if (tid == 0) {
+            a.len[u] = m;
+            if (a.shared) a.ws_m[u] = m;
+        }
         return;
     }
     {
@@ -380,6 +388,39 @@ __global__ void __launch_bounds__(NT) decode_merge_kernel(const DecodeArgs a) {
     const int len0 = a.len[u];
     if (len0 < 0 || len0 >= a.cap || len0 > a.S * a.chunk) return;  // skipped by the split kernel too
     merge_unit<D, NT>(a, u, len0, red_s, w_p, w_e);
+}
+
+// Shared score function (the paper's ablation of one score for all layers,
+// Sec. 4.4.1): every layer's contribution to token j of sequence/head bh is
+// summed in layer order, and every layer's copy of the score takes the same
+// sum, so all copies stay bit-identical and all layers evict the same tokens.
+constexpr int kShareThreads = 256;
+__global__ void __launch_bounds__(kShareThreads) share_kernel(const ShareArgs a) {
+    const int bh = blockIdx.x;
+    const int j = blockIdx.y * kShareThreads + threadIdx.x;
+    const int m = a.m[bh];
+    bool same = true;
+    for (int l = 1; l < a.L; ++l) same = same && (a.m[(size_t)l * a.BH + bh] == m);
+    if (!same) {  // layers that hold different token counts cannot share a score: leave them, report
+        if (j == 0) atomicAdd(a.ws_err, 1);
+        return;
+    }
+    if (j >= m || m > a.cap) return;  // m == 0: the decode launch skipped (and reported) these units
+    const size_t stride = (size_t)a.BH * a.cap, at = (size_t)bh * a.cap + j;
+    const float* src = a.inc ? a.inc : a.score;
+    float s = 0.0f;
+    for (int l = 0; l < a.L; ++l) s += src[l * stride + at];
+    const bool fresh = !a.inc || j == m - 1;  // prompt scores, or the token appended by this step
+    for (int l = 0; l < a.L; ++l) {
+        float* f = a.score + l * stride + at;
+        *f = fresh ? s : *f + s;
+    }
+}
+
+hipError_t launch_share(const ShareArgs& a, hipStream_t stream) {
+    const dim3 grid((unsigned)a.BH, (unsigned)((a.cap + kShareThreads - 1) / kShareThreads));
+    hipLaunchKernelGGL(share_kernel, grid, dim3(kShareThreads), 0, stream, a);
+    return hipGetLastError();
 }
 
 // -------------------------------------------------------------------- host

@@ -24,12 +24,14 @@ struct DecodeArgs {
     float* ws_part;    // [U][S][D+4] partial outputs and softmax statistics of each split
     float* ws_e;       // [U][cap]    un-normalised score increments of each token
     int32_t* ws_err;   // [1]         skipped-unit counter
+    int32_t* ws_m;     // [U]         shared score only: tokens this launch scored in each unit (0: skipped)
     int32_t B, H, cap, layer0;
     int32_t S;         // splits of a unit's token range
     int32_t chunk;     // tokens per split
     int32_t q_pos;
     int32_t noise;
     int32_t new_pos;   // position bias from slot indices instead of original positions
+    int32_t shared;    // one score for all layers: leave the normalised increments in ws_e, do not touch score
     float inv_tau;
     float scale;
 };
@@ -42,6 +44,18 @@ struct DecodePlan {
 DecodePlan plan_decode(int64_t U, int32_t m, int32_t d, int32_t dtype);
 hipError_t launch_decode(const DecodeArgs& a, int64_t U, int32_t d, int32_t dtype, size_t lds_bytes,
                          hipStream_t stream);
+
+// Shared score function: adds up the layers' contributions and gives every layer the same score.
+//   inc != NULL (decode): score[l][bh][j] += sum_l' inc[l'][bh][j] for the m[.][bh] tokens just scored
+//   inc == NULL (prompt): score[l][bh][j]  = sum_l' score[l'][bh][j] for j < n
+struct ShareArgs {
+    float* score;
+    const float* inc;
+    const int32_t* m;   // decode: [L][BH] tokens scored per unit;  prompt: the caches' len
+    int32_t* ws_err;
+    int32_t L, BH, cap;
+};
+hipError_t launch_share(const ShareArgs& a, hipStream_t stream);
 
 // ------------------------------------------------------------------ select
 struct SelectArgs {

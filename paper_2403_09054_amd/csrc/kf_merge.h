@@ -43,14 +43,18 @@ __device__ __forceinline__ void merge_unit(const DecodeArgs& a, int64_t u, int l
         for (int ss = 0; ss < S; ++ss) o = fmaf(w_p[ss], parts[(size_t)ss * PW + tid], o);
         a.out[u * D + tid] = o / sumP;
     }
-    const float* we = a.ws_e + (size_t)u * a.cap;
+    float* we = a.ws_e + (size_t)u * a.cap;
     const float inv = 1.0f / sumE;
     for (int j = tid; j < m; j += NT) {
         const float df = we[j] * (w_e[(j == len0) ? S - 1 : j / a.chunk] * inv);  // the new token belongs to the last split
-        if (j == len0) fu[j] = df;
+        if (a.shared) we[j] = df;  // summed over the layers by the launch that follows
+        else if (j == len0) fu[j] = df;
         else unsafeAtomicAdd(&fu[j], df);  // fire-and-forget add at the L2 (one per address: the plain fp32 sum)
     }
-    if (tid == 0) a.len[u] = m;
+    if (tid == 0) {
+        a.len[u] = m;
+        if (a.shared) a.ws_m[u] = m;
+    }
 }
 
 }  // namespace kf

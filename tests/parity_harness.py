@@ -167,8 +167,11 @@ class LockStep:
     hold the same state (scores are re-uploaded from the oracle after each
     decode step, everything after a tie-band event)."""
 
-    def __init__(self, wl: kw.Workload, noise=ko.NOISE_GUMBEL, layers=None, cap=None, layout=kf.LAYOUT_ORDERED):
+    def __init__(self, wl: kw.Workload, noise=ko.NOISE_GUMBEL, layers=None, cap=None, layout=kf.LAYOUT_ORDERED,
+                 shared=False):
         self.wl, self.noise, self.layout = wl, noise, layout
+        self.shared = shared            # one score function for all layers (the paper's "Shared" ablation)
+        self.score_mode = kf.SCORE_SHARED if shared else kf.SCORE_PER_LAYER
         self.cap = cap or wl.n
         dt = ko.F32 if wl.dtype == "f32" else ko.BF16
         self.oc = ko.OracleCache(wl.L, wl.B, wl.H, wl.d, self.cap, dt)
@@ -191,9 +194,9 @@ class LockStep:
         wl = self.wl
         tau_o, tau_g = ko.tau(0, wl.T, wl.tau_init, wl.tau_end), kf.kf_tau(0, wl.T, wl.tau_init, wl.tau_end)
         assert tau_o == tau_g
-        self.oc.prefill_score(self.Q, wl.n, tau_o, wl.scale, self.noise, self.seeds, self.slopes)
+        self.oc.prefill_score(self.Q, wl.n, tau_o, wl.scale, self.noise, self.seeds, self.slopes, shared=self.shared)
         kf.kf_prefill_score(self.gc, dev(self.Q), wl.n, tau_g, wl.scale, self.noise, self.d_seeds,
-                            self.d_slopes, self.ws)
+                            self.d_slopes, self.ws, score_mode=self.score_mode)
         torch.cuda.synchronize()
         lens = host(self.gc.len)
         np.testing.assert_array_equal(lens, self.oc.len)
@@ -240,13 +243,19 @@ class LockStep:
         tau_o, tau_g = ko.tau(t, wl.T, wl.tau_init, wl.tau_end), kf.kf_tau(t, wl.T, wl.tau_init, wl.tau_end)
         assert tau_o == tau_g
         out_ref = self.oc.decode_step(kw.to_oracle(q), kw.to_oracle(kn), kw.to_oracle(vn), q_pos, tau_o,
-                                      wl.scale, self.noise, self.seeds, self.slopes)
+                                      wl.scale, self.noise, self.seeds, self.slopes, shared=self.shared)
         kf.kf_decode_step(self.gc, q.cuda(), kn.cuda(), vn.cuda(), q_pos, min(wl.k + 1, self.cap), tau_g,
-                          wl.scale, self.noise, self.d_seeds, self.d_slopes, self.out, self.ws)
+                          wl.scale, self.noise, self.d_seeds, self.d_slopes, self.out, self.ws,
+                          score_mode=self.score_mode)
         torch.cuda.synchronize()
         assert error_word(self.ws) == 0
         lens = host(self.gc.len)
         np.testing.assert_array_equal(lens, self.oc.len)
+        if self.shared:                 # one function: every layer holds the same copy, bit for bit
+            g = host(self.gc.score)
+            for l in range(1, wl.L):
+                for b, h in np.ndindex(wl.B, wl.H):
+                    np.testing.assert_array_equal(g[l, b, h, : lens[l, b, h]], g[0, b, h, : lens[0, b, h]])
         self.stats["out_err"] = max(self.stats["out_err"], assert_close_out(host(self.out), out_ref))
         if self.layout == kf.LAYOUT_SLOT:
             _, _, g_score, g_pos, _, order = sort_by_pos(self.gc)

@@ -553,3 +553,68 @@ def test_select_evict_into_another_cache(dtype, d, n, k, w):
         kf.kf_select_evict_into(src, dst, 4, k, w, None, ws)      # layers 4,5 do not fit
     with pytest.raises(kf.KeyformerError):
         kf.kf_select_evict_into(src, src, 0, k, w, None, ws)      # must be another cache
+
+
+# ------------------------------------------------------------------ shared (cross-layer) score function
+@pytest.mark.parametrize("name,kwargs,steps,layout", [
+    ("tiny", dict(L=3), 32, kf.LAYOUT_ORDERED),                     # one split per unit
+    ("gptj", dict(L=3, H=4, T=512), 24, kf.LAYOUT_ORDERED),         # several splits: increments pass the merge
+    ("tiny", dict(L=2), 32, kf.LAYOUT_SLOT)])
+def test_shared_score_lockstep(name, kwargs, steps, layout):
+    wl = kw.CONFIGS[name].slice(**kwargs)
+    ls = LockStep(wl, shared=True, layout=layout)
+    ls.prefill()
+    for t in range(1, steps + 1):
+        ls.step(t, check_kv=(t == steps))
+    # all layers made the same decisions
+    pos = host(ls.gc.pos)
+    for l in range(1, wl.L):
+        np.testing.assert_array_equal(np.sort(pos[l, ..., : wl.k], axis=-1), np.sort(pos[0, ..., : wl.k], axis=-1))
+    print(name, "shared-score lockstep", ls.stats)
+
+
+def test_shared_score_fused_step_and_disagreeing_layers():
+    rng = np.random.default_rng(77)
+    L, B, H, d, cap = 3, 2, 2, 128, 301
+    lens = np.broadcast_to(rng.integers(250, 300, (1, B, H)), (L, B, H)).astype(np.int32)
+    oc = random_cache(rng, L, B, H, d, cap, ko.BF16, lens)
+    oc.pos[...] = oc.pos[0]            # shared score: all layers hold the same tokens ...
+    oc.score[...] = oc.score[0]        # ... with the same scores
+    q, kn, vn = (rnd(rng, (L, B, H, d), ko.BF16) for _ in range(3))
+    seeds = np.array([5, 6], np.uint64)
+    k, w = 240, 48
+    a, b_ = upload(oc), upload(oc)
+    ws = kf.new_workspace(a)
+    out_a = torch.zeros((L, B, H, d), dtype=torch.float32, device="cuda")
+    out_b = torch.zeros_like(out_a)
+    q_pos = int(oc.pos.max()) + 1
+    kf.kf_decode_step(a, dev(q), dev(kn), dev(vn), q_pos, 0, 1.4, 0.09, kf.NOISE_GUMBEL, dev(seeds), None, out_a, ws,
+                      score_mode=kf.SCORE_SHARED)
+    kf.kf_select_evict(a, k, w, None, ws)
+    kf.kf_decode_select_step(b_, dev(q), dev(kn), dev(vn), q_pos, 0, 1.4, 0.09, kf.NOISE_GUMBEL, dev(seeds), None, out_b,
+                             k=k, w=w, workspace=ws, score_mode=kf.SCORE_SHARED)
+    torch.cuda.synchronize()
+    assert error_word(ws) == 0
+    assert torch.equal(out_a, out_b)
+    for nm in ("len", "pos", "score", "K", "V"):
+        ta, tb = getattr(a, nm), getattr(b_, nm)
+        assert torch.equal(ta[..., :k] if nm in ("pos", "score") else (ta[..., :k, :] if nm in ("K", "V") else ta),
+                           tb[..., :k] if nm in ("pos", "score") else (tb[..., :k, :] if nm in ("K", "V") else tb)), nm
+    out_ref = oc.decode_step(q, kn, vn, q_pos, 1.4, 0.09, ko.NOISE_GUMBEL, seeds, None, shared=True)
+    oc.select_evict(k, w)
+    assert_close_out(host(out_a), out_ref)
+    np.testing.assert_array_equal(host(a.pos)[..., :k], oc.pos[..., :k])
+    assert_close_score(host(a.score), oc.score, oc.len)
+
+    # layers that disagree in length cannot share a score: reported, their scores left alone
+    oc2 = random_cache(rng, L, B, H, d, cap, ko.BF16, lens)
+    oc2.len[1, 0, 1] -= 1
+    c = upload(oc2)
+    ws2 = kf.new_workspace(c)
+    before = c.score.clone()
+    kf.kf_decode_step(c, dev(q), dev(kn), dev(vn), q_pos + 99, 0, 1.4, 0.09, kf.NOISE_GUMBEL, dev(seeds), None, out_a,
+                      ws2, score_mode=kf.SCORE_SHARED)
+    torch.cuda.synchronize()
+    assert error_word(ws2) == 1
+    assert torch.equal(c.score[:, 0, 1, :200], before[:, 0, 1, :200])
+    assert not torch.equal(c.score[:, 0, 0, :200], before[:, 0, 0, :200])
