@@ -233,24 +233,32 @@ def main():
         return {"steps_per_s": round(K_steps / dt_, 2), "ms_per_step": round(dt_ * 1e3 / K_steps, 4)}
 
     def graph_variant(layout):
-        """The same K fused steps captured once in a HIP graph and replayed: no launch gaps, no host work."""
+        """A run of fused steps captured once in a HIP graph and replayed: no launch gaps, no host work.  The
+        captured calls take the step number from device memory (kf_decode_select_step_at), so every replay
+        continues the generation (q_pos and tau move on) instead of repeating the captured steps."""
         base_t = W_steps + K_steps + 8
+        n_cap = min(n_distinct, K_steps)
+        reps = max(1, K_steps // n_cap)
+        step = torch.full((1,), base_t + 4, dtype=torch.int32, device="cuda")
         g = torch.cuda.CUDAGraph()
         with torch.cuda.graph(g):
-            for i in range(K_steps):
-                t = base_t + 4 + i
-                q, kn, vn = steps_in[(t - 1) % n_distinct]
-                kf.kf_decode_select_step(cache, q, kn, vn, wl.n + t - 1, m, kf.kf_tau(min(t, wl.T), wl.T), wl.scale,
-                                         noise, seeds, slopes, out, k=wl.k, w=wl.w, layout=layout, workspace=ws)
+            for i in range(n_cap):
+                q, kn, vn = steps_in[i]
+                kf.kf_decode_select_step_at(cache, q, kn, vn, wl.n, wl.T, wl.tau_init, wl.tau_end, step, m, wl.scale,
+                                            noise, seeds, slopes, out, k=wl.k, w=wl.w, layout=layout, workspace=ws)
         g.replay()                      # warm replay
         torch.cuda.synchronize()
+        t_before = int(step.item())
         c0 = time.perf_counter()
-        g.replay()
+        for _ in range(reps):
+            g.replay()
         torch.cuda.synchronize()
         dt_ = time.perf_counter() - c0
+        assert int(step.item()) == t_before + reps * n_cap
         assert int(ws[:4].view(torch.int32)[0].item()) == 0
         assert int(cache.len.min()) == wl.k and int(cache.len.max()) == wl.k
-        return {"steps_per_s": round(K_steps / dt_, 2), "ms_per_step": round(dt_ * 1e3 / K_steps, 4)}
+        return {"steps_per_s": round(reps * n_cap / dt_, 2), "ms_per_step": round(dt_ * 1e3 / (reps * n_cap), 4),
+                "steps_per_graph": n_cap, "replays": reps}
 
     variants = None
     if not args.no_variants:

@@ -214,6 +214,34 @@ kf_status kf_decode_select_step(kf_cache *c, const void *q, const void *k_new, c
                                 int32_t k, int32_t w, int32_t layout, int32_t *kept_idx, void *workspace,
                                 size_t workspace_bytes, void *stream);
 
+/* The generation schedule of Algorithm 1, for the call below that takes the
+ * step number from device memory. */
+typedef struct {
+    int32_t n;       /* prompt length: decode step t appends the token at position n + t - 1 */
+    int32_t T;       /* planned generation length of Eq. 12; steps beyond T keep tau_end      */
+    float tau_init;  /* temperature of the prompt iteration (t = 0)                           */
+    float tau_end;   /* temperature of step T                                                 */
+} kf_schedule;
+
+/*
+ * kf_decode_select_step with the step number t read from DEVICE memory when the
+ * kernels run: q_pos = n + t - 1 and tau = kf_tau(min(t, T), T, tau_init,
+ * tau_end) (the same fp32 operations, so the same bits; cfg->tau is ignored),
+ * and the last kernel of the step stores t + 1 back.  One such call captured in
+ * a HIP graph therefore replays as successive generation steps (Algorithm 1's
+ * loop over t) with no host work in between; the caller refreshes q, k_new and
+ * v_new in place between replays, or captures several calls with their own
+ * input buffers.  `step` is DEVICE [1] int32, set to 1 by the caller before the
+ * first decode step; values below 1 are read as 1.  `sched` is HOST memory read
+ * during the call.  Everything else as kf_decode_select_step.
+ * Errors: additionally KF_EINVAL if step or sched is NULL, n < 0, T < 1, or the
+ * temperatures are not finite and positive.
+ */
+kf_status kf_decode_select_step_at(kf_cache *c, const void *q, const void *k_new, const void *v_new,
+                                   const kf_schedule *sched, int32_t *step, int32_t m_hint,
+                                   const kf_score_cfg *cfg, float *out, int32_t k, int32_t w, int32_t layout,
+                                   int32_t *kept_idx, void *workspace, size_t workspace_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

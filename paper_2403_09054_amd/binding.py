@@ -23,7 +23,7 @@ KF_OK, KF_EINVAL, KF_EUNSUPPORTED, KF_EWORKSPACE, KF_EDEVICE = 0, -1, -2, -3, -4
 # every symbol include/keyformer.h declares
 SYMBOLS = ("kf_version", "kf_last_error", "kf_tau", "kf_noise_bits", "kf_workspace_bytes",
            "kf_prefill_score", "kf_decode_step", "kf_select_evict", "kf_select_evict_into", "kf_decode_select_step",
-           "kf_decode_launch_shape")
+           "kf_decode_launch_shape", "kf_decode_select_step_at")
 
 
 class KeyformerError(RuntimeError):
@@ -42,6 +42,10 @@ class kf_score_cfg(C.Structure):
     _fields_ = [("tau", C.c_float), ("scale", C.c_float), ("noise", C.c_int32),
                 ("seeds", C.c_void_p), ("alibi_slopes", C.c_void_p), ("pos_mode", C.c_int32),
                 ("score_mode", C.c_int32)]
+
+
+class kf_schedule(C.Structure):
+    _fields_ = [("n", C.c_int32), ("T", C.c_int32), ("tau_init", C.c_float), ("tau_end", C.c_float)]
 
 
 _lib = None
@@ -89,6 +93,10 @@ def lib():
         L.kf_decode_select_step.argtypes = [C.POINTER(kf_cache), vp, vp, vp, C.c_int32, C.c_int32,
                                             C.POINTER(kf_score_cfg), vp, C.c_int32, C.c_int32, C.c_int32, vp, vp,
                                             C.c_size_t, vp]
+        L.kf_decode_select_step_at.restype = C.c_int
+        L.kf_decode_select_step_at.argtypes = [C.POINTER(kf_cache), vp, vp, vp, C.POINTER(kf_schedule), vp, C.c_int32,
+                                               C.POINTER(kf_score_cfg), vp, C.c_int32, C.c_int32, C.c_int32, vp, vp,
+                                               C.c_size_t, vp]
         _lib = L
     return _lib
 
@@ -236,3 +244,17 @@ def kf_decode_select_step(cache: Cache, q, k_new, v_new, q_pos: int, m_hint: int
     _check(lib().kf_decode_select_step(C.byref(cs), _ptr(q), _ptr(k_new), _ptr(v_new), q_pos, m_hint,
                                        C.byref(cfg), _ptr(out), k, w, layout, _ptr(kept_idx), wp, wb,
                                        _stream(stream)))
+
+
+def kf_decode_select_step_at(cache: Cache, q, k_new, v_new, n: int, T: int, tau_init: float, tau_end: float, step,
+                             m_hint: int, scale: float, noise: int = NOISE_GUMBEL, seeds=None, slopes=None,
+                             out=None, k: int = 0, w: int = 0, layout: int = LAYOUT_ORDERED, kept_idx=None,
+                             workspace=None, stream=None, pos_mode: int = POS_ORIGINAL,
+                             score_mode: int = SCORE_PER_LAYER) -> None:
+    """`step`: int32 device tensor of one element holding the decode step number."""
+    cs, cfg = cache.c_struct(), _cfg(1.0, scale, noise, seeds, slopes, pos_mode, score_mode)
+    sched = kf_schedule(n, T, tau_init, tau_end)
+    wp, wb = _ws(workspace)
+    _check(lib().kf_decode_select_step_at(C.byref(cs), _ptr(q), _ptr(k_new), _ptr(v_new), C.byref(sched),
+                                          _ptr(step), m_hint, C.byref(cfg), _ptr(out), k, w, layout,
+                                          _ptr(kept_idx), wp, wb, _stream(stream)))

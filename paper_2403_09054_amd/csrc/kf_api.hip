@@ -110,7 +110,7 @@ const char* kf_last_error(void) { return g_err; }
 
 float kf_tau(int32_t t, int32_t T, float tau_init, float tau_end) {
     const float dtau = (tau_end - tau_init) / (float)T;
-    return tau_init + (float)t * dtau;
+    return kf::schedule_tau(tau_init, dtau, t);
 }
 
 uint32_t kf_noise_bits(uint64_t seed, uint32_t layer, uint32_t head, uint32_t q_pos, uint32_t k_pos) {
@@ -234,6 +234,11 @@ static kf_status prepare_decode(kf_cache* c, const void* q, const void* k_new, c
     a->noise = cfg->noise;
     a->new_pos = cfg->pos_mode == KF_POS_NEW ? 1 : 0;
     a->shared = cfg->score_mode == KF_SCORE_SHARED ? 1 : 0;
+    a->step = nullptr;
+    a->n0 = 0;
+    a->T = 1;
+    a->tau_init = 0.0f;
+    a->dtau = 0.0f;
     a->inv_tau = 1.0f / cfg->tau;
     a->scale = cfg->scale;
     *plan = p;
@@ -281,6 +286,7 @@ static kf_status prepare_select(kf_cache* c, int32_t k, int32_t w, int32_t layou
     a->layout = layout;
     a->move = 1;
     a->ws_err = (int32_t*)workspace + KF_WS_ERROR_WORD;
+    a->step_inc = nullptr;
     (void)U;
     return KF_OK;
 }
@@ -358,10 +364,11 @@ kf_status kf_select_evict_into(const kf_cache* src, kf_cache* dst, int32_t dst_l
     return KF_OK;
 }
 
-kf_status kf_decode_select_step(kf_cache* c, const void* q, const void* k_new, const void* v_new, int32_t q_pos,
-                                int32_t m_hint, const kf_score_cfg* cfg, float* out, int32_t k, int32_t w,
-                                int32_t layout, int32_t* kept_idx, void* workspace, size_t workspace_bytes,
-                                void* stream) {
+// One generation step in one call.  With a schedule, the step number comes from device memory.
+static kf_status fused_step(kf_cache* c, const void* q, const void* k_new, const void* v_new, int32_t q_pos,
+                            const kf_schedule* sched, int32_t* step, int32_t m_hint, const kf_score_cfg* cfg,
+                            float* out, int32_t k, int32_t w, int32_t layout, int32_t* kept_idx, void* workspace,
+                            size_t workspace_bytes, void* stream) {
     kf::DecodeArgs da;
     kf::DecodePlan p;
     kf_status st = prepare_decode(c, q, k_new, v_new, q_pos, m_hint, cfg, out, workspace, workspace_bytes, &da, &p);
@@ -369,6 +376,14 @@ kf_status kf_decode_select_step(kf_cache* c, const void* q, const void* k_new, c
     kf::SelectArgs sa;
     st = prepare_select(c, k, w, layout, kept_idx, workspace, workspace_bytes, true, &sa);
     if (st != KF_OK) return st;
+    if (sched) {
+        da.step = step;
+        da.n0 = sched->n;
+        da.T = sched->T;
+        da.tau_init = sched->tau_init;
+        da.dtau = (sched->tau_end - sched->tau_init) / (float)sched->T;  // as in kf_tau
+        sa.step_inc = step;
+    }
     const int64_t U = (int64_t)c->L * c->B * c->H;
     hipError_t e;
     if (da.shared) {  // the layers' increments must be added up between the merge and the selection
@@ -385,6 +400,30 @@ kf_status kf_decode_select_step(kf_cache* c, const void* q, const void* k_new, c
     if (e != hipSuccess) return fail(KF_EDEVICE, "step launch: %s", hipGetErrorString(e));
     g_err[0] = 0;
     return KF_OK;
+}
+
+kf_status kf_decode_select_step(kf_cache* c, const void* q, const void* k_new, const void* v_new, int32_t q_pos,
+                                int32_t m_hint, const kf_score_cfg* cfg, float* out, int32_t k, int32_t w,
+                                int32_t layout, int32_t* kept_idx, void* workspace, size_t workspace_bytes,
+                                void* stream) {
+    return fused_step(c, q, k_new, v_new, q_pos, nullptr, nullptr, m_hint, cfg, out, k, w, layout, kept_idx,
+                      workspace, workspace_bytes, stream);
+}
+
+kf_status kf_decode_select_step_at(kf_cache* c, const void* q, const void* k_new, const void* v_new,
+                                   const kf_schedule* sched, int32_t* step, int32_t m_hint, const kf_score_cfg* cfg,
+                                   float* out, int32_t k, int32_t w, int32_t layout, int32_t* kept_idx,
+                                   void* workspace, size_t workspace_bytes, void* stream) {
+    if (!sched || !step) return fail(KF_EINVAL, "sched and step must not be NULL");
+    if (sched->n < 0 || sched->T < 1) return fail(KF_EINVAL, "schedule needs n >= 0 and T >= 1");
+    if (!(sched->tau_init > 0.0f) || !(sched->tau_end > 0.0f) || !isfinite(sched->tau_init) ||
+        !isfinite(sched->tau_end))
+        return fail(KF_EINVAL, "schedule temperatures must be finite and positive");
+    if (!cfg) return fail(KF_EINVAL, "score configuration is NULL");
+    kf_score_cfg cfg2 = *cfg;
+    cfg2.tau = sched->tau_init;  // ignored by the kernels; keeps the common validation meaningful
+    return fused_step(c, q, k_new, v_new, 0, sched, step, m_hint, &cfg2, out, k, w, layout, kept_idx, workspace,
+                      workspace_bytes, stream);
 }
 
 }  // extern "C"

@@ -147,6 +147,15 @@ __global__ void __launch_bounds__(NT) decode_kernel(const DecodeArgs a) {
     const int s = blockIdx.x % S;
     const int h = (int)(u % a.H), b = (int)((u / a.H) % a.B), l = a.layer0 + (int)(u / ((int64_t)a.H * a.B));
 
+    // query position and temperature of this step: from the host, or from the device step counter
+    // (same fp32 operations, in the same order, as the host's schedule function)
+    int q_pos = a.q_pos;
+    float inv_tau = a.inv_tau;
+    if (a.step) {
+        const int t = max(*a.step, 1);  // decode steps count from 1 (0 is the prompt iteration)
+        q_pos = a.n0 + t - 1;
+        inv_tau = 1.0f / schedule_tau(a.tau_init, a.dtau, min(t, a.T));  // IEEE division, as on the host
+    }
     const int len0 = a.len[u];
     const int m = len0 + 1;
     if (len0 < 0 || len0 >= a.cap || len0 > S * a.chunk) {
@@ -182,7 +191,7 @@ __global__ void __launch_bounds__(NT) decode_kernel(const DecodeArgs a) {
     if (owner) {
         if (wv == 0 && lane < LPR) ((uint4*)(a.K))[((size_t)u * a.cap + len0) * LPR + lane] = ((const uint4*)knew)[lane];
         if (wv == 1 && lane < LPR) ((uint4*)(a.V))[((size_t)u * a.cap + len0) * LPR + lane] = ((const uint4*)vnew)[lane];
-        if (tid == 2 * kWave) pu[len0] = a.q_pos;
+        if (tid == 2 * kWave) pu[len0] = q_pos;
     }
 
     QueryPiece<T> qp;
@@ -257,14 +266,14 @@ __global__ void __launch_bounds__(NT) decode_kernel(const DecodeArgs a) {
     const float slope = a.slopes ? a.slopes[h] : 0.0f;
     uint32_t rkey = 0;
     if (a.noise == kNoiseGumbel || a.noise == kNoiseGaussian)
-        rkey = row_key(unit_key(a.seeds[b], (uint32_t)l, (uint32_t)h), (uint32_t)a.q_pos);
+        rkey = row_key(unit_key(a.seeds[b], (uint32_t)l, (uint32_t)h), (uint32_t)q_pos);
     float mx = -INFINITY, my = -INFINITY;
     for (int t = tid; t < cnt; t += NT) {
-        const int pj = (t == cnt_c) ? a.q_pos : pu[j0 + t];  // t == cnt_c: the new token
+        const int pj = (t == cnt_c) ? q_pos : pu[j0 + t];  // t == cnt_c: the new token
         // base-2 domain: x2 = log2(e)*x, y2 = log2(e)*(x + zeta)/tau
-        const int dist = a.new_pos ? (len0 - (j0 + t)) : (a.q_pos - pj);  // the new token: 0 either way
+        const int dist = a.new_pos ? (len0 - (j0 + t)) : (q_pos - pj);  // the new token: 0 either way
         const float x = (xs[t] - slope * (float)((t == cnt_c) ? 0 : dist)) * kLog2e;
-        const float y = (x + zeta_log2e(a.noise, rkey, (uint32_t)pj)) * a.inv_tau;
+        const float y = (x + zeta_log2e(a.noise, rkey, (uint32_t)pj)) * inv_tau;
         xs[t] = x;
         ys[t] = y;
         mx = fmaxf(mx, x);

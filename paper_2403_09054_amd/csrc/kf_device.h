@@ -122,6 +122,15 @@ __host__ __device__ __forceinline__ uint32_t logit_bits(uint32_t rkey, uint32_t 
 // also where u is next to 1; exp2 is within 8.3e-8 relative on [-40, 20].
 __device__ __forceinline__ float hw_log2(float x) { return __builtin_amdgcn_logf(x); }
 __device__ __forceinline__ float hw_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+// Temperature schedule (Eq. 12) in fp32: one multiplication, one addition, each
+// rounded on its own.  Host and device must produce the same bits, so the
+// compiler may not contract the pair into a fused multiply-add.
+__host__ __device__ inline float schedule_tau(float tau_init, float dtau, int t) {
+#pragma clang fp contract(off)
+    const float ramp = (float)t * dtau;
+    return tau_init + ramp;
+}
+
 constexpr float kLog2e = 1.44269504088896340736f;
 constexpr float kLn2 = 0.69314718055994530942f;
 constexpr float kLog2Ln2 = -0.52876637294489779f;  // log2(ln 2)

@@ -32,6 +32,11 @@ struct DecodeArgs {
     int32_t noise;
     int32_t new_pos;   // position bias from slot indices instead of original positions
     int32_t shared;    // one score for all layers: leave the normalised increments in ws_e, do not touch score
+    // Step taken from device memory (non-NULL `step`): t = *step, q_pos = n0 + t - 1,
+    // tau = tau_init + min(t, T)*dtau; q_pos and inv_tau above are then ignored.
+    const int32_t* step;
+    int32_t n0, T;
+    float tau_init, dtau;
     float inv_tau;
     float scale;
 };
@@ -71,6 +76,7 @@ struct SelectArgs {
     int32_t layout;         // kf_layout
     int32_t move;           // 0: only write the survivor index list (rows are gathered elsewhere)
     int32_t* ws_err;        // [1] skipped-unit counter
+    int32_t* step_inc;      // NULL, or the device step counter this launch advances by one when it is done
 };
 hipError_t launch_select(const SelectArgs& a, int64_t U, hipStream_t stream);
 struct GatherArgs {

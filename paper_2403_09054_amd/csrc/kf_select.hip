@@ -469,9 +469,17 @@ __device__ __forceinline__ void select_unit(const SelectArgs& a, int64_t u) {
     if (tid == 0) a.len[u] = k;
 }
 
+// Last launch of a step whose number lives in device memory: one lane moves the
+// counter on.  No workgroup of this launch reads the counter, and the next
+// step's launches start after this one has drained.
+__device__ __forceinline__ void advance_step(const SelectArgs& a) {
+    if (a.step_inc && blockIdx.x == 0 && threadIdx.x == 0) *a.step_inc += 1;
+}
+
 template <int NT>
 __global__ void __launch_bounds__(NT) select_kernel(const SelectArgs a) {
     select_unit<NT>(a, (int64_t)blockIdx.x);
+    advance_step(a);
 }
 
 // Tail of a fused generation step: merge the decode kernel's split records of
@@ -488,6 +496,7 @@ __global__ void __launch_bounds__(NT) step_tail_kernel(const DecodeArgs d, const
         __syncthreads();  // the merged scores and the new length are visible to the whole workgroup
     }
     select_unit<NT>(a, u);
+    advance_step(a);
 }
 
 template <int NT>

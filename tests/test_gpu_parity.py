@@ -618,3 +618,77 @@ def test_shared_score_fused_step_and_disagreeing_layers():
     assert error_word(ws2) == 1
     assert torch.equal(c.score[:, 0, 1, :200], before[:, 0, 1, :200])
     assert not torch.equal(c.score[:, 0, 0, :200], before[:, 0, 0, :200])
+
+
+# ------------------------------------------------------------------ step number in device memory
+@pytest.mark.parametrize("name,kwargs,shared", [("gptj", dict(L=2, H=8, T=12), False),   # splits + fused tail
+                                                ("tiny", dict(T=12), False),             # one split per unit
+                                                ("tiny", dict(L=2, T=12), True)])
+def test_one_captured_step_replays_as_successive_steps(name, kwargs, shared):
+    """kf_decode_select_step_at reads t from device memory (q_pos = n+t-1, tau = tau_t) and advances it: ONE
+    step captured in a HIP graph, replayed with refreshed inputs, must equal the eager host-driven steps
+    bit for bit -- including the steps past T, which keep tau_end."""
+    wl = kw.CONFIGS[name].slice(**kwargs)
+    rng = np.random.default_rng(5)
+    dt = ko.F32 if wl.dtype == "f32" else ko.BF16
+    k, cap = wl.k, wl.k + 1
+    oc = random_cache(rng, wl.L, wl.B, wl.H, wl.d, cap, dt, k)
+    oc.pos[...] = np.arange(wl.n - k, wl.n - k + cap)       # the k most recent prompt positions
+    if shared:
+        oc.score[...] = oc.score[0]
+    seeds = dev(kw.noise_seeds(wl))
+    n_steps = wl.T + 3
+    inputs = [tuple(t.cuda() for t in kw.decode_inputs(wl, t)) for t in range(1, n_steps + 1)]
+    mode = kf.SCORE_SHARED if shared else kf.SCORE_PER_LAYER
+
+    # eager, host-driven reference
+    a = upload(oc)
+    ws_a = kf.new_workspace(a)
+    out_a = torch.zeros((wl.L, wl.B, wl.H, wl.d), dtype=torch.float32, device="cuda")
+    ref = []
+    for t in range(1, n_steps + 1):
+        q, kn, vn = inputs[t - 1]
+        kf.kf_decode_select_step(a, q, kn, vn, wl.n + t - 1, cap, kf.kf_tau(min(t, wl.T), wl.T, wl.tau_init, wl.tau_end),
+                                 wl.scale, kf.NOISE_GUMBEL, seeds, None, out_a, k=k, w=wl.w, workspace=ws_a,
+                                 score_mode=mode)
+        torch.cuda.synchronize()
+        ref.append([host(x).copy() for x in (out_a, a.score, a.pos, a.len)])
+    assert error_word(ws_a) == 0
+
+    # one captured step, replayed
+    b_ = upload(oc)
+    ws_b = kf.new_workspace(b_)
+    out_b = torch.zeros_like(out_a)
+    step = torch.ones(1, dtype=torch.int32, device="cuda")
+    qb, kb, vb = (torch.empty_like(x) for x in inputs[0])
+
+    def one():
+        kf.kf_decode_select_step_at(b_, qb, kb, vb, wl.n, wl.T, wl.tau_init, wl.tau_end, step, cap, wl.scale,
+                                    kf.NOISE_GUMBEL, seeds, None, out_b, k=k, w=wl.w, workspace=ws_b, score_mode=mode)
+
+    for src, dst in zip(inputs[0], (qb, kb, vb)):
+        dst.copy_(src)
+    one()                                  # step 1 eagerly (loads the kernels before the capture)
+    torch.cuda.synchronize()
+    assert int(step.item()) == 2
+    for x, y in zip([host(x) for x in (out_b, b_.score, b_.pos, b_.len)], ref[0]):
+        np.testing.assert_array_equal(x, y)
+    g = torch.cuda.CUDAGraph()
+    state = [x.clone() for x in (b_.K, b_.V, b_.score, b_.pos, b_.len)]
+    with torch.cuda.graph(g):
+        one()
+    # the capture did not execute anything: restore is not needed, but the counter must still say 2
+    torch.cuda.synchronize()
+    assert int(step.item()) == 2
+    for x, y in zip((b_.K, b_.V, b_.score, b_.pos, b_.len), state):
+        assert torch.equal(x, y)
+    for t in range(2, n_steps + 1):
+        for src, dst in zip(inputs[t - 1], (qb, kb, vb)):
+            dst.copy_(src)
+        (out_b * 0).sum().item()           # unrelated eager work + a synchronisation between replays
+        g.replay()
+        torch.cuda.synchronize()
+        assert int(step.item()) == t + 1
+        for x, y in zip([host(x) for x in (out_b, b_.score, b_.pos, b_.len)], ref[t - 1]):
+            np.testing.assert_array_equal(x, y)
+    assert error_word(ws_b) == 0

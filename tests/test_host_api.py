@@ -155,3 +155,25 @@ def test_decode_launch_plan_is_consistent_with_workspace():
         nbytes = kf.kf_workspace_bytes(c, 0)
         U = L * B * H
         assert nbytes >= U * cap * 4 + U * 4          # at least the increments and the counters
+
+
+def test_step_from_device_memory_argument_validation():
+    c = fake_cache()
+    good = dict(n=64, T=32, tau_init=1.0, tau_end=2.0, step=0x6000, score_mode=kf.SCORE_PER_LAYER, k=8, w=2)
+
+    def call(**over):
+        a = dict(good)
+        a.update(over)
+        kf.kf_decode_select_step_at(c, 0x1000, 0x2000, 0x3000, a["n"], a["T"], a["tau_init"], a["tau_end"], a["step"],
+                                    0, 0.1, kf.NOISE_GUMBEL, 0x4000, None, 0x5000, k=a["k"], w=a["w"], workspace=WS,
+                                    stream=0, score_mode=a["score_mode"])
+
+    for bad in (dict(step=None), dict(n=-1), dict(T=0), dict(tau_init=0.0), dict(tau_end=float("nan")),
+                dict(tau_end=float("inf")), dict(score_mode=5), dict(k=0), dict(w=9)):
+        expect(binding.KF_EINVAL, call, **bad)
+
+
+def test_unknown_score_mode_is_rejected():
+    c = fake_cache()
+    expect(binding.KF_EINVAL, kf.kf_decode_step, c, 0x1000, 0x2000, 0x3000, 10, 0, 1.5, 0.1, kf.NOISE_GUMBEL, 0x4000,
+           None, 0x5000, WS, 0, score_mode=2)
