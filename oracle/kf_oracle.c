@@ -22,6 +22,9 @@
  *                      order-preserving compaction                [Alg. 1 last three lines, Sec. 3.4]
  *   (shared != 0 in the two scoring calls: the "Shared" score function of the
  *    ablation -- one f for all layers, each layer's increments added to it)  [Sec. 4.4.1]
+ *   (G > 1 in the two scoring calls: grouped-query / multi-query attention, which
+ *    the paper says the method applies to unchanged -- G query heads read one
+ *    cached head and its f takes the sum of their increments)               [Sec. 6]
  *
  * All arithmetic is done in double on the exact input bits (fp32, or bf16
  * given as uint16).  State that persists between steps (the accumulated score
@@ -187,14 +190,17 @@ static void softmax_inplace(double *v, int m)
 /*   y_ij = (x_ij + zeta_ij)/tau                                         */
 /*   z_i  = softmax_j(y_i.)                                              */
 /*   f[j] = sum_{i>=j} z_ij ;  pos[j] = j ; len = n                       */
-/* Q is [U][n][d]; K is the cache's K, [U][cap][d], rows 0..n-1 filled.  */
+/* Q is [U*G][n][d]; K is the cache's K, [U][cap][d], rows 0..n-1 filled. */
+/* G > 1: grouped-query attention [Sec. 6]: the cache's head h serves the   */
+/* query heads h*G .. h*G+G-1 (each with its own slope and noise stream);   */
+/* its f is the sum of their column sums.                                  */
 /* ------------------------------------------------------------------ */
 int kfo_prefill_score(const void *Q, const void *K, float *score, int32_t *pos,
                       int32_t *len, int L, int B, int H, int d, int cap,
                       int dtype, int layer0, int n, float tau, float scale, int noise,
-                      const uint64_t *seeds, const float *slopes, int shared)
+                      const uint64_t *seeds, const float *slopes, int shared, int G)
 {
-    if (n < 1 || n > cap || !(tau > 0.0f)) return -1;
+    if (n < 1 || n > cap || !(tau > 0.0f) || G < 1) return -1;
     int U = L * B * H;
     /* "Shared" score function [Sec. 4.4.1]: every layer's column sums, kept in
      * double until the layers have been added up */
@@ -204,51 +210,54 @@ int kfo_prefill_score(const void *Q, const void *K, float *score, int32_t *pos,
         if (!fall) return -2;
     }
     for (int u = 0; u < U; ++u) {
-        int h = u % H, b = (u / H) % B, l = layer0 + u / (H * B);
-        double slope = slopes ? (double)slopes[h] : 0.0;
+        int hk = u % H, b = (u / H) % B, l = layer0 + u / (H * B);
         uint64_t seed = seeds ? seeds[b] : 0;
         double *q = (double *)malloc((size_t)n * d * sizeof(double));
         double *kk = (double *)malloc((size_t)n * d * sizeof(double));
         double *f = (double *)calloc((size_t)n, sizeof(double));
         if (!q || !kk || !f) { free(q); free(kk); free(f); free(fall); return -2; }
-        for (size_t e = 0; e < (size_t)n * d; ++e) {
-            q[e] = load_elem(Q, dtype, (size_t)u * n * d + e);
+        for (size_t e = 0; e < (size_t)n * d; ++e)
             kk[e] = load_elem(K, dtype, (size_t)u * cap * d + e);
-        }
         int failed = 0;
+        for (int g = 0; g < G; ++g) {
+            int h = hk * G + g;                        /* the query head */
+            double slope = slopes ? (double)slopes[h] : 0.0;
+            for (size_t e = 0; e < (size_t)n * d; ++e)
+                q[e] = load_elem(Q, dtype, ((size_t)u * G + g) * n * d + e);
 #pragma omp parallel
-        {
-            double *fl = (double *)calloc((size_t)n, sizeof(double));
-            double *row = (double *)malloc((size_t)n * sizeof(double));
-            int ok = fl && row;
-            if (!ok) {
+            {
+                double *fl = (double *)calloc((size_t)n, sizeof(double));
+                double *row = (double *)malloc((size_t)n * sizeof(double));
+                int ok = fl && row;
+                if (!ok) {
 #pragma omp atomic write
-                failed = 1;
-            }
-#pragma omp for schedule(dynamic, 8)
-            for (int i = 0; i < n; ++i) {
-                if (!ok) continue;
-                for (int j = 0; j <= i; ++j) {
-                    double dot = 0.0;
-                    for (int c = 0; c < d; ++c)
-                        dot += q[(size_t)i * d + c] * kk[(size_t)j * d + c];
-                    double x = (double)scale * dot - slope * (double)(i - j);
-                    double z = zeta(noise, seed, (uint32_t)l, (uint32_t)h,
-                                    (uint32_t)i, (uint32_t)j);
-                    row[j] = (x + z) / (double)tau;
+                    failed = 1;
                 }
-                softmax_inplace(row, i + 1);
-                for (int j = 0; j <= i; ++j)
-                    fl[j] += row[j];
-            }
-            /* add the threads' column sums one thread at a time */
-            if (ok) {
+#pragma omp for schedule(dynamic, 8)
+                for (int i = 0; i < n; ++i) {
+                    if (!ok) continue;
+                    for (int j = 0; j <= i; ++j) {
+                        double dot = 0.0;
+                        for (int c = 0; c < d; ++c)
+                            dot += q[(size_t)i * d + c] * kk[(size_t)j * d + c];
+                        double x = (double)scale * dot - slope * (double)(i - j);
+                        double z = zeta(noise, seed, (uint32_t)l, (uint32_t)h,
+                                        (uint32_t)i, (uint32_t)j);
+                        row[j] = (x + z) / (double)tau;
+                    }
+                    softmax_inplace(row, i + 1);
+                    for (int j = 0; j <= i; ++j)
+                        fl[j] += row[j];
+                }
+                /* add the threads' column sums one thread at a time */
+                if (ok) {
 #pragma omp critical
-                for (int j = 0; j < n; ++j)
-                    f[j] += fl[j];
+                    for (int j = 0; j < n; ++j)
+                        f[j] += fl[j];
+                }
+                free(fl);
+                free(row);
             }
-            free(fl);
-            free(row);
         }
         if (failed) { free(q); free(kk); free(f); free(fall); return -2; }
         for (int j = 0; j < n; ++j) {
@@ -284,17 +293,21 @@ int kfo_prefill_score(const void *Q, const void *K, float *score, int32_t *pos,
 /*   x_j = scale*<q,K_j> - slope_h*(q_pos - pos_j)                       */
 /*   attention: p = softmax(x),          out = sum_j p_j V_j             */
 /*   score:     df = softmax((x+zeta)/tau),  f_j += df_j  for all j < m  */
-/* q, k_new, v_new are [U][d]; out is [U][d] fp32.                       */
-/* Optional debug outputs (may be NULL): dbg_p, dbg_df [U][cap] doubles. */
+/* k_new, v_new are [U][d]; q is [U*G][d]; out is [U*G][d] fp32.         */
+/* G > 1: grouped-query attention [Sec. 6]: the cache's head h serves the */
+/* query heads h*G .. h*G+G-1, each with its own logits, attention output, */
+/* slope and noise stream; f takes the sum of their increments (the heads  */
+/* share the cached tokens, so they share the decision what to keep).     */
+/* Optional debug outputs (may be NULL): dbg_p, dbg_df [U*G][cap] doubles. */
 /* ------------------------------------------------------------------ */
 int kfo_decode_step(void *K, void *V, float *score, int32_t *pos, int32_t *len,
                     int L, int B, int H, int d, int cap, int dtype, int layer0,
                     const void *q, const void *k_new, const void *v_new,
                     int32_t q_pos, float tau, float scale, int noise,
                     const uint64_t *seeds, const float *slopes, int new_pos, int shared,
-                    float *out, double *dbg_p, double *dbg_df)
+                    int G, float *out, double *dbg_p, double *dbg_df)
 {
-    if (!(tau > 0.0f)) return -1;
+    if (!(tau > 0.0f) || G < 1) return -1;
     int U = L * B * H;
     size_t es = elem_size(dtype);
     for (int u = 0; u < U; ++u)
@@ -316,8 +329,7 @@ int kfo_decode_step(void *K, void *V, float *score, int32_t *pos, int32_t *len,
     int failed = 0;
 #pragma omp parallel for schedule(dynamic, 1)
     for (int u = 0; u < U; ++u) {
-        int h = u % H, b = (u / H) % B, l = layer0 + u / (H * B);
-        double slope = slopes ? (double)slopes[h] : 0.0;
+        int hk = u % H, b = (u / H) % B, l = layer0 + u / (H * B);
         uint64_t seed = seeds ? seeds[b] : 0;
         char *Ku = (char *)K + (size_t)u * cap * d * es;
         char *Vu = (char *)V + (size_t)u * cap * d * es;
@@ -335,42 +347,52 @@ int kfo_decode_step(void *K, void *V, float *score, int32_t *pos, int32_t *len,
 
         double *p = (double *)malloc((size_t)m * sizeof(double));
         double *y = (double *)malloc((size_t)m * sizeof(double));
-        if (!p || !y) {
-            free(p); free(y);
+        double *df = (double *)calloc((size_t)m, sizeof(double));
+        if (!p || !y || !df) {
+            free(p); free(y); free(df);
 #pragma omp atomic write
             failed = 1;
             continue;
         }
-        for (int j = 0; j < m; ++j) {
-            double dot = 0.0;
-            for (int c = 0; c < d; ++c)
-                dot += load_elem(q, dtype, (size_t)u * d + c) *
-                       load_elem(Ku, dtype, (size_t)j * d + c);
-            /* distance behind the position bias: original positions ("Org Pos"), or -- the
-             * paper's "New Pos" ablation, Sec. 4.4.2 -- positions within the reduced cache,
-             * where the query sits at slot m-1 and key j at slot j */
-            double dist = new_pos ? (double)(m - 1 - j) : (double)(q_pos - pu[j]);
-            double x = (double)scale * dot - slope * dist;
-            p[j] = x;
-            y[j] = (x + zeta(noise, seed, (uint32_t)l, (uint32_t)h,
-                             (uint32_t)q_pos, (uint32_t)pu[j])) / (double)tau;
+        for (int g = 0; g < G; ++g) {
+            int h = hk * G + g;                        /* the query head */
+            size_t uq = (size_t)u * G + g;
+            double slope = slopes ? (double)slopes[h] : 0.0;
+            for (int j = 0; j < m; ++j) {
+                double dot = 0.0;
+                for (int c = 0; c < d; ++c)
+                    dot += load_elem(q, dtype, uq * d + c) *
+                           load_elem(Ku, dtype, (size_t)j * d + c);
+                /* distance behind the position bias: original positions ("Org Pos"), or -- the
+                 * paper's "New Pos" ablation, Sec. 4.4.2 -- positions within the reduced cache,
+                 * where the query sits at slot m-1 and key j at slot j */
+                double dist = new_pos ? (double)(m - 1 - j) : (double)(q_pos - pu[j]);
+                double x = (double)scale * dot - slope * dist;
+                p[j] = x;
+                y[j] = (x + zeta(noise, seed, (uint32_t)l, (uint32_t)h,
+                                 (uint32_t)q_pos, (uint32_t)pu[j])) / (double)tau;
+            }
+            softmax_inplace(p, m); /* attention probabilities: clean logits */
+            softmax_inplace(y, m); /* score increment: perturbed, tempered logits */
+            for (int c = 0; c < d; ++c) {
+                double o = 0.0;
+                for (int j = 0; j < m; ++j)
+                    o += p[j] * load_elem(Vu, dtype, (size_t)j * d + c);
+                out[uq * d + c] = (float)o;
+            }
+            for (int j = 0; j < m; ++j) {
+                df[j] += y[j];
+                if (dbg_p) dbg_p[uq * cap + j] = p[j];
+                if (dbg_df) dbg_df[uq * cap + j] = y[j];
+            }
         }
-        softmax_inplace(p, m); /* attention probabilities: clean logits */
-        softmax_inplace(y, m); /* score increment: perturbed, tempered logits */
-        for (int c = 0; c < d; ++c) {
-            double o = 0.0;
-            for (int j = 0; j < m; ++j)
-                o += p[j] * load_elem(Vu, dtype, (size_t)j * d + c);
-            out[(size_t)u * d + c] = (float)o;
-        }
         for (int j = 0; j < m; ++j) {
-            if (shared) dfall[(size_t)u * cap + j] = y[j];
-            else fu[j] = (float)((double)fu[j] + y[j]);
-            if (dbg_p) dbg_p[(size_t)u * cap + j] = p[j];
-            if (dbg_df) dbg_df[(size_t)u * cap + j] = y[j];
+            if (shared) dfall[(size_t)u * cap + j] = df[j];
+            else fu[j] = (float)((double)fu[j] + df[j]);
         }
         free(p);
         free(y);
+        free(df);
     }
     if (shared && !failed) {
         int BH = B * H;

@@ -53,10 +53,10 @@ def lib():
         vp = C.c_void_p
         L.kfo_prefill_score.restype = C.c_int
         L.kfo_prefill_score.argtypes = [vp, vp, vp, vp, vp] + [C.c_int] * 8 + [
-            C.c_float, C.c_float, C.c_int, vp, vp, C.c_int]
+            C.c_float, C.c_float, C.c_int, vp, vp, C.c_int, C.c_int]
         L.kfo_decode_step.restype = C.c_int
         L.kfo_decode_step.argtypes = [vp, vp, vp, vp, vp] + [C.c_int] * 7 + [
-            vp, vp, vp, C.c_int32, C.c_float, C.c_float, C.c_int, vp, vp, C.c_int, C.c_int, vp, vp, vp]
+            vp, vp, vp, C.c_int32, C.c_float, C.c_float, C.c_int, vp, vp, C.c_int, C.c_int, C.c_int, vp, vp, vp]
         L.kfo_select_evict.restype = C.c_int
         L.kfo_select_evict.argtypes = [vp, vp, vp, vp, vp] + [C.c_int] * 8 + [vp]
         _lib = L
@@ -120,36 +120,41 @@ class OracleCache:
             if a is not None:
                 assert a.flags["C_CONTIGUOUS"]
 
-    def prefill_score(self, Q, n, tau_, scale, noise=NOISE_GUMBEL, seeds=None, slopes=None, shared=False):
-        """Q: [L,B,H,n,d] same element type as K; K rows 0..n-1 must be filled.
-        shared: one score function for all layers (the sum of the layers' scores)."""
-        assert Q.shape == (self.L, self.B, self.H, n, self.d) and _dtype_code(Q) == self.dtype
+    def prefill_score(self, Q, n, tau_, scale, noise=NOISE_GUMBEL, seeds=None, slopes=None, shared=False,
+                      q_per_kv=1):
+        """Q: [L,B,H*q_per_kv,n,d] same element type as K; K rows 0..n-1 must be filled.
+        shared: one score function for all layers (the sum of the layers' scores).
+        q_per_kv: query heads per cached head (grouped-query attention)."""
+        assert Q.shape == (self.L, self.B, self.H * q_per_kv, n, self.d) and _dtype_code(Q) == self.dtype
         seeds = None if seeds is None else np.ascontiguousarray(seeds, np.uint64)
         slopes = None if slopes is None else np.ascontiguousarray(slopes, np.float32)
         Q = np.ascontiguousarray(Q)
         rc = lib().kfo_prefill_score(_p(Q), _p(self.K), _p(self.score), _p(self.pos), _p(self.len),
                                      *self._dims(), self.layer0, n, tau_, scale, noise, _p(seeds), _p(slopes),
-                                     int(shared))
+                                     int(shared), int(q_per_kv))
         if rc:
             raise ValueError("kfo_prefill_score rc=%d" % rc)
 
     def decode_step(self, q, k_new, v_new, q_pos, tau_, scale, noise=NOISE_GUMBEL,
-                    seeds=None, slopes=None, debug=False, new_pos=False, shared=False):
-        """q, k_new, v_new: [L,B,H,d].  Returns out [L,B,H,d] float32
-        (and, with debug, the attention probabilities and the score increment
-        as float64 [L,B,H,cap])."""
+                    seeds=None, slopes=None, debug=False, new_pos=False, shared=False,
+                    q_per_kv=1):
+        """k_new, v_new: [L,B,H,d]; q: [L,B,H*q_per_kv,d].  Returns out [L,B,H*q_per_kv,d]
+        float32 (and, with debug, every query head's attention probabilities and score
+        increment as float64 [L,B,H*q_per_kv,cap])."""
         shp = (self.L, self.B, self.H, self.d)
+        qshp = (self.L, self.B, self.H * q_per_kv, self.d)
         q, k_new, v_new = (np.ascontiguousarray(a) for a in (q, k_new, v_new))
-        for a in (q, k_new, v_new):
-            assert a.shape == shp and _dtype_code(a) == self.dtype
+        for a, sh_ in ((q, qshp), (k_new, shp), (v_new, shp)):
+            assert a.shape == sh_ and _dtype_code(a) == self.dtype
         seeds = None if seeds is None else np.ascontiguousarray(seeds, np.uint64)
         slopes = None if slopes is None else np.ascontiguousarray(slopes, np.float32)
-        out = np.zeros(shp, np.float32)
-        dp = np.zeros(self.score.shape, np.float64) if debug else None
-        df = np.zeros(self.score.shape, np.float64) if debug else None
+        out = np.zeros(qshp, np.float32)
+        dshape = (self.L, self.B, self.H * q_per_kv, self.cap)
+        dp = np.zeros(dshape, np.float64) if debug else None
+        df = np.zeros(dshape, np.float64) if debug else None
         rc = lib().kfo_decode_step(_p(self.K), _p(self.V), _p(self.score), _p(self.pos), _p(self.len),
                                    *self._dims(), self.layer0, _p(q), _p(k_new), _p(v_new), q_pos, tau_, scale,
-                                   noise, _p(seeds), _p(slopes), int(new_pos), int(shared), _p(out), _p(dp), _p(df))
+                                   noise, _p(seeds), _p(slopes), int(new_pos), int(shared), int(q_per_kv), _p(out), _p(dp), _p(df))
         if rc:
             raise ValueError("kfo_decode_step rc=%d" % rc)
         return (out, dp, df) if debug else out

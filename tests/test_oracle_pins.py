@@ -472,6 +472,69 @@ def test_shared_score_special_cases():
 
 
 # ----------------------------------------------------------------------------
+# Grouped-query attention (Sec. 6): G query heads per cached head
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("G", [2, 4])
+def test_grouped_queries_equal_replicated_kv_heads(G):
+    """A cache whose head serves G query heads computes what a one-query-per-head cache with that head's
+    K/V replicated G times computes (attention outputs, per-head increments); its score is the sum of the
+    replicas' scores.  The replicated run is the already pinned path, so head numbering, slopes and noise
+    streams of the grouped run are pinned through it."""
+    rng = np.random.default_rng(31 + G)
+    L, B, H, d, n, cap = 2, 2, 2, 16, 19, 26
+    grp = make_cache(rng, L, B, H, d, cap, n, ko.BF16)
+    rep = ko.OracleCache(L, B, H * G, d, cap, ko.BF16)
+    for h in range(H * G):
+        rep.K[:, :, h], rep.V[:, :, h] = grp.K[:, :, h // G], grp.V[:, :, h // G]
+    Q = rand_vec(rng, (L, B, H * G, n, d), ko.BF16)
+    seeds = np.array([41, 42], np.uint64)
+    slopes = (0.5 ** np.arange(1, H * G + 1)).astype(np.float32)
+    grp.prefill_score(Q, n, 1.25, 0.25, ko.NOISE_GUMBEL, seeds, slopes, q_per_kv=G)
+    rep.prefill_score(Q, n, 1.25, 0.25, ko.NOISE_GUMBEL, seeds, slopes)
+    f_sum = rep.score.astype(np.float64).reshape(L, B, H, G, cap).sum(axis=3)
+    np.testing.assert_allclose(grp.score[..., :n], f_sum[..., :n], rtol=3e-7)
+    assert abs(grp.score[..., :n].astype(np.float64).sum() - L * B * H * G * n) < 1e-3
+    assert (grp.len == n).all() and (grp.pos[..., :n] == np.arange(n)).all()
+
+    rep.score[...] = np.repeat(grp.score, G, axis=2) / G          # any common starting point will do
+    start = grp.score.copy()
+    q = rand_vec(rng, (L, B, H * G, d), ko.BF16)
+    kn, vn = (rand_vec(rng, (L, B, H, d), ko.BF16) for _ in range(2))
+    out_g, p_g, df_g = grp.decode_step(q, kn, vn, n, 1.5, 0.25, ko.NOISE_GUMBEL, seeds, slopes, debug=True, q_per_kv=G)
+    out_r, p_r, df_r = rep.decode_step(q, np.repeat(kn, G, axis=2), np.repeat(vn, G, axis=2), n, 1.5, 0.25,
+                                       ko.NOISE_GUMBEL, seeds, slopes, debug=True)
+    np.testing.assert_array_equal(out_g, out_r)
+    np.testing.assert_array_equal(p_g, p_r)
+    np.testing.assert_array_equal(df_g, df_r)
+    m = n + 1
+    inc = df_r.reshape(L, B, H, G, cap).sum(axis=3)
+    want = np.concatenate([start[..., :n].astype(np.float64), np.zeros((L, B, H, 1))], axis=-1) + inc[..., :m]
+    np.testing.assert_allclose(grp.score[..., :m], want, rtol=2e-7)
+    assert (grp.len == m).all() and (grp.pos[..., n] == n).all()
+    assert (grp.K[..., n, :] == kn).all() and (grp.V[..., n, :] == vn).all()
+
+
+def test_grouped_queries_special_cases():
+    rng = np.random.default_rng(33)
+    B, H, d, n, cap, G = 1, 2, 8, 10, 12, 4
+    # identical query heads, no adjustment: every head attends alike, the score gains G times one head's increment
+    one = make_cache(rng, 1, B, H, d, cap, n)
+    many = one.copy()
+    q1 = rand_vec(rng, (1, B, H, d), ko.F32)
+    kn, vn = (rand_vec(rng, (1, B, H, d), ko.F32) for _ in range(2))
+    o1, _, df1 = one.decode_step(q1, kn, vn, n, 1.0, 0.3, ko.NOISE_NONE, debug=True)
+    oG, _, dfG = many.decode_step(np.repeat(q1, G, axis=2), kn, vn, n, 1.0, 0.3, ko.NOISE_NONE, debug=True, q_per_kv=G)
+    np.testing.assert_array_equal(oG, np.repeat(o1, G, axis=2))
+    np.testing.assert_allclose(many.score[..., :n + 1], G * one.score[..., :n + 1].astype(np.float64), rtol=2e-7)
+    # each head draws its own noise: with the adjustment on, identical queries no longer score alike
+    noisy = make_cache(rng, 1, B, H, d, cap, n)
+    _, _, dfn = noisy.decode_step(np.repeat(q1, G, axis=2), kn, vn, n, 1.0, 0.3, ko.NOISE_GUMBEL,
+                                  np.array([9], np.uint64), debug=True, q_per_kv=G)
+    assert np.abs(dfn[0, 0, 0, :n + 1] - dfn[0, 0, 1, :n + 1]).max() > 1e-3
+    assert abs(dfn[0, 0, :, :n + 1].sum() - H * G) < 1e-9          # a probability vector per query head
+
+
+# ----------------------------------------------------------------------------
 # Selection + compaction (Alg. 1: S_w, S_key = argmax_(k-w) f[:-w], S_k)
 # ----------------------------------------------------------------------------
 def brute_force_keep(f, n, k, w):
