@@ -23,7 +23,7 @@
  *    library leaves it reusable after every call.  Calls that share a workspace
  *    must be ordered on one stream.
  *  - Supported element type / head dimension pairs: bf16 with d in {64,128,256},
- *    fp32 with d in {64,128}.
+ *    fp32 with d in {64,128}; query heads per cached head: 1, 2, 4 or 8.
  */
 #ifndef KEYFORMER_H
 #define KEYFORMER_H
@@ -77,6 +77,13 @@ typedef struct {
     int32_t dtype;  /* kf_dtype */
     int32_t layer0; /* model-wide index of the cache's first layer; enters the noise key only, so
                        a cache that holds a subset of the layers draws the same noise */
+    int32_t q_per_kv; /* query heads served by each cached head: 1 (or 0) = multi-head attention;
+                       2, 4 or 8 = grouped-query / multi-query attention (Sec. 6: the method applies
+                       unchanged).  Cached head h then serves query heads h*G .. h*G+G-1: Q, q and
+                       out hold H*G heads ([L][B][H*G]...), alibi_slopes holds H*G slopes, each query
+                       head has its own logits, attention output and noise stream (keyed by the
+                       QUERY head index), and score[.][.][h] accumulates the SUM of its G query
+                       heads' increments -- the heads share the cached tokens, hence the decision */
 } kf_cache;
 
 /* Which positions the position bias sees (Sec. 4.4.2): the tokens' original

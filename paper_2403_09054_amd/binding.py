@@ -35,7 +35,8 @@ class KeyformerError(RuntimeError):
 class kf_cache(C.Structure):
     _fields_ = [("K", C.c_void_p), ("V", C.c_void_p), ("score", C.c_void_p), ("pos", C.c_void_p),
                 ("len", C.c_void_p), ("L", C.c_int32), ("B", C.c_int32), ("H", C.c_int32),
-                ("d", C.c_int32), ("cap", C.c_int32), ("dtype", C.c_int32), ("layer0", C.c_int32)]
+                ("d", C.c_int32), ("cap", C.c_int32), ("dtype", C.c_int32), ("layer0", C.c_int32),
+                ("q_per_kv", C.c_int32)]
 
 
 class kf_score_cfg(C.Structure):
@@ -143,9 +144,10 @@ class Cache:
     cap: int
     dtype: int
     layer0: int = 0
+    q_per_kv: int = 1      # query heads served by each cached head (grouped-query attention if > 1)
 
     @staticmethod
-    def allocate(L, B, H, d, cap, dtype=BF16, device="cuda", layer0=0):
+    def allocate(L, B, H, d, cap, dtype=BF16, device="cuda", layer0=0, q_per_kv=1):
         import torch
         et = torch.float32 if dtype == F32 else torch.bfloat16
         return Cache(K=torch.zeros((L, B, H, cap, d), dtype=et, device=device),
@@ -153,11 +155,11 @@ class Cache:
                      score=torch.zeros((L, B, H, cap), dtype=torch.float32, device=device),
                      pos=torch.zeros((L, B, H, cap), dtype=torch.int32, device=device),
                      len=torch.zeros((L, B, H), dtype=torch.int32, device=device),
-                     L=L, B=B, H=H, d=d, cap=cap, dtype=dtype, layer0=layer0)
+                     L=L, B=B, H=H, d=d, cap=cap, dtype=dtype, layer0=layer0, q_per_kv=q_per_kv)
 
     def c_struct(self) -> kf_cache:
         return kf_cache(_ptr(self.K), _ptr(self.V), _ptr(self.score), _ptr(self.pos), _ptr(self.len),
-                        self.L, self.B, self.H, self.d, self.cap, self.dtype, self.layer0)
+                        self.L, self.B, self.H, self.d, self.cap, self.dtype, self.layer0, self.q_per_kv)
 
 
 def kf_workspace_bytes(cache: Cache, n_max: int = 0) -> int:

@@ -28,6 +28,9 @@ bool supported(int32_t dtype, int32_t d) {
     return false;
 }
 
+bool group_supported(int32_t g) { return g == 0 || g == 1 || g == 2 || g == 4 || g == 8; }
+int32_t group_of(const kf_cache* c) { return c->q_per_kv > 1 ? c->q_per_kv : 1; }
+
 kf_status check_cache(const kf_cache* c) {
     if (!c) return fail(KF_EINVAL, "cache is NULL");
     if (!c->K || !c->V || !c->score || !c->pos || !c->len) return fail(KF_EINVAL, "cache has a NULL buffer");
@@ -40,6 +43,9 @@ kf_status check_cache(const kf_cache* c) {
     if (!supported(c->dtype, c->d))
         return fail(KF_EUNSUPPORTED, "dtype %d with head dimension %d is not built", c->dtype, c->d);
     if (((uintptr_t)c->K | (uintptr_t)c->V) & 15) return fail(KF_EINVAL, "K and V must be 16-byte aligned");
+    if (c->q_per_kv < 0) return fail(KF_EINVAL, "q_per_kv must not be negative");
+    if (!group_supported(c->q_per_kv))
+        return fail(KF_EUNSUPPORTED, "%d query heads per cached head is not built (1, 2, 4 or 8)", c->q_per_kv);
     return KF_OK;
 }
 
@@ -61,19 +67,22 @@ kf_status check_cfg(const kf_score_cfg* cfg) {
 // Workspace layout (all regions 256-byte aligned):
 //   [0]        error word + padding (the only part that must start as zero)
 //   region X   the largest of
-//                decode : partial records U*S*(d+4) floats, then increments U*cap floats, then
+//                decode : partial records U*S*G*(d+4) floats, then increments U*G*cap floats, then
 //                         per-unit token counts U int32 (shared score), then (fused step) the
 //                         survivor index list U*cap int32
 //                select : survivor index list U*cap int32
-//                prefill: row normalisers U*n_pad floats, then row keys U*n_pad uint32
+//                prefill: row normalisers U*G*n_pad floats, then row keys U*G*n_pad uint32, then
+//                         (G > 1) per-query-head column sums U*G*n_pad floats
+//              (G = query heads per cached head)
 struct WsLayout {
     size_t region, fused_idx, total;
 };
 
 size_t decode_region(int64_t U, const kf_cache* c) {
-    const kf::DecodePlan p = kf::plan_decode(U, c->cap, c->d, c->dtype);
-    return align_up((size_t)U * p.S * (c->d + 4) * sizeof(float), 256) +
-           align_up((size_t)U * c->cap * sizeof(float), 256) + align_up((size_t)U * sizeof(int32_t), 256);
+    const int32_t G = group_of(c);
+    const kf::DecodePlan p = kf::plan_decode(U, c->cap, c->d, c->dtype, G);
+    return align_up((size_t)U * p.S * G * (c->d + 4) * sizeof(float), 256) +
+           align_up((size_t)U * G * c->cap * sizeof(float), 256) + align_up((size_t)U * sizeof(int32_t), 256);
 }
 
 WsLayout ws_layout(const kf_cache* c, int32_t n_max) {
@@ -86,7 +95,8 @@ WsLayout ws_layout(const kf_cache* c, int32_t n_max) {
     size_t x = dec + sel;
     if (n_max > 0) {
         const size_t n_pad = align_up((size_t)n_max, kf::kPrefillRowPad);
-        const size_t pre = 2 * align_up((size_t)U * n_pad * sizeof(float), 256);
+        const int32_t G = group_of(c);
+        const size_t pre = (G > 1 ? 3 : 2) * align_up((size_t)U * G * n_pad * sizeof(float), 256);
         if (pre > x) x = pre;
     }
     w.total = w.region + x;
@@ -119,6 +129,7 @@ uint32_t kf_noise_bits(uint64_t seed, uint32_t layer, uint32_t head, uint32_t q_
 
 size_t kf_workspace_bytes(const kf_cache* c, int32_t n_max) {
     if (!c || c->L < 1 || c->B < 1 || c->H < 1 || c->cap < 1 || !supported(c->dtype, c->d)) return 0;
+    if (!group_supported(c->q_per_kv)) return 0;
     if (n_max < 0) n_max = 0;
     return ws_layout(c, n_max).total;
 }
@@ -129,7 +140,10 @@ kf_status kf_decode_launch_shape(const kf_cache* c, int32_t m_hint, int32_t* spl
     if (!supported(c->dtype, c->d))
         return fail(KF_EUNSUPPORTED, "dtype %d with head dimension %d is not built", c->dtype, c->d);
     if (m_hint < 0 || m_hint > c->cap) return fail(KF_EINVAL, "m_hint %d outside [0, cap=%d]", m_hint, c->cap);
-    const kf::DecodePlan p = kf::plan_decode((int64_t)c->L * c->B * c->H, m_hint ? m_hint : c->cap, c->d, c->dtype);
+    if (!group_supported(c->q_per_kv))
+        return fail(KF_EUNSUPPORTED, "%d query heads per cached head is not built", c->q_per_kv);
+    const kf::DecodePlan p =
+        kf::plan_decode((int64_t)c->L * c->B * c->H, m_hint ? m_hint : c->cap, c->d, c->dtype, group_of(c));
     *splits = p.S;
     *chunk = p.chunk;
     return KF_OK;
@@ -148,7 +162,8 @@ kf_status kf_prefill_score(const kf_cache* c, const void* Q, int32_t n, const kf
     st = check_ws(workspace, workspace_bytes, w.total);
     if (st != KF_OK) return st;
 
-    const int64_t U = (int64_t)c->L * c->B * c->H;
+    const int32_t G = group_of(c);
+    const int64_t U = (int64_t)c->L * c->B * c->H * G;  // query units
     const size_t n_pad = align_up((size_t)n, kf::kPrefillRowPad);
     kf::PrefillArgs a;
     a.Q = Q;
@@ -160,8 +175,10 @@ kf_status kf_prefill_score(const kf_cache* c, const void* Q, int32_t n, const kf
     a.slopes = cfg->alibi_slopes;
     a.ws_c = (float*)((char*)workspace + w.region);
     a.ws_r = (uint32_t*)((char*)workspace + w.region + align_up((size_t)U * n_pad * sizeof(float), 256));
+    a.ws_f = (float*)((char*)workspace + w.region + 2 * align_up((size_t)U * n_pad * sizeof(float), 256));
+    a.G = G;
     a.B = c->B;
-    a.H = c->H;
+    a.H = c->H * G;
     a.cap = c->cap;
     a.layer0 = c->layer0;
     a.n = n;
@@ -179,6 +196,7 @@ kf_status kf_prefill_score(const kf_cache* c, const void* Q, int32_t n, const kf
         sh.L = c->L;
         sh.BH = c->B * c->H;
         sh.cap = c->cap;
+        sh.inc_unit = 0;
         e = kf::launch_share(sh, (hipStream_t)stream);
     }
     if (e != hipSuccess) return fail(KF_EDEVICE, "prefill launch: %s", hipGetErrorString(e));
@@ -205,9 +223,10 @@ static kf_status prepare_decode(kf_cache* c, const void* q, const void* k_new, c
     if (st != KF_OK) return st;
 
     const int64_t U = (int64_t)c->L * c->B * c->H;
-    const kf::DecodePlan p = kf::plan_decode(U, m_hint, c->d, c->dtype);
+    const int32_t G = group_of(c);
+    const kf::DecodePlan p = kf::plan_decode(U, m_hint, c->d, c->dtype, G);
     // the partial-record region is sized for the plan at m = cap, the largest
-    const kf::DecodePlan pmax = kf::plan_decode(U, c->cap, c->d, c->dtype);
+    const kf::DecodePlan pmax = kf::plan_decode(U, c->cap, c->d, c->dtype, G);
     if (p.S > pmax.S) return fail(KF_EWORKSPACE, "internal: split count %d exceeds the sized %d", p.S, pmax.S);
     a->K = c->K;
     a->V = c->V;
@@ -222,8 +241,10 @@ static kf_status prepare_decode(kf_cache* c, const void* q, const void* k_new, c
     a->slopes = cfg->alibi_slopes;
     a->ws_err = (int32_t*)workspace + KF_WS_ERROR_WORD;
     a->ws_part = (float*)((char*)workspace + w.region);
-    a->ws_e = (float*)((char*)workspace + w.region + align_up((size_t)U * pmax.S * (c->d + 4) * sizeof(float), 256));
-    a->ws_m = (int32_t*)((char*)a->ws_e + align_up((size_t)U * c->cap * sizeof(float), 256));
+    a->ws_e =
+        (float*)((char*)workspace + w.region + align_up((size_t)U * pmax.S * G * (c->d + 4) * sizeof(float), 256));
+    a->ws_m = (int32_t*)((char*)a->ws_e + align_up((size_t)U * G * c->cap * sizeof(float), 256));
+    a->G = G;
     a->B = c->B;
     a->H = c->H;
     a->cap = c->cap;
@@ -255,6 +276,7 @@ static hipError_t share_after_decode(const kf_cache* c, const kf::DecodeArgs& a,
     sh.L = c->L;
     sh.BH = c->B * c->H;
     sh.cap = c->cap;
+    sh.inc_unit = a.G * c->cap;
     return kf::launch_share(sh, stream);
 }
 
@@ -386,9 +408,10 @@ static kf_status fused_step(kf_cache* c, const void* q, const void* k_new, const
     }
     const int64_t U = (int64_t)c->L * c->B * c->H;
     hipError_t e;
-    if (da.shared) {  // the layers' increments must be added up between the merge and the selection
+    if (da.shared || da.G > 1) {  // shared score: the layers' increments are added up between the merge and
+                                  // the selection; the merge folded into the selection serves one query head
         e = kf::launch_decode(da, U, c->d, c->dtype, p.lds_bytes, (hipStream_t)stream);
-        if (e == hipSuccess) e = share_after_decode(c, da, (hipStream_t)stream);
+        if (e == hipSuccess && da.shared) e = share_after_decode(c, da, (hipStream_t)stream);
         if (e == hipSuccess) e = kf::launch_select(sa, U, (hipStream_t)stream);
     } else if (da.S > 1) {
         e = kf::launch_decode_split(da, U, c->d, c->dtype, p.lds_bytes, (hipStream_t)stream);

@@ -29,6 +29,7 @@ constexpr int kDecodeMinBlocks = 1024;  // workgroups wanted on the chip
 constexpr int kComputeUnits = 256;                      // MI355X
 constexpr int kDecodeBlockOverheadTokens = 48;          // fixed cost of a workgroup, in tokens' worth of time
 constexpr int kDecodeMinChunk = 128;
+constexpr size_t kDecodeLdsBudget = 65536 - 1024;       // dynamic LDS a workgroup may ask for
 
 constexpr int kDecodeUnroll = 4;  // 16-byte loads a lane keeps in flight per tile (2 and 8 measured within 2 %)
 
@@ -83,62 +84,67 @@ struct QueryPiece<bf16_t> {
     }
 };
 
-// Block-wide max / sum of two values at once (one pair of barriers).
-template <int NT>
-__device__ __forceinline__ void block_max2(float& x, float& y, float* red /* [2*NT/64] */) {
-    x = wave_max(x);
-    y = wave_max(y);
+// Block-wide max / sum of N values at once (one pair of barriers).
+template <int NT, int N>
+__device__ __forceinline__ void block_max_n(float (&v)[N], float* red /* [N*NT/64] */) {
+#pragma unroll
+    for (int i = 0; i < N; ++i) v[i] = wave_max(v[i]);
     __syncthreads();
     if ((threadIdx.x & 63) == 0) {
-        red[2 * (threadIdx.x >> 6)] = x;
-        red[2 * (threadIdx.x >> 6) + 1] = y;
+#pragma unroll
+        for (int i = 0; i < N; ++i) red[N * (threadIdx.x >> 6) + i] = v[i];
     }
     __syncthreads();
-    x = red[0];
-    y = red[1];
 #pragma unroll
-    for (int i = 1; i < NT / 64; ++i) {
-        x = fmaxf(x, red[2 * i]);
-        y = fmaxf(y, red[2 * i + 1]);
+    for (int i = 0; i < N; ++i) {
+        float r = red[i];
+#pragma unroll
+        for (int w = 1; w < NT / 64; ++w) r = fmaxf(r, red[N * w + i]);
+        v[i] = r;
     }
 }
-template <int NT>
-__device__ __forceinline__ void block_sum2(float& x, float& y, float* red) {
-    x = wave_sum(x);
-    y = wave_sum(y);
+template <int NT, int N>
+__device__ __forceinline__ void block_sum_n(float (&v)[N], float* red) {
+#pragma unroll
+    for (int i = 0; i < N; ++i) v[i] = wave_sum(v[i]);
     __syncthreads();
     if ((threadIdx.x & 63) == 0) {
-        red[2 * (threadIdx.x >> 6)] = x;
-        red[2 * (threadIdx.x >> 6) + 1] = y;
+#pragma unroll
+        for (int i = 0; i < N; ++i) red[N * (threadIdx.x >> 6) + i] = v[i];
     }
     __syncthreads();
-    x = red[0];
-    y = red[1];
 #pragma unroll
-    for (int i = 1; i < NT / 64; ++i) {
-        x += red[2 * i];
-        y += red[2 * i + 1];
+    for (int i = 0; i < N; ++i) {
+        float r = red[i];
+#pragma unroll
+        for (int w = 1; w < NT / 64; ++w) r += red[N * w + i];
+        v[i] = r;
     }
 }
 
-template <typename T, int D, int NT>
+// One workgroup streams the cache rows [j0, j1) of one cached head ("unit") once
+// and serves the G query heads that read it (G = 1: ordinary multi-head
+// attention; G > 1: grouped-query attention, query head hq = h*G + g).
+template <typename T, int D, int NT, int G>
 __global__ void __launch_bounds__(NT) decode_kernel(const DecodeArgs a) {
     constexpr int EPV = ElemTraits<T>::kPerVec;  // elements per 16-byte vector
     constexpr int LPR = D / EPV;                 // lanes that share one row
     constexpr int RPW = kWave / LPR;             // rows per wave-wide load
     constexpr int NW = NT / kWave;
     constexpr int RPB = RPW * NW;                // rows per block-wide load
-    constexpr int UNR = kDecodeUnroll;             // independent loads in flight per lane
+    constexpr int UNR = (G >= 8) ? 2 : kDecodeUnroll;  // independent loads in flight per lane (8 query heads: registers are short)
     constexpr int TILE = RPB * UNR;              // rows per tile of the workgroup
     constexpr int PW = D + 4;                    // floats in a partial record
     constexpr size_t ROWB = (size_t)D * sizeof(T);
     static_assert(LPR <= 32 && D <= NT, "row must fit half a wave, output a block");
 
     extern __shared__ float smem[];
-    float* xs = smem;                // [chunk+1] logits, then attention weights (+1: the new token)
-    float* ys = smem + a.chunk + 1;  // [chunk+1] perturbed logits / tau, then their exponentials
-    float* red_o = ys + a.chunk + 1; // [NW][D] per-wave output partials
-    __shared__ float red_s[2 * NW];
+    const int CS = a.chunk + 1;        // logits of the split's rows (+1: the new token)
+    float* xs = smem;                  // [G][CS] logits, then attention weights
+    float* ys = smem + G * CS;         // [G][CS] perturbed logits / tau, then their exponentials
+    float* red_o = ys + G * CS;        // [NW][G*D] per-wave output partials
+    __shared__ float red_s[2 * G * NW];
+    __shared__ float stat[4 * G];      // per query head: max x, sum p, max y, sum e
 
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int sub = lane / LPR, cl = lane % LPR;
@@ -162,7 +168,7 @@ __global__ void __launch_bounds__(NT) decode_kernel(const DecodeArgs a) {
         // no room for the new token (or a launch shaped for fewer tokens):
         // leave the unit alone and report it
         if (s == 0) {
-            if (tid < D) a.out[u * D + tid] = 0.0f;
+            for (int c = tid; c < G * D; c += NT) a.out[u * G * D + c] = 0.0f;
             if (tid == 0) {
                 atomicAdd(a.ws_err, 1);
                 if (a.shared) a.ws_m[u] = 0;
@@ -181,7 +187,7 @@ __global__ void __launch_bounds__(NT) decode_kernel(const DecodeArgs a) {
 
     const char* Ku = (const char*)a.K + (size_t)u * a.cap * ROWB;
     const char* Vu = (const char*)a.V + (size_t)u * a.cap * ROWB;
-    const T* qu = (const T*)a.q + (size_t)u * D;
+    const T* qu = (const T*)a.q + (size_t)u * G * D;
     const char* knew = (const char*)a.k_new + (size_t)u * ROWB;
     const char* vnew = (const char*)a.v_new + (size_t)u * ROWB;
     float* fu = a.score + (size_t)u * a.cap;
@@ -194,8 +200,9 @@ __global__ void __launch_bounds__(NT) decode_kernel(const DecodeArgs a) {
         if (tid == 2 * kWave) pu[len0] = q_pos;
     }
 
-    QueryPiece<T> qp;
-    qp.load(((const uint4*)qu)[cl]);
+    QueryPiece<T> qp[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) qp[g].load(((const uint4*)(qu + (size_t)g * D))[cl]);
 
     // This lane's piece of row (base + i*RPB + sub) sits at lane_off + base*ROWB + i*RPB*ROWB.
     const size_t lane_off = (size_t)sub * ROWB + (size_t)cl * 16;
@@ -223,15 +230,24 @@ __global__ void __launch_bounds__(NT) decode_kernel(const DecodeArgs a) {
     // ---- phase 1: stream K (next tile in flight while this one is reduced), logits into LDS
     uint4 cur[UNR], nxt[UNR];
     auto logits_of = [&](int base) {
-        float p[UNR];
+        float p[G][UNR];
 #pragma unroll
-        for (int i = 0; i < UNR; ++i) p[i] = qp.dot(cur[i]);
+        for (int g = 0; g < G; ++g) {
 #pragma unroll
-        for (int i = 0; i < UNR; ++i) p[i] = group_sum<LPR>(p[i]);
+            for (int i = 0; i < UNR; ++i) p[g][i] = qp[g].dot(cur[i]);
+        }
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+#pragma unroll
+            for (int i = 0; i < UNR; ++i) p[g][i] = group_sum<LPR>(p[g][i]);
+        }
 #pragma unroll
         for (int i = 0; i < UNR; ++i) {
             const int j = base + i * RPB + sub;
-            if (cl == 0 && j < j1) xs[j - j0] = p[i] * a.scale;
+            if (cl == 0 && j < j1) {
+#pragma unroll
+                for (int g = 0; g < G; ++g) xs[g * CS + j - j0] = p[g][i] * a.scale;
+            }
         }
     };
     {
@@ -254,62 +270,93 @@ __global__ void __launch_bounds__(NT) decode_kernel(const DecodeArgs a) {
             base += TILE;
         }
     }
-    if (owner && wv == 0) {  // the new token's own logit (distance 0: no position bias)
-        const float p = group_sum<LPR>(qp.dot(((const uint4*)knew)[cl]));
-        if (lane == 0) xs[cnt_c] = p * a.scale;
+    if (owner && wv == 0) {  // the new token's own logits (distance 0: no position bias)
+        const uint4 kv = ((const uint4*)knew)[cl];
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            const float p = group_sum<LPR>(qp[g].dot(kv));
+            if (lane == 0) xs[g * CS + cnt_c] = p * a.scale;
+        }
     }
     // first V tile: in flight while the softmax statistics are formed
     if (base0 < j1) load_tile(Vu, base0, cur);
     __syncthreads();
 
     // ---- phase 1.5: position bias, logit adjustment, the two softmaxes' statistics
-    const float slope = a.slopes ? a.slopes[h] : 0.0f;
-    uint32_t rkey = 0;
-    if (a.noise == kNoiseGumbel || a.noise == kNoiseGaussian)
-        rkey = row_key(unit_key(a.seeds[b], (uint32_t)l, (uint32_t)h), (uint32_t)q_pos);
-    float mx = -INFINITY, my = -INFINITY;
+    float slope[G];
+    uint32_t rkey[G];
+    const bool rnd = (a.noise == kNoiseGumbel || a.noise == kNoiseGaussian);
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        const int hq = h * G + g;
+        slope[g] = a.slopes ? a.slopes[hq] : 0.0f;
+        rkey[g] = rnd ? row_key(unit_key(a.seeds[b], (uint32_t)l, (uint32_t)hq), (uint32_t)q_pos) : 0u;
+    }
+    float mxy[2 * G];
+#pragma unroll
+    for (int i = 0; i < 2 * G; ++i) mxy[i] = -INFINITY;
     for (int t = tid; t < cnt; t += NT) {
         const int pj = (t == cnt_c) ? q_pos : pu[j0 + t];  // t == cnt_c: the new token
-        // base-2 domain: x2 = log2(e)*x, y2 = log2(e)*(x + zeta)/tau
         const int dist = a.new_pos ? (len0 - (j0 + t)) : (q_pos - pj);  // the new token: 0 either way
-        const float x = (xs[t] - slope * (float)((t == cnt_c) ? 0 : dist)) * kLog2e;
-        const float y = (x + zeta_log2e(a.noise, rkey, (uint32_t)pj)) * inv_tau;
-        xs[t] = x;
-        ys[t] = y;
-        mx = fmaxf(mx, x);
-        my = fmaxf(my, y);
+        const float fdist = (float)((t == cnt_c) ? 0 : dist);
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            // base-2 domain: x2 = log2(e)*x, y2 = log2(e)*(x + zeta)/tau
+            const float x = (xs[g * CS + t] - slope[g] * fdist) * kLog2e;
+            const float y = (x + zeta_log2e(a.noise, rkey[g], (uint32_t)pj)) * inv_tau;
+            xs[g * CS + t] = x;
+            ys[g * CS + t] = y;
+            mxy[2 * g] = fmaxf(mxy[2 * g], x);
+            mxy[2 * g + 1] = fmaxf(mxy[2 * g + 1], y);
+        }
     }
-    block_max2<NT>(mx, my, red_s);
-    float sp = 0.0f, se = 0.0f;
+    block_max_n<NT, 2 * G>(mxy, red_s);
+    float spe[2 * G];
+#pragma unroll
+    for (int i = 0; i < 2 * G; ++i) spe[i] = 0.0f;
     for (int t = tid; t < cnt; t += NT) {
-        const float p = hw_exp2(xs[t] - mx);
-        const float e = hw_exp2(ys[t] - my);
-        xs[t] = p;
-        ys[t] = e;
-        sp += p;
-        se += e;
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            const float p = hw_exp2(xs[g * CS + t] - mxy[2 * g]);
+            const float e = hw_exp2(ys[g * CS + t] - mxy[2 * g + 1]);
+            xs[g * CS + t] = p;
+            ys[g * CS + t] = e;
+            spe[2 * g] += p;
+            spe[2 * g + 1] += e;
+        }
     }
-    block_sum2<NT>(sp, se, red_s);  // its barriers also publish the attention weights in xs
+    block_sum_n<NT, 2 * G>(spe, red_s);  // its barriers also publish the attention weights in xs
+    if (tid == 0) {
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            stat[4 * g + 0] = mxy[2 * g];
+            stat[4 * g + 1] = spe[2 * g];
+            stat[4 * g + 2] = mxy[2 * g + 1];
+            stat[4 * g + 3] = spe[2 * g + 1];
+        }
+    }
     // (The score increments in ys are written out after the V stream: stores issued here
     // would have to drain before the first V tile could be consumed.)
 
     // ---- phase 2: stream V, weighted sum
-    float acc[EPV];
+    float acc[G][EPV];
 #pragma unroll
-    for (int e = 0; e < EPV; ++e) acc[e] = 0.0f;
+    for (int g = 0; g < G; ++g) {
+#pragma unroll
+        for (int e = 0; e < EPV; ++e) acc[g][e] = 0.0f;
+    }
     auto weigh = [&](int base) {
-        float p[UNR];
 #pragma unroll
         for (int i = 0; i < UNR; ++i) {
             const int j = base + i * RPB + sub;
-            p[i] = (j < j1) ? xs[j - j0] : 0.0f;
-        }
-#pragma unroll
-        for (int i = 0; i < UNR; ++i) {
             float vvals[EPV];
             unpack16<T>(cur[i], vvals);
 #pragma unroll
-            for (int e = 0; e < EPV; ++e) acc[e] = fmaf(p[i], vvals[e], acc[e]);
+            for (int g = 0; g < G; ++g) {
+                const float p = (j < j1) ? xs[g * CS + j - j0] : 0.0f;
+#pragma unroll
+                for (int e = 0; e < EPV; ++e) acc[g][e] = fmaf(p, vvals[e], acc[g][e]);
+            }
         }
     };
     {
@@ -332,71 +379,88 @@ __global__ void __launch_bounds__(NT) decode_kernel(const DecodeArgs a) {
     if (owner && wv == 0 && sub == 0) {  // the new token's value row
         float vvals[EPV];
         unpack16<T>(((const uint4*)vnew)[cl], vvals);
-        const float p = xs[cnt_c];
 #pragma unroll
-        for (int e = 0; e < EPV; ++e) acc[e] = fmaf(p, vvals[e], acc[e]);
+        for (int g = 0; g < G; ++g) {
+            const float p = xs[g * CS + cnt_c];
+#pragma unroll
+            for (int e = 0; e < EPV; ++e) acc[g][e] = fmaf(p, vvals[e], acc[g][e]);
+        }
     }
     // rows of one wave-wide load live in different lane groups: fold them
 #pragma unroll
     for (int o = LPR; o < kWave; o <<= 1) {
 #pragma unroll
-        for (int e = 0; e < EPV; ++e) acc[e] += __shfl_xor(acc[e], o, kWave);
+        for (int g = 0; g < G; ++g) {
+#pragma unroll
+            for (int e = 0; e < EPV; ++e) acc[g][e] += __shfl_xor(acc[g][e], o, kWave);
+        }
     }
     if (sub == 0) {
 #pragma unroll
-        for (int e = 0; e < EPV; ++e) red_o[wv * D + cl * EPV + e] = acc[e];
-    }
-    __syncthreads();
-    float o_c = 0.0f;
-    if (tid < D) {
+        for (int g = 0; g < G; ++g) {
 #pragma unroll
-        for (int w2 = 0; w2 < NW; ++w2) o_c += red_o[w2 * D + tid];
+            for (int e = 0; e < EPV; ++e) red_o[(wv * G + g) * D + cl * EPV + e] = acc[g][e];
+        }
     }
+    __syncthreads();  // red_o and stat are complete
 
     if (S == 1) {
-        // the whole unit is here: accumulate the normalised score increment
-        const float inv = 1.0f / se;
-        float* we = a.ws_e + (size_t)u * a.cap;
+        // the whole unit is here: accumulate the normalised score increment of all its query heads
+        float inv[G];
+#pragma unroll
+        for (int g = 0; g < G; ++g) inv[g] = 1.0f / spe[2 * g + 1];
+        float* we = a.ws_e + (size_t)u * G * a.cap;
         for (int t = tid; t < cnt; t += NT) {
             const int slot = (t == cnt_c) ? len0 : j0 + t;
+            float df = 0.0f;
+#pragma unroll
+            for (int g = 0; g < G; ++g) df = fmaf(ys[g * CS + t], inv[g], df);
             // existing scores take the increment as a fire-and-forget atomic add at the L2: no load,
             // no round trip (one add per address and launch, so the result is the plain fp32 sum)
-            if (a.shared) we[slot] = ys[t] * inv;  // summed over the layers by the launch that follows
-            else if (t == cnt_c) fu[slot] = ys[t] * inv;
-            else unsafeAtomicAdd(&fu[slot], ys[t] * inv);
+            if (a.shared) we[slot] = df;  // summed over the layers by the launch that follows
+            else if (t == cnt_c) fu[slot] = df;
+            else unsafeAtomicAdd(&fu[slot], df);
         }
-        if (tid < D) a.out[u * D + tid] = o_c / sp;
+        for (int c = tid; c < G * D; c += NT) {
+            float o_c = 0.0f;
+#pragma unroll
+            for (int w2 = 0; w2 < NW; ++w2) o_c += red_o[w2 * G * D + c];
+            a.out[u * G * D + c] = o_c / stat[4 * (c / D) + 1];
+        }
         if (tid == 0) {
             a.len[u] = m;
             if (a.shared) a.ws_m[u] = m;
         }
         return;
     }
+    // ---- S > 1: leave the un-normalised increments and a partial record per query head for the merge
     {
-        float* we = a.ws_e + (size_t)u * a.cap;
-        for (int t = tid; t < cnt; t += NT) we[(t == cnt_c) ? len0 : j0 + t] = ys[t];
+        float* we = a.ws_e + (size_t)u * G * a.cap;
+        for (int t = tid; t < cnt; t += NT) {
+            const int slot = (t == cnt_c) ? len0 : j0 + t;
+#pragma unroll
+            for (int g = 0; g < G; ++g) we[(size_t)g * a.cap + slot] = ys[g * CS + t];
+        }
     }
-
-    // ---- S > 1: leave a partial record for the merge
-    float* part = a.ws_part + ((size_t)u * S + s) * PW;
-    if (tid < D) part[tid] = o_c;
-    if (tid == 0) {
-        part[D + 0] = mx;
-        part[D + 1] = sp;
-        part[D + 2] = my;
-        part[D + 3] = se;
+    float* part = a.ws_part + ((size_t)u * S + s) * G * PW;
+    for (int c = tid; c < G * D; c += NT) {
+        float o_c = 0.0f;
+#pragma unroll
+        for (int w2 = 0; w2 < NW; ++w2) o_c += red_o[w2 * G * D + c];
+        part[(c / D) * PW + (c % D)] = o_c;
     }
+    if (tid < 4 * G) part[(tid >> 2) * PW + D + (tid & 3)] = stat[tid];
 }
 
 // Merge kernel: one workgroup per unit, launched after the split kernel.
-template <int D, int NT>
+template <int D, int NT, int G>
 __global__ void __launch_bounds__(NT) decode_merge_kernel(const DecodeArgs a) {
     __shared__ float red_s[NT / kWave];
-    __shared__ float w_p[kDecodeMaxSplits], w_e[kDecodeMaxSplits];
+    __shared__ float w_p[G * kDecodeMaxSplits], w_e[G * kDecodeMaxSplits];
     const int64_t u = blockIdx.x;
     const int len0 = a.len[u];
     if (len0 < 0 || len0 >= a.cap || len0 > a.S * a.chunk) return;  // skipped by the split kernel too
-    merge_unit<D, NT>(a, u, len0, red_s, w_p, w_e);
+    merge_unit<D, NT, G>(a, u, len0, red_s, w_p, w_e);
 }
 
 // Shared score function (the paper's ablation of one score for all layers,
@@ -416,9 +480,12 @@ __global__ void __launch_bounds__(kShareThreads) share_kernel(const ShareArgs a)
     }
     if (j >= m || m > a.cap) return;  // m == 0: the decode launch skipped (and reported) these units
     const size_t stride = (size_t)a.BH * a.cap, at = (size_t)bh * a.cap + j;
-    const float* src = a.inc ? a.inc : a.score;
     float s = 0.0f;
-    for (int l = 0; l < a.L; ++l) s += src[l * stride + at];
+    if (a.inc) {  // a unit's increments sit inc_unit floats apart (one row per query head, the sum in the first)
+        for (int l = 0; l < a.L; ++l) s += a.inc[((size_t)l * a.BH + bh) * a.inc_unit + j];
+    } else {
+        for (int l = 0; l < a.L; ++l) s += a.score[l * stride + at];
+    }
     const bool fresh = !a.inc || j == m - 1;  // prompt scores, or the token appended by this step
     for (int l = 0; l < a.L; ++l) {
         float* f = a.score + l * stride + at;
@@ -445,13 +512,20 @@ static int rows_per_block(int32_t d, int32_t dtype) {
 // number of workgroups the busiest unit gets times the tokens (plus a fixed
 // per-workgroup overhead) each of them streams.  Candidates that leave the chip
 // with too few workgroups to hide memory latency are skipped when a better
-// filled one exists.
-DecodePlan plan_decode(int64_t U, int32_t m, int32_t d, int32_t dtype) {
+// filled one exists.  With G query heads per unit a workgroup keeps G logit
+// rows in LDS, so its chunk is at most 1/G of the single-head maximum.
+DecodePlan plan_decode(int64_t U, int32_t m, int32_t d, int32_t dtype, int32_t G) {
     DecodePlan p;
     const int rpb = rows_per_block(d, dtype);
+    // LDS of a workgroup: 2*G*(chunk+1) logits + one G*d output row per wave, within 64 KB less the small static arrays
+    const int lds_rows = (int)((kDecodeLdsBudget - (size_t)(kDecodeThreads / kWave) * G * d * sizeof(float)) /
+                               (2 * G * sizeof(float))) - 1;
+    int max_chunk = kDecodeMaxChunk / G;
+    if (lds_rows < max_chunk) max_chunk = lds_rows / rpb * rpb;
+    const int min_chunk = kDecodeMinChunk < max_chunk ? kDecodeMinChunk : max_chunk;
     const int64_t rows = m > 1 ? m - 1 : 1;  // cache rows; the new token rides with the last split
-    int64_t s_hi = (m + kDecodeMinChunk - 1) / kDecodeMinChunk;
-    int64_t s_lo = (m + kDecodeMaxChunk - 1) / kDecodeMaxChunk;
+    int64_t s_hi = (m + min_chunk - 1) / min_chunk;
+    int64_t s_lo = (m + max_chunk - 1) / max_chunk;
     if (s_hi > kDecodeMaxSplits) s_hi = kDecodeMaxSplits;
     if (s_lo < 1) s_lo = 1;
     if (s_hi < s_lo) s_hi = s_lo;
@@ -461,11 +535,12 @@ DecodePlan plan_decode(int64_t U, int32_t m, int32_t d, int32_t dtype) {
     for (int64_t S = s_lo; S <= s_hi && S <= s_lo + 63; ++S) {
         int64_t chunk = (rows + S - 1) / S;
         chunk = (chunk + rpb - 1) / rpb * rpb;
+        if (chunk > max_chunk) continue;  // rounding up to whole block-wide loads overshot: take more splits
         const int64_t blocks = U * S;
         const int64_t per_cu = (blocks + kComputeUnits - 1) / kComputeUnits;
         const double cost = (double)per_cu * (double)(chunk + kDecodeBlockOverheadTokens);
         const bool filled = blocks >= kDecodeMinBlocks;
-        if (S == s_lo || (filled && !best_filled) || (filled == best_filled && cost < best_cost)) {
+        if (best_cost == 0.0 || (filled && !best_filled) || (filled == best_filled && cost < best_cost)) {
             best_S = S;
             best_cost = cost;
             best_filled = filled;
@@ -475,25 +550,36 @@ DecodePlan plan_decode(int64_t U, int32_t m, int32_t d, int32_t dtype) {
     chunk = (chunk + rpb - 1) / rpb * rpb;
     p.S = (int32_t)best_S;
     p.chunk = (int32_t)chunk;
-    p.lds_bytes = (size_t)(2 * (chunk + 1) + (kDecodeThreads / kWave) * d) * sizeof(float);
+    p.lds_bytes = (size_t)(2 * G * (chunk + 1) + (kDecodeThreads / kWave) * G * d) * sizeof(float);
     return p;
 }
 
-template <typename T, int D>
-static hipError_t launch_decode_t(const DecodeArgs& a, int64_t U, size_t lds, hipStream_t st, bool merge) {
+template <typename T, int D, int G>
+static hipError_t launch_decode_g(const DecodeArgs& a, int64_t U, size_t lds, hipStream_t st, bool merge) {
     const dim3 grid((unsigned)(U * a.S)), block(kDecodeThreads);
-    hipLaunchKernelGGL((decode_kernel<T, D, kDecodeThreads>), grid, block, lds, st, a);
+    hipLaunchKernelGGL((decode_kernel<T, D, kDecodeThreads, G>), grid, block, lds, st, a);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess && a.S > 1 && merge) {
-        hipLaunchKernelGGL((decode_merge_kernel<D, kDecodeThreads>), dim3((unsigned)U), block, 0, st, a);
+        hipLaunchKernelGGL((decode_merge_kernel<D, kDecodeThreads, G>), dim3((unsigned)U), block, 0, st, a);
         e = hipGetLastError();
     }
     return e;
 }
 
+template <typename T, int D>
+static hipError_t launch_decode_t(const DecodeArgs& a, int64_t U, size_t lds, hipStream_t st, bool merge) {
+    switch (a.G) {
+        case 1: return launch_decode_g<T, D, 1>(a, U, lds, st, merge);
+        case 2: return launch_decode_g<T, D, 2>(a, U, lds, st, merge);
+        case 4: return launch_decode_g<T, D, 4>(a, U, lds, st, merge);
+        case 8: return launch_decode_g<T, D, 8>(a, U, lds, st, merge);
+        default: return hipErrorInvalidValue;
+    }
+}
+
 static hipError_t launch_decode_any(const DecodeArgs& a, int64_t U, int32_t d, int32_t dtype, size_t lds_bytes,
                                     hipStream_t stream, bool merge) {
-    if (a.chunk > kDecodeMaxChunk || a.S > kDecodeMaxSplits) return hipErrorInvalidValue;
+    if (a.chunk * a.G > kDecodeMaxChunk || a.S > kDecodeMaxSplits) return hipErrorInvalidValue;
     if (dtype == KF_BF16) {
         if (d == 64) return launch_decode_t<bf16_t, 64>(a, U, lds_bytes, stream, merge);
         if (d == 128) return launch_decode_t<bf16_t, 128>(a, U, lds_bytes, stream, merge);

@@ -21,11 +21,12 @@ struct DecodeArgs {
     float* out;
     const uint64_t* seeds;
     const float* slopes;
-    float* ws_part;    // [U][S][D+4] partial outputs and softmax statistics of each split
-    float* ws_e;       // [U][cap]    un-normalised score increments of each token
+    float* ws_part;    // [U][S][G][D+4] partial outputs and softmax statistics of each split and query head
+    float* ws_e;       // [U][G][cap]    un-normalised score increments of each token
     int32_t* ws_err;   // [1]         skipped-unit counter
     int32_t* ws_m;     // [U]         shared score only: tokens this launch scored in each unit (0: skipped)
     int32_t B, H, cap, layer0;
+    int32_t G;         // query heads per cached head (q and out hold H*G heads)
     int32_t S;         // splits of a unit's token range
     int32_t chunk;     // tokens per split
     int32_t q_pos;
@@ -46,7 +47,7 @@ struct DecodePlan {
     int32_t S, chunk;
     size_t lds_bytes;
 };
-DecodePlan plan_decode(int64_t U, int32_t m, int32_t d, int32_t dtype);
+DecodePlan plan_decode(int64_t U, int32_t m, int32_t d, int32_t dtype, int32_t G);
 hipError_t launch_decode(const DecodeArgs& a, int64_t U, int32_t d, int32_t dtype, size_t lds_bytes,
                          hipStream_t stream);
 
@@ -59,6 +60,7 @@ struct ShareArgs {
     const int32_t* m;   // decode: [L][BH] tokens scored per unit;  prompt: the caches' len
     int32_t* ws_err;
     int32_t L, BH, cap;
+    int32_t inc_unit;   // floats between the increments of consecutive units (G*cap)
 };
 hipError_t launch_share(const ShareArgs& a, hipStream_t stream);
 
@@ -111,9 +113,11 @@ struct PrefillArgs {
     int32_t* len;
     const uint64_t* seeds;
     const float* slopes;
-    float* ws_c;        // [U][n_pad] per-row log2 normaliser
+    float* ws_c;        // [U][n_pad] per-row log2 normaliser            (U = L*B*H query units)
     uint32_t* ws_r;     // [U][n_pad] per-row noise key
-    int32_t B, H, cap, layer0, n, n_pad;
+    float* ws_f;        // [U][n_pad] per-query-head column sums (G > 1 only)
+    int32_t B, H, cap, layer0, n, n_pad;  // H counts QUERY heads; the caches hold H/G heads
+    int32_t G;          // query heads per cached head
     int32_t noise;
     float inv_tau;
     float scale;

@@ -105,7 +105,7 @@ __global__ void __launch_bounds__(kPrefillThreads) prefill_rowstats_kernel(const
     const int h = (int)(u % a.H), b = (int)((u / a.H) % a.B), l = a.layer0 + (int)(u / ((int64_t)a.H * a.B));
     const int i = i0 + n0;
     const T* Qu = (const T*)a.Q + (size_t)u * n * D;
-    const T* Ku = (const T*)a.K + (size_t)u * a.cap * D;
+    const T* Ku = (const T*)a.K + (size_t)(u / a.G) * a.cap * D;  // G query heads read one cached head
 
     uint4 bq[NG];
     {
@@ -205,12 +205,13 @@ __global__ void __launch_bounds__(kPrefillThreads) prefill_colsum_kernel(const P
     if (u >= units) return;
     const int n = a.n;
     const int j0 = cb * (4 * kTile) + wv * kTile;
-    if (cb == 0 && threadIdx.x == 0) a.len[u] = n;
+    const bool first_of_group = (u % a.G) == 0;
+    if (cb == 0 && threadIdx.x == 0 && first_of_group) a.len[u / a.G] = n;
     if (j0 >= n) return;  // wave-uniform; no workgroup barrier in this kernel
     const int h = (int)(u % a.H);
     const int j = j0 + n0;
     const T* Qu = (const T*)a.Q + (size_t)u * n * D;
-    const T* Ku = (const T*)a.K + (size_t)u * a.cap * D;
+    const T* Ku = (const T*)a.K + (size_t)(u / a.G) * a.cap * D;  // G query heads read one cached head
 
     uint4 bk[NG];
     {
@@ -290,9 +291,23 @@ __global__ void __launch_bounds__(kPrefillThreads) prefill_colsum_kernel(const P
     }
     colsum += __shfl_xor(colsum, 32, kWave);
     if (half == 0 && j < n) {
-        a.score[(size_t)u * a.cap + j] = colsum;
-        a.pos[(size_t)u * a.cap + j] = j;
+        // one query head per cached head: the column sum is the score; else the heads' sums are
+        // added up by the launch that follows
+        if (a.G == 1) a.score[(size_t)u * a.cap + j] = colsum;
+        else a.ws_f[(size_t)u * a.n_pad + j] = colsum;
+        if (first_of_group) a.pos[(size_t)(u / a.G) * a.cap + j] = j;
     }
+}
+
+// Grouped-query attention: the score of a cached head is the sum of its query heads' column sums
+// (added in head order, so the result does not depend on scheduling).
+__global__ void __launch_bounds__(256) prefill_group_sum_kernel(const PrefillArgs a, int64_t kv_units) {
+    const int64_t u = blockIdx.x;
+    const int j = blockIdx.y * 256 + threadIdx.x;
+    if (u >= kv_units || j >= a.n) return;
+    float s = 0.0f;
+    for (int g = 0; g < a.G; ++g) s += a.ws_f[((size_t)u * a.G + g) * a.n_pad + j];
+    a.score[(size_t)u * a.cap + j] = s;
 }
 
 template <typename T, int D>
@@ -304,6 +319,10 @@ static hipError_t launch_prefill_t(const PrefillArgs& a, int64_t U, hipStream_t 
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL((prefill_colsum_kernel<T, D>), grid, block, 0, st, a, nblk, U);
+    e = hipGetLastError();
+    if (e != hipSuccess || a.G == 1) return e;
+    hipLaunchKernelGGL(prefill_group_sum_kernel, dim3((unsigned)(U / a.G), (unsigned)((a.n + 255) / 256)), dim3(256), 0,
+                       st, a, U / a.G);
     return hipGetLastError();
 }
 

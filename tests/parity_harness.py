@@ -29,9 +29,10 @@ def dev(a):
     return kw.from_oracle(a).cuda()
 
 
-def upload(oc: ko.OracleCache) -> kf.Cache:
+def upload(oc: ko.OracleCache, q_per_kv=1) -> kf.Cache:
     return kf.Cache(K=dev(oc.K), V=dev(oc.V), score=dev(oc.score), pos=dev(oc.pos), len=dev(oc.len),
-                    L=oc.L, B=oc.B, H=oc.H, d=oc.d, cap=oc.cap, dtype=oc.dtype, layer0=oc.layer0)
+                    L=oc.L, B=oc.B, H=oc.H, d=oc.d, cap=oc.cap, dtype=oc.dtype, layer0=oc.layer0,
+                    q_per_kv=q_per_kv)
 
 
 def upload_into(gc: kf.Cache, oc: ko.OracleCache, kv=True):
@@ -168,33 +169,36 @@ class LockStep:
     decode step, everything after a tie-band event)."""
 
     def __init__(self, wl: kw.Workload, noise=ko.NOISE_GUMBEL, layers=None, cap=None, layout=kf.LAYOUT_ORDERED,
-                 shared=False):
+                 shared=False, q_per_kv=1):
         self.wl, self.noise, self.layout = wl, noise, layout
+        self.G = G = q_per_kv           # grouped queries: wl.H counts QUERY heads, the caches hold wl.H // G
         self.shared = shared            # one score function for all layers (the paper's "Shared" ablation)
         self.score_mode = kf.SCORE_SHARED if shared else kf.SCORE_PER_LAYER
         self.cap = cap or wl.n
         dt = ko.F32 if wl.dtype == "f32" else ko.BF16
-        self.oc = ko.OracleCache(wl.L, wl.B, wl.H, wl.d, self.cap, dt)
+        assert wl.H % G == 0
+        self.oc = ko.OracleCache(wl.L, wl.B, wl.H // G, wl.d, self.cap, dt)
         self.Q = np.zeros((wl.L, wl.B, wl.H, wl.n, wl.d), self.oc.K.dtype)
         for l in range(wl.L):
             Q, K, V = kw.prompt_layer(wl, l)
             self.Q[l] = kw.to_oracle(Q)
-            self.oc.K[l, :, :, : wl.n] = kw.to_oracle(K)
-            self.oc.V[l, :, :, : wl.n] = kw.to_oracle(V)
+            self.oc.K[l, :, :, : wl.n] = kw.to_oracle(K)[:, ::G]
+            self.oc.V[l, :, :, : wl.n] = kw.to_oracle(V)[:, ::G]
         self.seeds = kw.noise_seeds(wl)
         self.slopes = kw.alibi_slopes(wl)
-        self.gc = upload(self.oc)
+        self.gc = upload(self.oc, G)
         self.ws = kf.new_workspace(self.gc, wl.n)
         self.d_seeds, self.d_slopes = dev(self.seeds), dev(self.slopes)
         self.out = torch.zeros((wl.L, wl.B, wl.H, wl.d), dtype=torch.float32, device="cuda")
-        self.kept = torch.zeros((wl.L, wl.B, wl.H, wl.k), dtype=torch.int32, device="cuda")
+        self.kept = torch.zeros((wl.L, wl.B, wl.H // G, wl.k), dtype=torch.int32, device="cuda")
         self.stats = dict(out_err=0.0, score_err=0.0, tie_events=0, steps=0)
 
     def prefill(self):
         wl = self.wl
         tau_o, tau_g = ko.tau(0, wl.T, wl.tau_init, wl.tau_end), kf.kf_tau(0, wl.T, wl.tau_init, wl.tau_end)
         assert tau_o == tau_g
-        self.oc.prefill_score(self.Q, wl.n, tau_o, wl.scale, self.noise, self.seeds, self.slopes, shared=self.shared)
+        self.oc.prefill_score(self.Q, wl.n, tau_o, wl.scale, self.noise, self.seeds, self.slopes, shared=self.shared,
+                              q_per_kv=self.G)
         kf.kf_prefill_score(self.gc, dev(self.Q), wl.n, tau_g, wl.scale, self.noise, self.d_seeds,
                             self.d_slopes, self.ws, score_mode=self.score_mode)
         torch.cuda.synchronize()
@@ -239,11 +243,13 @@ class LockStep:
     def step(self, t, check_kv=False):
         wl = self.wl
         q, kn, vn = kw.decode_inputs(wl, t)
+        kn, vn = kn[:, :, ::self.G].contiguous(), vn[:, :, ::self.G].contiguous()
         q_pos = wl.n + t - 1
         tau_o, tau_g = ko.tau(t, wl.T, wl.tau_init, wl.tau_end), kf.kf_tau(t, wl.T, wl.tau_init, wl.tau_end)
         assert tau_o == tau_g
         out_ref = self.oc.decode_step(kw.to_oracle(q), kw.to_oracle(kn), kw.to_oracle(vn), q_pos, tau_o,
-                                      wl.scale, self.noise, self.seeds, self.slopes, shared=self.shared)
+                                      wl.scale, self.noise, self.seeds, self.slopes, shared=self.shared,
+                                      q_per_kv=self.G)
         kf.kf_decode_step(self.gc, q.cuda(), kn.cuda(), vn.cuda(), q_pos, min(wl.k + 1, self.cap), tau_g,
                           wl.scale, self.noise, self.d_seeds, self.d_slopes, self.out, self.ws,
                           score_mode=self.score_mode)
@@ -254,7 +260,7 @@ class LockStep:
         if self.shared:                 # one function: every layer holds the same copy, bit for bit
             g = host(self.gc.score)
             for l in range(1, wl.L):
-                for b, h in np.ndindex(wl.B, wl.H):
+                for b, h in np.ndindex(wl.B, wl.H // self.G):
                     np.testing.assert_array_equal(g[l, b, h, : lens[l, b, h]], g[0, b, h, : lens[0, b, h]])
         self.stats["out_err"] = max(self.stats["out_err"], assert_close_out(host(self.out), out_ref))
         if self.layout == kf.LAYOUT_SLOT:

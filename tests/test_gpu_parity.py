@@ -692,3 +692,138 @@ def test_one_captured_step_replays_as_successive_steps(name, kwargs, shared):
         for x, y in zip([host(x) for x in (out_b, b_.score, b_.pos, b_.len)], ref[t - 1]):
             np.testing.assert_array_equal(x, y)
     assert error_word(ws_b) == 0
+
+
+# ------------------------------------------------------------------ grouped-query attention
+@pytest.mark.parametrize("dtype,d", DTYPES)
+@pytest.mark.parametrize("G", [2, 4, 8])
+@pytest.mark.parametrize("cap", [97, 1300])      # one split per unit; several splits (ragged last one) and a merge
+def test_grouped_query_decode_matches_oracle(dtype, d, G, cap):
+    rng = np.random.default_rng(7000 + d + cap + G)
+    L, B, H = 2, 2, 2                              # cached heads; G query heads each
+    lens = rng.integers(cap // 2, cap, (L, B, H)).astype(np.int32)
+    lens[0, 0, 0] = 0
+    lens[0, 0, 1] = cap - 1
+    lens[1, 1, 1] = cap                            # full: skipped and reported
+    oc = random_cache(rng, L, B, H, d, cap, dtype, lens)
+    gc = upload(oc, G)
+    ws = kf.new_workspace(gc)
+    q = rnd(rng, (L, B, H * G, d), dtype)
+    kn, vn = (rnd(rng, (L, B, H, d), dtype) for _ in range(2))
+    seeds = np.array([11, 2 ** 63 + 12], np.uint64)
+    slopes = (0.7 ** np.arange(1, H * G + 1)).astype(np.float32)
+    q_pos = int(oc.pos.max()) + 2
+    tau, scale = 1.3125, float(1.0 / np.sqrt(np.float32(d)))
+    out = torch.full((L, B, H * G, d), 7.0, dtype=torch.float32, device="cuda")
+    kf.kf_decode_step(gc, dev(q), dev(kn), dev(vn), q_pos, 0, tau, scale, kf.NOISE_GUMBEL, dev(seeds), dev(slopes),
+                      out, ws)
+    torch.cuda.synchronize()
+    assert error_word(ws) == 1
+    oc.len[1, 1, 1] = 0                            # the oracle refuses a full unit: run it emptied, skip it below
+    out_ref = oc.decode_step(q, kn, vn, q_pos, tau, scale, ko.NOISE_GUMBEL, seeds, slopes, q_per_kv=G)
+    ok = np.ones((L, B, H), bool)
+    ok[1, 1, 1] = False
+    okq = np.repeat(ok, G, axis=2)
+    got_out, got_len = host(out), host(gc.len)
+    assert (got_out[~okq] == 0).all() and got_len[1, 1, 1] == cap
+    assert (got_len[ok] == oc.len[ok]).all()
+    assert_close_out(got_out[okq], out_ref[okq])
+    assert_close_score(host(gc.score), oc.score, np.where(ok, oc.len, 0))
+    gK, gpos = host(gc.K), host(gc.pos)
+    for l, b, h in itertools.product(range(L), range(B), range(H)):
+        if ok[l, b, h]:
+            m = int(oc.len[l, b, h])
+            np.testing.assert_array_equal(gK[l, b, h, :m], oc.K[l, b, h, :m])
+            np.testing.assert_array_equal(gpos[l, b, h, :m], oc.pos[l, b, h, :m])
+
+
+@pytest.mark.parametrize("dtype,d,G", [(ko.BF16, 128, 4), (ko.BF16, 256, 2), (ko.F32, 64, 8)])
+@pytest.mark.parametrize("n", [33, 300])
+def test_grouped_query_prefill_matches_oracle(dtype, d, G, n):
+    rng = np.random.default_rng(7100 + d + n)
+    L, B, H = 1, 2, 2
+    oc = random_cache(rng, L, B, H, d, n + 7, dtype, 0)
+    Q = rnd(rng, (L, B, H * G, n, d), dtype)
+    seeds = np.array([5, 6], np.uint64)
+    slopes = (0.5 ** np.arange(1, H * G + 1)).astype(np.float32)
+    gc = upload(oc, G)
+    ws = kf.new_workspace(gc, n)
+    scale = float(1.0 / np.sqrt(np.float32(d)))
+    kf.kf_prefill_score(gc, dev(Q), n, 1.0, scale, kf.NOISE_GUMBEL, dev(seeds), dev(slopes), ws)
+    torch.cuda.synchronize()
+    oc.prefill_score(Q, n, 1.0, scale, ko.NOISE_GUMBEL, seeds, slopes, q_per_kv=G)
+    np.testing.assert_array_equal(host(gc.len), oc.len)
+    np.testing.assert_array_equal(host(gc.pos)[..., :n], oc.pos[..., :n])
+    assert_close_score(host(gc.score), oc.score, oc.len, "grouped prefill score")
+
+
+@pytest.mark.parametrize("G,shared,layout", [(4, False, kf.LAYOUT_ORDERED), (2, True, kf.LAYOUT_ORDERED),
+                                            (8, False, kf.LAYOUT_SLOT)])
+def test_grouped_query_lockstep(G, shared, layout):
+    # mpt-like per-unit shape with position bias: 8 query heads on 8/G cached heads, prompt to generation
+    wl = kw.CONFIGS["mpt"].slice(L=2 if shared else 1, B=2, H=8, T=1024, n=512, k=256, w=51)
+    ls = LockStep(wl, q_per_kv=G, shared=shared, layout=layout)
+    ls.prefill()
+    for t in range(1, 25):
+        ls.step(t, check_kv=(t == 24))
+    print("grouped-query lockstep G=%d" % G, ls.stats)
+
+
+def test_grouped_query_fused_and_device_step_equal_the_two_calls():
+    rng = np.random.default_rng(7200)
+    L, B, H, d, G, cap = 1, 2, 2, 128, 4, 701
+    k, w = 700, 140
+    oc = random_cache(rng, L, B, H, d, cap, ko.BF16, k)
+    oc.pos[...] = np.arange(cap)
+    q = rnd(rng, (L, B, H * G, d), ko.BF16)
+    kn, vn = (rnd(rng, (L, B, H, d), ko.BF16) for _ in range(2))
+    seeds = dev(np.array([1, 2], np.uint64))
+    n, T, t = 1000, 64, 9
+    q_pos, tau = n + t - 1, kf.kf_tau(t, T, 1.0, 2.0)
+    caches = [upload(oc, G) for _ in range(3)]
+    wss = [kf.new_workspace(c) for c in caches]
+    outs = [torch.zeros((L, B, H * G, d), dtype=torch.float32, device="cuda") for _ in range(3)]
+    kf.kf_decode_step(caches[0], dev(q), dev(kn), dev(vn), q_pos, 0, tau, 0.09, kf.NOISE_GUMBEL, seeds, None, outs[0],
+                      wss[0])
+    kf.kf_select_evict(caches[0], k, w, None, wss[0])
+    kf.kf_decode_select_step(caches[1], dev(q), dev(kn), dev(vn), q_pos, 0, tau, 0.09, kf.NOISE_GUMBEL, seeds, None,
+                             outs[1], k=k, w=w, workspace=wss[1])
+    step = torch.full((1,), t, dtype=torch.int32, device="cuda")
+    kf.kf_decode_select_step_at(caches[2], dev(q), dev(kn), dev(vn), n, T, 1.0, 2.0, step, 0, 0.09, kf.NOISE_GUMBEL,
+                                seeds, None, outs[2], k=k, w=w, workspace=wss[2])
+    torch.cuda.synchronize()
+    assert int(step.item()) == t + 1
+    for i in (1, 2):
+        assert error_word(wss[i]) == 0
+        assert torch.equal(outs[0], outs[i])
+        assert torch.equal(caches[0].len, caches[i].len)
+        for nm in ("score", "pos"):
+            assert torch.equal(getattr(caches[0], nm)[..., :k], getattr(caches[i], nm)[..., :k]), nm
+        for nm in ("K", "V"):
+            assert torch.equal(getattr(caches[0], nm)[..., :k, :], getattr(caches[i], nm)[..., :k, :]), nm
+
+
+def test_grouped_query_decode_at_the_largest_lds_footprint():
+    # 1024 units fill the chip without splits: one workgroup per unit keeps 8 x 489 logit slots (twice) and
+    # four 8 x 256 output rows in LDS -- the most the launch plan allows
+    rng = np.random.default_rng(7300)
+    L, B, H, d, G, cap = 4, 8, 32, 256, 8, 488
+    c0 = kf.Cache(K=0x10000, V=0x20000, score=0x30000, pos=0x40000, len=0x50000, L=L, B=B, H=H, d=d, cap=cap,
+                  dtype=kf.BF16, q_per_kv=G)
+    assert kf.kf_decode_launch_shape(c0, cap) == (1, 488)
+    lens = rng.integers(cap - 40, cap, (L, B, H)).astype(np.int32)
+    lens[0, 0, 0] = cap - 1
+    oc = random_cache(rng, L, B, H, d, cap, ko.BF16, lens)
+    gc = upload(oc, G)
+    ws = kf.new_workspace(gc)
+    q = rnd(rng, (L, B, H * G, d), ko.BF16)
+    kn, vn = (rnd(rng, (L, B, H, d), ko.BF16) for _ in range(2))
+    seeds = np.arange(B).astype(np.uint64) + 77
+    q_pos = int(oc.pos.max()) + 1
+    out = torch.zeros((L, B, H * G, d), dtype=torch.float32, device="cuda")
+    kf.kf_decode_step(gc, dev(q), dev(kn), dev(vn), q_pos, cap, 1.5, 0.0625, kf.NOISE_GUMBEL, dev(seeds), None, out, ws)
+    torch.cuda.synchronize()
+    assert error_word(ws) == 0
+    out_ref = oc.decode_step(q, kn, vn, q_pos, 1.5, 0.0625, ko.NOISE_GUMBEL, seeds, None, q_per_kv=G)
+    assert_close_out(host(out), out_ref)
+    assert_close_score(host(gc.score), oc.score, oc.len)

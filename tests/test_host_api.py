@@ -177,3 +177,17 @@ def test_unknown_score_mode_is_rejected():
     c = fake_cache()
     expect(binding.KF_EINVAL, kf.kf_decode_step, c, 0x1000, 0x2000, 0x3000, 10, 0, 1.5, 0.1, kf.NOISE_GUMBEL, 0x4000,
            None, 0x5000, WS, 0, score_mode=2)
+
+
+def test_query_group_validation_and_sizes():
+    for g in (3, 5, 16):
+        expect(binding.KF_EUNSUPPORTED, kf.kf_select_evict, fake_cache(q_per_kv=g), 8, 2, None, WS, 0)
+        assert kf.kf_workspace_bytes(fake_cache(q_per_kv=g), 0) == 0
+    expect(binding.KF_EINVAL, kf.kf_select_evict, fake_cache(q_per_kv=-1), 8, 2, None, WS, 0)
+    sizes = [kf.kf_workspace_bytes(fake_cache(q_per_kv=g), 2048) for g in (0, 1, 2, 4, 8)]
+    assert sizes[0] == sizes[1] and sizes[1] < sizes[2] < sizes[3] < sizes[4]
+    # a workgroup keeps G logit rows in LDS: its chunk shrinks with G, and the splits cover the rows
+    for g in (1, 2, 4, 8):
+        for cap in (1025, 9831, 40000):
+            S, chunk = kf.kf_decode_launch_shape(fake_cache(L=4, B=2, H=8, cap=cap, q_per_kv=g), cap)
+            assert chunk * g <= 4096 and S * chunk >= cap - 1 and 1 <= S <= 256, (g, cap, S, chunk)
