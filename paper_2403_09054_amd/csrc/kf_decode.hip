@@ -122,6 +122,26 @@ __device__ __forceinline__ void block_sum_n(float (&v)[N], float* red) {
     }
 }
 
+// Logits of a query group on the matrix cores.  With 8 bf16 query heads per
+// cached head the logits are a small dense contraction, rows x head dimension x
+// heads, and the lane-group reductions of the vector form cost more registers
+// and issue slots than the chip has to spare (4 heads still run faster in the
+// vector form: 64 % against 58 % of the HBM peak measured).  A wave multiplies a tile of 16 key rows (A operand: lane l holds eight
+// consecutive elements of row l%16, the l/16-th eight of every 32) by the query
+// group padded to 16 heads (B operand, same element assignment, kept in
+// registers), D/32 MFMAs per tile, and lane l receives the logits of rows
+// 4*(l/16) .. +3 for head l%16.  No dot products, no lane-group reductions.
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+template <typename T, int G>
+struct MfmaLogits {
+    static constexpr bool value = false;
+};
+template <int G>
+struct MfmaLogits<bf16_t, G> {
+    static constexpr bool value = (G >= 8);
+};
+
 // One workgroup streams the cache rows [j0, j1) of one cached head ("unit") once
 // and serves the G query heads that read it (G = 1: ordinary multi-head
 // attention; G > 1: grouped-query attention, query head hq = h*G + g).
@@ -200,10 +220,6 @@ __global__ void __launch_bounds__(NT) decode_kernel(const DecodeArgs a) {
         if (tid == 2 * kWave) pu[len0] = q_pos;
     }
 
-    QueryPiece<T> qp[G];
-#pragma unroll
-    for (int g = 0; g < G; ++g) qp[g].load(((const uint4*)(qu + (size_t)g * D))[cl]);
-
     // This lane's piece of row (base + i*RPB + sub) sits at lane_off + base*ROWB + i*RPB*ROWB.
     const size_t lane_off = (size_t)sub * ROWB + (size_t)cl * 16;
     const int base0 = j0 + wv * RPW;
@@ -229,53 +245,112 @@ __global__ void __launch_bounds__(NT) decode_kernel(const DecodeArgs a) {
 
     // ---- phase 1: stream K (next tile in flight while this one is reduced), logits into LDS
     uint4 cur[UNR], nxt[UNR];
-    auto logits_of = [&](int base) {
-        float p[G][UNR];
+    if constexpr (MfmaLogits<T, G>::value) {
+        constexpr int KK = D / 32;  // MFMAs (and 16-byte loads per lane) per 16-row tile
+        const int mrow = lane & 15, c4 = lane >> 4;
+        uint4 bq[KK];
 #pragma unroll
-        for (int g = 0; g < G; ++g) {
-#pragma unroll
-            for (int i = 0; i < UNR; ++i) p[g][i] = qp[g].dot(cur[i]);
+        for (int kk = 0; kk < KK; ++kk) {  // heads G..15 of the padded group are zero
+            bq[kk] = ((const uint4*)(qu + (size_t)min(mrow, G - 1) * D))[kk * 4 + c4];
+            if (mrow >= G) bq[kk] = make_uint4(0u, 0u, 0u, 0u);
         }
+        // rows past the split re-read its last row (the address stays inside the cache); their logits are dropped
+        auto load_rows = [&](int base, uint4(&raw)[KK]) {
+            const int row = min(base + wv * 16 + mrow, j1 - 1);
+            const uint4* p = (const uint4*)(Ku + (size_t)row * ROWB) + c4;
 #pragma unroll
-        for (int g = 0; g < G; ++g) {
+            for (int kk = 0; kk < KK; ++kk) raw[kk] = stream_load(p + kk * 4);
+        };
+        auto logits_of = [&](int base, const uint4(&raw)[KK]) {
+            f32x4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-            for (int i = 0; i < UNR; ++i) p[g][i] = group_sum<LPR>(p[g][i]);
+            for (int kk = 0; kk < KK; ++kk)
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, raw[kk]),
+                                                              __builtin_bit_cast(bf16x8_t, bq[kk]), acc, 0, 0, 0);
+            if (mrow < G) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int row = base + wv * 16 + c4 * 4 + r;
+                    if (row < j1) xs[mrow * CS + row - j0] = acc[r] * a.scale;
+                }
+            }
+        };
+        if (cnt_c > 0) {
+            uint4 kcur[KK], knxt[KK];
+            int base = j0;
+            load_rows(base, kcur);
+            while (base + 4 * 16 < j1) {
+                load_rows(base + 4 * 16, knxt);
+                logits_of(base, kcur);
+#pragma unroll
+                for (int kk = 0; kk < KK; ++kk) kcur[kk] = knxt[kk];
+                base += 4 * 16;
+            }
+            logits_of(base, kcur);
         }
+        if (owner && wv == 0) {  // the new token's own logits (distance 0: no position bias)
+            const uint4 kv = ((const uint4*)knew)[cl];
 #pragma unroll
-        for (int i = 0; i < UNR; ++i) {
-            const int j = base + i * RPB + sub;
-            if (cl == 0 && j < j1) {
-#pragma unroll
-                for (int g = 0; g < G; ++g) xs[g * CS + j - j0] = p[g][i] * a.scale;
+            for (int g = 0; g < G; ++g) {
+                QueryPiece<T> qg;
+                qg.load(((const uint4*)(qu + (size_t)g * D))[cl]);
+                const float p = group_sum<LPR>(qg.dot(kv));
+                if (lane == 0) xs[g * CS + cnt_c] = p * a.scale;
             }
         }
-    };
-    {
-        int base = base0;
-        if (base < j1) load_tile(Ku, base, cur);
-        // steady state: the next tile needs no bounds checks, so the loop body is
-        // branch-free and only the older tile's loads are waited for
-        while (plain(base + TILE)) {
-            load_plain(Ku, base + TILE, nxt);
-            logits_of(base);
+    } else {
+        QueryPiece<T> qp[G];
 #pragma unroll
-            for (int i = 0; i < UNR; ++i) cur[i] = nxt[i];
-            base += TILE;
+        for (int g = 0; g < G; ++g) qp[g].load(((const uint4*)(qu + (size_t)g * D))[cl]);
+
+        auto logits_of = [&](int base) {
+            float p[G][UNR];
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+#pragma unroll
+                for (int i = 0; i < UNR; ++i) p[g][i] = qp[g].dot(cur[i]);
+            }
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+#pragma unroll
+                for (int i = 0; i < UNR; ++i) p[g][i] = group_sum<LPR>(p[g][i]);
+            }
+#pragma unroll
+            for (int i = 0; i < UNR; ++i) {
+                const int j = base + i * RPB + sub;
+                if (cl == 0 && j < j1) {
+#pragma unroll
+                    for (int g = 0; g < G; ++g) xs[g * CS + j - j0] = p[g][i] * a.scale;
+                }
+            }
+        };
+        {
+            int base = base0;
+            if (base < j1) load_tile(Ku, base, cur);
+            // steady state: the next tile needs no bounds checks, so the loop body is
+            // branch-free and only the older tile's loads are waited for
+            while (plain(base + TILE)) {
+                load_plain(Ku, base + TILE, nxt);
+                logits_of(base);
+#pragma unroll
+                for (int i = 0; i < UNR; ++i) cur[i] = nxt[i];
+                base += TILE;
+            }
+            while (base < j1) {  // the last one or two tiles of the split
+                if (base + TILE < j1) load_edge(Ku, base + TILE, nxt);
+                logits_of(base);
+#pragma unroll
+                for (int i = 0; i < UNR; ++i) cur[i] = nxt[i];
+                base += TILE;
+            }
         }
-        while (base < j1) {  // the last one or two tiles of the split
-            if (base + TILE < j1) load_edge(Ku, base + TILE, nxt);
-            logits_of(base);
+        if (owner && wv == 0) {  // the new token's own logits (distance 0: no position bias)
+            const uint4 kv = ((const uint4*)knew)[cl];
 #pragma unroll
-            for (int i = 0; i < UNR; ++i) cur[i] = nxt[i];
-            base += TILE;
-        }
-    }
-    if (owner && wv == 0) {  // the new token's own logits (distance 0: no position bias)
-        const uint4 kv = ((const uint4*)knew)[cl];
-#pragma unroll
-        for (int g = 0; g < G; ++g) {
-            const float p = group_sum<LPR>(qp[g].dot(kv));
-            if (lane == 0) xs[g * CS + cnt_c] = p * a.scale;
+            for (int g = 0; g < G; ++g) {
+                const float p = group_sum<LPR>(qp[g].dot(kv));
+                if (lane == 0) xs[g * CS + cnt_c] = p * a.scale;
+            }
         }
     }
     // first V tile: in flight while the softmax statistics are formed
