@@ -260,13 +260,100 @@ def main():
         return {"steps_per_s": round(reps * n_cap / dt_, 2), "ms_per_step": round(dt_ * 1e3 / (reps * n_cap), 4),
                 "steps_per_graph": n_cap, "replays": reps}
 
+    def noise_variant(mode):
+        """The two-call step with another logit adjustment of the paper's ablation (same kernels)."""
+        base_t = W_steps + 2 * K_steps + 80
+        n_v = min(K_steps, 64)
+        ev2 = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(n_v)]
+        for i in range(n_v + 2):
+            t = base_t + i
+            q, kn, vn = steps_in[(t - 1) % n_distinct]
+            e = ev2[i - 2] if i >= 2 else (None, None, None)
+            if e[0] is not None:
+                e[0].record()
+            kf.kf_decode_step(cache, q, kn, vn, wl.n + t - 1, m, kf.kf_tau(min(t, wl.T), wl.T, wl.tau_init, wl.tau_end),
+                              wl.scale, mode, seeds, slopes, out, ws)
+            if e[1] is not None:
+                e[1].record()
+            kf.kf_select_evict(cache, wl.k, wl.w, None, ws)
+            if e[2] is not None:
+                e[2].record()
+        torch.cuda.synchronize()
+        dec = sum(e[0].elapsed_time(e[1]) for e in ev2) / n_v
+        sel = sum(e[1].elapsed_time(e[2]) for e in ev2) / n_v
+        return {"decode_us": round(dec * 1e3, 2), "select_us": round(sel * 1e3, 2),
+                "decode_frac_of_peak": round(decode_bytes(wl, m) / (dec * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+
+    def shared_variant():
+        """One score function for all layers (the paper's "Shared" ablation): fused steps, ordered layout.
+        All layers must hold the same tokens: layer 0's positions and scores are given to every layer."""
+        cache.pos.copy_(cache.pos[0:1].expand_as(cache.pos).clone())
+        cache.score.copy_(cache.score[0:1].expand_as(cache.score).clone())
+        base_t = W_steps + 2 * K_steps + 200
+        n_v = min(K_steps, 64)
+        for phase in range(2):
+            if phase == 1:
+                torch.cuda.synchronize()
+                c0 = time.perf_counter()
+            for i in range(4 if phase == 0 else n_v):
+                t = base_t + 4 * phase + i
+                q, kn, vn = steps_in[(t - 1) % n_distinct]
+                kf.kf_decode_select_step(cache, q, kn, vn, wl.n + t - 1, m, kf.kf_tau(min(t, wl.T), wl.T), wl.scale,
+                                         noise, seeds, slopes, out, k=wl.k, w=wl.w, layout=kf.LAYOUT_ORDERED,
+                                         workspace=ws, score_mode=kf.SCORE_SHARED)
+        torch.cuda.synchronize()
+        dt_ = time.perf_counter() - c0
+        assert int(ws[:4].view(torch.int32)[0].item()) == 0
+        assert bool((cache.pos[:, :, :, : wl.k] == cache.pos[0:1, :, :, : wl.k]).all()), "layers kept different tokens"
+        return {"steps_per_s": round(n_v / dt_, 2), "ms_per_step": round(dt_ * 1e3 / n_v, 4)}
+
+    def gqa_variant(G):
+        """Decode call with G query heads per cached head (grouped-query attention): the workload's query
+        heads on H/G cached heads, same per-unit shape; K+V algorithmic bytes over the call's duration."""
+        Hk = wl.H // G
+        c2 = kf.Cache.allocate(wl.L, wl.B, Hk, wl.d, wl.k + 1, dt, q_per_kv=G)
+        c2.K.normal_()
+        c2.V.normal_()
+        c2.score.uniform_()
+        c2.pos.copy_(torch.arange(wl.k + 1, device="cuda", dtype=torch.int32).expand_as(c2.pos))
+        ws2 = kf.new_workspace(c2)
+        q2 = steps_in[0][0]
+        kn2, vn2 = (x[:, :, ::G].contiguous() for x in steps_in[0][1:])
+        out2 = torch.zeros((wl.L, wl.B, wl.H, wl.d), dtype=torch.float32, device="cuda")
+        n_v = 20
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        tot = 0.0
+        for i in range(n_v + 3):
+            c2.len.fill_(wl.k)
+            e0.record()
+            kf.kf_decode_step(c2, q2, kn2, vn2, wl.n + 7, m, 1.5, wl.scale, noise, seeds, slopes, out2, ws2)
+            e1.record()
+            torch.cuda.synchronize()
+            if i >= 3:
+                tot += e0.elapsed_time(e1)
+        assert int(ws2[:4].view(torch.int32)[0].item()) == 0
+        ms = tot / n_v
+        byt = wl.L * wl.B * Hk * (m * (2 * wl.d * wl.elem_bytes + 12))
+        return {"cached_heads": Hk, "decode_us": round(ms * 1e3, 2),
+                "frac_of_peak": round(byt / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                "query_head_rows_per_s": round(wl.L * wl.B * wl.H * m / (ms * 1e-3), 0)}
+
     variants = None
     if not args.no_variants:
         variants = {"fused_step_ordered_layout": timed_variant(kf.LAYOUT_ORDERED),
                     "graph_fused_step_ordered_layout": graph_variant(kf.LAYOUT_ORDERED),
-                    # slot layout last: it unsorts the cache
-                    "fused_step_slot_layout": timed_variant(kf.LAYOUT_SLOT),
-                    "graph_fused_step_slot_layout": graph_variant(kf.LAYOUT_SLOT)}
+                    # the paper's ablations of the logit adjustment (two-call step, ordered layout)
+                    "noise_none": noise_variant(kf.NOISE_NONE),
+                    "noise_constant": noise_variant(kf.NOISE_CONSTANT),
+                    "noise_gaussian": noise_variant(kf.NOISE_GAUSSIAN)}
+        if Ls >= wl.L:   # every layer in one cache: the shared score function can be timed
+            variants["shared_score_fused_step_ordered_layout"] = shared_variant()
+        # slot layout last: it unsorts the cache
+        variants["fused_step_slot_layout"] = timed_variant(kf.LAYOUT_SLOT)
+        variants["graph_fused_step_slot_layout"] = graph_variant(kf.LAYOUT_SLOT)
+        for G in (2, 4, 8):
+            if wl.H % G == 0:
+                variants["grouped_query_decode_G%d" % G] = gqa_variant(G)
 
     # prompt-phase scoring: dense causal QK^T twice (row statistics, column sums)
     prefill_flops = wl.units * 2 * (2.0 * wl.d * wl.n * (wl.n + 1) / 2)
