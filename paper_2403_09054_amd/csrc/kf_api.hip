@@ -22,6 +22,8 @@ kf_status fail(kf_status st, const char* fmt, ...) {
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+constexpr int64_t kMaxGrid = 0x7fffffff;  // workgroups of a one-dimensional launch
+
 bool supported(int32_t dtype, int32_t d) {
     if (dtype == KF_BF16) return d == 64 || d == 128 || d == 256;
     if (dtype == KF_F32) return d == 64 || d == 128;
@@ -164,6 +166,8 @@ kf_status kf_prefill_score(const kf_cache* c, const void* Q, int32_t n, const kf
 
     const int32_t G = group_of(c);
     const int64_t U = (int64_t)c->L * c->B * c->H * G;  // query units
+    if ((U + 7) / 8 * 8 * ((n + 127) / 128) > kMaxGrid)  // one workgroup per 128 prompt rows of a unit
+        return fail(KF_EUNSUPPORTED, "%lld query units of %d prompt rows exceed the largest launch", (long long)U, n);
     const size_t n_pad = align_up((size_t)n, kf::kPrefillRowPad);
     kf::PrefillArgs a;
     a.Q = Q;
@@ -228,6 +232,8 @@ static kf_status prepare_decode(kf_cache* c, const void* q, const void* k_new, c
     // the partial-record region is sized for the plan at m = cap, the largest
     const kf::DecodePlan pmax = kf::plan_decode(U, c->cap, c->d, c->dtype, G);
     if (p.S > pmax.S) return fail(KF_EWORKSPACE, "internal: split count %d exceeds the sized %d", p.S, pmax.S);
+    if (U * p.S > kMaxGrid)
+        return fail(KF_EUNSUPPORTED, "%lld units in %d splits each exceed the largest launch", (long long)U, p.S);
     a->K = c->K;
     a->V = c->V;
     a->score = c->score;

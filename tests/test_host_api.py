@@ -191,3 +191,12 @@ def test_query_group_validation_and_sizes():
         for cap in (1025, 9831, 40000):
             S, chunk = kf.kf_decode_launch_shape(fake_cache(L=4, B=2, H=8, cap=cap, q_per_kv=g), cap)
             assert chunk * g <= 4096 and S * chunk >= cap - 1 and 1 <= S <= 256, (g, cap, S, chunk)
+
+
+def test_launches_beyond_the_grid_limit_are_refused():
+    # 2^24 units of a million tokens would need 2^32 decode workgroups; 2^24 units of 2^20 prompt rows 2^37
+    huge = fake_cache(L=256, B=256, H=256, d=64, cap=1 << 20)
+    expect(binding.KF_EUNSUPPORTED, kf.kf_decode_step, huge, 0x1000, 0x2000, 0x3000, 10, 0, 1.5, 0.1, kf.NOISE_GUMBEL,
+           0x4000, None, 0x5000, (0x100000, 1 << 62), 0)
+    expect(binding.KF_EUNSUPPORTED, kf.kf_prefill_score, huge, 0x1000, 1 << 20, 1.0, 0.1, kf.NOISE_GUMBEL, 0x4000, None,
+           (0x100000, 1 << 62), 0)
