@@ -347,6 +347,70 @@ def test_gptj_full_size_in_bench_launch_shape_sampled_layers():
     assert int(cache.len.min()) == wl.k and int(cache.len.max()) == wl.k
 
 
+@pytest.mark.parametrize("name", ["mpt", "long", "batched"])
+def test_full_size_decode_and_select_on_sampled_sequences(name):
+    """The other configurations at their FULL size (all units in one launch, cap = k+1: the launch shape a
+    bench run of that configuration uses), from a synthetic cache state, three generation steps in
+    lock-step; the oracle computes three whole (layer, sequence) rows -- first, last and one in between."""
+    wl = kw.CONFIGS[name]
+    k, cap = wl.k, wl.k + 1
+    g = torch.Generator(device="cuda")
+    g.manual_seed(99)
+    cache = kf.Cache.allocate(wl.L, wl.B, wl.H, wl.d, cap, kf.BF16)
+    for l in range(wl.L):                       # layer by layer: no full-size temporaries
+        cache.K[l].normal_(generator=g)
+        cache.V[l].normal_(generator=g)
+        cache.score[l].uniform_(0.0, 3.0, generator=g)
+    cache.pos.copy_(torch.arange(wl.n - k, wl.n - k + cap, device="cuda", dtype=torch.int32).expand_as(cache.pos))
+    cache.len.fill_(k)
+    ws = kf.new_workspace(cache)
+    seeds = kw.noise_seeds(wl)
+    slopes = kw.alibi_slopes(wl)
+    d_seeds, d_slopes = dev(seeds), dev(slopes)
+    out = torch.zeros((wl.L, wl.B, wl.H, wl.d), dtype=torch.float32, device="cuda")
+    kept = torch.zeros((wl.L, wl.B, wl.H, k), dtype=torch.int32, device="cuda")
+    rows = [(0, 0), (wl.L // 2, wl.B // 2), (wl.L - 1, wl.B - 1)]
+    ocs = {}
+    for l, b in rows:
+        oc = ko.OracleCache(1, 1, wl.H, wl.d, cap, ko.BF16, layer0=l)
+        oc.K[0, 0], oc.V[0, 0] = host(cache.K[l, b]), host(cache.V[l, b])
+        oc.score[0, 0], oc.pos[0, 0], oc.len[0, 0] = host(cache.score[l, b]), host(cache.pos[l, b]), host(cache.len[l, b])
+        ocs[(l, b)] = oc
+    ties = 0
+    for t in range(1, 4):
+        q, kn, vn = kw.decode_inputs(wl, t, device="cuda")
+        q_pos = wl.n + t - 1
+        kf.kf_decode_step(cache, q, kn, vn, q_pos, cap, kf.kf_tau(t, wl.T, wl.tau_init, wl.tau_end), wl.scale,
+                          kf.NOISE_GUMBEL, d_seeds, d_slopes, out, ws)
+        torch.cuda.synchronize()
+        assert error_word(ws) == 0 and int(cache.len.min()) == cap
+        before = {}
+        for (l, b), oc in ocs.items():
+            out_ref = oc.decode_step(host(q[l, b])[None, None], host(kn[l, b])[None, None], host(vn[l, b])[None, None],
+                                     q_pos, ko.tau(t, wl.T, wl.tau_init, wl.tau_end), wl.scale, ko.NOISE_GUMBEL,
+                                     seeds[b:b + 1], slopes)
+            assert_close_out(host(out[l, b])[None, None], out_ref, "out (%d,%d)" % (l, b))
+            assert_close_score(host(cache.score[l, b])[None, None], oc.score, oc.len, "score (%d,%d)" % (l, b))
+            cache.score[l, b].copy_(dev(oc.score)[0, 0])          # lock-step: same scores before selection
+            before[(l, b)] = (oc.score.copy(), oc.len.copy())
+        kf.kf_select_evict(cache, k, wl.w, kept, ws)
+        torch.cuda.synchronize()
+        assert error_word(ws) == 0 and int(cache.len.max()) == k
+        for (l, b), oc in ocs.items():
+            kept_ref = oc.select_evict(k, wl.w)
+            ev = compare_kept(host(kept[l, b])[None, None], kept_ref, before[(l, b)][0], before[(l, b)][1], k, wl.w)
+            ties += ev
+            sub = kf.Cache(K=cache.K[l:l + 1, b:b + 1], V=cache.V[l:l + 1, b:b + 1], score=cache.score[l:l + 1, b:b + 1],
+                           pos=cache.pos[l:l + 1, b:b + 1], len=cache.len[l:l + 1, b:b + 1], L=1, B=1, H=wl.H, d=wl.d,
+                           cap=cap, dtype=kf.BF16)
+            if ev:                                  # adopt the oracle's choice inside the tie band and go on
+                for nm in ("K", "V", "score", "pos", "len"):
+                    getattr(cache, nm)[l, b].copy_(dev(getattr(oc, nm))[0, 0])
+            else:
+                assert_state_equal(sub, oc, kv=(t == 3))
+    print(name, "full size: tie-band events", ties)
+
+
 def test_layer_offset_draws_the_full_models_noise():
     # a cache holding only layer 5 (layer0 = 5) must reproduce layer 5 of a six-layer cache
     rng = np.random.default_rng(21)
