@@ -179,7 +179,10 @@ def main():
         sel_ms = sum(e[1].elapsed_time(e[2]) for e in evs) / K_steps
         nbytes = decode_bytes(wl, m)
         achieved = nbytes / (dec_ms * 1e-3) / 1e9
-        roofline = {"bound": "hbm", "kernel": "kf_decode_step = decode_kernel + decode_merge_kernel",
+        splits, chunk = kf.kf_decode_launch_shape(cache, m)
+        roofline = {"bound": "hbm",
+                    "kernel": "kf_decode_step = decode_kernel" + (" + decode_merge_kernel" if splits > 1 else ""),
+                    "launch_shape": {"splits_per_unit": splits, "rows_per_split": chunk},
                     "achieved": round(achieved, 1),
                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                     "traffic": None, "bytes_per_launch": nbytes, "avg_launch_us": round(dec_ms * 1e3, 2)}

@@ -134,13 +134,21 @@ def test_decode_launch_shape_covers_the_rows_and_balances_the_chip():
         c = fake_cache(L=L, B=B, H=H, d=d, cap=cap, dtype=dt)
         S, chunk = kf.kf_decode_launch_shape(c, hint)
         rows = (hint or cap) - 1
-        assert 1 <= S <= 256 and 1 <= chunk <= 4096
+        assert 1 <= S <= 256 and 1 <= chunk <= (10240 if S == 1 else 4096)     # LDS: 80 KB single, 64 KB split
         assert S * chunk >= rows                      # every cache row belongs to a split
         assert (S - 1) * chunk < max(rows, 1) or S == 1   # no split is entirely beyond the rows
-    # the GPT-J-shaped workload: 448 units -> 4 splits of 256 rows = 1792 workgroups = 7 per compute unit
-    assert kf.kf_decode_launch_shape(fake_cache(L=28, B=1, H=16, d=256, cap=1025), 1025) == (4, 256)
-    # plenty of units: one workgroup per unit, nothing to merge
-    assert kf.kf_decode_launch_shape(fake_cache(L=32, B=64, H=32, d=128, cap=1025), 1025)[0] == 1
+    # more than one unit per compute unit and the logits fit LDS: one workgroup per unit, nothing to merge
+    assert kf.kf_decode_launch_shape(fake_cache(L=28, B=1, H=16, d=256, cap=1025), 1025) == (1, 1024)
+    assert kf.kf_decode_launch_shape(fake_cache(L=32, B=64, H=32, d=128, cap=1025), 1025) == (1, 1024)
+    assert kf.kf_decode_launch_shape(fake_cache(L=32, B=1, H=32, d=128, cap=9831), 9831) == (1, 9840)
+    # too few units to fill the chip that way: 256 units -> 4 splits of 256 rows = 1024 workgroups
+    assert kf.kf_decode_launch_shape(fake_cache(L=16, B=1, H=16, d=256, cap=1025), 1025) == (4, 256)
+    # logits of one unit beyond what two workgroups per compute unit can hold in LDS: splits of at most 4096 rows
+    S, chunk = kf.kf_decode_launch_shape(fake_cache(L=32, B=1, H=32, d=128, cap=20000), 20000)
+    assert S >= 5 and chunk <= 4096
+    # 8 query heads per cached head never take the single-workgroup shape
+    S, chunk = kf.kf_decode_launch_shape(fake_cache(L=32, B=8, H=8, d=128, cap=2049, q_per_kv=8), 2049)
+    assert S >= 4 and chunk <= 512
     expect(binding.KF_EINVAL, kf.kf_decode_launch_shape, fake_cache(), 2000)
     expect(binding.KF_EUNSUPPORTED, kf.kf_decode_launch_shape, fake_cache(d=96), 0)
 
@@ -190,7 +198,7 @@ def test_query_group_validation_and_sizes():
     for g in (1, 2, 4, 8):
         for cap in (1025, 9831, 40000):
             S, chunk = kf.kf_decode_launch_shape(fake_cache(L=4, B=2, H=8, cap=cap, q_per_kv=g), cap)
-            assert chunk * g <= 4096 and S * chunk >= cap - 1 and 1 <= S <= 256, (g, cap, S, chunk)
+            assert (chunk * g <= 4096 or S == 1) and S * chunk >= cap - 1 and 1 <= S <= 256, (g, cap, S, chunk)
 
 
 def test_launches_beyond_the_grid_limit_are_refused():
