@@ -298,6 +298,8 @@ int kfo_prefill_score(const void *Q, const void *K, float *score, int32_t *pos,
 /* query heads h*G .. h*G+G-1, each with its own logits, attention output, */
 /* slope and noise stream; f takes the sum of their increments (the heads  */
 /* share the cached tokens, so they share the decision what to keep).     */
+/* q_pos_seq, tau_seq (may be NULL): [B] per-sequence query position and    */
+/* temperature, replacing the scalars q_pos and tau.                       */
 /* Optional debug outputs (may be NULL): dbg_p, dbg_df [U*G][cap] doubles. */
 /* ------------------------------------------------------------------ */
 int kfo_decode_step(void *K, void *V, float *score, int32_t *pos, int32_t *len,
@@ -305,9 +307,13 @@ int kfo_decode_step(void *K, void *V, float *score, int32_t *pos, int32_t *len,
                     const void *q, const void *k_new, const void *v_new,
                     int32_t q_pos, float tau, float scale, int noise,
                     const uint64_t *seeds, const float *slopes, int new_pos, int shared,
-                    int G, float *out, double *dbg_p, double *dbg_df)
+                    int G, const int32_t *q_pos_seq, const float *tau_seq,
+                    float *out, double *dbg_p, double *dbg_df)
 {
     if (!(tau > 0.0f) || G < 1) return -1;
+    if (tau_seq)
+        for (int b = 0; b < B; ++b)
+            if (!(tau_seq[b] > 0.0f)) return -1;
     int U = L * B * H;
     size_t es = elem_size(dtype);
     for (int u = 0; u < U; ++u)
@@ -331,6 +337,10 @@ int kfo_decode_step(void *K, void *V, float *score, int32_t *pos, int32_t *len,
     for (int u = 0; u < U; ++u) {
         int hk = u % H, b = (u / H) % B, l = layer0 + u / (H * B);
         uint64_t seed = seeds ? seeds[b] : 0;
+        /* a batch whose sequences are at different points of their generation: each
+         * has its own query position and its own temperature tau_t  [Eq. 12 per sequence] */
+        int32_t q_pos_u = q_pos_seq ? q_pos_seq[b] : q_pos;
+        double tau_u = tau_seq ? (double)tau_seq[b] : (double)tau;
         char *Ku = (char *)K + (size_t)u * cap * d * es;
         char *Vu = (char *)V + (size_t)u * cap * d * es;
         float *fu = score + (size_t)u * cap;
@@ -340,7 +350,7 @@ int kfo_decode_step(void *K, void *V, float *score, int32_t *pos, int32_t *len,
         int slot = len[u];
         memcpy(Ku + (size_t)slot * d * es, (const char *)k_new + (size_t)u * d * es, d * es);
         memcpy(Vu + (size_t)slot * d * es, (const char *)v_new + (size_t)u * d * es, d * es);
-        pu[slot] = q_pos;
+        pu[slot] = q_pos_u;
         fu[slot] = 0.0f;
         int m = slot + 1;
         len[u] = m;
@@ -366,11 +376,11 @@ int kfo_decode_step(void *K, void *V, float *score, int32_t *pos, int32_t *len,
                 /* distance behind the position bias: original positions ("Org Pos"), or -- the
                  * paper's "New Pos" ablation, Sec. 4.4.2 -- positions within the reduced cache,
                  * where the query sits at slot m-1 and key j at slot j */
-                double dist = new_pos ? (double)(m - 1 - j) : (double)(q_pos - pu[j]);
+                double dist = new_pos ? (double)(m - 1 - j) : (double)(q_pos_u - pu[j]);
                 double x = (double)scale * dot - slope * dist;
                 p[j] = x;
                 y[j] = (x + zeta(noise, seed, (uint32_t)l, (uint32_t)h,
-                                 (uint32_t)q_pos, (uint32_t)pu[j])) / (double)tau;
+                                 (uint32_t)q_pos_u, (uint32_t)pu[j])) / tau_u;
             }
             softmax_inplace(p, m); /* attention probabilities: clean logits */
             softmax_inplace(y, m); /* score increment: perturbed, tempered logits */

@@ -56,7 +56,7 @@ def lib():
             C.c_float, C.c_float, C.c_int, vp, vp, C.c_int, C.c_int]
         L.kfo_decode_step.restype = C.c_int
         L.kfo_decode_step.argtypes = [vp, vp, vp, vp, vp] + [C.c_int] * 7 + [
-            vp, vp, vp, C.c_int32, C.c_float, C.c_float, C.c_int, vp, vp, C.c_int, C.c_int, C.c_int, vp, vp, vp]
+            vp, vp, vp, C.c_int32, C.c_float, C.c_float, C.c_int, vp, vp, C.c_int, C.c_int, C.c_int, vp, vp, vp, vp, vp]
         L.kfo_select_evict.restype = C.c_int
         L.kfo_select_evict.argtypes = [vp, vp, vp, vp, vp] + [C.c_int] * 8 + [vp]
         _lib = L
@@ -137,10 +137,11 @@ class OracleCache:
 
     def decode_step(self, q, k_new, v_new, q_pos, tau_, scale, noise=NOISE_GUMBEL,
                     seeds=None, slopes=None, debug=False, new_pos=False, shared=False,
-                    q_per_kv=1):
+                    q_per_kv=1, q_pos_seq=None, tau_seq=None):
         """k_new, v_new: [L,B,H,d]; q: [L,B,H*q_per_kv,d].  Returns out [L,B,H*q_per_kv,d]
         float32 (and, with debug, every query head's attention probabilities and score
-        increment as float64 [L,B,H*q_per_kv,cap])."""
+        increment as float64 [L,B,H*q_per_kv,cap]).  q_pos_seq / tau_seq: [B] per-sequence
+        query position and temperature, replacing the scalars."""
         shp = (self.L, self.B, self.H, self.d)
         qshp = (self.L, self.B, self.H * q_per_kv, self.d)
         q, k_new, v_new = (np.ascontiguousarray(a) for a in (q, k_new, v_new))
@@ -148,13 +149,18 @@ class OracleCache:
             assert a.shape == sh_ and _dtype_code(a) == self.dtype
         seeds = None if seeds is None else np.ascontiguousarray(seeds, np.uint64)
         slopes = None if slopes is None else np.ascontiguousarray(slopes, np.float32)
+        q_pos_seq = None if q_pos_seq is None else np.ascontiguousarray(q_pos_seq, np.int32)
+        tau_seq = None if tau_seq is None else np.ascontiguousarray(tau_seq, np.float32)
+        for a in (q_pos_seq, tau_seq):
+            assert a is None or a.shape == (self.B,)
         out = np.zeros(qshp, np.float32)
         dshape = (self.L, self.B, self.H * q_per_kv, self.cap)
         dp = np.zeros(dshape, np.float64) if debug else None
         df = np.zeros(dshape, np.float64) if debug else None
         rc = lib().kfo_decode_step(_p(self.K), _p(self.V), _p(self.score), _p(self.pos), _p(self.len),
                                    *self._dims(), self.layer0, _p(q), _p(k_new), _p(v_new), q_pos, tau_, scale,
-                                   noise, _p(seeds), _p(slopes), int(new_pos), int(shared), int(q_per_kv), _p(out), _p(dp), _p(df))
+                                   noise, _p(seeds), _p(slopes), int(new_pos), int(shared), int(q_per_kv), _p(q_pos_seq), _p(tau_seq),
+                                   _p(out), _p(dp), _p(df))
         if rc:
             raise ValueError("kfo_decode_step rc=%d" % rc)
         return (out, dp, df) if debug else out

@@ -535,6 +535,37 @@ def test_grouped_queries_special_cases():
 
 
 # ----------------------------------------------------------------------------
+# A batch whose sequences are at different steps: per-sequence position and temperature
+# ----------------------------------------------------------------------------
+def test_per_sequence_position_and_temperature_equal_separate_runs():
+    rng = np.random.default_rng(41)
+    L, B, H, d, cap = 2, 3, 2, 16, 24
+    lens = rng.integers(8, 20, (1, B, 1)).repeat(L, 0).repeat(H, 2).astype(np.int32)
+    c = make_cache(rng, L, B, H, d, cap, 20, ko.BF16)
+    c.len[...] = lens
+    c.score[...] = rng.random(c.score.shape).astype(np.float32)
+    q, kn, vn = (rand_vec(rng, (L, B, H, d), ko.BF16) for _ in range(3))
+    seeds = np.array([5, 6, 7], np.uint64)
+    slopes = np.array([0.25, 0.03], np.float32)
+    q_pos = np.array([40, 25, 33], np.int32)
+    taus = np.array([1.25, 1.0, 1.9], np.float32)
+    whole = c.copy()
+    out = whole.decode_step(q, kn, vn, 0, 1.0, 0.25, ko.NOISE_GUMBEL, seeds, slopes, q_pos_seq=q_pos, tau_seq=taus)
+    for b in range(B):                                   # each sequence alone, through the scalar arguments
+        one = ko.OracleCache(L, 1, H, d, cap, ko.BF16)
+        for nm in ("K", "V", "score", "pos", "len"):
+            getattr(one, nm)[...] = getattr(c, nm)[:, b:b + 1]
+        o = one.decode_step(q[:, b:b + 1], kn[:, b:b + 1], vn[:, b:b + 1], int(q_pos[b]), float(taus[b]), 0.25,
+                            ko.NOISE_GUMBEL, seeds[b:b + 1], slopes)
+        np.testing.assert_array_equal(out[:, b:b + 1], o)
+        for nm in ("K", "V", "score", "pos", "len"):
+            np.testing.assert_array_equal(getattr(whole, nm)[:, b:b + 1], getattr(one, nm))
+    assert (whole.pos[0, np.arange(B), 0, lens[0, :, 0]] == q_pos).all()   # each appended token carries its own position
+    with pytest.raises(ValueError):
+        c.copy().decode_step(q, kn, vn, 0, 1.0, 0.25, ko.NOISE_GUMBEL, seeds, slopes, tau_seq=np.array([1.0, 0.0, 1.0]))
+
+
+# ----------------------------------------------------------------------------
 # Selection + compaction (Alg. 1: S_w, S_key = argmax_(k-w) f[:-w], S_k)
 # ----------------------------------------------------------------------------
 def brute_force_keep(f, n, k, w):
