@@ -113,6 +113,12 @@ typedef struct {
                                   the logits (MPT's position bias)                        */
     int32_t pos_mode;          /* kf_pos_mode; only matters with alibi_slopes, decode only */
     int32_t score_mode;        /* kf_score_mode                                           */
+    const int32_t *seq_q_pos;  /* DEVICE [B] or NULL.  Decode only: sequence b's new token sits at
+                                  seq_q_pos[b] instead of the call's q_pos -- for batches whose
+                                  sequences are at different points of their generation         */
+    const float *seq_tau;      /* DEVICE [B] or NULL.  Decode only: sequence b's temperature of this
+                                  step (Eq. 12 with its own t and T) instead of tau; every entry
+                                  must be finite and positive (not checked: device memory)      */
 } kf_score_cfg;
 
 /* Library version, for the binding to check it loaded what it expects. */
@@ -190,7 +196,9 @@ kf_status kf_decode_step(kf_cache *c, const void *q, const void *k_new, const vo
  * slot of every survivor (identity, then -1 padding, for untouched units).
  * layout is a kf_layout.  With KF_LAYOUT_SLOT a unit more than one token over
  * budget is left untouched and the workspace error word is incremented; the
- * recent window is then "the w largest pos", equal scores keep the lower pos.
+ * recent window is then the entries with pos > newest pos - w (the w largest
+ * positions, given that a generation appends consecutive positions), and equal
+ * scores keep the lower pos.
  * Errors: KF_EINVAL if k < 1, w < 0, w > k, k > cap or layout unknown.
  */
 kf_status kf_select_evict(kf_cache *c, int32_t k, int32_t w, int32_t layout, int32_t *kept_idx,

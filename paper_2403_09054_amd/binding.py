@@ -42,7 +42,7 @@ class kf_cache(C.Structure):
 class kf_score_cfg(C.Structure):
     _fields_ = [("tau", C.c_float), ("scale", C.c_float), ("noise", C.c_int32),
                 ("seeds", C.c_void_p), ("alibi_slopes", C.c_void_p), ("pos_mode", C.c_int32),
-                ("score_mode", C.c_int32)]
+                ("score_mode", C.c_int32), ("seq_q_pos", C.c_void_p), ("seq_tau", C.c_void_p)]
 
 
 class kf_schedule(C.Structure):
@@ -201,8 +201,9 @@ def _ws(workspace):
     return workspace.data_ptr(), workspace.numel() * workspace.element_size()
 
 
-def _cfg(tau, scale, noise, seeds, slopes, pos_mode=0, score_mode=0) -> kf_score_cfg:
-    return kf_score_cfg(tau, scale, noise, _ptr(seeds), _ptr(slopes), pos_mode, score_mode)
+def _cfg(tau, scale, noise, seeds, slopes, pos_mode=0, score_mode=0, seq_q_pos=None, seq_tau=None) -> kf_score_cfg:
+    return kf_score_cfg(tau, scale, noise, _ptr(seeds), _ptr(slopes), pos_mode, score_mode, _ptr(seq_q_pos),
+                        _ptr(seq_tau))
 
 
 def kf_prefill_score(cache: Cache, Q, n: int, tau: float, scale: float, noise: int = NOISE_GUMBEL,
@@ -215,8 +216,9 @@ def kf_prefill_score(cache: Cache, Q, n: int, tau: float, scale: float, noise: i
 
 def kf_decode_step(cache: Cache, q, k_new, v_new, q_pos: int, m_hint: int, tau: float, scale: float,
                    noise: int = NOISE_GUMBEL, seeds=None, slopes=None, out=None, workspace=None,
-                   stream=None, pos_mode: int = POS_ORIGINAL, score_mode: int = SCORE_PER_LAYER) -> None:
-    cs, cfg = cache.c_struct(), _cfg(tau, scale, noise, seeds, slopes, pos_mode, score_mode)
+                   stream=None, pos_mode: int = POS_ORIGINAL, score_mode: int = SCORE_PER_LAYER,
+                   seq_q_pos=None, seq_tau=None) -> None:
+    cs, cfg = cache.c_struct(), _cfg(tau, scale, noise, seeds, slopes, pos_mode, score_mode, seq_q_pos, seq_tau)
     wp, wb = _ws(workspace)
     _check(lib().kf_decode_step(C.byref(cs), _ptr(q), _ptr(k_new), _ptr(v_new), q_pos, m_hint,
                                 C.byref(cfg), _ptr(out), wp, wb, _stream(stream)))
@@ -240,8 +242,9 @@ def kf_select_evict_into(src: Cache, dst: Cache, dst_layer0: int, k: int, w: int
 def kf_decode_select_step(cache: Cache, q, k_new, v_new, q_pos: int, m_hint: int, tau: float, scale: float,
                           noise: int = NOISE_GUMBEL, seeds=None, slopes=None, out=None, k: int = 0, w: int = 0,
                           layout: int = LAYOUT_ORDERED, kept_idx=None, workspace=None, stream=None,
-                          pos_mode: int = POS_ORIGINAL, score_mode: int = SCORE_PER_LAYER) -> None:
-    cs, cfg = cache.c_struct(), _cfg(tau, scale, noise, seeds, slopes, pos_mode, score_mode)
+                          pos_mode: int = POS_ORIGINAL, score_mode: int = SCORE_PER_LAYER,
+                          seq_q_pos=None, seq_tau=None) -> None:
+    cs, cfg = cache.c_struct(), _cfg(tau, scale, noise, seeds, slopes, pos_mode, score_mode, seq_q_pos, seq_tau)
     wp, wb = _ws(workspace)
     _check(lib().kf_decode_select_step(C.byref(cs), _ptr(q), _ptr(k_new), _ptr(v_new), q_pos, m_hint,
                                        C.byref(cfg), _ptr(out), k, w, layout, _ptr(kept_idx), wp, wb,

@@ -261,6 +261,8 @@ static kf_status prepare_decode(kf_cache* c, const void* q, const void* k_new, c
     a->noise = cfg->noise;
     a->new_pos = cfg->pos_mode == KF_POS_NEW ? 1 : 0;
     a->shared = cfg->score_mode == KF_SCORE_SHARED ? 1 : 0;
+    a->seq_q_pos = cfg->seq_q_pos;
+    a->seq_tau = cfg->seq_tau;
     a->step = nullptr;
     a->n0 = 0;
     a->T = 1;

@@ -184,6 +184,8 @@ __global__ void __launch_bounds__(NT) decode_kernel(const DecodeArgs a) {
         q_pos = a.n0 + t - 1;
         inv_tau = 1.0f / schedule_tau(a.tau_init, a.dtau, min(t, a.T));  // IEEE division, as on the host
     }
+    if (a.seq_q_pos) q_pos = a.seq_q_pos[b];  // a batch whose sequences are at different steps
+    if (a.seq_tau) inv_tau = 1.0f / a.seq_tau[b];
     const int len0 = a.len[u];
     const int m = len0 + 1;
     if (len0 < 0 || len0 >= a.cap || len0 > S * a.chunk) {

@@ -38,6 +38,9 @@ struct DecodeArgs {
     const int32_t* step;
     int32_t n0, T;
     float tau_init, dtau;
+    // Per-sequence query position / temperature (either may be NULL): [B], override the above.
+    const int32_t* seq_q_pos;
+    const float* seq_tau;
     float inv_tau;
     float scale;
 };

@@ -891,3 +891,38 @@ def test_grouped_query_decode_at_the_largest_lds_footprint():
     out_ref = oc.decode_step(q, kn, vn, q_pos, 1.5, 0.0625, ko.NOISE_GUMBEL, seeds, None, q_per_kv=G)
     assert_close_out(host(out), out_ref)
     assert_close_score(host(gc.score), oc.score, oc.len)
+
+
+# ------------------------------------------------------------------ sequences at different steps
+@pytest.mark.parametrize("cap,layout", [(120, kf.LAYOUT_ORDERED), (1500, kf.LAYOUT_ORDERED), (300, kf.LAYOUT_SLOT)])
+def test_per_sequence_position_and_temperature(cap, layout):
+    rng = np.random.default_rng(cap)
+    L, B, H, d = 2, 3, 4, 128
+    k, w = cap - 1, (cap - 1) // 5
+    lens = np.broadcast_to(np.array([k, k - 7, k // 2], np.int32)[None, :, None], (L, B, H)).copy()
+    oc = random_cache(rng, L, B, H, d, cap, ko.BF16, lens)
+    q, kn, vn = (rnd(rng, (L, B, H, d), ko.BF16) for _ in range(3))
+    seeds = np.array([1, 2, 3], np.uint64)
+    slopes = np.array([0.5, 0.25, 0.0, 0.01], np.float32)
+    oc.pos[...] = np.arange(cap)           # consecutive positions, as a generation leaves them at the recent end
+    q_pos = lens[0, :, 0].copy()           # every sequence appends its own next position
+    taus = np.array([1.0, 1.5, 1.96875], np.float32)
+    gc = upload(oc)
+    ws = kf.new_workspace(gc)
+    out = torch.zeros((L, B, H, d), dtype=torch.float32, device="cuda")
+    kept = torch.zeros((L, B, H, k), dtype=torch.int32, device="cuda")
+    kf.kf_decode_select_step(gc, dev(q), dev(kn), dev(vn), 0, 0, 1.0, 0.09, kf.NOISE_GUMBEL, dev(seeds), dev(slopes), out,
+                             k=k, w=w, layout=layout, kept_idx=kept, workspace=ws, seq_q_pos=dev(q_pos), seq_tau=dev(taus))
+    torch.cuda.synchronize()
+    assert error_word(ws) == 0
+    out_ref = oc.decode_step(q, kn, vn, 0, 1.0, 0.09, ko.NOISE_GUMBEL, seeds, slopes, q_pos_seq=q_pos, tau_seq=taus)
+    assert_close_out(host(out), out_ref)
+    before_score, before_len = oc.score.copy(), oc.len.copy()
+    kept_ref = oc.select_evict(k, w)
+    np.testing.assert_array_equal(host(gc.len), oc.len)          # only the sequence that was full lost a token
+    if layout == kf.LAYOUT_ORDERED:
+        assert compare_kept(host(kept), kept_ref, before_score, before_len, k, w) == 0
+        assert_state_equal(gc, oc, kv=True, score_exact=False)
+        assert_close_score(host(gc.score), oc.score, oc.len)
+    else:
+        assert_set_equal(gc, oc, kv=True, score_exact=False)
