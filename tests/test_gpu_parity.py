@@ -237,9 +237,9 @@ def test_tiny_config_full_lockstep_and_free_running():
 
 SLICES = {
     # name: (slice kwargs, decode steps checked)
-    "gptj": (dict(L=2, H=16, T=512), 128),
-    "mpt": (dict(L=1, B=2, H=8, T=1024), 64),
-    "batched": (dict(L=1, B=4, H=8, T=1024), 64),
+    "gptj": (dict(L=2, H=16, T=512), 512),           # the whole generation: tau runs from tau_init to tau_end
+    "mpt": (dict(L=1, B=2, H=8, T=1024), 256),
+    "batched": (dict(L=1, B=4, H=8, T=1024), 256),
 }
 
 
@@ -256,11 +256,11 @@ def test_config_slice_lockstep(name):
 
 def test_long_config_slice_lockstep():
     # full per-unit shape of the long-context configuration (n = 32768, k = 9830)
-    wl = kw.CONFIGS["long"].slice(L=1, H=4, T=2048)
+    wl = kw.CONFIGS["long"].slice(L=1, H=8, T=2048)
     ls = LockStep(wl)
     ls.prefill()
-    for t in range(1, 17):
-        ls.step(t, check_kv=(t == 16))
+    for t in range(1, 129):
+        ls.step(t, check_kv=(t == 128))
     print("long slice lockstep", ls.stats)
 
 
