@@ -9,7 +9,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libkeyformer.so")
 SOURCES = ["kf_api.hip", "kf_decode.hip", "kf_select.hip", "kf_prefill.hip"]
-HEADERS = ["kf_device.h", "kf_internal.h", os.path.join("..", "..", "include", "keyformer.h")]
+HEADERS = ["kf_device.h", "kf_internal.h", "kf_merge.h", os.path.join("..", "..", "include", "keyformer.h")]
+EXAMPLE_SRC = os.path.join(HERE, "examples", "generate_loop.cpp")
+EXAMPLE_BIN = os.path.join(HERE, "examples", "generate_loop")
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -33,7 +35,22 @@ def build(force: bool = True, verbose: bool = False) -> str:
         if verbose:
             print(" ".join(cmd), flush=True)
         subprocess.check_call(cmd)
+    build_example(force, verbose)
     return LIB
+
+
+def build_example(force: bool = True, verbose: bool = False) -> str:
+    """The stand-alone C++ user of the C ABI (no Python, no torch), linked against the in-tree library."""
+    if force or not os.path.exists(EXAMPLE_BIN) or os.path.getmtime(EXAMPLE_BIN) < max(
+            os.path.getmtime(EXAMPLE_SRC), os.path.getmtime(LIB)):
+        hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+        cmd = [hipcc, "--offload-arch=gfx950", "-O2", "-std=c++17", "-Wall", "-Wextra", EXAMPLE_SRC,
+               "-I", os.path.join(HERE, "..", "include"), "-L", HERE, "-lkeyformer", "-Wl,-rpath,$ORIGIN/..",
+               "-o", EXAMPLE_BIN]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.check_call(cmd)
+    return EXAMPLE_BIN
 
 
 if __name__ == "__main__":

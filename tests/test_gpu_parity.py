@@ -926,3 +926,18 @@ def test_per_sequence_position_and_temperature(cap, layout):
         assert_close_score(host(gc.score), oc.score, oc.len)
     else:
         assert_set_equal(gc, oc, kv=True, score_exact=False)
+
+
+# ------------------------------------------------------------------ the C ABI without Python
+def test_standalone_cpp_user_of_the_c_abi():
+    """examples/generate_loop.cpp: hipMalloc'ed buffers, prompt scoring, eviction into the generation cache,
+    then 30 steps replayed from one captured HIP-graph step; it checks Algorithm 1's invariants itself."""
+    import os
+    import subprocess
+    exe = os.path.join(os.path.dirname(kf.lib_path()), "examples", "generate_loop")
+    if not os.path.exists(exe):
+        pytest.skip("examples/generate_loop is not built (python -m paper_2403_09054_amd.build builds it)")
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    print(r.stdout, r.stderr)
+    assert r.returncode == 0, r.stderr
+    assert "all invariants hold" in r.stdout
