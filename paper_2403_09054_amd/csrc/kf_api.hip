@@ -263,6 +263,9 @@ static kf_status prepare_decode(kf_cache* c, const void* q, const void* k_new, c
     a->shared = cfg->score_mode == KF_SCORE_SHARED ? 1 : 0;
     a->seq_q_pos = cfg->seq_q_pos;
     a->seq_tau = cfg->seq_tau;
+    a->fuse_k = 0;
+    a->fuse_w = 0;
+    a->fuse_idx = nullptr;
     a->step = nullptr;
     a->n0 = 0;
     a->T = 1;
@@ -416,7 +419,14 @@ static kf_status fused_step(kf_cache* c, const void* q, const void* k_new, const
     }
     const int64_t U = (int64_t)c->L * c->B * c->H;
     hipError_t e;
-    if (da.shared || da.G > 1) {  // shared score: the layers' increments are added up between the merge and
+    if (da.S == 1 && layout == KF_LAYOUT_SLOT && !da.shared) {
+        // one workgroup owns each unit and nothing orders the slots: the whole step is one launch
+        da.fuse_k = k;
+        da.fuse_w = w;
+        da.fuse_idx = kept_idx;
+        e = kf::launch_decode(da, U, c->d, c->dtype, p.lds_bytes, (hipStream_t)stream);
+        if (e == hipSuccess && sched) e = kf::launch_advance_step(step, (hipStream_t)stream);
+    } else if (da.shared || da.G > 1) {  // shared score: the layers' increments are added up between the merge and
                                   // the selection; the merge folded into the selection serves one query head
         e = kf::launch_decode(da, U, c->d, c->dtype, p.lds_bytes, (hipStream_t)stream);
         if (e == hipSuccess && da.shared) e = share_after_decode(c, da, (hipStream_t)stream);

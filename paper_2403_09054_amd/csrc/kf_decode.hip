@@ -167,6 +167,9 @@ __global__ void __launch_bounds__(NT) decode_kernel(const DecodeArgs a) {
     float* red_o = ys + G * CS;        // [NW][G*D] per-wave output partials
     __shared__ float red_s[2 * G * NW];
     __shared__ float stat[4 * G];      // per query head: max x, sum p, max y, sum e
+    __shared__ unsigned long long evict_min[NW];  // whole-step launch: per-wave smallest (score, position) pack
+    __shared__ int evict_slot;
+    __shared__ float new_score;
 
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int sub = lane / LPR, cl = lane % LPR;
@@ -196,6 +199,9 @@ __global__ void __launch_bounds__(NT) decode_kernel(const DecodeArgs a) {
             if (tid == 0) {
                 atomicAdd(a.ws_err, 1);
                 if (a.shared) a.ws_m[u] = 0;
+                // whole-step launch: the selection would have refused this unit as well (slot layout,
+                // more than one token over budget) and reported it on its own
+                if (a.fuse_k > 0 && len0 > a.fuse_k + 1) atomicAdd(a.ws_err, 1);
             }
         }
         return;
@@ -217,8 +223,13 @@ __global__ void __launch_bounds__(NT) decode_kernel(const DecodeArgs a) {
     float* fu = a.score + (size_t)u * a.cap;
     int32_t* pu = a.pos + (size_t)u * a.cap;
 
+    // Whole-step launch (S == 1): a unit exactly one token over its budget evicts in this launch, and the
+    // new token then goes straight into the freed slot instead of being appended first.
+    const bool over = a.fuse_k > 0 && m > a.fuse_k;
+    const bool evict_here = over && m == a.fuse_k + 1;
+
     // ---- append: the last split stores the new row (nobody reads it back in this launch)
-    if (owner) {
+    if (owner && !evict_here) {
         if (wv == 0 && lane < LPR) ((uint4*)(a.K))[((size_t)u * a.cap + len0) * LPR + lane] = ((const uint4*)knew)[lane];
         if (wv == 1 && lane < LPR) ((uint4*)(a.V))[((size_t)u * a.cap + len0) * LPR + lane] = ((const uint4*)vnew)[lane];
         if (tid == 2 * kWave) pu[len0] = q_pos;
@@ -489,11 +500,35 @@ __global__ void __launch_bounds__(NT) decode_kernel(const DecodeArgs a) {
 #pragma unroll
         for (int g = 0; g < G; ++g) inv[g] = 1.0f / spe[2 * g + 1];
         float* we = a.ws_e + (size_t)u * G * a.cap;
+        // whole-step launch: this lane's smallest candidate, as (order-preserving score key, ~position):
+        // the lowest score leaves, the highest position among equal scores (lower positions are kept)
+        unsigned long long best = ~0ull;
+        int best_slot = -1;
         for (int t = tid; t < cnt; t += NT) {
             const int slot = (t == cnt_c) ? len0 : j0 + t;
             float df = 0.0f;
 #pragma unroll
             for (int g = 0; g < G; ++g) df = fmaf(ys[g * CS + t], inv[g], df);
+            if (evict_here) {
+                // the scores are needed at once: read, add, keep the sum for the selection
+                float f_new = df;
+                int pj = q_pos;
+                if (t == cnt_c) {
+                    new_score = df;
+                } else {
+                    f_new = fu[slot] + df;
+                    fu[slot] = f_new;
+                    pj = pu[slot];
+                }
+                if (pj <= q_pos - a.fuse_w) {  // outside the recent window: a candidate
+                    const unsigned long long pack = ((unsigned long long)float_key(f_new) << 32) | (uint32_t)(~(uint32_t)pj);
+                    if (pack < best) {
+                        best = pack;
+                        best_slot = slot;
+                    }
+                }
+                continue;
+            }
             // existing scores take the increment as a fire-and-forget atomic add at the L2: no load,
             // no round trip (one add per address and launch, so the result is the plain fp32 sum)
             if (a.shared) we[slot] = df;  // summed over the layers by the launch that follows
@@ -506,10 +541,62 @@ __global__ void __launch_bounds__(NT) decode_kernel(const DecodeArgs a) {
             for (int w2 = 0; w2 < NW; ++w2) o_c += red_o[w2 * G * D + c];
             a.out[u * G * D + c] = o_c / stat[4 * (c / D) + 1];
         }
-        if (tid == 0) {
-            a.len[u] = m;
-            if (a.shared) a.ws_m[u] = m;
+        if (!evict_here) {
+            if (tid == 0) {
+                a.len[u] = m;
+                if (a.shared) a.ws_m[u] = m;
+                if (over) atomicAdd(a.ws_err, 1);  // more than one token over budget: appended, not evicted, reported
+            }
+            if (a.fuse_idx && !over) {  // within budget: untouched, identity then -1 padding
+                int32_t* idx = a.fuse_idx + (size_t)u * a.fuse_k;
+                for (int i = tid; i < a.fuse_k; i += NT) idx[i] = i < m ? i : -1;
+            }
+            return;
         }
+        // ---- eviction by this workgroup (slot layout): the candidate with the smallest score leaves
+        const unsigned long long mine = best;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            const unsigned long long t2 = __shfl_xor(best, o, kWave);
+            best = t2 < best ? t2 : best;
+        }
+        if (lane == 0) evict_min[wv] = best;
+        if (tid == 0) evict_slot = -1;
+        __syncthreads();  // also orders the score stores above before the one into the freed slot
+        unsigned long long gbest = evict_min[0];
+#pragma unroll
+        for (int i = 1; i < NW; ++i) gbest = evict_min[i] < gbest ? evict_min[i] : gbest;
+        // positions are unique, so exactly one lane's own candidate carries the winning pack
+        if (gbest != ~0ull && mine == gbest) evict_slot = best_slot;
+        __syncthreads();
+        const int e = evict_slot;
+        const int k = a.fuse_k;
+        if (e < 0) {
+            // nothing lies outside the window (positions not consecutive at the recent end): append after
+            // all, leave the unit one over budget and report it, as the selection launch would
+            if (wv == 0 && lane < LPR) ((uint4*)(a.K))[((size_t)u * a.cap + len0) * LPR + lane] = ((const uint4*)knew)[lane];
+            if (wv == 1 && lane < LPR) ((uint4*)(a.V))[((size_t)u * a.cap + len0) * LPR + lane] = ((const uint4*)vnew)[lane];
+            if (tid == 2 * kWave) {
+                pu[len0] = q_pos;
+                fu[len0] = new_score;
+                a.len[u] = m;
+                atomicAdd(a.ws_err, 1);
+            }
+            return;
+        }
+        if (e != len0) {  // e == len0: the new token itself leaves (only without a recent window)
+            if (wv == 0 && lane < LPR) ((uint4*)(a.K))[((size_t)u * a.cap + e) * LPR + lane] = ((const uint4*)knew)[lane];
+            if (wv == 1 && lane < LPR) ((uint4*)(a.V))[((size_t)u * a.cap + e) * LPR + lane] = ((const uint4*)vnew)[lane];
+            if (tid == 2 * kWave) {
+                pu[e] = q_pos;
+                fu[e] = new_score;
+            }
+        }
+        if (a.fuse_idx) {  // survivors by pre-compaction slot: the new token counts as slot k
+            int32_t* idx = a.fuse_idx + (size_t)u * k;
+            for (int i = tid; i < k; i += NT) idx[i] = (i == e) ? k : i;
+        }
+        if (tid == 0) a.len[u] = k;
         return;
     }
     // ---- S > 1: leave the un-normalised increments and a partial record per query head for the merge
@@ -570,6 +657,14 @@ __global__ void __launch_bounds__(kShareThreads) share_kernel(const ShareArgs a)
         float* f = a.score + l * stride + at;
         *f = fresh ? s : *f + s;
     }
+}
+
+__global__ void advance_step_kernel(int32_t* step) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) *step += 1;
+}
+hipError_t launch_advance_step(int32_t* step, hipStream_t stream) {
+    hipLaunchKernelGGL(advance_step_kernel, dim3(1), dim3(kWave), 0, stream, step);
+    return hipGetLastError();
 }
 
 hipError_t launch_share(const ShareArgs& a, hipStream_t stream) {

@@ -41,6 +41,10 @@ struct DecodeArgs {
     // Per-sequence query position / temperature (either may be NULL): [B], override the above.
     const int32_t* seq_q_pos;
     const float* seq_tau;
+    // Whole step in this launch (single split, slot layout): after the scores are updated the workgroup
+    // evicts for its unit and stores the new token straight into the freed slot.  fuse_k = 0: off.
+    int32_t fuse_k, fuse_w;
+    int32_t* fuse_idx;  // NULL, or [U][k] survivor list as the selection kernel writes it
     float inv_tau;
     float scale;
 };
@@ -66,6 +70,8 @@ struct ShareArgs {
     int32_t inc_unit;   // floats between the increments of consecutive units (G*cap)
 };
 hipError_t launch_share(const ShareArgs& a, hipStream_t stream);
+// *step += 1 by a single lane: closes a step whose last launch also reads the counter
+hipError_t launch_advance_step(int32_t* step, hipStream_t stream);
 
 // ------------------------------------------------------------------ select
 struct SelectArgs {
