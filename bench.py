@@ -394,7 +394,7 @@ def main():
                "host_cpus": os.cpu_count()}
 
     line = {
-        "metric": "decode steps/s (fused attn+score+evict) at %d%% KV budget" % round(100 * wl.k / wl.n),
+        "metric": "decode steps/s + achieved HBM GB/s (fused attn+score+evict) at %d%% KV budget" % round(100 * wl.k / wl.n),
         "value": round(value, 2), "unit": "steps/s", "n_gpus": 1, "steps": K_steps, "warmup": W_steps,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
