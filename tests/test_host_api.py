@@ -208,3 +208,13 @@ def test_launches_beyond_the_grid_limit_are_refused():
            0x4000, None, 0x5000, (0x100000, 1 << 62), 0)
     expect(binding.KF_EUNSUPPORTED, kf.kf_prefill_score, huge, 0x1000, 1 << 20, 1.0, 0.1, kf.NOISE_GUMBEL, 0x4000, None,
            (0x100000, 1 << 62), 0)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0 and "ONE GPU" in r.stderr and r.stdout.strip() == ""

@@ -700,3 +700,38 @@ def test_tiny_config_end_to_end_invariants():
         assert (np.diff(pos, axis=-1) > 0).all()
         assert (pos[..., wl.k - wl.w:] == np.arange(q_pos - wl.w + 1, q_pos + 1)).all()   # w most recent
         total = c.score[..., :wl.k].astype(np.float64).sum()
+
+
+# ----------------------------------------------------------------------------
+# Property test: the selection against numpy's stable sort on random shapes with ties
+# ----------------------------------------------------------------------------
+def test_select_random_shapes_against_stable_sort():
+    from hypothesis import given, settings, strategies as st
+
+    @settings(max_examples=150, deadline=None)
+    @given(st.integers(1, 40), st.integers(0, 40), st.integers(0, 40), st.integers(0, 2 ** 31 - 1), st.integers(1, 6))
+    def check(n, k_raw, w_raw, seed, levels):
+        k = max(1, min(k_raw, n + 3))
+        w = min(w_raw, k)
+        rng = np.random.default_rng(seed)
+        c = make_cache(rng, 1, 1, 1, 4, n + 4, n)
+        f = rng.integers(0, levels, n).astype(np.float32) * 0.5 - 1.0     # few distinct values: many ties, negatives
+        c.score[0, 0, 0, :n] = f
+        c.pos[0, 0, 0, :n] = np.cumsum(rng.integers(1, 4, n))
+        before = c.copy()
+        kept = c.select_evict(k, w)[0, 0, 0]
+        if n <= k:
+            assert c.len[0, 0, 0] == n and (kept[:n] == np.arange(n)).all() and (kept[n:] == -1).all()
+            return
+        wn = min(w, n)
+        cand = n - wn
+        # (k-w) largest of the candidates; among equal scores the lower slot: a stable sort of -f does exactly that
+        order = np.argsort(-f[:cand], kind="stable")[: k - wn]
+        want = np.sort(np.concatenate([order, np.arange(cand, n)])).astype(np.int32)
+        np.testing.assert_array_equal(kept, want)
+        assert c.len[0, 0, 0] == k
+        np.testing.assert_array_equal(c.pos[0, 0, 0, :k], before.pos[0, 0, 0, want])
+        np.testing.assert_array_equal(c.score[0, 0, 0, :k], before.score[0, 0, 0, want])
+        np.testing.assert_array_equal(c.K[0, 0, 0, :k], before.K[0, 0, 0, want])
+
+    check()
