@@ -159,6 +159,31 @@ def test_select_evict_matches_oracle(dtype, d, n, k, w):
     assert_state_equal(gc2, oc)
 
 
+@pytest.mark.parametrize("seed", range(6))
+def test_select_random_ragged_units(seed):
+    """Units of every length in one call (empty, under budget, one over, far over, full), random budget and
+    window, scores with many exact ties: survivor lists and compacted state bit-exact against the oracle."""
+    rng = np.random.default_rng(400 + seed)
+    d, dtype = [(64, ko.BF16), (128, ko.F32), (256, ko.BF16), (128, ko.BF16), (64, ko.F32), (256, ko.BF16)][seed]
+    cap = int(rng.integers(40, 700))
+    k = int(rng.integers(1, cap + 1))
+    w = int(rng.integers(0, k + 1))
+    L, B, H = 2, 3, 4
+    lens = rng.integers(0, cap + 1, (L, B, H)).astype(np.int32)
+    lens.flat[:5] = [0, min(cap, k + 1), cap, k, max(0, k - 1)]
+    oc = random_cache(rng, L, B, H, d, cap, dtype, lens)
+    oc.score[...] = rng.integers(0, 7, oc.score.shape).astype(np.float32) * 0.25 - 0.5
+    gc = upload(oc)
+    ws = kf.new_workspace(gc)
+    kept = torch.full((L, B, H, k), -5, dtype=torch.int32, device="cuda")
+    kept_ref = oc.select_evict(k, w)
+    kf.kf_select_evict(gc, k, w, kept, ws)
+    torch.cuda.synchronize()
+    assert error_word(ws) == 0
+    np.testing.assert_array_equal(host(kept), kept_ref)
+    assert_state_equal(gc, oc)
+
+
 def test_select_adversarial_eviction_slots():
     # decode shape, evicted slot at the very front, at the last candidate, and mid-way
     rng = np.random.default_rng(3)
