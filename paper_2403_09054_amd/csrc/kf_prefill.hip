@@ -87,21 +87,65 @@ __device__ __forceinline__ float logit2_other(const LogitParams& lp, float acc, 
     return fmaf(acc, lp.sc1, fmaf(dist, -lp.slope1, zeta_log2e(lp.noise, rkey, k_pos) * lp.inv_tau));
 }
 
+// ------------------------------------------------------------------ streamed tiles through LDS
+// The four waves of a workgroup work on four 32-row groups of the SAME 128-row
+// block and walk the same sequence of 32-row tiles of the other operand.  That
+// tile is fetched once per workgroup (each thread a few 16-byte pieces, fully
+// coalesced), parked in LDS and read from there as MFMA operands -- a quarter of
+// the L2 traffic and D/4 fewer registers per lane than every wave loading its
+// own copy, which is what lets more than two waves per SIMD overlap the MFMAs
+// of one with the transcendental epilogue of another.  Two buffers; one
+// barrier per tile.  Rows are padded by 16 bytes so that the 32 rows a wave
+// reads in one instruction spread over the banks.
+template <typename T, int D>
+struct TileStage {
+    static constexpr int kRowBytes = D * (int)sizeof(T);
+    static constexpr int kPitch = kRowBytes + 16;                 // bytes between rows in LDS
+    static constexpr int kPieces = kTile * kRowBytes / 16;        // 16-byte pieces of a tile
+    static constexpr int NP = kPieces / kPrefillThreads;          // pieces per thread (1, 2 or 4)
+    static constexpr int PPR = kRowBytes / 16;                    // pieces per row
+    static constexpr int kBufBytes = kTile * kPitch;
+    static_assert(kPieces % kPrefillThreads == 0, "a tile is a whole number of pieces per thread");
+
+    // rows [row0, row0+32) of `rows` (clamped to n-1) -> registers
+    static __device__ __forceinline__ void fetch(const T* rows, int row0, int n, uint4 (&reg)[NP]) {
+#pragma unroll
+        for (int i = 0; i < NP; ++i) {
+            const int p = threadIdx.x + i * kPrefillThreads;
+            const int r = min(row0 + p / PPR, n - 1);
+            reg[i] = *(const uint4*)((const char*)rows + (size_t)r * kRowBytes + (p % PPR) * 16);
+        }
+    }
+    static __device__ __forceinline__ void park(char* buf, const uint4 (&reg)[NP]) {
+#pragma unroll
+        for (int i = 0; i < NP; ++i) {
+            const int p = threadIdx.x + i * kPrefillThreads;
+            *(uint4*)(buf + (p / PPR) * kPitch + (p % PPR) * 16) = reg[i];
+        }
+    }
+    // the 16 bytes lane (row n0, half) feeds MFMA group g
+    static __device__ __forceinline__ uint4 operand(const char* buf, int n0, int half, int g) {
+        return *(const uint4*)(buf + n0 * kPitch + (2 * g + half) * 16);
+    }
+};
+
 // ------------------------------------------------------------------ pass 1
 template <typename T, int D>
 __global__ void __launch_bounds__(kPrefillThreads) prefill_rowstats_kernel(const PrefillArgs a, int nblk, int64_t units) {
     constexpr int EPV = ElemTraits<T>::kPerVec;
     constexpr int NG = D / (2 * EPV);
+    using Stage = TileStage<T, D>;
+    __shared__ __attribute__((aligned(16))) char kbuf[2][Stage::kBufBytes];
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int n0 = lane & 31, half = lane >> 5;
     int64_t u;
     int blk;
     unit_and_block(nblk, u, blk);
-    if (u >= units) return;
+    if (u >= units) return;  // workgroup-uniform
     const int rb = nblk - 1 - blk;  // longest rows first
     const int n = a.n;
     const int i0 = rb * (4 * kTile) + wv * kTile;
-    if (i0 >= n) return;  // wave-uniform; this kernel has no workgroup barrier
+    const bool active = i0 < n;  // wave-uniform; inactive waves still fetch tiles and meet the barriers
     const int h = (int)(u % a.H), b = (int)((u / a.H) % a.B), l = a.layer0 + (int)(u / ((int64_t)a.H * a.B));
     const int i = i0 + n0;
     const T* Qu = (const T*)a.Q + (size_t)u * n * D;
@@ -127,61 +171,63 @@ __global__ void __launch_bounds__(kPrefillThreads) prefill_rowstats_kernel(const
     const uint32_t kmul_lane = (uint32_t)(half * 4) * kKposMul;
 
     float M = -INFINITY, Ssum = 0.0f;
-    const int jt_end = min(i0 + kTile - 1, n - 1) / kTile;
-    uint4 ak[NG];
-    {
-        const T* row = Ku + (size_t)min(n0, n - 1) * D + half * EPV;
+    const int jt_end = min(i0 + kTile - 1, n - 1) / kTile;                      // this wave's last key tile
+    const int jt_last = min(rb * (4 * kTile) + 4 * kTile - 1, n - 1) / kTile;   // the workgroup's
+    uint4 stage[Stage::NP];
+    Stage::fetch(Ku, 0, n, stage);
+    Stage::park(kbuf[0], stage);
+    __syncthreads();
+    for (int jt = 0; jt <= jt_last; ++jt) {
+        // the next tile (the last one again at the end: rows stay in range), in flight during this tile's work
+        Stage::fetch(Ku, min(jt + 1, jt_last) * kTile, n, stage);
+        if (active && jt <= jt_end) {
+            const char* kb = kbuf[jt & 1];
+            f32x16 acc;
 #pragma unroll
-        for (int g = 0; g < NG; ++g) ak[g] = *(const uint4*)(row + g * 2 * EPV);
+            for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+#pragma unroll
+            for (int g = 0; g < NG; ++g) acc = Mma<T>::group(Stage::operand(kb, n0, half, g), bq[g], acc);
+            const int jb = jt * kTile;
+            const int jl = jb + half * 4;                       // first key of this lane in the tile
+            const uint32_t kmul = (uint32_t)jb * kKposMul + kmul_lane;
+            const float dist0 = (float)(i - jl);
+            float y2[16];
+            if (a.noise == kNoiseGumbel) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int ro = (r >> 2) * 8 + (r & 3);
+                    y2[r] = logit2_gumbel(lp, acc[r], dist0 - (float)ro, rkey ^ (kmul + (uint32_t)ro * kKposMul));
+                }
+            } else {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int ro = (r >> 2) * 8 + (r & 3);
+                    y2[r] = logit2_other(lp, acc[r], dist0 - (float)ro, rkey, (uint32_t)(jl + ro));
+                }
+            }
+            if (jb + kTile - 1 > i0) {  // the tile crosses the diagonal for some lane: causal mask
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int ro = (r >> 2) * 8 + (r & 3);
+                    y2[r] = (jl + ro <= i) ? y2[r] : -INFINITY;
+                }
+            }
+            float tmax = y2[0];
+#pragma unroll
+            for (int r = 1; r < 16; ++r) tmax = fmaxf(tmax, y2[r]);
+            const float Mn = fmaxf(M, tmax);
+            if (Mn > -INFINITY) {
+                float ssum = 0.0f;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) ssum += hw_exp2(y2[r] - Mn);
+                Ssum = Ssum * hw_exp2(M - Mn) + ssum;
+                M = Mn;
+            }
+        }
+        if (jt < jt_last) Stage::park(kbuf[(jt + 1) & 1], stage);
+        __syncthreads();
     }
-    for (int jt = 0; jt <= jt_end; ++jt) {
-        f32x16 acc;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
-#pragma unroll
-        for (int g = 0; g < NG; ++g) acc = Mma<T>::group(ak[g], bq[g], acc);
-        if (jt < jt_end) {  // next key tile's rows, in flight during the epilogue
-            const T* row = Ku + (size_t)min((jt + 1) * kTile + n0, n - 1) * D + half * EPV;
-#pragma unroll
-            for (int g = 0; g < NG; ++g) ak[g] = *(const uint4*)(row + g * 2 * EPV);
-        }
-        const int jb = jt * kTile;
-        const int jl = jb + half * 4;                       // first key of this lane in the tile
-        const uint32_t kmul = (uint32_t)jb * kKposMul + kmul_lane;
-        const float dist0 = (float)(i - jl);
-        float y2[16];
-        if (a.noise == kNoiseGumbel) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int ro = (r >> 2) * 8 + (r & 3);
-                y2[r] = logit2_gumbel(lp, acc[r], dist0 - (float)ro, rkey ^ (kmul + (uint32_t)ro * kKposMul));
-            }
-        } else {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int ro = (r >> 2) * 8 + (r & 3);
-                y2[r] = logit2_other(lp, acc[r], dist0 - (float)ro, rkey, (uint32_t)(jl + ro));
-            }
-        }
-        if (jb + kTile - 1 > i0) {  // the tile crosses the diagonal for some lane: causal mask
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int ro = (r >> 2) * 8 + (r & 3);
-                y2[r] = (jl + ro <= i) ? y2[r] : -INFINITY;
-            }
-        }
-        float tmax = y2[0];
-#pragma unroll
-        for (int r = 1; r < 16; ++r) tmax = fmaxf(tmax, y2[r]);
-        const float Mn = fmaxf(M, tmax);
-        if (Mn > -INFINITY) {
-            float ssum = 0.0f;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) ssum += hw_exp2(y2[r] - Mn);
-            Ssum = Ssum * hw_exp2(M - Mn) + ssum;
-            M = Mn;
-        }
-    }
+    if (!active) return;
     // the two halves of the wave hold disjoint key subsets of the same query
     const float M2 = __shfl_xor(M, 32, kWave), S2 = __shfl_xor(Ssum, 32, kWave);
     const float Mt = fmaxf(M, M2);
@@ -197,17 +243,21 @@ template <typename T, int D>
 __global__ void __launch_bounds__(kPrefillThreads) prefill_colsum_kernel(const PrefillArgs a, int nblk, int64_t units) {
     constexpr int EPV = ElemTraits<T>::kPerVec;
     constexpr int NG = D / (2 * EPV);
+    using Stage = TileStage<T, D>;
+    __shared__ __attribute__((aligned(16))) char qbuf[2][Stage::kBufBytes];
+    __shared__ __attribute__((aligned(16))) float cbuf[2][kTile];     // the tile's row normalisers ...
+    __shared__ __attribute__((aligned(16))) uint32_t rbuf[2][kTile];  // ... and row noise keys
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int n0 = lane & 31, half = lane >> 5;
     int64_t u;
     int cb;  // longest columns (lowest keys) first
     unit_and_block(nblk, u, cb);
-    if (u >= units) return;
+    if (u >= units) return;  // workgroup-uniform
     const int n = a.n;
     const int j0 = cb * (4 * kTile) + wv * kTile;
     const bool first_of_group = (u % a.G) == 0;
     if (cb == 0 && threadIdx.x == 0 && first_of_group) a.len[u / a.G] = n;
-    if (j0 >= n) return;  // wave-uniform; no workgroup barrier in this kernel
+    const bool active = j0 < n;  // wave-uniform; inactive waves still fetch tiles and meet the barriers
     const int h = (int)(u % a.H);
     const int j = j0 + n0;
     const T* Qu = (const T*)a.Q + (size_t)u * n * D;
@@ -231,64 +281,77 @@ __global__ void __launch_bounds__(kPrefillThreads) prefill_colsum_kernel(const P
     const uint32_t* wr = a.ws_r + (size_t)u * a.n_pad;
 
     float colsum = 0.0f;
-    const int it_begin = j0 / kTile, it_end = (n - 1) / kTile;
-    uint4 aq[NG];
-    {
-        const T* row = Qu + (size_t)min(it_begin * kTile + n0, n - 1) * D + half * EPV;
-#pragma unroll
-        for (int g = 0; g < NG; ++g) aq[g] = *(const uint4*)(row + g * 2 * EPV);
-    }
-    // row statistics (normaliser, noise key) of the tile's 16 rows this lane sees: fetched one tile ahead
-    float4 c4[4];
-    uint4 r4[4];
-    auto load_stats = [&](int ib) {
-#pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-            const int ir = ib + q4 * 8 + half * 4;  // 4 consecutive query rows, 16-byte aligned
-            c4[q4] = *(const float4*)(wc + ir);
-            r4[q4] = *(const uint4*)(wr + ir);
+    const int it_begin = j0 / kTile;                    // this wave's first query tile (the diagonal one)
+    const int it_first = cb * 4, it_end = (n - 1) / kTile;  // the workgroup's range of query tiles
+    // a tile's 32 row statistics ride with the tile: one wave fetches them (n_pad covers whole tiles)
+    uint4 stage[Stage::NP];
+    float c_st = 0.0f;
+    uint32_t r_st = 0u;
+    auto fetch_stats = [&](int it) {
+        if (threadIdx.x < kTile) {
+            c_st = wc[it * kTile + threadIdx.x];
+            r_st = wr[it * kTile + threadIdx.x];
         }
     };
-    load_stats(it_begin * kTile);
-    for (int it = it_begin; it <= it_end; ++it) {
-        f32x16 acc;
+    auto park_stats = [&](int buf) {
+        if (threadIdx.x < kTile) {
+            cbuf[buf][threadIdx.x] = c_st;
+            rbuf[buf][threadIdx.x] = r_st;
+        }
+    };
+    Stage::fetch(Qu, it_first * kTile, n, stage);
+    fetch_stats(it_first);
+    Stage::park(qbuf[0], stage);
+    park_stats(0);
+    __syncthreads();
+    for (int it = it_first; it <= it_end; ++it) {
+        const int cur = (it - it_first) & 1;
+        // the next tile (the last one again at the end: rows stay in range), in flight during this tile's work
+        Stage::fetch(Qu, min(it + 1, it_end) * kTile, n, stage);
+        fetch_stats(min(it + 1, it_end));
+        if (active && it >= it_begin) {
+            const char* qb = qbuf[cur];
+            f32x16 acc;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+            for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
 #pragma unroll
-        for (int g = 0; g < NG; ++g) acc = Mma<T>::group(aq[g], bk[g], acc);
+            for (int g = 0; g < NG; ++g) acc = Mma<T>::group(Stage::operand(qb, n0, half, g), bk[g], acc);
+            const int ib = it * kTile;
+            const bool edge = (ib < j0 + kTile) || (ib + kTile > n);  // crosses the diagonal or the end of the prompt
+            float z[16];
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const int ir = ib + q4 * 8 + half * 4;  // 4 consecutive query rows
+                const float4 c4 = *(const float4*)&cbuf[cur][q4 * 8 + half * 4];
+                const uint4 r4 = *(const uint4*)&rbuf[cur][q4 * 8 + half * 4];
+                const float cs[4] = {c4.x, c4.y, c4.z, c4.w};
+                const uint32_t rs[4] = {r4.x, r4.y, r4.z, r4.w};
+                const float dist0 = (float)(ir - j);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float y = (a.noise == kNoiseGumbel)
+                                        ? logit2_gumbel(lp, acc[q4 * 4 + e], dist0 + (float)e, rs[e] ^ kmul)
+                                        : logit2_other(lp, acc[q4 * 4 + e], dist0 + (float)e, rs[e], (uint32_t)j);
+                    z[q4 * 4 + e] = hw_exp2(y - cs[e]);
+                }
+            }
+            if (edge) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int i = ib + (r >> 2) * 8 + half * 4 + (r & 3);
+                    z[r] = (i >= j && i < n) ? z[r] : 0.0f;
+                }
+            }
+#pragma unroll
+            for (int r = 0; r < 16; ++r) colsum += z[r];
+        }
         if (it < it_end) {
-            const T* row = Qu + (size_t)min((it + 1) * kTile + n0, n - 1) * D + half * EPV;
-#pragma unroll
-            for (int g = 0; g < NG; ++g) aq[g] = *(const uint4*)(row + g * 2 * EPV);
+            Stage::park(qbuf[cur ^ 1], stage);
+            park_stats(cur ^ 1);
         }
-        const int ib = it * kTile;
-        const bool edge = (ib < j0 + kTile) || (ib + kTile > n);  // crosses the diagonal or the end of the prompt
-        float z[16];
-#pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-            const int ir = ib + q4 * 8 + half * 4;
-            const float cs[4] = {c4[q4].x, c4[q4].y, c4[q4].z, c4[q4].w};
-            const uint32_t rs[4] = {r4[q4].x, r4[q4].y, r4[q4].z, r4[q4].w};
-            const float dist0 = (float)(ir - j);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const float y = (a.noise == kNoiseGumbel)
-                                    ? logit2_gumbel(lp, acc[q4 * 4 + e], dist0 + (float)e, rs[e] ^ kmul)
-                                    : logit2_other(lp, acc[q4 * 4 + e], dist0 + (float)e, rs[e], (uint32_t)j);
-                z[q4 * 4 + e] = hw_exp2(y - cs[e]);
-            }
-        }
-        if (it < it_end) load_stats(ib + kTile);  // in flight during the next tile's MFMAs
-        if (edge) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int i = ib + (r >> 2) * 8 + half * 4 + (r & 3);
-                z[r] = (i >= j && i < n) ? z[r] : 0.0f;
-            }
-        }
-#pragma unroll
-        for (int r = 0; r < 16; ++r) colsum += z[r];
+        __syncthreads();
     }
+    if (!active) return;
     colsum += __shfl_xor(colsum, 32, kWave);
     if (half == 0 && j < n) {
         // one query head per cached head: the column sum is the score; else the heads' sums are
