@@ -198,7 +198,7 @@ __global__ void __launch_bounds__(NT) decode_kernel(const DecodeArgs a) {
             for (int c = tid; c < G * D; c += NT) a.out[u * G * D + c] = 0.0f;
             if (tid == 0) {
                 atomicAdd(a.ws_err, 1);
-                if (a.shared) a.ws_m[u] = 0;
+                a.ws_m[u] = 0;  // tokens scored in this unit by this launch: none
                 // whole-step launch: the selection would have refused this unit as well (slot layout,
                 // more than one token over budget) and reported it on its own
                 if (a.fuse_k > 0 && len0 > a.fuse_k + 1) atomicAdd(a.ws_err, 1);
@@ -608,6 +608,7 @@ __global__ void __launch_bounds__(NT) decode_kernel(const DecodeArgs a) {
             for (int g = 0; g < G; ++g) we[(size_t)g * a.cap + slot] = ys[g * CS + t];
         }
     }
+    if (owner && tid == 0) a.ws_m[u] = m;  // tokens scored in this unit: the merge reads the length from here
     float* part = a.ws_part + ((size_t)u * S + s) * G * PW;
     for (int c = tid; c < G * D; c += NT) {
         float o_c = 0.0f;
@@ -618,15 +619,19 @@ __global__ void __launch_bounds__(NT) decode_kernel(const DecodeArgs a) {
     if (tid < 4 * G) part[(tid >> 2) * PW + D + (tid & 3)] = stat[tid];
 }
 
-// Merge kernel: one workgroup per unit, launched after the split kernel.
+// Merge kernel, launched after the split kernel: gridDim.y workgroups per unit share the token range of
+// the score update (each re-derives the few per-split weights); the first also writes the outputs.  The
+// unit's token count comes from the split kernel's record, not from len, which the first workgroup updates.
 template <int D, int NT, int G>
 __global__ void __launch_bounds__(NT) decode_merge_kernel(const DecodeArgs a) {
     __shared__ float red_s[NT / kWave];
     __shared__ float w_p[G * kDecodeMaxSplits], w_e[G * kDecodeMaxSplits];
     const int64_t u = blockIdx.x;
-    const int len0 = a.len[u];
-    if (len0 < 0 || len0 >= a.cap || len0 > a.S * a.chunk) return;  // skipped by the split kernel too
-    merge_unit<D, NT, G>(a, u, len0, red_s, w_p, w_e);
+    const int m = a.ws_m[u];
+    if (m <= 0) return;  // skipped by the split kernel
+    const int per = ((m + (int)gridDim.y - 1) / (int)gridDim.y + NT - 1) / NT * NT;
+    const int j_begin = (int)blockIdx.y * per;
+    merge_unit<D, NT, G>(a, u, m - 1, red_s, w_p, w_e, j_begin, j_begin + per, blockIdx.y == 0);
 }
 
 // Shared score function (the paper's ablation of one score for all layers,
@@ -758,7 +763,12 @@ static hipError_t launch_decode_g(const DecodeArgs& a, int64_t U, size_t lds, hi
     hipLaunchKernelGGL((decode_kernel<T, D, kDecodeThreads, G>), grid, block, lds, st, a);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess && a.S > 1 && merge) {
-        hipLaunchKernelGGL((decode_merge_kernel<D, kDecodeThreads, G>), dim3((unsigned)U), block, 0, st, a);
+        // enough workgroups per unit that each walks at most ~8 strides of the token range, and the chip is filled
+        const int64_t tokens = (int64_t)a.S * a.chunk;
+        int64_t slices = (tokens + 8 * kDecodeThreads - 1) / (8 * kDecodeThreads);
+        if (slices > 16) slices = 16;
+        if (slices < 1) slices = 1;
+        hipLaunchKernelGGL((decode_merge_kernel<D, kDecodeThreads, G>), dim3((unsigned)U, (unsigned)slices), block, 0, st, a);
         e = hipGetLastError();
     }
     return e;

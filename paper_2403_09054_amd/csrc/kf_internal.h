@@ -24,7 +24,7 @@ struct DecodeArgs {
     float* ws_part;    // [U][S][G][D+4] partial outputs and softmax statistics of each split and query head
     float* ws_e;       // [U][G][cap]    un-normalised score increments of each token
     int32_t* ws_err;   // [1]         skipped-unit counter
-    int32_t* ws_m;     // [U]         shared score only: tokens this launch scored in each unit (0: skipped)
+    int32_t* ws_m;     // [U]         tokens this launch scored in each unit (0: skipped); written when split or shared
     int32_t B, H, cap, layer0;
     int32_t G;         // query heads per cached head (q and out hold H*G heads)
     int32_t S;         // splits of a unit's token range

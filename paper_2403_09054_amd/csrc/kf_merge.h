@@ -13,9 +13,11 @@ constexpr int kDecodeMaxSplits = 256;  // one thread per split in the merge: <= 
 // head-wide maxima, normalises, accumulates the scores (summed over the unit's
 // G query heads) and publishes the new length.  Called by a whole workgroup.
 // w_p, w_e: LDS, G*S floats each.
+// The workgroup handles tokens [j_begin, j_end) of the score update; the `lead`
+// workgroup of a unit also writes the attention outputs and the new length.
 template <int D, int NT, int G>
 __device__ __forceinline__ void merge_unit(const DecodeArgs& a, int64_t u, int len0, float* red_s, float* w_p,
-                                           float* w_e) {
+                                           float* w_e, int j_begin, int j_end, bool lead) {
     constexpr int PW = D + 4;
     const int tid = threadIdx.x, S = a.S, m = len0 + 1;
     const float* parts = a.ws_part + (size_t)u * S * G * PW;
@@ -43,7 +45,7 @@ __device__ __forceinline__ void merge_unit(const DecodeArgs& a, int64_t u, int l
             w_e[g * S + tid] = we_;
         }
         __syncthreads();
-        if (tid < D) {
+        if (lead && tid < D) {
             float o = 0.0f;
             for (int ss = 0; ss < S; ++ss) o = fmaf(w_p[g * S + ss], parts[((size_t)ss * G + g) * PW + tid], o);
             a.out[(u * G + g) * D + tid] = o / sumP;
@@ -51,7 +53,7 @@ __device__ __forceinline__ void merge_unit(const DecodeArgs& a, int64_t u, int l
         inv[g] = 1.0f / sumE;
     }
     float* we = a.ws_e + (size_t)u * G * a.cap;
-    for (int j = tid; j < m; j += NT) {
+    for (int j = j_begin + tid; j < min(j_end, m); j += NT) {
         const int split = (j == len0) ? S - 1 : j / a.chunk;  // the new token belongs to the last split
         float df = 0.0f;
 #pragma unroll
@@ -60,10 +62,7 @@ __device__ __forceinline__ void merge_unit(const DecodeArgs& a, int64_t u, int l
         else if (j == len0) fu[j] = df;
         else unsafeAtomicAdd(&fu[j], df);  // fire-and-forget add at the L2 (one per address: the plain fp32 sum)
     }
-    if (tid == 0) {
-        a.len[u] = m;
-        if (a.shared) a.ws_m[u] = m;
-    }
+    if (lead && tid == 0) a.len[u] = m;
 }
 
 }  // namespace kf

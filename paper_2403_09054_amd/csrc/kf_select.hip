@@ -492,7 +492,7 @@ __global__ void __launch_bounds__(NT) step_tail_kernel(const DecodeArgs d, const
     const int64_t u = blockIdx.x;
     const int len0 = d.len[u];
     if (len0 >= 0 && len0 < d.cap && len0 <= d.S * d.chunk) {  // else: skipped by the split kernel too
-        merge_unit<D, NT, 1>(d, u, len0, red_s, w_p, w_e);  // one query head per unit only
+        merge_unit<D, NT, 1>(d, u, len0, red_s, w_p, w_e, 0, len0 + 1, true);  // one query head per unit only
         __syncthreads();  // the merged scores and the new length are visible to the whole workgroup
     }
     select_unit<NT>(a, u);
