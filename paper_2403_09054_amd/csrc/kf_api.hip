@@ -23,6 +23,10 @@ kf_status fail(kf_status st, const char* fmt, ...) {
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 constexpr int64_t kMaxGrid = 0x7fffffff;  // workgroups of a one-dimensional launch
+// A fused step folds the merge of a split unit into the selection kernel (one workgroup per unit) only
+// while that workgroup walks the unit's tokens in a few strides; longer units take the merge launch,
+// which spreads a unit over several workgroups (32 heads x 9.8k tokens: 55.5 us folded, 52.6 us apart).
+constexpr int64_t kTailMergeMaxTokens = 4096;
 
 bool supported(int32_t dtype, int32_t d) {
     if (dtype == KF_BF16) return d == 64 || d == 128 || d == 256;
@@ -431,10 +435,10 @@ static kf_status fused_step(kf_cache* c, const void* q, const void* k_new, const
         e = kf::launch_decode(da, U, c->d, c->dtype, p.lds_bytes, (hipStream_t)stream);
         if (e == hipSuccess && da.shared) e = share_after_decode(c, da, (hipStream_t)stream);
         if (e == hipSuccess) e = kf::launch_select(sa, U, (hipStream_t)stream);
-    } else if (da.S > 1) {
+    } else if (da.S > 1 && (int64_t)da.S * da.chunk <= kTailMergeMaxTokens) {
         e = kf::launch_decode_split(da, U, c->d, c->dtype, p.lds_bytes, (hipStream_t)stream);
         if (e == hipSuccess) e = kf::launch_step_tail(da, sa, U, c->d, (hipStream_t)stream);
-    } else {  // the decode kernel finishes each unit itself: nothing to merge
+    } else {  // one workgroup per unit (nothing to merge), or units too long to merge inside the selection
         e = kf::launch_decode(da, U, c->d, c->dtype, p.lds_bytes, (hipStream_t)stream);
         if (e == hipSuccess) e = kf::launch_select(sa, U, (hipStream_t)stream);
     }
