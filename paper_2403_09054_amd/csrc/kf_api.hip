@@ -27,6 +27,7 @@ constexpr int64_t kMaxGrid = 0x7fffffff;  // workgroups of a one-dimensional lau
 // while that workgroup walks the unit's tokens in a few strides; longer units take the merge launch,
 // which spreads a unit over several workgroups (32 heads x 9.8k tokens: 55.5 us folded, 52.6 us apart).
 constexpr int64_t kTailMergeMaxTokens = 4096;
+constexpr int64_t kWideMaxUnits = 256;
 
 bool supported(int32_t dtype, int32_t d) {
     if (dtype == KF_BF16) return d == 64 || d == 128 || d == 256;
@@ -81,8 +82,13 @@ kf_status check_cfg(const kf_score_cfg* cfg) {
 //                         (G > 1) per-query-head column sums U*G*n_pad floats
 //              (G = query heads per cached head)
 struct WsLayout {
-    size_t region, fused_idx, total;
+    size_t region, fused_idx, wide, total;  // wide: boundary entries of the two-launch ordered eviction
+    int32_t nb;                             // boundary slots per unit
 };
+
+// Bytes of the wide eviction's scratch: evicted slot per unit, then per unit and boundary the K and V rows,
+// then the scores, then the positions (each part 256-byte aligned).
+size_t wide_part(size_t bytes) { return align_up(bytes, 256); }
 
 size_t decode_region(int64_t U, const kf_cache* c) {
     const int32_t G = group_of(c);
@@ -105,9 +111,19 @@ WsLayout ws_layout(const kf_cache* c, int32_t n_max) {
         const size_t pre = (G > 1 ? 3 : 2) * align_up((size_t)U * G * n_pad * sizeof(float), 256);
         if (pre > x) x = pre;
     }
-    w.total = w.region + x;
+    w.wide = w.region + x;
+    const int32_t row_bytes = c->d * (c->dtype == KF_F32 ? 4 : 2);
+    w.nb = c->cap / kf::wide_chunk_rows(row_bytes);
+    w.total = w.wide + wide_part((size_t)U * 4) + wide_part((size_t)U * w.nb * 2 * row_bytes) +
+              2 * wide_part((size_t)U * w.nb * 4);
     return w;
 }
+
+// Whether the two-launch ordered eviction is the faster one for U units of budget k.
+// Measured (MI355X): 32 units x 32k tokens 770 -> 240 us per step, 32 x 9.8k 237 -> 88, 16 x 1k 53 -> 29,
+// 256 x 2k 129 -> 125; from a few hundred units on one workgroup per unit moves the rows at the chip's copy
+// rate by itself (448 x 1k: 49 vs 53 us, 8192 x 2k: 1229 vs 1324 us).
+bool wide_pays(int64_t U, int32_t k) { return U <= kWideMaxUnits && k >= 64; }
 
 kf_status check_ws(const void* ws, size_t have, size_t need) {
     if (!ws) return fail(KF_EWORKSPACE, "workspace is NULL");
@@ -324,7 +340,19 @@ static kf_status prepare_select(kf_cache* c, int32_t k, int32_t w, int32_t layou
     a->move = 1;
     a->ws_err = (int32_t*)workspace + KF_WS_ERROR_WORD;
     a->step_inc = nullptr;
-    (void)U;
+    // Few units, or long ones: one workgroup per unit cannot move the rows of an ordered eviction at the
+    // chip's rate, so a second launch spreads every unit's rows over many workgroups.
+    a->chunk_rows = kf::wide_chunk_rows(a->row_bytes);
+    a->nb = wl.nb;
+    a->wide = (layout == KF_LAYOUT_ORDERED && a->nb > 0 && wide_pays(U, k)) ? 1 : 0;
+    char* wp = (char*)workspace + wl.wide;
+    a->ws_evict = (int32_t*)wp;
+    wp += wide_part((size_t)U * 4);
+    a->ws_brow = wp;
+    wp += wide_part((size_t)U * wl.nb * 2 * a->row_bytes);
+    a->ws_bscore = (float*)wp;
+    wp += wide_part((size_t)U * wl.nb * 4);
+    a->ws_bpos = (int32_t*)wp;
     return KF_OK;
 }
 
@@ -374,6 +402,7 @@ kf_status kf_select_evict_into(const kf_cache* src, kf_cache* dst, int32_t dst_l
     st = prepare_select(&src_mut, k, w, KF_LAYOUT_ORDERED, kept_idx, workspace, workspace_bytes, false, &a);
     if (st != KF_OK) return st;
     a.move = 0;
+    a.wide = 0;  // rows are gathered out of place by the launch below
     const int64_t U = (int64_t)src->L * src->B * src->H;
     hipError_t e = kf::launch_select(a, U, (hipStream_t)stream);
     if (e != hipSuccess) return fail(KF_EDEVICE, "select launch: %s", hipGetErrorString(e));
@@ -435,7 +464,7 @@ static kf_status fused_step(kf_cache* c, const void* q, const void* k_new, const
         e = kf::launch_decode(da, U, c->d, c->dtype, p.lds_bytes, (hipStream_t)stream);
         if (e == hipSuccess && da.shared) e = share_after_decode(c, da, (hipStream_t)stream);
         if (e == hipSuccess) e = kf::launch_select(sa, U, (hipStream_t)stream);
-    } else if (da.S > 1 && (int64_t)da.S * da.chunk <= kTailMergeMaxTokens) {
+    } else if (da.S > 1 && (int64_t)da.S * da.chunk <= kTailMergeMaxTokens && !sa.wide) {
         e = kf::launch_decode_split(da, U, c->d, c->dtype, p.lds_bytes, (hipStream_t)stream);
         if (e == hipSuccess) e = kf::launch_step_tail(da, sa, U, c->d, (hipStream_t)stream);
     } else {  // one workgroup per unit (nothing to merge), or units too long to merge inside the selection

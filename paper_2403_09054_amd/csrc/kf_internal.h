@@ -88,7 +88,18 @@ struct SelectArgs {
     int32_t move;           // 0: only write the survivor index list (rows are gathered elsewhere)
     int32_t* ws_err;        // [1] skipped-unit counter
     int32_t* step_inc;      // NULL, or the device step counter this launch advances by one when it is done
+    // Ordered layout, decode shape, rows moved by a second launch of several workgroups per unit
+    // ("wide"): the selection launch only finds the evicted slot and saves the chunk-boundary entries.
+    int32_t wide;           // 0: the selection workgroup moves the rows itself
+    int32_t chunk_rows;     // R: rows a workgroup of the second launch moves
+    int32_t nb;             // boundary slots kept per unit: cap / R
+    int32_t* ws_evict;      // [U]                  evicted slot, or -1 (nothing for the second launch)
+    void* ws_brow;          // [U][nb][2][row_bytes] K and V rows at slots R, 2R, ... saved before anything moves
+    float* ws_bscore;       // [U][nb]              their scores
+    int32_t* ws_bpos;       // [U][nb]              their positions
 };
+// rows per workgroup of the wide shift: 2048 16-byte pieces per tensor, i.e. 32 KB of K and 32 KB of V
+inline int32_t wide_chunk_rows(int32_t row_bytes) { return 2048 / (row_bytes >> 4); }
 hipError_t launch_select(const SelectArgs& a, int64_t U, hipStream_t stream);
 struct GatherArgs {
     const void* src_K;

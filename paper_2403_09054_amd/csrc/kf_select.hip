@@ -293,6 +293,120 @@ __device__ __forceinline__ void evict_one_slot(const SelectArgs& a, int64_t u, i
     if (tid == 0) a.len[u] = k;
 }
 
+// Decode-shape eviction in the ordered layout, first of two launches ("wide" mode, for workloads whose
+// units are too few or too long for one workgroup each to move the rows): find the evicted slot e exactly
+// as evict_one does, and save the entries at slots R, 2R, ... behind it.  The second launch gives every
+// R-slot chunk of [e, k) to a workgroup of its own; a chunk's last source is the next chunk's first
+// destination, and that one entry is read from the copy saved here, so the chunks need no order.
+template <int NT>
+__device__ __forceinline__ void evict_find(const SelectArgs& a, int64_t u, int n, bool write_idx) {
+    constexpr int NW = NT / kWave;
+    __shared__ unsigned long long wmin_f[NW];
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int k = a.k, w = a.w;
+    const int ncand = n - w;
+    const float* fu = a.score + (size_t)u * a.cap;
+    const int32_t* pu = a.pos + (size_t)u * a.cap;
+    unsigned long long best = ~0ull;
+    for (int j = tid; j < ncand; j += NT) {
+        const unsigned long long pack = ((unsigned long long)float_key(fu[j]) << 32) | (uint32_t)(~(uint32_t)j);
+        best = pack < best ? pack : best;
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const unsigned long long t = __shfl_xor(best, o, kWave);
+        best = t < best ? t : best;
+    }
+    if (lane == 0) wmin_f[wv] = best;
+    __syncthreads();
+    best = wmin_f[0];
+#pragma unroll
+    for (int i = 1; i < NW; ++i) best = wmin_f[i] < best ? wmin_f[i] : best;
+    const int e = (int)(~(uint32_t)(best & 0xFFFFFFFFull));  // evicted slot, in [0, ncand)
+    if (write_idx) {
+        int32_t* idx = a.idx + (size_t)u * k;
+        for (int i = tid; i < k; i += NT) idx[i] = i + (i >= e ? 1 : 0);
+    }
+    // boundary entries at slots b = (c+1)*R with e < b <= k
+    const int R = a.chunk_rows, PPR = a.row_bytes >> 4;
+    const int c0 = e / R, c1 = k / R;  // boundaries c0 .. c1-1
+    const uint4* Kr = (const uint4*)((const char*)a.K + (size_t)u * a.cap * a.row_bytes);
+    const uint4* Vr = (const uint4*)((const char*)a.V + (size_t)u * a.cap * a.row_bytes);
+    uint4* brow = (uint4*)((char*)a.ws_brow + (size_t)u * a.nb * 2 * a.row_bytes);
+    const int per = 2 * PPR;  // pieces per boundary: the K row, then the V row
+    for (int p = tid; p < (c1 - c0) * per; p += NT) {
+        const int c = c0 + p / per, q = p % per;
+        const int b = (c + 1) * R;
+        brow[(size_t)c * per + q] = (q < PPR) ? Kr[(size_t)b * PPR + q] : Vr[(size_t)b * PPR + q - PPR];
+    }
+    for (int c = c0 + tid; c < c1; c += NT) {
+        a.ws_bscore[(size_t)u * a.nb + c] = fu[(c + 1) * R];
+        a.ws_bpos[(size_t)u * a.nb + c] = pu[(c + 1) * R];
+    }
+    if (tid == 0) {
+        a.ws_evict[u] = e;
+        a.len[u] = k;
+    }
+}
+
+// Second launch of the wide mode: workgroup (unit u, chunk c) moves entries [max(e, cR)+1, min(k, (c+1)R)]
+// down by one slot.  Everything it reads is in registers before its one barrier; its last source, if it is
+// the next chunk's first destination, comes from the copy the first launch saved.
+constexpr int kWideThreads = 256;
+constexpr int kWidePieces = 2048 / kWideThreads;  // 16-byte pieces per thread and tensor
+__global__ void __launch_bounds__(kWideThreads) shift_chunk_kernel(const SelectArgs a, int nchunks, int64_t units) {
+    // chunk-major: the chunks that have work are the same few of every unit (those behind the evicted slot),
+    // and consecutive workgroup ids go round-robin to the 8 XCDs -- unit-major ids would park all the work on
+    // the XCDs those chunk numbers map to (measured: half the chip idle, 84 instead of 40 us)
+    const int64_t u = blockIdx.x % units;
+    const int c = (int)(blockIdx.x / units);
+    const int e = a.ws_evict[u];
+    if (e < 0) return;
+    const int R = a.chunk_rows, k = a.k, PPR = a.row_bytes >> 4;
+    const int lo = max(e, c * R), hi = min(k, (c + 1) * R);
+    if (lo >= hi) return;
+    const int rows = hi - lo, bnd = (c + 1) * R;  // sources lo+1 .. hi; source `bnd` is saved
+    const int tid = threadIdx.x;
+    uint4* Kr = (uint4*)((char*)a.K + (size_t)u * a.cap * a.row_bytes);
+    uint4* Vr = (uint4*)((char*)a.V + (size_t)u * a.cap * a.row_bytes);
+    const uint4* brow = (const uint4*)((const char*)a.ws_brow + ((size_t)u * a.nb + c) * 2 * a.row_bytes);
+    float* fu = a.score + (size_t)u * a.cap;
+    int32_t* pu = a.pos + (size_t)u * a.cap;
+    // branch-free: a lane past the chunk's end re-reads the last source, the saved entry is a pointer choice
+    uint4 kreg[kWidePieces], vreg[kWidePieces];
+#pragma unroll
+    for (int i = 0; i < kWidePieces; ++i) {
+        const int p = tid + i * kWideThreads;
+        const int q = p % PPR;
+        const int src = lo + min(p / PPR, rows - 1) + 1;
+        const uint4* ks = (src == bnd) ? brow + q : Kr + (size_t)src * PPR + q;
+        const uint4* vs = (src == bnd) ? brow + PPR + q : Vr + (size_t)src * PPR + q;
+        kreg[i] = stream_load(ks);
+        vreg[i] = stream_load(vs);
+    }
+    float fs = 0.0f;
+    int32_t ps = 0;
+    if (tid < rows) {
+        const int src = lo + tid + 1;
+        fs = (src == bnd) ? a.ws_bscore[(size_t)u * a.nb + c] : fu[src];
+        ps = (src == bnd) ? a.ws_bpos[(size_t)u * a.nb + c] : pu[src];
+    }
+    __syncthreads();  // (with its wait for the loads) every source of the chunk is in registers
+#pragma unroll
+    for (int i = 0; i < kWidePieces; ++i) {
+        const int p = tid + i * kWideThreads;
+        const int r = p / PPR, q = p % PPR;
+        if (r < rows) {
+            stream_store(Kr + (size_t)(lo + r) * PPR + q, kreg[i]);
+            stream_store(Vr + (size_t)(lo + r) * PPR + q, vreg[i]);
+        }
+    }
+    if (tid < rows) {
+        fu[lo + tid] = fs;
+        pu[lo + tid] = ps;
+    }
+}
+
 // Selection and compaction of one unit by one workgroup.
 template <int NT>
 __device__ __forceinline__ void select_unit(const SelectArgs& a, int64_t u) {
@@ -307,6 +421,7 @@ __device__ __forceinline__ void select_unit(const SelectArgs& a, int64_t u) {
     const int k = a.k, w = a.w;
     int32_t* idx = a.idx + (size_t)u * k;
 
+    if (a.wide && tid == 0) a.ws_evict[u] = -1;  // unless the decode-shape branch below says otherwise
     if (n <= k) {  // under budget: nothing leaves
         if (a.idx_is_output || !a.move)
             for (int i = tid; i < k; i += NT) idx[i] = (i < n) ? i : -1;
@@ -321,7 +436,12 @@ __device__ __forceinline__ void select_unit(const SelectArgs& a, int64_t u) {
         return;
     }
     if (n == k + 1 && a.move) {  // decode shape
-        evict_one<NT>(a, u, n, a.idx_is_output != 0);
+        if (a.wide) {
+            __syncthreads();  // the -1 above is stored before this workgroup's own slot number
+            evict_find<NT>(a, u, n, a.idx_is_output != 0);
+        } else {
+            evict_one<NT>(a, u, n, a.idx_is_output != 0);
+        }
         return;
     }
     const int ncand = n - w, nkey = k - w;
@@ -574,7 +694,13 @@ hipError_t launch_select(const SelectArgs& a, int64_t U, hipStream_t stream) {
         hipLaunchKernelGGL((select_kernel<kSelectThreadsSlot>), grid, dim3(kSelectThreadsSlot), 0, stream, a);
     else
         hipLaunchKernelGGL((select_kernel<kSelectThreads>), grid, dim3(kSelectThreads), 0, stream, a);
-    return hipGetLastError();
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess && a.wide) {
+        const int nchunks = (a.k + a.chunk_rows - 1) / a.chunk_rows;
+        hipLaunchKernelGGL(shift_chunk_kernel, dim3((unsigned)(U * nchunks)), dim3(kWideThreads), 0, stream, a, nchunks, U);
+        e = hipGetLastError();
+    }
+    return e;
 }
 
 }  // namespace kf

@@ -206,6 +206,35 @@ def test_select_adversarial_eviction_slots():
     assert [sorted(set(range(n)) - set(kept_ref[0, 0, h].tolist()))[0] for h in range(4)] == [0, n - w - 1, 100, 150]
 
 
+@pytest.mark.parametrize("d,dtype,k,w", [(128, ko.BF16, 256, 0), (128, ko.BF16, 300, 40), (128, ko.BF16, 100, 10),
+                                        (256, ko.BF16, 128, 0), (64, ko.F32, 257, 1), (64, ko.BF16, 512, 100)])
+def test_select_two_launch_eviction_at_chunk_boundaries(d, dtype, k, w):
+    """Few units: the ordered eviction runs as two launches, the second moving the rows chunk by chunk (R rows
+    per workgroup, R = 32 KB / row bytes).  Evicted slots on, next to and far from chunk boundaries, budgets that
+    are a multiple of R, smaller than R, and without a window."""
+    row_bytes = d * (4 if dtype == ko.F32 else 2)
+    R = 2048 // (row_bytes // 16)
+    n = k + 1
+    ncand = n - w
+    slots = sorted({s for s in (0, 1, R - 1, R, R + 1, 2 * R - 1, 2 * R, ncand - 1, ncand - 2, ncand // 2) if 0 <= s < ncand})
+    rng = np.random.default_rng(k + d)
+    oc = random_cache(rng, 1, 1, len(slots), d, n + 3, dtype, n)
+    oc.score[...] += 1.0
+    for h, s_ in enumerate(slots):
+        oc.score[0, 0, h, s_] = 0.5
+    gc = upload(oc)
+    ws = kf.new_workspace(gc)
+    kept = torch.zeros((1, 1, len(slots), k), dtype=torch.int32, device="cuda")
+    kept_ref = oc.select_evict(k, w)
+    kf.kf_select_evict(gc, k, w, kept, ws)
+    torch.cuda.synchronize()
+    assert error_word(ws) == 0
+    np.testing.assert_array_equal(host(kept), kept_ref)
+    assert_state_equal(gc, oc)
+    for h, s_ in enumerate(slots):
+        assert s_ not in set(kept_ref[0, 0, h].tolist())
+
+
 # ------------------------------------------------------------------ prefill
 @pytest.mark.parametrize("dtype,d", DTYPES)
 @pytest.mark.parametrize("n", [1, 31, 33, 128, 129, 300])
