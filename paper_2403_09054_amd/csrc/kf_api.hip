@@ -28,6 +28,7 @@ constexpr int64_t kMaxGrid = 0x7fffffff;  // workgroups of a one-dimensional lau
 // which spreads a unit over several workgroups (32 heads x 9.8k tokens: 55.5 us folded, 52.6 us apart).
 constexpr int64_t kTailMergeMaxTokens = 4096;
 constexpr int64_t kWideMaxUnits = 256;
+constexpr int32_t kPreselMinTokens = 4096;
 
 bool supported(int32_t dtype, int32_t d) {
     if (dtype == KF_BF16) return d == 64 || d == 128 || d == 256;
@@ -115,7 +116,8 @@ WsLayout ws_layout(const kf_cache* c, int32_t n_max) {
     const int32_t row_bytes = c->d * (c->dtype == KF_F32 ? 4 : 2);
     w.nb = c->cap / kf::wide_chunk_rows(row_bytes);
     w.total = w.wide + wide_part((size_t)U * 4) + wide_part((size_t)U * w.nb * 2 * row_bytes) +
-              2 * wide_part((size_t)U * w.nb * 4);
+              2 * wide_part((size_t)U * w.nb * 4) + wide_part((size_t)U * kf::kPreselMaxSlices * 8) +
+              wide_part((size_t)U * kf::kPreselMaxSlices * 4);
     return w;
 }
 
@@ -353,6 +355,16 @@ static kf_status prepare_select(kf_cache* c, int32_t k, int32_t w, int32_t layou
     a->ws_bscore = (float*)wp;
     wp += wide_part((size_t)U * wl.nb * 4);
     a->ws_bpos = (int32_t*)wp;
+    wp += wide_part((size_t)U * wl.nb * 4);
+    // long units of a small launch: the candidate scan is cut into slices by a launch of its own
+    a->presel = 0;
+    if (U <= kWideMaxUnits && c->cap >= kPreselMinTokens) {
+        a->presel = (c->cap + 2047) / 2048;
+        if (a->presel > kf::kPreselMaxSlices) a->presel = kf::kPreselMaxSlices;
+    }
+    a->ws_pmin = (unsigned long long*)wp;
+    wp += wide_part((size_t)U * kf::kPreselMaxSlices * 8);
+    a->ws_pslot = (int32_t*)wp;
     return KF_OK;
 }
 
@@ -403,6 +415,7 @@ kf_status kf_select_evict_into(const kf_cache* src, kf_cache* dst, int32_t dst_l
     if (st != KF_OK) return st;
     a.move = 0;
     a.wide = 0;  // rows are gathered out of place by the launch below
+    a.presel = 0;
     const int64_t U = (int64_t)src->L * src->B * src->H;
     hipError_t e = kf::launch_select(a, U, (hipStream_t)stream);
     if (e != hipSuccess) return fail(KF_EDEVICE, "select launch: %s", hipGetErrorString(e));
@@ -464,7 +477,7 @@ static kf_status fused_step(kf_cache* c, const void* q, const void* k_new, const
         e = kf::launch_decode(da, U, c->d, c->dtype, p.lds_bytes, (hipStream_t)stream);
         if (e == hipSuccess && da.shared) e = share_after_decode(c, da, (hipStream_t)stream);
         if (e == hipSuccess) e = kf::launch_select(sa, U, (hipStream_t)stream);
-    } else if (da.S > 1 && (int64_t)da.S * da.chunk <= kTailMergeMaxTokens && !sa.wide) {
+    } else if (da.S > 1 && (int64_t)da.S * da.chunk <= kTailMergeMaxTokens && !sa.wide && !sa.presel) {
         e = kf::launch_decode_split(da, U, c->d, c->dtype, p.lds_bytes, (hipStream_t)stream);
         if (e == hipSuccess) e = kf::launch_step_tail(da, sa, U, c->d, (hipStream_t)stream);
     } else {  // one workgroup per unit (nothing to merge), or units too long to merge inside the selection

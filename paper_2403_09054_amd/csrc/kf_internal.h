@@ -97,7 +97,13 @@ struct SelectArgs {
     void* ws_brow;          // [U][nb][2][row_bytes] K and V rows at slots R, 2R, ... saved before anything moves
     float* ws_bscore;       // [U][nb]              their scores
     int32_t* ws_bpos;       // [U][nb]              their positions
+    // Long units in the decode shape: a launch ahead of the selection cuts the candidate scan of a unit
+    // into `presel` slices, one workgroup each, and leaves every slice's smallest candidate here.
+    int32_t presel;             // 0: the selection workgroup scans the candidates itself
+    unsigned long long* ws_pmin;  // [U][presel] smallest (score key, tie-break) pack of the slice, ~0 if none
+    int32_t* ws_pslot;          // [U][presel] its slot
 };
+constexpr int32_t kPreselMaxSlices = 16;
 // rows per workgroup of the wide shift: 2048 16-byte pieces per tensor, i.e. 32 KB of K and 32 KB of V
 inline int32_t wide_chunk_rows(int32_t row_bytes) { return 2048 / (row_bytes >> 4); }
 hipError_t launch_select(const SelectArgs& a, int64_t U, hipStream_t stream);

@@ -215,6 +215,80 @@ __device__ __forceinline__ void evict_one(const SelectArgs& a, int64_t u, int n,
     if (tid == 0) a.len[u] = k;
 }
 
+// Candidate scan of long units ahead of the selection launch: workgroup (unit, slice) finds the smallest
+// candidate of its slice of a decode-shape unit (len = k+1) -- by slot in the ordered layout (candidates are
+// the slots below len-w, equal scores: the higher slot leaves), by position in the slot layout (candidates
+// are the entries at least w positions behind the newest, equal scores: the higher position leaves).
+constexpr int kPreselThreads = 256;
+__global__ void __launch_bounds__(kPreselThreads) presel_kernel(const SelectArgs a, int64_t units) {
+    __shared__ unsigned long long wmin_p[kPreselThreads / kWave];
+    __shared__ int wslot_p[kPreselThreads / kWave];
+    const int64_t u = blockIdx.x % units;  // slice-major ids: every XCD gets slices of every kind
+    const int sl = (int)(blockIdx.x / units);
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int n = a.len[u];
+    if (n != a.k + 1) return;  // the selection launch does not look at the slices of such a unit
+    const float* fu = a.score + (size_t)u * a.cap;
+    const int32_t* pu = a.pos + (size_t)u * a.cap;
+    const int per = ((n + a.presel - 1) / a.presel + kPreselThreads - 1) / kPreselThreads * kPreselThreads;
+    const int j0 = sl * per, j1 = min(n, j0 + per);
+    const bool by_pos = a.layout == KF_LAYOUT_SLOT;
+    const int newest = by_pos ? pu[n - 1] : 0;
+    unsigned long long best = ~0ull;
+    int best_slot = -1;
+    for (int j = j0 + tid; j < j1; j += kPreselThreads) {
+        const int pj = by_pos ? pu[j] : 0;
+        const bool cand = by_pos ? (pj <= newest - a.w) : (j < n - a.w);
+        if (cand) {
+            const unsigned long long pack =
+                ((unsigned long long)float_key(fu[j]) << 32) | (uint32_t)(~(uint32_t)(by_pos ? pj : j));
+            if (pack < best) {
+                best = pack;
+                best_slot = j;
+            }
+        }
+    }
+    const unsigned long long mine = best;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const unsigned long long t = __shfl_xor(best, o, kWave);
+        best = t < best ? t : best;
+    }
+    // slots and positions are unique: one lane of the wave owns the wave's minimum
+    const unsigned long long owner = __ballot(mine == best && best != ~0ull);
+    const int wslot = __shfl(best_slot, owner ? __ffsll((long long)owner) - 1 : 0, kWave);
+    if (lane == 0) {
+        wmin_p[wv] = best;
+        wslot_p[wv] = owner ? wslot : -1;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        unsigned long long g = wmin_p[0];
+        int gs = wslot_p[0];
+        for (int i = 1; i < kPreselThreads / kWave; ++i)
+            if (wmin_p[i] < g) {
+                g = wmin_p[i];
+                gs = wslot_p[i];
+            }
+        a.ws_pmin[(size_t)u * a.presel + sl] = g;
+        a.ws_pslot[(size_t)u * a.presel + sl] = gs;
+    }
+}
+
+// The evicted slot from the slices' minima (every lane gets it), -1 if no slice had a candidate.
+__device__ __forceinline__ int presel_pick(const SelectArgs& a, int64_t u) {
+    unsigned long long g = ~0ull;
+    int gs = -1;
+    for (int i = 0; i < a.presel; ++i) {
+        const unsigned long long v = a.ws_pmin[(size_t)u * a.presel + i];
+        if (v < g) {
+            g = v;
+            gs = a.ws_pslot[(size_t)u * a.presel + i];
+        }
+    }
+    return gs;
+}
+
 // Slot-replacement variant of the same eviction (layout KF_LAYOUT_SLOT): the
 // cache is an unordered set of (pos, K, V, score) entries.  The recent window
 // is the w largest original positions -- positions are consecutive at the
@@ -233,43 +307,45 @@ __device__ __forceinline__ void evict_one_slot(const SelectArgs& a, int64_t u, i
     int32_t* pu = a.pos + (size_t)u * a.cap;
     const int newest = pu[n - 1];
 
-    unsigned long long best = ~0ull, mine[2] = {~0ull, ~0ull};
-    for (int j = tid, c = 0; j < n; j += NT, ++c) {
-        const int pj = pu[j];
-        unsigned long long pack = ~0ull;
-        if (pj <= newest - w)  // a candidate: outside the recent window
-            pack = ((unsigned long long)float_key(fu[j]) << 32) | (uint32_t)(~(uint32_t)pj);
-        best = pack < best ? pack : best;
-        if (c < 2) mine[c] = pack;
-    }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-        const unsigned long long t = __shfl_xor(best, o, kWave);
-        best = t < best ? t : best;
-    }
-    if (lane == 0) wmin_s[wv] = best;
-    if (tid == 0) s_slot = -1;
-    __syncthreads();
-    best = wmin_s[0];
-#pragma unroll
-    for (int i = 1; i < NW; ++i) best = wmin_s[i] < best ? wmin_s[i] : best;
-    // positions are unique, so exactly one entry carries the winning pack
-    if (best != ~0ull) {
+    if (!a.presel) {  // else the launch ahead scanned the candidates
+        unsigned long long best = ~0ull, mine[2] = {~0ull, ~0ull};
         for (int j = tid, c = 0; j < n; j += NT, ++c) {
-            unsigned long long pack;
-            if (c < 2) {
-                pack = mine[c];
-            } else {
-                const int pj = pu[j];
-                pack = (pj <= newest - w)
-                           ? (((unsigned long long)float_key(fu[j]) << 32) | (uint32_t)(~(uint32_t)pj))
-                           : ~0ull;
-            }
-            if (pack == best) s_slot = j;
+            const int pj = pu[j];
+            unsigned long long pack = ~0ull;
+            if (pj <= newest - w)  // a candidate: outside the recent window
+                pack = ((unsigned long long)float_key(fu[j]) << 32) | (uint32_t)(~(uint32_t)pj);
+            best = pack < best ? pack : best;
+            if (c < 2) mine[c] = pack;
         }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            const unsigned long long t = __shfl_xor(best, o, kWave);
+            best = t < best ? t : best;
+        }
+        if (lane == 0) wmin_s[wv] = best;
+        if (tid == 0) s_slot = -1;
+        __syncthreads();
+        best = wmin_s[0];
+#pragma unroll
+        for (int i = 1; i < NW; ++i) best = wmin_s[i] < best ? wmin_s[i] : best;
+        // positions are unique, so exactly one entry carries the winning pack
+        if (best != ~0ull) {
+            for (int j = tid, c = 0; j < n; j += NT, ++c) {
+                unsigned long long pack;
+                if (c < 2) {
+                    pack = mine[c];
+                } else {
+                    const int pj = pu[j];
+                    pack = (pj <= newest - w)
+                               ? (((unsigned long long)float_key(fu[j]) << 32) | (uint32_t)(~(uint32_t)pj))
+                               : ~0ull;
+                }
+                if (pack == best) s_slot = j;
+            }
+        }
+        __syncthreads();
     }
-    __syncthreads();
-    const int e = s_slot;
+    const int e = a.presel ? presel_pick(a, u) : s_slot;
     if (e < 0) {  // no entry lies outside the window (positions not consecutive at the recent end): report
         if (tid == 0) atomicAdd(a.ws_err, 1);
         return;
@@ -307,22 +383,27 @@ __device__ __forceinline__ void evict_find(const SelectArgs& a, int64_t u, int n
     const int ncand = n - w;
     const float* fu = a.score + (size_t)u * a.cap;
     const int32_t* pu = a.pos + (size_t)u * a.cap;
-    unsigned long long best = ~0ull;
-    for (int j = tid; j < ncand; j += NT) {
-        const unsigned long long pack = ((unsigned long long)float_key(fu[j]) << 32) | (uint32_t)(~(uint32_t)j);
-        best = pack < best ? pack : best;
-    }
+    int e;
+    if (a.presel) {
+        e = presel_pick(a, u);  // the launch ahead scanned the candidates
+    } else {
+        unsigned long long best = ~0ull;
+        for (int j = tid; j < ncand; j += NT) {
+            const unsigned long long pack = ((unsigned long long)float_key(fu[j]) << 32) | (uint32_t)(~(uint32_t)j);
+            best = pack < best ? pack : best;
+        }
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-        const unsigned long long t = __shfl_xor(best, o, kWave);
-        best = t < best ? t : best;
-    }
-    if (lane == 0) wmin_f[wv] = best;
-    __syncthreads();
-    best = wmin_f[0];
+        for (int o = 32; o > 0; o >>= 1) {
+            const unsigned long long t = __shfl_xor(best, o, kWave);
+            best = t < best ? t : best;
+        }
+        if (lane == 0) wmin_f[wv] = best;
+        __syncthreads();
+        best = wmin_f[0];
 #pragma unroll
-    for (int i = 1; i < NW; ++i) best = wmin_f[i] < best ? wmin_f[i] : best;
-    const int e = (int)(~(uint32_t)(best & 0xFFFFFFFFull));  // evicted slot, in [0, ncand)
+        for (int i = 1; i < NW; ++i) best = wmin_f[i] < best ? wmin_f[i] : best;
+        e = (int)(~(uint32_t)(best & 0xFFFFFFFFull));  // evicted slot, in [0, ncand)
+    }
     if (write_idx) {
         int32_t* idx = a.idx + (size_t)u * k;
         for (int i = tid; i < k; i += NT) idx[i] = i + (i >= e ? 1 : 0);
@@ -690,6 +771,11 @@ hipError_t launch_gather(const GatherArgs& g, hipStream_t stream) {
 
 hipError_t launch_select(const SelectArgs& a, int64_t U, hipStream_t stream) {
     const dim3 grid((unsigned)U);
+    if (a.presel) {
+        hipLaunchKernelGGL(presel_kernel, dim3((unsigned)(U * a.presel)), dim3(kPreselThreads), 0, stream, a, U);
+        const hipError_t e0 = hipGetLastError();
+        if (e0 != hipSuccess) return e0;
+    }
     if (a.layout == KF_LAYOUT_SLOT)
         hipLaunchKernelGGL((select_kernel<kSelectThreadsSlot>), grid, dim3(kSelectThreadsSlot), 0, stream, a);
     else
