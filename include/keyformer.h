@@ -89,7 +89,8 @@ typedef struct {
 /* Which positions the position bias sees (Sec. 4.4.2): the tokens' original
  * positions ("Org Pos", the default and the better ablation), or their positions
  * within the reduced cache ("New Pos": key j at slot j, the query at slot m-1).
- * The noise key always uses original positions. */
+ * The noise key always uses original positions.  KF_POS_NEW reads a token's position off its slot, so it
+ * presumes the ordered layout (in KF_LAYOUT_SLOT the slots carry no order). */
 typedef enum { KF_POS_ORIGINAL = 0, KF_POS_NEW = 1 } kf_pos_mode;
 
 /* Whether every layer accumulates its own score (the method, and the better

@@ -168,7 +168,7 @@ class LockStep:
     hold the same state (scores are re-uploaded from the oracle after each
     decode step, everything after a tie-band event)."""
 
-    def __init__(self, wl: kw.Workload, noise=ko.NOISE_GUMBEL, layers=None, cap=None, layout=kf.LAYOUT_ORDERED,
+    def __init__(self, wl: kw.Workload, noise=ko.NOISE_GUMBEL, cap=None, layout=kf.LAYOUT_ORDERED,
                  shared=False, q_per_kv=1):
         self.wl, self.noise, self.layout = wl, noise, layout
         self.G = G = q_per_kv           # grouped queries: wl.H counts QUERY heads, the caches hold wl.H // G
