@@ -114,7 +114,7 @@ WsLayout ws_layout(const kf_cache* c, int32_t n_max) {
     }
     w.wide = w.region + x;
     const int32_t row_bytes = c->d * (c->dtype == KF_F32 ? 4 : 2);
-    w.nb = c->cap / kf::wide_chunk_rows(row_bytes);
+    w.nb = U <= kWideMaxUnits ? c->cap / kf::wide_chunk_rows(row_bytes) : 0;  // only small launches go wide
     w.total = w.wide + wide_part((size_t)U * 4) + wide_part((size_t)U * w.nb * 2 * row_bytes) +
               2 * wide_part((size_t)U * w.nb * 4) + wide_part((size_t)U * kf::kPreselMaxSlices * 8) +
               wide_part((size_t)U * kf::kPreselMaxSlices * 4);
