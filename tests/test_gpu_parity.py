@@ -1099,3 +1099,37 @@ def test_single_launch_slot_step_from_the_device_counter_and_in_a_graph():
         for x, y in zip([host(x) for x in (out_b, b_.score[..., :k], b_.pos[..., :k], b_.len)], ref[t - 1]):
             np.testing.assert_array_equal(x, y)
     assert error_word(ws_b) == 0
+
+
+# ------------------------------------------------------------------ temperature away from the schedule's range
+@pytest.mark.parametrize("tau", [0.05, 0.5, 8.0, 1000.0])
+def test_decode_at_extreme_temperatures(tau):
+    """Sec. 3.3.1: small tau sharpens the score distribution towards one-hot, large tau flattens it towards
+    uniform; the kernels keep everything in the base-2 domain with running maxima, so neither end overflows."""
+    rng = np.random.default_rng(int(tau * 100))
+    L, B, H, d, cap = 1, 2, 3, 128, 900
+    lens = rng.integers(600, cap, (L, B, H)).astype(np.int32)
+    oc = random_cache(rng, L, B, H, d, cap, ko.BF16, lens)
+    q, kn, vn = (rnd(rng, (L, B, H, d), ko.BF16) for _ in range(3))
+    seeds = np.array([21, 22], np.uint64)
+    gc = upload(oc)
+    ws = kf.new_workspace(gc)
+    out = torch.zeros((L, B, H, d), dtype=torch.float32, device="cuda")
+    q_pos = int(oc.pos.max()) + 1
+    before = oc.score.copy()
+    kf.kf_decode_step(gc, dev(q), dev(kn), dev(vn), q_pos, 0, tau, 0.0884, kf.NOISE_GUMBEL, dev(seeds), None, out, ws)
+    torch.cuda.synchronize()
+    out_ref, _, df = oc.decode_step(q, kn, vn, q_pos, tau, 0.0884, ko.NOISE_GUMBEL, seeds, None, debug=True)
+    assert_close_out(host(out), out_ref)
+    # increments: 2e-3 relative where they matter, plus an absolute floor of 1e-7 of the step's unit mass
+    # (at tau = 0.05 most increments are far below fp32's resolution next to the scores they are added to)
+    got = host(gc.score).astype(np.float64) - np.where(np.arange(cap) < lens[..., None], before, 0.0)
+    for l, b, h in np.ndindex(L, B, H):
+        m = int(lens[l, b, h]) + 1
+        g, r = got[l, b, h, :m], df[l, b, h, :m]
+        assert np.all(np.abs(g - r) <= 2e-3 * np.abs(r) + 2e-7 * (1.0 + np.abs(before[l, b, h, :m]))), (tau, l, b, h)
+        assert abs(g.sum() - 1.0) < 1e-3
+    if tau <= 0.05:
+        assert df.max(axis=-1).min() > 0.5          # nearly one-hot
+    if tau >= 1000.0:
+        assert df[0, 0, 0, : lens[0, 0, 0] + 1].max() < 2.0 / lens[0, 0, 0]   # nearly uniform
