@@ -1133,3 +1133,30 @@ def test_decode_at_extreme_temperatures(tau):
         assert df.max(axis=-1).min() > 0.5          # nearly one-hot
     if tau >= 1000.0:
         assert df[0, 0, 0, : lens[0, 0, 0] + 1].max() < 2.0 / lens[0, 0, 0]   # nearly uniform
+
+
+# ------------------------------------------------------------------ free-running on a bf16 slice (informational)
+def test_gptj_slice_free_running_reports_first_divergence():
+    """No resynchronisation at all on a GPT-J-shaped slice: GPU and oracle each follow their own scores.  A
+    near-tie at the eviction threshold may eventually send them apart (then every later step differs), so only
+    the start is asserted; the step of the first difference, if any, is printed."""
+    wl = kw.CONFIGS["gptj"].slice(L=1, H=4, T=512)
+    fr = LockStep(wl)
+    fr.oc.prefill_score(fr.Q, wl.n, ko.tau(0, wl.T), wl.scale, fr.noise, fr.seeds, fr.slopes)
+    kf.kf_prefill_score(fr.gc, dev(fr.Q), wl.n, kf.kf_tau(0, wl.T), wl.scale, fr.noise, fr.d_seeds, None, fr.ws)
+    fr.oc.select_evict(wl.k, wl.w)
+    kf.kf_select_evict(fr.gc, wl.k, wl.w, None, fr.ws)
+    first_div = None
+    steps = 128
+    for t in range(1, steps + 1):
+        q, kn, vn = kw.decode_inputs(wl, t)
+        fr.oc.decode_step(kw.to_oracle(q), kw.to_oracle(kn), kw.to_oracle(vn), wl.n + t - 1, ko.tau(t, wl.T), wl.scale,
+                          fr.noise, fr.seeds)
+        kf.kf_decode_select_step(fr.gc, q.cuda(), kn.cuda(), vn.cuda(), wl.n + t - 1, wl.k + 1, kf.kf_tau(t, wl.T), wl.scale,
+                                 fr.noise, fr.d_seeds, None, fr.out, k=wl.k, w=wl.w, workspace=fr.ws)
+        fr.oc.select_evict(wl.k, wl.w)
+        torch.cuda.synchronize()
+        if first_div is None and not (host(fr.gc.pos)[..., : wl.k] == fr.oc.pos[..., : wl.k]).all():
+            first_div = t
+    print("gptj slice free-running: first divergence step:", first_div, "of", steps)
+    assert first_div is None or first_div > 16
