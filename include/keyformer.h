@@ -153,6 +153,8 @@ kf_status kf_decode_launch_shape(const kf_cache *c, int32_t m_hint, int32_t *spl
  * the SLOT layout on a unit more than one token over budget).  Exposed as a
  * constant so callers can read it back themselves. */
 #define KF_WS_ERROR_WORD 0
+/* The second int32 of the workspace is a counter the library uses within a launch and leaves at zero. */
+#define KF_WS_TICKET_WORD 1
 
 /*
  * Prompt-phase scoring (Sec. 3.4, Algorithm 1 prompt branch).  For every unit,

@@ -283,11 +283,14 @@ static kf_status prepare_decode(kf_cache* c, const void* q, const void* k_new, c
     a->noise = cfg->noise;
     a->new_pos = cfg->pos_mode == KF_POS_NEW ? 1 : 0;
     a->shared = cfg->score_mode == KF_SCORE_SHARED ? 1 : 0;
+    if (a->shared && c->L > 65535) return fail(KF_EUNSUPPORTED, "a shared score over %d layers is not built", c->L);
     a->seq_q_pos = cfg->seq_q_pos;
     a->seq_tau = cfg->seq_tau;
     a->fuse_k = 0;
     a->fuse_w = 0;
     a->fuse_idx = nullptr;
+    a->step_inc = nullptr;
+    a->ws_ticket = (int32_t*)workspace + KF_WS_TICKET_WORD;
     a->step = nullptr;
     a->n0 = 0;
     a->T = 1;
@@ -470,8 +473,8 @@ static kf_status fused_step(kf_cache* c, const void* q, const void* k_new, const
         da.fuse_k = k;
         da.fuse_w = w;
         da.fuse_idx = kept_idx;
+        if (sched) da.step_inc = step;  // the launch's last workgroup moves the step number on
         e = kf::launch_decode(da, U, c->d, c->dtype, p.lds_bytes, (hipStream_t)stream);
-        if (e == hipSuccess && sched) e = kf::launch_advance_step(step, (hipStream_t)stream);
     } else if (da.shared || da.G > 1) {  // shared score: the layers' increments are added up between the merge and
                                   // the selection; the merge folded into the selection serves one query head
         e = kf::launch_decode(da, U, c->d, c->dtype, p.lds_bytes, (hipStream_t)stream);

@@ -148,7 +148,7 @@ struct MfmaLogits<bf16_t, G> {
 // and serves the G query heads that read it (G = 1: ordinary multi-head
 // attention; G > 1: grouped-query attention, query head hq = h*G + g).
 template <typename T, int D, int NT, int G>
-__global__ void __launch_bounds__(NT) decode_kernel(const DecodeArgs a) {
+__device__ __forceinline__ void decode_block(const DecodeArgs& a) {
     constexpr int EPV = ElemTraits<T>::kPerVec;  // elements per 16-byte vector
     constexpr int LPR = D / EPV;                 // lanes that share one row
     constexpr int RPW = kWave / LPR;             // rows per wave-wide load
@@ -619,6 +619,19 @@ __global__ void __launch_bounds__(NT) decode_kernel(const DecodeArgs a) {
     if (tid < 4 * G) part[(tid >> 2) * PW + D + (tid & 3)] = stat[tid];
 }
 
+template <typename T, int D, int NT, int G>
+__global__ void __launch_bounds__(NT) decode_kernel(const DecodeArgs a) {
+    decode_block<T, D, NT, G>(a);
+    // Whole-step launch with the step number in device memory: every workgroup read the number when it
+    // started, so the one that finishes last may move it on (and clears the ticket counter for the next launch).
+    if (a.step_inc && threadIdx.x == 0) {
+        if (atomicAdd(a.ws_ticket, 1) == (int)gridDim.x - 1) {
+            *a.ws_ticket = 0;
+            *a.step_inc += 1;
+        }
+    }
+}
+
 // Merge kernel, launched after the split kernel: gridDim.y workgroups per unit share the token range of
 // the score update (each re-derives the few per-split weights); the first also writes the outputs.  The
 // unit's token count comes from the split kernel's record, not from len, which the first workgroup updates.
@@ -646,34 +659,37 @@ __global__ void __launch_bounds__(kShareThreads) share_kernel(const ShareArgs a)
     bool same = true;
     for (int l = 1; l < a.L; ++l) same = same && (a.m[(size_t)l * a.BH + bh] == m);
     if (!same) {  // layers that hold different token counts cannot share a score: leave them, report
-        if (j == 0) atomicAdd(a.ws_err, 1);
+        if (j == 0 && blockIdx.z == 0) atomicAdd(a.ws_err, 1);
         return;
     }
     if (j >= m || m > a.cap) return;  // m == 0: the decode launch skipped (and reported) these units
     const size_t stride = (size_t)a.BH * a.cap, at = (size_t)bh * a.cap + j;
+    if (a.inc) {
+        // decode: a workgroup per layer (gridDim.z = L); each adds up all layers' increments itself, in layer
+        // order (every copy gets the same bits), and updates its own layer's score.  A unit's increments sit
+        // inc_unit floats apart (one row per query head, the sum in the first).
+        float s = 0.0f;
+        int l = 0;
+        for (; l + 4 <= a.L; l += 4) {  // four loads in flight
+            const float v0 = a.inc[((size_t)(l + 0) * a.BH + bh) * a.inc_unit + j];
+            const float v1 = a.inc[((size_t)(l + 1) * a.BH + bh) * a.inc_unit + j];
+            const float v2 = a.inc[((size_t)(l + 2) * a.BH + bh) * a.inc_unit + j];
+            const float v3 = a.inc[((size_t)(l + 3) * a.BH + bh) * a.inc_unit + j];
+            s = (((s + v0) + v1) + v2) + v3;
+        }
+        for (; l < a.L; ++l) s += a.inc[((size_t)l * a.BH + bh) * a.inc_unit + j];
+        float* f = a.score + (size_t)blockIdx.z * stride + at;
+        *f = (j == m - 1) ? s : *f + s;  // m-1: the token appended by this step
+        return;
+    }
+    // prompt: the layers' scores are summed in place, so one thread owns a token in every layer
     float s = 0.0f;
-    if (a.inc) {  // a unit's increments sit inc_unit floats apart (one row per query head, the sum in the first)
-        for (int l = 0; l < a.L; ++l) s += a.inc[((size_t)l * a.BH + bh) * a.inc_unit + j];
-    } else {
-        for (int l = 0; l < a.L; ++l) s += a.score[l * stride + at];
-    }
-    const bool fresh = !a.inc || j == m - 1;  // prompt scores, or the token appended by this step
-    for (int l = 0; l < a.L; ++l) {
-        float* f = a.score + l * stride + at;
-        *f = fresh ? s : *f + s;
-    }
-}
-
-__global__ void advance_step_kernel(int32_t* step) {
-    if (blockIdx.x == 0 && threadIdx.x == 0) *step += 1;
-}
-hipError_t launch_advance_step(int32_t* step, hipStream_t stream) {
-    hipLaunchKernelGGL(advance_step_kernel, dim3(1), dim3(kWave), 0, stream, step);
-    return hipGetLastError();
+    for (int l = 0; l < a.L; ++l) s += a.score[l * stride + at];
+    for (int l = 0; l < a.L; ++l) a.score[l * stride + at] = s;
 }
 
 hipError_t launch_share(const ShareArgs& a, hipStream_t stream) {
-    const dim3 grid((unsigned)a.BH, (unsigned)((a.cap + kShareThreads - 1) / kShareThreads));
+    const dim3 grid((unsigned)a.BH, (unsigned)((a.cap + kShareThreads - 1) / kShareThreads), a.inc ? (unsigned)a.L : 1u);
     hipLaunchKernelGGL(share_kernel, grid, dim3(kShareThreads), 0, stream, a);
     return hipGetLastError();
 }

@@ -45,6 +45,8 @@ struct DecodeArgs {
     // evicts for its unit and stores the new token straight into the freed slot.  fuse_k = 0: off.
     int32_t fuse_k, fuse_w;
     int32_t* fuse_idx;  // NULL, or [U][k] survivor list as the selection kernel writes it
+    int32_t* step_inc;   // NULL, or the device step counter the launch's last workgroup advances (whole-step launch)
+    int32_t* ws_ticket;  // [1] workgroups of this launch that are done (zero between launches)
     float inv_tau;
     float scale;
 };
@@ -70,8 +72,6 @@ struct ShareArgs {
     int32_t inc_unit;   // floats between the increments of consecutive units (G*cap)
 };
 hipError_t launch_share(const ShareArgs& a, hipStream_t stream);
-// *step += 1 by a single lane: closes a step whose last launch also reads the counter
-hipError_t launch_advance_step(int32_t* step, hipStream_t stream);
 
 // ------------------------------------------------------------------ select
 struct SelectArgs {
