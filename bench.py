@@ -377,7 +377,7 @@ def main():
         sl_units = wl.B * wl.H
         cpu_steps, cpu_time = 0, 0.0
         t = W_steps + 1
-        while cpu_time < args.cpu_seconds and cpu_steps < 4096:   # a bounded sample: about cpu_seconds of oracle work
+        while cpu_time < args.cpu_seconds and cpu_steps < 1000000:   # a bounded sample: about cpu_seconds of oracle work
             q, kn, vn = (kw.to_oracle(a[0:1]) for a in steps_in[(t - 1) % n_distinct])
             c0 = time.perf_counter()
             oc.decode_step(q, kn, vn, wl.n + t - 1, ko.tau(min(t, wl.T), wl.T, wl.tau_init, wl.tau_end),
