@@ -13,7 +13,7 @@
  *  - Every pointer marked DEVICE is GPU memory owned by the caller; the library
  *    never allocates, frees or keeps it.  Pointers marked HOST are read during
  *    the call only.
- *  - The three hot calls only enqueue kernels on `stream` (a hipStream_t passed
+ *  - The calls that take a stream only enqueue kernels on `stream` (a hipStream_t passed
  *    as void*, NULL = the default stream) and return; they do not synchronise.
  *  - Arguments are validated on the host before anything is launched; a call
  *    that returns an error has launched nothing.  kf_last_error() describes the
@@ -137,7 +137,7 @@ float kf_tau(int32_t t, int32_t T, float tau_init, float tau_end);
  * u = (2*(bits>>9)+1)/2^24 and the Gumbel variate of Eq. 7 is -ln(-ln u). */
 uint32_t kf_noise_bits(uint64_t seed, uint32_t layer, uint32_t head, uint32_t q_pos, uint32_t k_pos);
 
-/* Bytes of workspace that suffice for any of the three hot calls on this
+/* Bytes of workspace that suffice for any call of this library on this
  * cache, with prompt length up to n_max (pass 0 if kf_prefill_score is not
  * used).  Only the cache's dimensions are read. */
 size_t kf_workspace_bytes(const kf_cache *c, int32_t n_max);
@@ -223,9 +223,12 @@ kf_status kf_select_evict_into(const kf_cache *src, kf_cache *dst, int32_t dst_l
 /*
  * One whole generation step: kf_decode_step followed by kf_select_evict, with
  * the same arguments, results and error behaviour as the two calls in a row,
- * in two kernel launches instead of three (the merge of the decode kernel's
- * split-wise results rides in the selection kernel).  Algorithm 1, one
- * iteration of the else-branch including the S_w / S_key / S_k lines.
+ * in as few kernel launches as the shape allows: one in the slot layout when
+ * every unit is handled by a single workgroup (that workgroup also evicts and
+ * stores the new token straight into the freed slot), else the merge of the
+ * decode kernel's split-wise results rides in the selection kernel where that
+ * pays.  Algorithm 1, one iteration of the else-branch including the S_w /
+ * S_key / S_k lines.
  */
 kf_status kf_decode_select_step(kf_cache *c, const void *q, const void *k_new, const void *v_new,
                                 int32_t q_pos, int32_t m_hint, const kf_score_cfg *cfg, float *out,
