@@ -120,6 +120,9 @@ typedef struct {
     const float *seq_tau;      /* DEVICE [B] or NULL.  Decode only: sequence b's temperature of this
                                   step (Eq. 12 with its own t and T) instead of tau; every entry
                                   must be finite and positive (not checked: device memory)      */
+    const int32_t *seq_n;      /* DEVICE [B] or NULL.  Prompt scoring only: sequence b's prompt has
+                                  seq_n[b] tokens, rows seq_n[b]..n-1 of its Q and K are padding
+                                  (a batch of prompts of different lengths, padded at the end)   */
 } kf_score_cfg;
 
 /* Library version, for the binding to check it loaded what it expects. */
@@ -163,6 +166,11 @@ kf_status kf_decode_launch_shape(const kf_cache *c, int32_t m_hint, int32_t *spl
  *     z_i  = softmax_j((x_ij + zeta_ij)/tau)                    (Eq. 4, Eq. 11)
  *     score[j] = sum_{i>=j} z_ij ;  pos[j] = j ;  len = n
  * Q is DEVICE [L][B][H][n][d] in the cache's dtype.  V is not touched.
+ * With cfg->seq_n every unit of sequence b is scored over its own first
+ * n_b = seq_n[b] rows exactly as if it had been passed alone with n = n_b (the
+ * padding rows are neither queries nor keys; score and pos beyond n_b are left
+ * as they were; len = n_b); Q keeps the row stride n.  A sequence whose seq_n[b]
+ * lies outside [1, n] is skipped and each of its units counted in the error word.
  * Errors: KF_EINVAL if n < 1 or n > cap, tau not finite or <= 0, null pointers,
  * seeds missing for a random adjustment.
  */

@@ -121,11 +121,26 @@ class OracleCache:
                 assert a.flags["C_CONTIGUOUS"]
 
     def prefill_score(self, Q, n, tau_, scale, noise=NOISE_GUMBEL, seeds=None, slopes=None, shared=False,
-                      q_per_kv=1):
+                      q_per_kv=1, n_seq=None):
         """Q: [L,B,H*q_per_kv,n,d] same element type as K; K rows 0..n-1 must be filled.
         shared: one score function for all layers (the sum of the layers' scores).
-        q_per_kv: query heads per cached head (grouped-query attention)."""
+        q_per_kv: query heads per cached head (grouped-query attention).
+        n_seq: [B] prompt length of every sequence of a batch padded to n rows: a sequence is
+        scored on its own first n_seq[b] rows, by itself, exactly as if the padding did not exist."""
         assert Q.shape == (self.L, self.B, self.H * q_per_kv, n, self.d) and _dtype_code(Q) == self.dtype
+        if n_seq is not None:
+            assert len(n_seq) == self.B
+            for b in range(self.B):
+                nb = int(n_seq[b])
+                assert 1 <= nb <= n
+                one = OracleCache(self.L, 1, self.H, self.d, self.cap, self.dtype, self.layer0)
+                for nm in ("K", "V", "score", "pos", "len"):
+                    setattr(one, nm, np.ascontiguousarray(getattr(self, nm)[:, b:b + 1]))
+                one.prefill_score(np.ascontiguousarray(Q[:, b:b + 1, :, :nb]), nb, tau_, scale, noise,
+                                  None if seeds is None else np.asarray(seeds)[b:b + 1], slopes, shared, q_per_kv)
+                for nm in ("score", "pos", "len"):
+                    getattr(self, nm)[:, b:b + 1] = getattr(one, nm)
+            return
         seeds = None if seeds is None else np.ascontiguousarray(seeds, np.uint64)
         slopes = None if slopes is None else np.ascontiguousarray(slopes, np.float32)
         Q = np.ascontiguousarray(Q)

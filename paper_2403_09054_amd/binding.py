@@ -42,7 +42,8 @@ class kf_cache(C.Structure):
 class kf_score_cfg(C.Structure):
     _fields_ = [("tau", C.c_float), ("scale", C.c_float), ("noise", C.c_int32),
                 ("seeds", C.c_void_p), ("alibi_slopes", C.c_void_p), ("pos_mode", C.c_int32),
-                ("score_mode", C.c_int32), ("seq_q_pos", C.c_void_p), ("seq_tau", C.c_void_p)]
+                ("score_mode", C.c_int32), ("seq_q_pos", C.c_void_p), ("seq_tau", C.c_void_p),
+                ("seq_n", C.c_void_p)]
 
 
 class kf_schedule(C.Structure):
@@ -201,15 +202,17 @@ def _ws(workspace):
     return workspace.data_ptr(), workspace.numel() * workspace.element_size()
 
 
-def _cfg(tau, scale, noise, seeds, slopes, pos_mode=0, score_mode=0, seq_q_pos=None, seq_tau=None) -> kf_score_cfg:
+def _cfg(tau, scale, noise, seeds, slopes, pos_mode=0, score_mode=0, seq_q_pos=None, seq_tau=None,
+         seq_n=None) -> kf_score_cfg:
     return kf_score_cfg(tau, scale, noise, _ptr(seeds), _ptr(slopes), pos_mode, score_mode, _ptr(seq_q_pos),
-                        _ptr(seq_tau))
+                        _ptr(seq_tau), _ptr(seq_n))
 
 
 def kf_prefill_score(cache: Cache, Q, n: int, tau: float, scale: float, noise: int = NOISE_GUMBEL,
                      seeds=None, slopes=None, workspace=None, stream=None,
-                     score_mode: int = SCORE_PER_LAYER) -> None:
-    cs, cfg = cache.c_struct(), _cfg(tau, scale, noise, seeds, slopes, 0, score_mode)
+                     score_mode: int = SCORE_PER_LAYER, seq_n=None) -> None:
+    """seq_n: int32 device tensor [B] of per-sequence prompt lengths (prompts padded to n), or None."""
+    cs, cfg = cache.c_struct(), _cfg(tau, scale, noise, seeds, slopes, 0, score_mode, seq_n=seq_n)
     wp, wb = _ws(workspace)
     _check(lib().kf_prefill_score(C.byref(cs), _ptr(Q), n, C.byref(cfg), wp, wb, _stream(stream)))
 

@@ -199,6 +199,8 @@ kf_status kf_prefill_score(const kf_cache* c, const void* Q, int32_t n, const kf
     a.len = c->len;
     a.seeds = cfg->seeds;
     a.slopes = cfg->alibi_slopes;
+    a.seq_n = cfg->seq_n;
+    a.ws_err = (int32_t*)workspace + KF_WS_ERROR_WORD;
     a.ws_c = (float*)((char*)workspace + w.region);
     a.ws_r = (uint32_t*)((char*)workspace + w.region + align_up((size_t)U * n_pad * sizeof(float), 256));
     a.ws_f = (float*)((char*)workspace + w.region + 2 * align_up((size_t)U * n_pad * sizeof(float), 256));

@@ -139,6 +139,8 @@ struct PrefillArgs {
     int32_t* len;
     const uint64_t* seeds;
     const float* slopes;
+    const int32_t* seq_n;  // [B] per-sequence prompt length, or null: every sequence has n rows
+    int32_t* ws_err;       // device error counter
     float* ws_c;        // [U][n_pad] per-row log2 normaliser            (U = L*B*H query units)
     uint32_t* ws_r;     // [U][n_pad] per-row noise key
     float* ws_f;        // [U][n_pad] per-query-head column sums (G > 1 only)

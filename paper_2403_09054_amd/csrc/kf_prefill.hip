@@ -143,12 +143,14 @@ __global__ void __launch_bounds__(kPrefillThreads) prefill_rowstats_kernel(const
     unit_and_block(nblk, u, blk);
     if (u >= units) return;  // workgroup-uniform
     const int rb = nblk - 1 - blk;  // longest rows first
-    const int n = a.n;
+    const int h = (int)(u % a.H), b = (int)((u / a.H) % a.B), l = a.layer0 + (int)(u / ((int64_t)a.H * a.B));
+    const int n = a.seq_n ? a.seq_n[b] : a.n;  // this sequence's prompt length; rows n..a.n-1 are padding
+    // workgroup-uniform exits: a length out of range (the second pass reports it), a block inside the padding
+    if (n < 1 || n > a.n || rb * (4 * kTile) >= n) return;
     const int i0 = rb * (4 * kTile) + wv * kTile;
     const bool active = i0 < n;  // wave-uniform; inactive waves still fetch tiles and meet the barriers
-    const int h = (int)(u % a.H), b = (int)((u / a.H) % a.B), l = a.layer0 + (int)(u / ((int64_t)a.H * a.B));
     const int i = i0 + n0;
-    const T* Qu = (const T*)a.Q + (size_t)u * n * D;
+    const T* Qu = (const T*)a.Q + (size_t)u * a.n * D;
     const T* Ku = (const T*)a.K + (size_t)(u / a.G) * a.cap * D;  // G query heads read one cached head
 
     uint4 bq[NG];
@@ -253,14 +255,19 @@ __global__ void __launch_bounds__(kPrefillThreads) prefill_colsum_kernel(const P
     int cb;  // longest columns (lowest keys) first
     unit_and_block(nblk, u, cb);
     if (u >= units) return;  // workgroup-uniform
-    const int n = a.n;
-    const int j0 = cb * (4 * kTile) + wv * kTile;
+    const int h = (int)(u % a.H), b = (int)((u / a.H) % a.B);
+    const int n = a.seq_n ? a.seq_n[b] : a.n;  // this sequence's prompt length; rows n..a.n-1 are padding
     const bool first_of_group = (u % a.G) == 0;
+    if (n < 1 || n > a.n) {  // workgroup-uniform: the unit is skipped and counted
+        if (cb == 0 && threadIdx.x == 0 && first_of_group) atomicAdd(a.ws_err, 1);
+        return;
+    }
     if (cb == 0 && threadIdx.x == 0 && first_of_group) a.len[u / a.G] = n;
+    if (cb * (4 * kTile) >= n) return;  // workgroup-uniform: the block lies in the padding
+    const int j0 = cb * (4 * kTile) + wv * kTile;
     const bool active = j0 < n;  // wave-uniform; inactive waves still fetch tiles and meet the barriers
-    const int h = (int)(u % a.H);
     const int j = j0 + n0;
-    const T* Qu = (const T*)a.Q + (size_t)u * n * D;
+    const T* Qu = (const T*)a.Q + (size_t)u * a.n * D;
     const T* Ku = (const T*)a.K + (size_t)(u / a.G) * a.cap * D;  // G query heads read one cached head
 
     uint4 bk[NG];
@@ -367,7 +374,10 @@ __global__ void __launch_bounds__(kPrefillThreads) prefill_colsum_kernel(const P
 __global__ void __launch_bounds__(256) prefill_group_sum_kernel(const PrefillArgs a, int64_t kv_units) {
     const int64_t u = blockIdx.x;
     const int j = blockIdx.y * 256 + threadIdx.x;
-    if (u >= kv_units || j >= a.n) return;
+    if (u >= kv_units) return;
+    const int hkv = a.H / a.G, b = (int)((u / hkv) % a.B);
+    const int n = a.seq_n ? a.seq_n[b] : a.n;
+    if (n > a.n || j >= n) return;
     float s = 0.0f;
     for (int g = 0; g < a.G; ++g) s += a.ws_f[((size_t)u * a.G + g) * a.n_pad + j];
     a.score[(size_t)u * a.cap + j] = s;

@@ -258,6 +258,113 @@ def test_prefill_score_matches_oracle(dtype, d, n):
         assert_close_score(host(gc.score), oc.score, oc.len, "prefill noise=%d" % noise)
 
 
+@pytest.mark.parametrize("dtype,d,G,shared", [(ko.BF16, 128, 1, False), (ko.BF16, 256, 1, False), (ko.F32, 64, 1, False),
+                                              (ko.BF16, 64, 4, False), (ko.BF16, 128, 1, True)])
+def test_prefill_of_a_padded_batch_matches_oracle(dtype, d, G, shared):
+    """Prompts of different lengths padded to n rows (cfg.seq_n): every sequence is scored over its own rows."""
+    rng = np.random.default_rng(500 + d + G)
+    L, H, n = 2, 2, 300
+    n_seq = np.array([300, 1, 129, 37, 128, 256], np.int32)
+    B = len(n_seq)
+    oc = random_cache(rng, L, B, H, d, n + 5, dtype, 3)
+    oc.score[...] = -3.0
+    oc.pos[...] = -7
+    Q = rnd(rng, (L, B, H * G, n, d), dtype)
+    seeds = (np.arange(B) * 1000 + 3).astype(np.uint64)
+    slopes = (0.5 ** np.arange(1, H * G + 1)).astype(np.float32)
+    scale = float(1.0 / np.sqrt(np.float32(d)))
+    gc = upload(oc, G)
+    ws = kf.new_workspace(gc, n)
+    kf.kf_prefill_score(gc, dev(Q), n, 1.0, scale, kf.NOISE_GUMBEL, dev(seeds), dev(slopes), ws,
+                        score_mode=kf.SCORE_SHARED if shared else kf.SCORE_PER_LAYER, seq_n=dev(n_seq))
+    torch.cuda.synchronize()
+    assert error_word(ws) == 0
+    oc.prefill_score(Q, n, 1.0, scale, ko.NOISE_GUMBEL, seeds, slopes, shared=shared, q_per_kv=G, n_seq=n_seq)
+    assert (oc.len == n_seq[None, :, None]).all()
+    np.testing.assert_array_equal(host(gc.len), oc.len)
+    np.testing.assert_array_equal(host(gc.pos), oc.pos)                     # -7 kept beyond every prompt's end
+    assert_close_score(host(gc.score), oc.score, oc.len, "padded batch")
+    for b in range(B):
+        assert (host(gc.score)[:, b, :, n_seq[b]:] == -3.0).all()
+
+
+def test_prefill_of_a_padded_batch_reports_lengths_out_of_range():
+    rng = np.random.default_rng(501)
+    L, B, H, d, n = 2, 3, 2, 64, 70
+    oc = random_cache(rng, L, B, H, d, n + 2, ko.BF16, 9)
+    Q = rnd(rng, (L, B, H, n, d), ko.BF16)
+    n_seq = np.array([0, 71, 33], np.int32)
+    seeds = np.array([1, 2, 3], np.uint64)
+    gc = upload(oc)
+    ws = kf.new_workspace(gc, n)
+    kf.kf_prefill_score(gc, dev(Q), n, 1.0, 0.125, kf.NOISE_GUMBEL, dev(seeds), None, ws, seq_n=dev(n_seq))
+    torch.cuda.synchronize()
+    assert error_word(ws) == 2 * L * H                                      # every unit of the two sequences
+    ref = oc.copy()
+    one = ko.OracleCache(L, 1, H, d, n + 2, ko.BF16)
+    for nm in ("K", "V", "score", "pos", "len"):
+        getattr(one, nm)[...] = getattr(oc, nm)[:, 2:3]
+    one.prefill_score(np.ascontiguousarray(Q[:, 2:3, :, :33]), 33, 1.0, 0.125, ko.NOISE_GUMBEL, seeds[2:3])
+    for nm in ("score", "pos", "len"):
+        getattr(ref, nm)[:, 2:3] = getattr(one, nm)
+    np.testing.assert_array_equal(host(gc.len), ref.len)                    # skipped units keep their state
+    np.testing.assert_array_equal(host(gc.pos), ref.pos)
+    np.testing.assert_array_equal(host(gc.score)[:, :2], ref.score[:, :2])
+    assert_close_score(host(gc.score), ref.score, ref.len)
+
+
+@pytest.mark.parametrize("layout", [kf.LAYOUT_ORDERED, kf.LAYOUT_SLOT])
+def test_padded_batch_from_prompt_through_generation(layout):
+    """Sequences with prompts of 40..700 tokens in one batch: prompt scoring with seq_n, the first eviction
+    (only the prompts over budget lose tokens), then steps in which every sequence is at its own position."""
+    rng = np.random.default_rng(502)
+    L, H, d, n, k, w, T = 1, 4, 128, 700, 200, 40, 16
+    n_seq = np.array([700, 40, 201, 333], np.int32)
+    B = len(n_seq)
+    cap = n
+    oc = ko.OracleCache(L, B, H, d, cap, ko.BF16)
+    oc.K[...] = rnd(rng, oc.K.shape, ko.BF16)
+    oc.V[...] = rnd(rng, oc.V.shape, ko.BF16)
+    Q = rnd(rng, (L, B, H, n, d), ko.BF16)
+    seeds = np.array([11, 12, 13, 14], np.uint64)
+    slopes = (0.5 ** np.arange(1, H + 1)).astype(np.float32)
+    scale = float(1.0 / np.sqrt(np.float32(d)))
+    gc = upload(oc)
+    ws = kf.new_workspace(gc, n)
+    kf.kf_prefill_score(gc, dev(Q), n, kf.kf_tau(0, T), scale, kf.NOISE_GUMBEL, dev(seeds), dev(slopes), ws, seq_n=dev(n_seq))
+    oc.prefill_score(Q, n, ko.tau(0, T), scale, ko.NOISE_GUMBEL, seeds, slopes, n_seq=n_seq)
+    kept = torch.zeros((L, B, H, k), dtype=torch.int32, device="cuda")
+    before_score, before_len = oc.score.copy(), oc.len.copy()
+    kf.kf_select_evict(gc, k, w, kept, ws)                                  # ordered: also what the slot layout starts from
+    kept_ref = oc.select_evict(k, w)
+    torch.cuda.synchronize()
+    assert error_word(ws) == 0
+    assert compare_kept(host(kept), kept_ref, before_score, before_len, k, w) == 0
+    assert (oc.len == np.minimum(n_seq, k)[None, :, None]).all()
+    assert_state_equal(gc, oc, kv=True, score_exact=False)
+    out = torch.zeros((L, B, H, d), dtype=torch.float32, device="cuda")
+    for t in range(1, T + 1):
+        q, kn, vn = (rnd(rng, (L, B, H, d), ko.BF16) for _ in range(3))
+        q_pos = (n_seq + t - 1).astype(np.int32)
+        taus = np.full(B, kf.kf_tau(t, T), np.float32)
+        kf.kf_decode_select_step(gc, dev(q), dev(kn), dev(vn), 0, 0, 1.0, scale, kf.NOISE_GUMBEL, dev(seeds), dev(slopes),
+                                 out, k=k, w=w, layout=layout, kept_idx=kept, workspace=ws, seq_q_pos=dev(q_pos),
+                                 seq_tau=dev(taus))
+        torch.cuda.synchronize()
+        assert error_word(ws) == 0
+        out_ref = oc.decode_step(q, kn, vn, 0, 1.0, scale, ko.NOISE_GUMBEL, seeds, slopes, q_pos_seq=q_pos, tau_seq=taus)
+        assert_close_out(host(out), out_ref, "out step %d" % t)
+        before_score, before_len = oc.score.copy(), oc.len.copy()
+        kept_ref = oc.select_evict(k, w)
+        if layout == kf.LAYOUT_ORDERED:
+            assert compare_kept(host(kept), kept_ref, before_score, before_len, k, w) == 0
+            assert_state_equal(gc, oc, kv=True, score_exact=False)
+            assert_close_score(host(gc.score), oc.score, oc.len, "score step %d" % t)
+        else:
+            assert_set_equal(gc, oc, kv=True, score_exact=False)
+    assert (oc.len == np.minimum(n_seq + T, k)[None, :, None]).all()      # the short prompt is still growing
+
+
 # ------------------------------------------------------------------ the five configurations
 def test_tiny_config_full_lockstep_and_free_running():
     wl = kw.CONFIGS["tiny"]

@@ -387,6 +387,49 @@ def test_prefill_first_row_and_uniform_case():
     np.testing.assert_allclose(c.score[0, 0, 0], ref, rtol=3e-7)
 
 
+def test_prefill_of_a_padded_batch_scores_every_prompt_by_itself():
+    # a batch of prompts of different lengths, padded at the end to n rows (the paper's performance runs
+    # make all prompts equally long; a serving batch is not): every sequence's f is the numpy column sum
+    # over ITS rows only -- the padding rows are neither queries nor keys -- whatever the padding holds;
+    # equal lengths reproduce the plain call
+    rng = np.random.default_rng(13)
+    L, B, H, d, n, cap = 2, 3, 2, 16, 29, 32
+    n_seq = np.array([29, 1, 12])
+    c = make_cache(rng, L, B, H, d, cap, n, ko.BF16)
+    Q = rand_vec(rng, (L, B, H, n, d), ko.BF16)
+    seeds = np.array([5, 6, 7], np.uint64)
+    slopes = np.array([0.0, 0.25], np.float32)
+    tau, scale = 1.0, 0.25
+    plain = c.copy()
+    plain.prefill_score(Q, n, tau, scale, ko.NOISE_GUMBEL, seeds, slopes)
+    same = c.copy()
+    same.prefill_score(Q, n, tau, scale, ko.NOISE_GUMBEL, seeds, slopes, n_seq=[n] * B)
+    np.testing.assert_array_equal(same.score, plain.score)
+    c.score[...] = -3.0
+    c.pos[...] = -7
+    r1 = c.copy()
+    r1.prefill_score(Q, n, tau, scale, ko.NOISE_GUMBEL, seeds, slopes, n_seq=n_seq)
+    c2, Q2 = c.copy(), Q.copy()
+    for b in range(B):     # other padding
+        c2.K[:, b, :, n_seq[b]:] = rand_vec(rng, c2.K[:, b, :, n_seq[b]:].shape, ko.BF16)
+        Q2[:, b, :, n_seq[b]:] = rand_vec(rng, Q2[:, b, :, n_seq[b]:].shape, ko.BF16)
+    r2 = c2.copy()
+    r2.prefill_score(Q2, n, tau, scale, ko.NOISE_GUMBEL, seeds, slopes, n_seq=n_seq)
+    np.testing.assert_array_equal(r1.score, r2.score)
+    for l, b, h in itertools.product(range(L), range(B), range(H)):
+        nb = int(n_seq[b])
+        assert r1.len[l, b, h] == nb
+        assert (r1.pos[l, b, h, :nb] == np.arange(nb)).all() and (r1.pos[l, b, h, nb:] == -7).all()
+        assert (r1.score[l, b, h, nb:] == -3.0).all()                     # beyond the prompt: untouched
+        i, j = np.meshgrid(np.arange(nb), np.arange(nb), indexing="ij")
+        x = np.float64(np.float32(scale)) * (as_f64(Q[l, b, h, :nb]) @ as_f64(c.K[l, b, h, :nb]).T)
+        x = x - float(slopes[h]) * (i - j)
+        y = (x + zeta_matrix(ko.NOISE_GUMBEL, int(seeds[b]), l, h, range(nb), range(nb))) / tau
+        f_ref = scipy.special.softmax(np.where(j <= i, y, -np.inf), axis=1).sum(axis=0)
+        np.testing.assert_allclose(r1.score[l, b, h, :nb], f_ref, rtol=3e-7)
+        assert abs(r1.score[l, b, h, :nb].astype(np.float64).sum() - nb) < 1e-4
+
+
 # ----------------------------------------------------------------------------
 # "Shared" score function (Sec. 4.4.1): one f for all layers, accumulated over
 # layers and decoding steps
