@@ -24,6 +24,8 @@
 namespace kf {
 
 constexpr int kDecodeThreads = 256;
+constexpr int kDecodeThreadsBig = 1024;  // one workgroup per CU with most of its LDS: 8 query heads, one split
+constexpr int kDecodeRedWaves = 4;       // rows of LDS in which a workgroup's waves fold their partial outputs
 constexpr int kDecodeMaxChunk = 4096;   // tokens per split the LDS arrays are sized for
 constexpr int kDecodeMinBlocks = 1024;  // workgroups wanted on the chip
 constexpr int kComputeUnits = 256;                      // MI355X
@@ -32,6 +34,8 @@ constexpr int kDecodeMinChunk = 128;
 constexpr size_t kDecodeLdsBudget = 65536 - 1024;       // dynamic LDS of a split workgroup
 constexpr size_t kDecodeLdsPair = 81920 - 1024;         // ... of a single-split workgroup: two fit a CU's 160 KB
 constexpr int kDecodeSingleMinUnits = 320;              // units from which one workgroup per unit fills the chip
+constexpr size_t kDecodeLdsWhole = 163840 - 2048;       // ... of a workgroup that has a CU to itself
+constexpr int kDecodeBigMinUnits = 256;                 // units from which one such workgroup per unit fills the chip
 
 constexpr int kDecodeUnroll = 4;  // 16-byte loads a lane keeps in flight per tile (2 and 8 measured within 2 %)
 
@@ -86,42 +90,85 @@ struct QueryPiece<bf16_t> {
     }
 };
 
-// Block-wide max / sum of N values at once (one pair of barriers).
-template <int NT, int N>
-__device__ __forceinline__ void block_max_n(float (&v)[N], float* red /* [N*NT/64] */) {
+// One step of a reduce-scatter over lane groups O lanes apart: a lane keeps one half of its values, sends
+// the other half to its partner and adds what the partner sends -- half the exchanges of folding every value
+// both ways, and afterwards the halves are spread over the two groups.
+template <int N, int O>
+__device__ __forceinline__ void halve(const float (&in)[N], float (&out)[N / 2], int lane) {
+    static_assert(O == 8 || O == 16 || O == 32, "partner distances of a wave's rows");
+    const bool up = (lane & O) != 0;
 #pragma unroll
-    for (int i = 0; i < N; ++i) v[i] = wave_max(v[i]);
+    for (int i = 0; i < N / 2; ++i) {
+        const float keep = up ? in[N / 2 + i] : in[i];
+        const float send = up ? in[i] : in[N / 2 + i];
+        float recv;
+        if constexpr (O == 8) recv = dpp_move<0x128>(send);  // row_ror:8
+        else if constexpr (O == 16)
+            recv = __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, send), 0x401F));
+        else recv = __shfl_xor(send, 32, kWave);
+        out[i] = keep + recv;
+    }
+}
+
+// Wave-wide max / sum: the data-parallel moves fold a 16-lane row, two exchanges through the LDS crossbar
+// (lane ^ 16, lane ^ 32) fold the four rows.  Every lane ends up with the result.
+__device__ __forceinline__ float wave_max_fast(float v) {
+    v = fmaxf(v, dpp_move<0xB1>(v));
+    v = fmaxf(v, dpp_move<0x4E>(v));
+    v = fmaxf(v, dpp_move<0x141>(v));
+    v = fmaxf(v, dpp_move<0x140>(v));
+    v = fmaxf(v, __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, v), 0x401F)));
+    return fmaxf(v, __shfl_xor(v, 32, kWave));
+}
+__device__ __forceinline__ float wave_sum_fast(float v) {
+    v = group_sum<32>(v);
+    return v + __shfl_xor(v, 32, kWave);
+}
+
+// Block-wide max / sum of N values at once.  `red` holds N*NT/64 + N floats.  With few values and waves
+// every thread folds the waves' results itself (one pair of barriers); with many (8 query heads, 16 waves:
+// 256 LDS reads per thread that way) N threads fold them once and publish the N results.
+template <int NT, int N, bool IS_MAX>
+__device__ __forceinline__ void block_reduce_n(float (&v)[N], float* red) {
+    constexpr int NW = NT / 64;
+    constexpr bool kTwoLevel = N * NW > 32;
+#pragma unroll
+    for (int i = 0; i < N; ++i) v[i] = kTwoLevel ? (IS_MAX ? wave_max_fast(v[i]) : wave_sum_fast(v[i]))
+                                                 : (IS_MAX ? wave_max(v[i]) : wave_sum(v[i]));
     __syncthreads();
     if ((threadIdx.x & 63) == 0) {
 #pragma unroll
         for (int i = 0; i < N; ++i) red[N * (threadIdx.x >> 6) + i] = v[i];
     }
     __syncthreads();
+    if constexpr (kTwoLevel) {
+        float* res = red + N * NW;
+        if (threadIdx.x < N) {
+            float r = red[threadIdx.x];
 #pragma unroll
-    for (int i = 0; i < N; ++i) {
-        float r = red[i];
+            for (int w = 1; w < NW; ++w) r = IS_MAX ? fmaxf(r, red[N * w + threadIdx.x]) : r + red[N * w + threadIdx.x];
+            res[threadIdx.x] = r;
+        }
+        __syncthreads();
 #pragma unroll
-        for (int w = 1; w < NT / 64; ++w) r = fmaxf(r, red[N * w + i]);
-        v[i] = r;
+        for (int i = 0; i < N; ++i) v[i] = res[i];
+    } else {
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            float r = red[i];
+#pragma unroll
+            for (int w = 1; w < NW; ++w) r = IS_MAX ? fmaxf(r, red[N * w + i]) : r + red[N * w + i];
+            v[i] = r;
+        }
     }
 }
 template <int NT, int N>
+__device__ __forceinline__ void block_max_n(float (&v)[N], float* red) {
+    block_reduce_n<NT, N, true>(v, red);
+}
+template <int NT, int N>
 __device__ __forceinline__ void block_sum_n(float (&v)[N], float* red) {
-#pragma unroll
-    for (int i = 0; i < N; ++i) v[i] = wave_sum(v[i]);
-    __syncthreads();
-    if ((threadIdx.x & 63) == 0) {
-#pragma unroll
-        for (int i = 0; i < N; ++i) red[N * (threadIdx.x >> 6) + i] = v[i];
-    }
-    __syncthreads();
-#pragma unroll
-    for (int i = 0; i < N; ++i) {
-        float r = red[i];
-#pragma unroll
-        for (int w = 1; w < NT / 64; ++w) r += red[N * w + i];
-        v[i] = r;
-    }
+    block_reduce_n<NT, N, false>(v, red);
 }
 
 // Logits of a query group on the matrix cores.  With 8 bf16 query heads per
@@ -154,9 +201,11 @@ __device__ __forceinline__ void decode_block(const DecodeArgs& a) {
     constexpr int RPW = kWave / LPR;             // rows per wave-wide load
     constexpr int NW = NT / kWave;
     constexpr int RPB = RPW * NW;                // rows per block-wide load
-    constexpr int UNR = (G >= 8) ? 2 : kDecodeUnroll;  // independent loads in flight per lane (8 query heads: registers are short)
+    // independent loads in flight per lane (8 query heads: registers are short, the more so with 16 waves)
+    constexpr int UNR = (G >= 8) ? (NT >= 1024 ? 1 : 2) : kDecodeUnroll;
     constexpr int TILE = RPB * UNR;              // rows per tile of the workgroup
     constexpr int PW = D + 4;                    // floats in a partial record
+    constexpr bool BIG = NW > kDecodeRedWaves;  // a workgroup that has a CU to itself: one split, 8 query heads
     constexpr size_t ROWB = (size_t)D * sizeof(T);
     static_assert(LPR <= 32 && D <= NT, "row must fit half a wave, output a block");
 
@@ -164,8 +213,8 @@ __device__ __forceinline__ void decode_block(const DecodeArgs& a) {
     const int CS = a.chunk + 1;        // logits of the split's rows (+1: the new token)
     float* xs = smem;                  // [G][CS] logits, then attention weights
     float* ys = smem + G * CS;         // [G][CS] perturbed logits / tau, then their exponentials
-    float* red_o = ys + G * CS;        // [NW][G*D] per-wave output partials
-    __shared__ float red_s[2 * G * NW];
+    float* red_o = smem + ((2 * G * CS + 3) & ~3);  // [NW][G*D] output partials, 16-byte aligned (not BIG)
+    __shared__ __attribute__((aligned(16))) float red_s[2 * G * (NW + 2)];
     __shared__ float stat[4 * G];      // per query head: max x, sum p, max y, sum e
     __shared__ unsigned long long evict_min[NW];  // whole-step launch: per-wave smallest (score, position) pack
     __shared__ int evict_slot;
@@ -269,48 +318,99 @@ __device__ __forceinline__ void decode_block(const DecodeArgs& a) {
             bq[kk] = ((const uint4*)(qu + (size_t)min(mrow, G - 1) * D))[kk * 4 + c4];
             if (mrow >= G) bq[kk] = make_uint4(0u, 0u, 0u, 0u);
         }
+        // The MFMA leaves lane (mrow, c4) with the logits of head mrow for rows 4*c4 .. +3, and nothing of use
+        // in the lanes of the padding heads (mrow >= G).  Those take rows 4*c4+2, +3 over from lane mrow-8
+        // (one data-parallel move each), so that all 64 lanes apply position bias and logit adjustment to two
+        // logits each, right here, while the next rows are in flight: the vector units idle during the K
+        // stream, and the statistics pass after it (one more sweep over all G x rows logits, with the
+        // workgroup's memory pipeline empty) shrinks to the two running maxima kept per lane.
+        static_assert(G == 8, "the padding half of the 16 MFMA columns takes half of the real heads' rows");
+        const int g_l = mrow & (G - 1), r_l = (mrow >= G) ? 2 : 0;
+        const int hq_l = h * G + g_l;
+        const float slope_l = a.slopes ? a.slopes[hq_l] : 0.0f;
+        const bool rnd_l = (a.noise == kNoiseGumbel || a.noise == kNoiseGaussian);
+        const uint32_t rkey_l = rnd_l ? row_key(unit_key(a.seeds[b], (uint32_t)l, (uint32_t)hq_l), (uint32_t)q_pos) : 0u;
+        float mx_l = -INFINITY, my_l = -INFINITY;
         // rows past the split re-read its last row (the address stays inside the cache); their logits are dropped
-        auto load_rows = [&](int base, uint4(&raw)[KK]) {
-            const int row = min(base + wv * 16 + mrow, j1 - 1);
+        auto load_rows = [&](int base, uint4(&raw)[KK], int(&pos2)[2]) {
+            const int row = min(base + wv * 16 + mrow, j1 - 1);  // a wave's 16 rows of the workgroup's NW*16
             const uint4* p = (const uint4*)(Ku + (size_t)row * ROWB) + c4;
 #pragma unroll
             for (int kk = 0; kk < KK; ++kk) raw[kk] = stream_load(p + kk * 4);
+#pragma unroll
+            for (int r = 0; r < 2; ++r) pos2[r] = pu[min(base + wv * 16 + c4 * 4 + r_l + r, j1 - 1)];
         };
-        auto logits_of = [&](int base, const uint4(&raw)[KK]) {
+        auto logits_of = [&](int base, const uint4(&raw)[KK], const int(&pos2)[2]) {
             f32x4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
             for (int kk = 0; kk < KK; ++kk)
                 acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, raw[kk]),
                                                               __builtin_bit_cast(bf16x8_t, bq[kk]), acc, 0, 0, 0);
-            if (mrow < G) {
+            const float from2 = dpp_move<0x118>(acc[2]), from3 = dpp_move<0x118>(acc[3]);  // row_shr:8
+            const float v[2] = {mrow >= G ? from2 : acc[0], mrow >= G ? from3 : acc[1]};
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int row = base + wv * 16 + c4 * 4 + r;
-                    if (row < j1) xs[mrow * CS + row - j0] = acc[r] * a.scale;
+            for (int r = 0; r < 2; ++r) {
+                const int row = base + wv * 16 + c4 * 4 + r_l + r;
+                if (row < j1) {
+                    const int dist = a.new_pos ? (len0 - row) : (q_pos - pos2[r]);
+                    // base-2 domain: x2 = log2(e)*x, y2 = log2(e)*(x + zeta)/tau
+                    const float x = (v[r] * a.scale - slope_l * (float)dist) * kLog2e;
+                    const float y = (x + zeta_log2e(a.noise, rkey_l, (uint32_t)pos2[r])) * inv_tau;
+                    xs[g_l * CS + row - j0] = x;
+                    ys[g_l * CS + row - j0] = y;
+                    mx_l = fmaxf(mx_l, x);
+                    my_l = fmaxf(my_l, y);
                 }
             }
         };
         if (cnt_c > 0) {
             uint4 kcur[KK], knxt[KK];
+            int pcur[2], pnxt[2];
             int base = j0;
-            load_rows(base, kcur);
-            while (base + 4 * 16 < j1) {
-                load_rows(base + 4 * 16, knxt);
-                logits_of(base, kcur);
+            load_rows(base, kcur, pcur);
+            while (base + NW * 16 < j1) {
+                load_rows(base + NW * 16, knxt, pnxt);
+                logits_of(base, kcur, pcur);
 #pragma unroll
                 for (int kk = 0; kk < KK; ++kk) kcur[kk] = knxt[kk];
-                base += 4 * 16;
+                pcur[0] = pnxt[0];
+                pcur[1] = pnxt[1];
+                base += NW * 16;
             }
-            logits_of(base, kcur);
+            logits_of(base, kcur, pcur);
         }
-        if (owner && wv == 0) {  // the new token's own logits (distance 0: no position bias)
+        // the eight lanes of a head (mrow, mrow+8 in each of the four 16-lane rows) fold their maxima; row NW of
+        // the table takes the new token's own logits (distance 0: no position bias), or nothing
+        mx_l = fmaxf(mx_l, dpp_move<0x128>(mx_l));  // row_ror:8
+        my_l = fmaxf(my_l, dpp_move<0x128>(my_l));
+        mx_l = fmaxf(mx_l, __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, mx_l), 0x401F)));
+        my_l = fmaxf(my_l, __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, my_l), 0x401F)));
+        mx_l = fmaxf(mx_l, __shfl_xor(mx_l, 32, kWave));
+        my_l = fmaxf(my_l, __shfl_xor(my_l, 32, kWave));
+        if (lane < G) {
+            red_s[2 * G * wv + 2 * lane] = mx_l;
+            red_s[2 * G * wv + 2 * lane + 1] = my_l;
+        }
+        if (wv == 0) {
             const uint4 kv = ((const uint4*)knew)[cl];
 #pragma unroll
             for (int g = 0; g < G; ++g) {
                 QueryPiece<T> qg;
                 qg.load(((const uint4*)(qu + (size_t)g * D))[cl]);
                 const float p = group_sum<LPR>(qg.dot(kv));
-                if (lane == 0) xs[g * CS + cnt_c] = p * a.scale;
+                if (lane == 0) {
+                    float x = -INFINITY, y = -INFINITY;
+                    if (owner) {
+                        const int hq = h * G + g;
+                        const uint32_t rk = rnd_l ? row_key(unit_key(a.seeds[b], (uint32_t)l, (uint32_t)hq), (uint32_t)q_pos) : 0u;
+                        x = (p * a.scale) * kLog2e;
+                        y = (x + zeta_log2e(a.noise, rk, (uint32_t)q_pos)) * inv_tau;
+                        xs[g * CS + cnt_c] = x;
+                        ys[g * CS + cnt_c] = y;
+                    }
+                    red_s[2 * G * NW + 2 * g] = x;
+                    red_s[2 * G * NW + 2 * g + 1] = y;
+                }
             }
         }
     } else {
@@ -373,34 +473,48 @@ __device__ __forceinline__ void decode_block(const DecodeArgs& a) {
     __syncthreads();
 
     // ---- phase 1.5: position bias, logit adjustment, the two softmaxes' statistics
-    float slope[G];
-    uint32_t rkey[G];
-    const bool rnd = (a.noise == kNoiseGumbel || a.noise == kNoiseGaussian);
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-        const int hq = h * G + g;
-        slope[g] = a.slopes ? a.slopes[hq] : 0.0f;
-        rkey[g] = rnd ? row_key(unit_key(a.seeds[b], (uint32_t)l, (uint32_t)hq), (uint32_t)q_pos) : 0u;
-    }
     float mxy[2 * G];
+    if constexpr (MfmaLogits<T, G>::value) {
+        // adjusted in the K stream; the waves' maxima (and the new token's logits) wait in red_s
+        float* res = red_s + 2 * G * (NW + 1);
+        if (tid < 2 * G) {
+            float r = red_s[tid];
 #pragma unroll
-    for (int i = 0; i < 2 * G; ++i) mxy[i] = -INFINITY;
-    for (int t = tid; t < cnt; t += NT) {
-        const int pj = (t == cnt_c) ? q_pos : pu[j0 + t];  // t == cnt_c: the new token
-        const int dist = a.new_pos ? (len0 - (j0 + t)) : (q_pos - pj);  // the new token: 0 either way
-        const float fdist = (float)((t == cnt_c) ? 0 : dist);
+            for (int w2 = 1; w2 <= NW; ++w2) r = fmaxf(r, red_s[2 * G * w2 + tid]);
+            res[tid] = r;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < 2 * G; ++i) mxy[i] = res[i];
+    } else {
+        float slope[G];
+        uint32_t rkey[G];
+        const bool rnd = (a.noise == kNoiseGumbel || a.noise == kNoiseGaussian);
 #pragma unroll
         for (int g = 0; g < G; ++g) {
-            // base-2 domain: x2 = log2(e)*x, y2 = log2(e)*(x + zeta)/tau
-            const float x = (xs[g * CS + t] - slope[g] * fdist) * kLog2e;
-            const float y = (x + zeta_log2e(a.noise, rkey[g], (uint32_t)pj)) * inv_tau;
-            xs[g * CS + t] = x;
-            ys[g * CS + t] = y;
-            mxy[2 * g] = fmaxf(mxy[2 * g], x);
-            mxy[2 * g + 1] = fmaxf(mxy[2 * g + 1], y);
+            const int hq = h * G + g;
+            slope[g] = a.slopes ? a.slopes[hq] : 0.0f;
+            rkey[g] = rnd ? row_key(unit_key(a.seeds[b], (uint32_t)l, (uint32_t)hq), (uint32_t)q_pos) : 0u;
         }
+#pragma unroll
+        for (int i = 0; i < 2 * G; ++i) mxy[i] = -INFINITY;
+        auto adjust = [&](int t, int pj) {  // t == cnt_c: the new token
+            const int dist = a.new_pos ? (len0 - (j0 + t)) : (q_pos - pj);  // the new token: 0 either way
+            const float fdist = (float)((t == cnt_c) ? 0 : dist);
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                // base-2 domain: x2 = log2(e)*x, y2 = log2(e)*(x + zeta)/tau
+                const float x = (xs[g * CS + t] - slope[g] * fdist) * kLog2e;
+                const float y = (x + zeta_log2e(a.noise, rkey[g], (uint32_t)pj)) * inv_tau;
+                xs[g * CS + t] = x;
+                ys[g * CS + t] = y;
+                mxy[2 * g] = fmaxf(mxy[2 * g], x);
+                mxy[2 * g + 1] = fmaxf(mxy[2 * g + 1], y);
+            }
+        };
+        for (int t = tid; t < cnt; t += NT) adjust(t, (t == cnt_c) ? q_pos : pu[j0 + t]);
+        block_max_n<NT, 2 * G>(mxy, red_s);
     }
-    block_max_n<NT, 2 * G>(mxy, red_s);
     float spe[2 * G];
 #pragma unroll
     for (int i = 0; i < 2 * G; ++i) spe[i] = 0.0f;
@@ -476,29 +590,73 @@ __device__ __forceinline__ void decode_block(const DecodeArgs& a) {
             for (int e = 0; e < EPV; ++e) acc[g][e] = fmaf(p, vvals[e], acc[g][e]);
         }
     }
-    // rows of one wave-wide load live in different lane groups: fold them
+    // Partial outputs of the waves meet in LDS.  Few accumulators per lane: the rows of one wave-wide load
+    // (RPW lane groups) are folded with exchanges, lane group 0 stores.  Many (8 query heads): the fold is a
+    // reduce-scatter, every lane group ends up with 1/RPW of the sums and stores those.  A workgroup of 16
+    // waves stores later, into the logit area, once nobody reads logits any more (see below).
+    constexpr int HV = G * EPV / RPW;  // sums a lane holds after the reduce-scatter
+    float fin[G >= 8 ? HV : 1];
+    int off = 0;
+    auto store_fin = [&](float* row) {  // this lane's sums -> its places in a [G][D] row of partial outputs
+        if constexpr (G >= 8) {
 #pragma unroll
-    for (int o = LPR; o < kWave; o <<= 1) {
-#pragma unroll
-        for (int g = 0; g < G; ++g) {
-#pragma unroll
-            for (int e = 0; e < EPV; ++e) acc[g][e] += __shfl_xor(acc[g][e], o, kWave);
+            for (int i4 = 0; i4 < HV / 4; ++i4) {
+                const int fi = off + 4 * i4;
+                *(float4*)&row[(fi / EPV) * D + cl * EPV + (fi % EPV)] =
+                    make_float4(fin[4 * i4], fin[4 * i4 + 1], fin[4 * i4 + 2], fin[4 * i4 + 3]);
+            }
         }
-    }
-    if (sub == 0) {
+    };
+    if constexpr (G >= 8) {
+        constexpr int N = G * EPV;
+        static_assert(HV % EPV == 0 && EPV % 4 == 0, "a lane group ends up with whole output-row pieces");
+        float flat[N];
 #pragma unroll
-        for (int g = 0; g < G; ++g) {
-#pragma unroll
-            for (int e = 0; e < EPV; ++e) red_o[(wv * G + g) * D + cl * EPV + e] = acc[g][e];
+        for (int i = 0; i < N; ++i) flat[i] = acc[i / EPV][i % EPV];
+        off = (lane & 32) ? N / 2 : 0;
+        if constexpr (RPW == 2) {
+            halve<N, 32>(flat, fin, lane);
+        } else if constexpr (RPW == 4) {
+            float t1[N / 2];
+            halve<N, 32>(flat, t1, lane);
+            halve<N / 2, 16>(t1, fin, lane);
+            off += (lane & 16) ? HV : 0;
+        } else {
+            static_assert(RPW == 8, "2, 4 or 8 rows per wave-wide load");
+            float t1[N / 2], t2[N / 4];
+            halve<N, 32>(flat, t1, lane);
+            halve<N / 2, 16>(t1, t2, lane);
+            halve<N / 4, 8>(t2, fin, lane);
+            off += ((lane & 16) ? N / 4 : 0) + ((lane & 8) ? HV : 0);
         }
+        if constexpr (!BIG) {
+            store_fin(red_o + (size_t)wv * G * D);
+            __syncthreads();  // red_o and stat are complete
+        }
+    } else {
+        static_assert(!BIG, "a 16-wave workgroup is built for 8 query heads");
+#pragma unroll
+        for (int o = LPR; o < kWave; o <<= 1) {
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+#pragma unroll
+                for (int e = 0; e < EPV; ++e) acc[g][e] += __shfl_xor(acc[g][e], o, kWave);
+            }
+        }
+        if (sub == 0) {
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+#pragma unroll
+                for (int e = 0; e < EPV; ++e) red_o[(wv * G + g) * D + cl * EPV + e] = acc[g][e];
+            }
+        }
+        __syncthreads();  // red_o and stat are complete
     }
-    __syncthreads();  // red_o and stat are complete
-
     if (S == 1) {
         // the whole unit is here: accumulate the normalised score increment of all its query heads
         float inv[G];
 #pragma unroll
-        for (int g = 0; g < G; ++g) inv[g] = 1.0f / spe[2 * g + 1];
+        for (int g = 0; g < G; ++g) inv[g] = 1.0f / (G >= 8 ? stat[4 * g + 3] : spe[2 * g + 1]);  // many heads: not kept in registers across the V stream
         float* we = a.ws_e + (size_t)u * G * a.cap;
         // whole-step launch: this lane's smallest candidate, as (order-preserving score key, ~position):
         // the lowest score leaves, the highest position among equal scores (lower positions are kept)
@@ -535,10 +693,19 @@ __device__ __forceinline__ void decode_block(const DecodeArgs& a) {
             else if (t == cnt_c) fu[slot] = df;
             else unsafeAtomicAdd(&fu[slot], df);
         }
+        const float* orows = red_o;
+        if constexpr (BIG) {
+            // 16 waves' partial outputs (64 KB and more) take the place of the logits: every wave is past the
+            // V stream (attention weights in xs) and the loop above (increments in ys) after this barrier
+            __syncthreads();
+            store_fin(smem + (size_t)wv * G * D);
+            __syncthreads();
+            orows = smem;
+        }
         for (int c = tid; c < G * D; c += NT) {
             float o_c = 0.0f;
 #pragma unroll
-            for (int w2 = 0; w2 < NW; ++w2) o_c += red_o[w2 * G * D + c];
+            for (int w2 = 0; w2 < NW; ++w2) o_c += orows[w2 * G * D + c];
             a.out[u * G * D + c] = o_c / stat[4 * (c / D) + 1];
         }
         if (!evict_here) {
@@ -600,6 +767,7 @@ __device__ __forceinline__ void decode_block(const DecodeArgs& a) {
         return;
     }
     // ---- S > 1: leave the un-normalised increments and a partial record per query head for the merge
+    if constexpr (BIG) return;  // never launched that way: a 16-wave workgroup takes a whole unit
     {
         float* we = a.ws_e + (size_t)u * G * a.cap;
         for (int t = tid; t < cnt; t += NT) {
@@ -702,7 +870,13 @@ static int rows_per_block(int32_t d, int32_t dtype) {
 }
 
 static size_t decode_lds_bytes(int32_t G, int64_t chunk, int32_t d) {
-    return (size_t)(2 * G * (chunk + 1) + (kDecodeThreads / kWave) * G * d) * sizeof(float);
+    return (size_t)(2 * G * (chunk + 1) + 3 + kDecodeRedWaves * G * d) * sizeof(float);
+}
+// ... of the 16-wave workgroup: its waves' partial outputs reuse the logit area
+static size_t decode_lds_bytes_big(int32_t G, int64_t chunk, int32_t d) {
+    const size_t logits = (size_t)(2 * G * (chunk + 1) + 3) * sizeof(float);
+    const size_t outs = (size_t)(kDecodeThreadsBig / kWave) * G * d * sizeof(float);
+    return logits > outs ? logits : outs;
 }
 
 // Chooses the number of splits S of a unit's token range.
@@ -728,6 +902,16 @@ DecodePlan plan_decode(int64_t U, int32_t m, int32_t d, int32_t dtype, int32_t G
     DecodePlan p;
     const int rpb = rows_per_block(d, dtype);
     const int64_t rows = m > 1 ? m - 1 : 1;  // cache rows; the new token rides with the last split
+    if (G == 8 && dtype == KF_BF16 && U >= kDecodeBigMinUnits) {
+        // one 1024-thread workgroup per CU, the unit's 2 x 8 logit rows in most of the CU's LDS
+        const int64_t chunk = (rows + rpb - 1) / rpb * rpb;
+        if (decode_lds_bytes_big(G, chunk, d) <= kDecodeLdsWhole) {
+            p.S = 1;
+            p.chunk = (int32_t)chunk;
+            p.lds_bytes = decode_lds_bytes_big(G, chunk, d);
+            return p;
+        }
+    }
     if (G <= 4 && U >= kDecodeSingleMinUnits) {
         const int64_t chunk = (rows + rpb - 1) / rpb * rpb;
         if (decode_lds_bytes(G, chunk, d) <= kDecodeLdsPair) {
@@ -738,7 +922,7 @@ DecodePlan plan_decode(int64_t U, int32_t m, int32_t d, int32_t dtype, int32_t G
         }
     }
     // LDS of a split workgroup: within 64 KB less the small static arrays
-    const int lds_rows = (int)((kDecodeLdsBudget - (size_t)(kDecodeThreads / kWave) * G * d * sizeof(float)) /
+    const int lds_rows = (int)((kDecodeLdsBudget - 3 * sizeof(float) - (size_t)kDecodeRedWaves * G * d * sizeof(float)) /
                                (2 * G * sizeof(float))) - 1;
     int max_chunk = kDecodeMaxChunk / G;
     if (lds_rows < max_chunk) max_chunk = lds_rows / rpb * rpb;
@@ -776,6 +960,15 @@ DecodePlan plan_decode(int64_t U, int32_t m, int32_t d, int32_t dtype, int32_t G
 template <typename T, int D, int G>
 static hipError_t launch_decode_g(const DecodeArgs& a, int64_t U, size_t lds, hipStream_t st, bool merge) {
     const dim3 grid((unsigned)(U * a.S)), block(kDecodeThreads);
+    if constexpr (G == 8 && MfmaLogits<T, G>::value) {
+        if (a.S == 1) {  // one split with 8 query heads: a CU-filling workgroup per unit
+            const size_t lds_big = decode_lds_bytes_big(G, a.chunk, D);
+            if (lds_big > kDecodeLdsWhole) return hipErrorInvalidValue;
+            hipLaunchKernelGGL((decode_kernel<T, D, kDecodeThreadsBig, G>), grid, dim3(kDecodeThreadsBig), lds_big, st, a);
+            return hipGetLastError();
+        }
+    }
+    if (lds > kDecodeLdsPair || lds < decode_lds_bytes(G, a.chunk, D)) return hipErrorInvalidValue;
     hipLaunchKernelGGL((decode_kernel<T, D, kDecodeThreads, G>), grid, block, lds, st, a);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess && a.S > 1 && merge) {
@@ -803,8 +996,7 @@ static hipError_t launch_decode_t(const DecodeArgs& a, int64_t U, size_t lds, hi
 
 static hipError_t launch_decode_any(const DecodeArgs& a, int64_t U, int32_t d, int32_t dtype, size_t lds_bytes,
                                     hipStream_t stream, bool merge) {
-    if (lds_bytes > kDecodeLdsPair || lds_bytes < decode_lds_bytes(a.G, a.chunk, d) || a.S > kDecodeMaxSplits)
-        return hipErrorInvalidValue;
+    if (a.S > kDecodeMaxSplits) return hipErrorInvalidValue;
     if (dtype == KF_BF16) {
         if (d == 64) return launch_decode_t<bf16_t, 64>(a, U, lds_bytes, stream, merge);
         if (d == 128) return launch_decode_t<bf16_t, 128>(a, U, lds_bytes, stream, merge);

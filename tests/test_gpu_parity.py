@@ -1054,6 +1054,51 @@ def test_grouped_query_decode_at_the_largest_lds_footprint():
     assert_close_score(host(gc.score), oc.score, oc.len)
 
 
+@pytest.mark.parametrize("d,noise,new_pos", [(128, ko.NOISE_GUMBEL, False), (64, ko.NOISE_GAUSSIAN, True),
+                                             (256, ko.NOISE_NONE, False)])
+def test_grouped_query_eight_heads_one_workgroup_per_unit(d, noise, new_pos):
+    """8 bf16 query heads per cached head and a unit per compute unit: one 16-wave workgroup streams a whole
+    unit (logits on the matrix cores, adjusted in the K stream, partial outputs folded into the logit area)."""
+    rng = np.random.default_rng(7400 + d)
+    L, B, H, G = 2, 8, 16, 8
+    cap = 2049 if d == 128 else 1500
+    c0 = kf.Cache(K=0x10000, V=0x20000, score=0x30000, pos=0x40000, len=0x50000, L=L, B=B, H=H, d=d, cap=cap,
+                  dtype=kf.BF16, q_per_kv=G)
+    S, chunk = kf.kf_decode_launch_shape(c0, cap)
+    assert S == 1 and chunk >= cap - 1
+    lens = rng.integers(cap - 300, cap, (L, B, H)).astype(np.int32)
+    lens[0, 0, 0] = 0            # the new token alone
+    lens[0, 0, 1] = cap - 1      # fills the cache exactly
+    lens[0, 0, 2] = 15           # less than one 16-row tile of one wave
+    lens[0, 0, 3] = 257          # one row into the second sweep of the 16 waves
+    lens[1, 7, 15] = cap         # no room: skipped and reported
+    oc = random_cache(rng, L, B, H, d, cap, ko.BF16, lens)
+    gc = upload(oc, G)
+    ws = kf.new_workspace(gc)
+    q = rnd(rng, (L, B, H * G, d), ko.BF16)
+    kn, vn = (rnd(rng, (L, B, H, d), ko.BF16) for _ in range(2))
+    seeds = (np.arange(B) * 7 + 1).astype(np.uint64)
+    slopes = (0.5 ** (np.arange(1, H * G + 1) / 16.0)).astype(np.float32) * 0.05
+    q_pos = int(oc.pos.max()) + 1
+    out = torch.zeros((L, B, H * G, d), dtype=torch.float32, device="cuda")
+    scale = float(1.0 / np.sqrt(np.float32(d)))
+    kf.kf_decode_step(gc, dev(q), dev(kn), dev(vn), q_pos, cap, 1.5, scale, noise, dev(seeds), dev(slopes), out, ws,
+                      pos_mode=kf.POS_NEW if new_pos else kf.POS_ORIGINAL)
+    torch.cuda.synchronize()
+    assert error_word(ws) == 1
+    oc.len[1, 7, 15] = 0         # the oracle refuses the whole call for a full unit: let it skip that one
+    out_ref = oc.decode_step(q, kn, vn, q_pos, 1.5, scale, noise, seeds, slopes, q_per_kv=G, new_pos=new_pos)
+    g_out, g_len = host(out), host(gc.len)
+    assert (g_out[1, 7, 15 * G:(15 + 1) * G] == 0).all() and g_len[1, 7, 15] == cap
+    g_out[1, 7, 15 * G:(15 + 1) * G] = out_ref[1, 7, 15 * G:(15 + 1) * G]
+    assert_close_out(g_out, out_ref)
+    g_len[1, 7, 15] = oc.len[1, 7, 15]
+    np.testing.assert_array_equal(g_len, oc.len)
+    g_score = host(gc.score)
+    g_score[1, 7, 15] = oc.score[1, 7, 15]
+    assert_close_score(g_score, oc.score, oc.len)
+
+
 # ------------------------------------------------------------------ sequences at different steps
 @pytest.mark.parametrize("cap,layout", [(120, kf.LAYOUT_ORDERED), (1500, kf.LAYOUT_ORDERED), (300, kf.LAYOUT_SLOT)])
 def test_per_sequence_position_and_temperature(cap, layout):
@@ -1106,7 +1151,8 @@ def test_standalone_cpp_user_of_the_c_abi():
 
 # ------------------------------------------------------------------ whole step in one launch (slot layout, one split)
 @pytest.mark.parametrize("dtype,d,G,w", [(ko.BF16, 64, 1, 26), (ko.BF16, 128, 1, 0), (ko.F32, 64, 1, 26),
-                                         (ko.BF16, 128, 2, 26), (ko.BF16, 64, 4, 129)])
+                                         (ko.BF16, 128, 2, 26), (ko.BF16, 64, 4, 129), (ko.BF16, 128, 8, 26),
+                                         (ko.BF16, 64, 8, 0), (ko.BF16, 256, 8, 50)])
 def test_single_launch_slot_step_equals_the_two_calls(dtype, d, G, w):
     """With at least 320 units of a length that fits LDS, kf_decode_select_step in the slot layout is ONE
     launch: the workgroup that scored a unit evicts for it and stores the new token straight into the freed
