@@ -24,7 +24,7 @@
 namespace kf {
 
 constexpr int kDecodeThreads = 256;
-constexpr int kDecodeThreadsBig = 1024;  // one workgroup per CU with most of its LDS: 8 query heads, one split
+constexpr int kDecodeThreadsBig = 512;   // 8 query heads, one split: a workgroup with up to most of a CU's LDS
 constexpr int kDecodeRedWaves = 4;       // rows of LDS in which a workgroup's waves fold their partial outputs
 constexpr int kDecodeMaxChunk = 4096;   // tokens per split the LDS arrays are sized for
 constexpr int kDecodeMinBlocks = 1024;  // workgroups wanted on the chip
@@ -35,6 +35,7 @@ constexpr size_t kDecodeLdsBudget = 65536 - 1024;       // dynamic LDS of a spli
 constexpr size_t kDecodeLdsPair = 81920 - 1024;         // ... of a single-split workgroup: two fit a CU's 160 KB
 constexpr int kDecodeSingleMinUnits = 320;              // units from which one workgroup per unit fills the chip
 constexpr size_t kDecodeLdsWhole = 163840 - 2048;       // ... of a workgroup that has a CU to itself
+constexpr size_t kDecodeLdsThird = 53248;               // three workgroups of at most this much fit a CU
 constexpr int kDecodeBigMinUnits = 256;                 // units from which one such workgroup per unit fills the chip
 
 constexpr int kDecodeUnroll = 4;  // 16-byte loads a lane keeps in flight per tile (2 and 8 measured within 2 %)
@@ -126,8 +127,8 @@ __device__ __forceinline__ float wave_sum_fast(float v) {
 }
 
 // Block-wide max / sum of N values at once.  `red` holds N*NT/64 + N floats.  With few values and waves
-// every thread folds the waves' results itself (one pair of barriers); with many (8 query heads, 16 waves:
-// 256 LDS reads per thread that way) N threads fold them once and publish the N results.
+// every thread folds the waves' results itself (one pair of barriers); with many (8 query heads, 8 waves:
+// 128 LDS reads per thread that way) N threads fold them once and publish the N results.
 template <int NT, int N, bool IS_MAX>
 __device__ __forceinline__ void block_reduce_n(float (&v)[N], float* red) {
     constexpr int NW = NT / 64;
@@ -201,11 +202,12 @@ __device__ __forceinline__ void decode_block(const DecodeArgs& a) {
     constexpr int RPW = kWave / LPR;             // rows per wave-wide load
     constexpr int NW = NT / kWave;
     constexpr int RPB = RPW * NW;                // rows per block-wide load
-    // independent loads in flight per lane (8 query heads: registers are short, the more so with 16 waves)
-    constexpr int UNR = (G >= 8) ? (NT >= 1024 ? 1 : 2) : kDecodeUnroll;
+    // independent loads in flight per lane (8 query heads: registers are short; one instead of two costs the
+    // 8-wave workgroup 15-20 %, four do not fit)
+    constexpr int UNR = (G >= 8) ? 2 : kDecodeUnroll;
     constexpr int TILE = RPB * UNR;              // rows per tile of the workgroup
     constexpr int PW = D + 4;                    // floats in a partial record
-    constexpr bool BIG = NW > kDecodeRedWaves;  // a workgroup that has a CU to itself: one split, 8 query heads
+    constexpr bool BIG = NW > kDecodeRedWaves;  // the 8-wave workgroup: one split, 8 query heads, up to most of a CU's LDS
     constexpr size_t ROWB = (size_t)D * sizeof(T);
     static_assert(LPR <= 32 && D <= NT, "row must fit half a wave, output a block");
 
@@ -310,86 +312,203 @@ __device__ __forceinline__ void decode_block(const DecodeArgs& a) {
     // ---- phase 1: stream K (next tile in flight while this one is reduced), logits into LDS
     uint4 cur[UNR], nxt[UNR];
     if constexpr (MfmaLogits<T, G>::value) {
-        constexpr int KK = D / 32;  // MFMAs (and 16-byte loads per lane) per 16-row tile
-        const int mrow = lane & 15, c4 = lane >> 4;
-        uint4 bq[KK];
-#pragma unroll
-        for (int kk = 0; kk < KK; ++kk) {  // heads G..15 of the padded group are zero
-            bq[kk] = ((const uint4*)(qu + (size_t)min(mrow, G - 1) * D))[kk * 4 + c4];
-            if (mrow >= G) bq[kk] = make_uint4(0u, 0u, 0u, 0u);
-        }
-        // The MFMA leaves lane (mrow, c4) with the logits of head mrow for rows 4*c4 .. +3, and nothing of use
-        // in the lanes of the padding heads (mrow >= G).  Those take rows 4*c4+2, +3 over from lane mrow-8
-        // (one data-parallel move each), so that all 64 lanes apply position bias and logit adjustment to two
-        // logits each, right here, while the next rows are in flight: the vector units idle during the K
-        // stream, and the statistics pass after it (one more sweep over all G x rows logits, with the
-        // workgroup's memory pipeline empty) shrinks to the two running maxima kept per lane.
-        static_assert(G == 8, "the padding half of the 16 MFMA columns takes half of the real heads' rows");
-        const int g_l = mrow & (G - 1), r_l = (mrow >= G) ? 2 : 0;
-        const int hq_l = h * G + g_l;
-        const float slope_l = a.slopes ? a.slopes[hq_l] : 0.0f;
         const bool rnd_l = (a.noise == kNoiseGumbel || a.noise == kNoiseGaussian);
-        const uint32_t rkey_l = rnd_l ? row_key(unit_key(a.seeds[b], (uint32_t)l, (uint32_t)hq_l), (uint32_t)q_pos) : 0u;
-        float mx_l = -INFINITY, my_l = -INFINITY;
-        // rows past the split re-read its last row (the address stays inside the cache); their logits are dropped
-        auto load_rows = [&](int base, uint4(&raw)[KK], int(&pos2)[2]) {
-            const int row = min(base + wv * 16 + mrow, j1 - 1);  // a wave's 16 rows of the workgroup's NW*16
-            const uint4* p = (const uint4*)(Ku + (size_t)row * ROWB) + c4;
+        if constexpr (D >= 128) {
+            // Rows of 256 bytes and more.  An MFMA row slot holds a QUARTER of a cache row: slot i = 4*r + s
+            // is row r of a group of four rows, pieces {s, 4+s, 8+s, 12+s} (16 bytes each) of every 256 bytes.
+            // Lane (i, kb) then loads piece 4*kb + s of row r: four adjacent lanes read 64 contiguous bytes,
+            // the 64 lanes of a load instruction four whole 256-byte row parts -- every cache line is asked
+            // for once, by one instruction (with a whole row per slot a line is split over two instructions
+            // and adjacent lanes sit 256 bytes apart: the K stream ran 28 us per 2048-token unit against
+            // 20 us for the V stream).  The B operand's column j = 4*g' + s' carries head g' of a group of
+            // four, restricted to the pieces of class s'; of the 16x16 products only those with s = s' are
+            // wanted, and their sum over s is the logit of (row r, head g') -- two MFMAs (two head groups) per
+            // four rows, twice the matrix work of the plain layout, on units that idle anyway.
+            constexpr int KS = D / 128;  // 256-byte parts of a row = MFMA k-steps
+            const int i4 = lane & 15, kb = lane >> 4, r4 = i4 >> 2, s4 = i4 & 3;
+            uint4 bq[2][KS];
 #pragma unroll
-            for (int kk = 0; kk < KK; ++kk) raw[kk] = stream_load(p + kk * 4);
+            for (int hh = 0; hh < 2; ++hh) {
 #pragma unroll
-            for (int r = 0; r < 2; ++r) pos2[r] = pu[min(base + wv * 16 + c4 * 4 + r_l + r, j1 - 1)];
-        };
-        auto logits_of = [&](int base, const uint4(&raw)[KK], const int(&pos2)[2]) {
-            f32x4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
+                for (int ks = 0; ks < KS; ++ks)
+                    bq[hh][ks] = ((const uint4*)(qu + (size_t)(hh * 4 + r4) * D))[16 * ks + 4 * kb + s4];
+            }
+            // After the MFMAs lane (j = i4, kb) holds, in register reg, the product of slot 4*kb + reg with
+            // column j: the wanted one is reg = s4 (row kb of the group, head r4 of the head group); the four
+            // lanes of a quad add theirs up.  A step is 16 rows (four groups) x 8 heads = 128 logits per
+            // wave: lane s4 of a quad keeps those of row group s4, i.e. ONE row and the heads r4, r4 + 4, and
+            // applies position bias and logit adjustment to them right here, while the next rows are in
+            // flight -- the statistics pass after the K stream shrinks to the running maxima kept per lane.
+            static_assert(G == 8, "two head groups of four");
+            float slope_l[2];
+            uint32_t rkey_l[2];
 #pragma unroll
-            for (int kk = 0; kk < KK; ++kk)
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, raw[kk]),
-                                                              __builtin_bit_cast(bf16x8_t, bq[kk]), acc, 0, 0, 0);
-            const float from2 = dpp_move<0x118>(acc[2]), from3 = dpp_move<0x118>(acc[3]);  // row_shr:8
-            const float v[2] = {mrow >= G ? from2 : acc[0], mrow >= G ? from3 : acc[1]};
+            for (int hh = 0; hh < 2; ++hh) {
+                const int hq = h * G + hh * 4 + r4;
+                slope_l[hh] = a.slopes ? a.slopes[hq] : 0.0f;
+                rkey_l[hh] = rnd_l ? row_key(unit_key(a.seeds[b], (uint32_t)l, (uint32_t)hq), (uint32_t)q_pos) : 0u;
+            }
+            float mx_l[2] = {-INFINITY, -INFINITY}, my_l[2] = {-INFINITY, -INFINITY};
+            // rows past the split re-read its last row (the address stays inside the cache); their logits are dropped
+            auto load_rows = [&](int base, uint4(&raw)[4][KS], int& pos1) {
 #pragma unroll
-            for (int r = 0; r < 2; ++r) {
-                const int row = base + wv * 16 + c4 * 4 + r_l + r;
+                for (int rg = 0; rg < 4; ++rg) {
+                    const int row = min(base + wv * 16 + rg * 4 + r4, j1 - 1);
+                    const uint4* p = (const uint4*)(Ku + (size_t)row * ROWB) + 4 * kb + s4;
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks) raw[rg][ks] = stream_load(p + 16 * ks);
+                }
+                pos1 = pu[min(base + wv * 16 + s4 * 4 + kb, j1 - 1)];
+            };
+            auto logits_of = [&](int base, const uint4(&raw)[4][KS], int pos1) {
+                float v[2] = {0.0f, 0.0f};
+#pragma unroll
+                for (int rg = 0; rg < 4; ++rg) {
+#pragma unroll
+                    for (int hh = 0; hh < 2; ++hh) {
+                        f32x4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+                        for (int ks = 0; ks < KS; ++ks)
+                            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, raw[rg][ks]),
+                                                                          __builtin_bit_cast(bf16x8_t, bq[hh][ks]), acc, 0, 0, 0);
+                        float t = s4 == 0 ? acc[0] : s4 == 1 ? acc[1] : s4 == 2 ? acc[2] : acc[3];
+                        t += dpp_move<0xB1>(t);  // the quad's four classes
+                        t += dpp_move<0x4E>(t);
+                        if (s4 == rg) v[hh] = t;
+                    }
+                }
+                const int row = base + wv * 16 + s4 * 4 + kb;
                 if (row < j1) {
-                    const int dist = a.new_pos ? (len0 - row) : (q_pos - pos2[r]);
-                    // base-2 domain: x2 = log2(e)*x, y2 = log2(e)*(x + zeta)/tau
-                    const float x = (v[r] * a.scale - slope_l * (float)dist) * kLog2e;
-                    const float y = (x + zeta_log2e(a.noise, rkey_l, (uint32_t)pos2[r])) * inv_tau;
-                    xs[g_l * CS + row - j0] = x;
-                    ys[g_l * CS + row - j0] = y;
-                    mx_l = fmaxf(mx_l, x);
-                    my_l = fmaxf(my_l, y);
+                    const int dist = a.new_pos ? (len0 - row) : (q_pos - pos1);
+#pragma unroll
+                    for (int hh = 0; hh < 2; ++hh) {
+                        // base-2 domain: x2 = log2(e)*x, y2 = log2(e)*(x + zeta)/tau
+                        const float x = (v[hh] * a.scale - slope_l[hh] * (float)dist) * kLog2e;
+                        const float y = (x + zeta_log2e(a.noise, rkey_l[hh], (uint32_t)pos1)) * inv_tau;
+                        xs[(hh * 4 + r4) * CS + row - j0] = x;
+                        ys[(hh * 4 + r4) * CS + row - j0] = y;
+                        mx_l[hh] = fmaxf(mx_l[hh], x);
+                        my_l[hh] = fmaxf(my_l[hh], y);
+                    }
+                }
+            };
+            if (cnt_c > 0) {
+                uint4 kcur[4][KS], knxt[4][KS];
+                int pcur, pnxt;
+                int base = j0;
+                load_rows(base, kcur, pcur);
+                while (base + NW * 16 < j1) {
+                    load_rows(base + NW * 16, knxt, pnxt);
+                    logits_of(base, kcur, pcur);
+#pragma unroll
+                    for (int rg = 0; rg < 4; ++rg) {
+#pragma unroll
+                        for (int ks = 0; ks < KS; ++ks) kcur[rg][ks] = knxt[rg][ks];
+                    }
+                    pcur = pnxt;
+                    base += NW * 16;
+                }
+                logits_of(base, kcur, pcur);
+            }
+            // the 16 lanes of a head pair (quad x four 16-lane rows) fold their maxima; row NW of the table
+            // takes the new token's own logits (distance 0: no position bias), or nothing
+#pragma unroll
+            for (int hh = 0; hh < 2; ++hh) {
+                float mx = mx_l[hh], my = my_l[hh];
+                mx = fmaxf(mx, dpp_move<0xB1>(mx));
+                my = fmaxf(my, dpp_move<0xB1>(my));
+                mx = fmaxf(mx, dpp_move<0x4E>(mx));
+                my = fmaxf(my, dpp_move<0x4E>(my));
+                mx = fmaxf(mx, __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, mx), 0x401F)));
+                my = fmaxf(my, __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, my), 0x401F)));
+                mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+                my = fmaxf(my, __shfl_xor(my, 32, kWave));
+                if (kb == 0 && s4 == 0) {
+                    red_s[2 * G * wv + 2 * (hh * 4 + r4)] = mx;
+                    red_s[2 * G * wv + 2 * (hh * 4 + r4) + 1] = my;
                 }
             }
-        };
-        if (cnt_c > 0) {
-            uint4 kcur[KK], knxt[KK];
-            int pcur[2], pnxt[2];
-            int base = j0;
-            load_rows(base, kcur, pcur);
-            while (base + NW * 16 < j1) {
-                load_rows(base + NW * 16, knxt, pnxt);
-                logits_of(base, kcur, pcur);
+        } else {
+            constexpr int KK = D / 32;  // MFMAs (and 16-byte loads per lane) per 16-row tile
+            const int mrow = lane & 15, c4 = lane >> 4;
+            uint4 bq[KK];
 #pragma unroll
-                for (int kk = 0; kk < KK; ++kk) kcur[kk] = knxt[kk];
-                pcur[0] = pnxt[0];
-                pcur[1] = pnxt[1];
-                base += NW * 16;
+            for (int kk = 0; kk < KK; ++kk) {  // heads G..15 of the padded group are zero
+                bq[kk] = ((const uint4*)(qu + (size_t)min(mrow, G - 1) * D))[kk * 4 + c4];
+                if (mrow >= G) bq[kk] = make_uint4(0u, 0u, 0u, 0u);
             }
-            logits_of(base, kcur, pcur);
-        }
-        // the eight lanes of a head (mrow, mrow+8 in each of the four 16-lane rows) fold their maxima; row NW of
-        // the table takes the new token's own logits (distance 0: no position bias), or nothing
-        mx_l = fmaxf(mx_l, dpp_move<0x128>(mx_l));  // row_ror:8
-        my_l = fmaxf(my_l, dpp_move<0x128>(my_l));
-        mx_l = fmaxf(mx_l, __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, mx_l), 0x401F)));
-        my_l = fmaxf(my_l, __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, my_l), 0x401F)));
-        mx_l = fmaxf(mx_l, __shfl_xor(mx_l, 32, kWave));
-        my_l = fmaxf(my_l, __shfl_xor(my_l, 32, kWave));
-        if (lane < G) {
-            red_s[2 * G * wv + 2 * lane] = mx_l;
-            red_s[2 * G * wv + 2 * lane + 1] = my_l;
+            // The MFMA leaves lane (mrow, c4) with the logits of head mrow for rows 4*c4 .. +3, and nothing of use
+            // in the lanes of the padding heads (mrow >= G).  Those take rows 4*c4+2, +3 over from lane mrow-8
+            // (one data-parallel move each), so that all 64 lanes apply position bias and logit adjustment to two
+            // logits each, right here, while the next rows are in flight: the vector units idle during the K
+            // stream, and the statistics pass after it (one more sweep over all G x rows logits, with the
+            // workgroup's memory pipeline empty) shrinks to the two running maxima kept per lane.
+            static_assert(G == 8, "the padding half of the 16 MFMA columns takes half of the real heads' rows");
+            const int g_l = mrow & (G - 1), r_l = (mrow >= G) ? 2 : 0;
+            const int hq_l = h * G + g_l;
+            const float slope_l = a.slopes ? a.slopes[hq_l] : 0.0f;
+            const uint32_t rkey_l = rnd_l ? row_key(unit_key(a.seeds[b], (uint32_t)l, (uint32_t)hq_l), (uint32_t)q_pos) : 0u;
+            float mx_l = -INFINITY, my_l = -INFINITY;
+            // rows past the split re-read its last row (the address stays inside the cache); their logits are dropped
+            auto load_rows = [&](int base, uint4(&raw)[KK], int(&pos2)[2]) {
+                const int row = min(base + wv * 16 + mrow, j1 - 1);  // a wave's 16 rows of the workgroup's NW*16
+                const uint4* p = (const uint4*)(Ku + (size_t)row * ROWB) + c4;
+#pragma unroll
+                for (int kk = 0; kk < KK; ++kk) raw[kk] = stream_load(p + kk * 4);
+#pragma unroll
+                for (int r = 0; r < 2; ++r) pos2[r] = pu[min(base + wv * 16 + c4 * 4 + r_l + r, j1 - 1)];
+            };
+            auto logits_of = [&](int base, const uint4(&raw)[KK], const int(&pos2)[2]) {
+                f32x4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+                for (int kk = 0; kk < KK; ++kk)
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, raw[kk]),
+                                                                  __builtin_bit_cast(bf16x8_t, bq[kk]), acc, 0, 0, 0);
+                const float from2 = dpp_move<0x118>(acc[2]), from3 = dpp_move<0x118>(acc[3]);  // row_shr:8
+                const float v[2] = {mrow >= G ? from2 : acc[0], mrow >= G ? from3 : acc[1]};
+#pragma unroll
+                for (int r = 0; r < 2; ++r) {
+                    const int row = base + wv * 16 + c4 * 4 + r_l + r;
+                    if (row < j1) {
+                        const int dist = a.new_pos ? (len0 - row) : (q_pos - pos2[r]);
+                        // base-2 domain: x2 = log2(e)*x, y2 = log2(e)*(x + zeta)/tau
+                        const float x = (v[r] * a.scale - slope_l * (float)dist) * kLog2e;
+                        const float y = (x + zeta_log2e(a.noise, rkey_l, (uint32_t)pos2[r])) * inv_tau;
+                        xs[g_l * CS + row - j0] = x;
+                        ys[g_l * CS + row - j0] = y;
+                        mx_l = fmaxf(mx_l, x);
+                        my_l = fmaxf(my_l, y);
+                    }
+                }
+            };
+            if (cnt_c > 0) {
+                uint4 kcur[KK], knxt[KK];
+                int pcur[2], pnxt[2];
+                int base = j0;
+                load_rows(base, kcur, pcur);
+                while (base + NW * 16 < j1) {
+                    load_rows(base + NW * 16, knxt, pnxt);
+                    logits_of(base, kcur, pcur);
+#pragma unroll
+                    for (int kk = 0; kk < KK; ++kk) kcur[kk] = knxt[kk];
+                    pcur[0] = pnxt[0];
+                    pcur[1] = pnxt[1];
+                    base += NW * 16;
+                }
+                logits_of(base, kcur, pcur);
+            }
+            // the eight lanes of a head (mrow, mrow+8 in each of the four 16-lane rows) fold their maxima; row NW of
+            // the table takes the new token's own logits (distance 0: no position bias), or nothing
+            mx_l = fmaxf(mx_l, dpp_move<0x128>(mx_l));  // row_ror:8
+            my_l = fmaxf(my_l, dpp_move<0x128>(my_l));
+            mx_l = fmaxf(mx_l, __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, mx_l), 0x401F)));
+            my_l = fmaxf(my_l, __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, my_l), 0x401F)));
+            mx_l = fmaxf(mx_l, __shfl_xor(mx_l, 32, kWave));
+            my_l = fmaxf(my_l, __shfl_xor(my_l, 32, kWave));
+            if (lane < G) {
+                red_s[2 * G * wv + 2 * lane] = mx_l;
+                red_s[2 * G * wv + 2 * lane + 1] = my_l;
+            }
         }
         if (wv == 0) {
             const uint4 kv = ((const uint4*)knew)[cl];
@@ -592,8 +711,8 @@ __device__ __forceinline__ void decode_block(const DecodeArgs& a) {
     }
     // Partial outputs of the waves meet in LDS.  Few accumulators per lane: the rows of one wave-wide load
     // (RPW lane groups) are folded with exchanges, lane group 0 stores.  Many (8 query heads): the fold is a
-    // reduce-scatter, every lane group ends up with 1/RPW of the sums and stores those.  A workgroup of 16
-    // waves stores later, into the logit area, once nobody reads logits any more (see below).
+    // reduce-scatter, every lane group ends up with 1/RPW of the sums and stores those.  The 8-wave
+    // workgroup stores later, into the logit area, once nobody reads logits any more (see below).
     constexpr int HV = G * EPV / RPW;  // sums a lane holds after the reduce-scatter
     float fin[G >= 8 ? HV : 1];
     int off = 0;
@@ -634,7 +753,7 @@ __device__ __forceinline__ void decode_block(const DecodeArgs& a) {
             __syncthreads();  // red_o and stat are complete
         }
     } else {
-        static_assert(!BIG, "a 16-wave workgroup is built for 8 query heads");
+        static_assert(!BIG, "the 8-wave workgroup is built for 8 query heads");
 #pragma unroll
         for (int o = LPR; o < kWave; o <<= 1) {
 #pragma unroll
@@ -695,7 +814,7 @@ __device__ __forceinline__ void decode_block(const DecodeArgs& a) {
         }
         const float* orows = red_o;
         if constexpr (BIG) {
-            // 16 waves' partial outputs (64 KB and more) take the place of the logits: every wave is past the
+            // 8 waves' partial outputs (32 KB and more) take the place of the logits: every wave is past the
             // V stream (attention weights in xs) and the loop above (increments in ys) after this barrier
             __syncthreads();
             store_fin(smem + (size_t)wv * G * D);
@@ -767,7 +886,7 @@ __device__ __forceinline__ void decode_block(const DecodeArgs& a) {
         return;
     }
     // ---- S > 1: leave the un-normalised increments and a partial record per query head for the merge
-    if constexpr (BIG) return;  // never launched that way: a 16-wave workgroup takes a whole unit
+    if constexpr (BIG) return;  // never launched that way: the 8-wave workgroup takes a whole unit
     {
         float* we = a.ws_e + (size_t)u * G * a.cap;
         for (int t = tid; t < cnt; t += NT) {
@@ -872,7 +991,7 @@ static int rows_per_block(int32_t d, int32_t dtype) {
 static size_t decode_lds_bytes(int32_t G, int64_t chunk, int32_t d) {
     return (size_t)(2 * G * (chunk + 1) + 3 + kDecodeRedWaves * G * d) * sizeof(float);
 }
-// ... of the 16-wave workgroup: its waves' partial outputs reuse the logit area
+// ... of the 8-wave workgroup: its waves' partial outputs reuse the logit area
 static size_t decode_lds_bytes_big(int32_t G, int64_t chunk, int32_t d) {
     const size_t logits = (size_t)(2 * G * (chunk + 1) + 3) * sizeof(float);
     const size_t outs = (size_t)(kDecodeThreadsBig / kWave) * G * d * sizeof(float);
@@ -903,7 +1022,7 @@ DecodePlan plan_decode(int64_t U, int32_t m, int32_t d, int32_t dtype, int32_t G
     const int rpb = rows_per_block(d, dtype);
     const int64_t rows = m > 1 ? m - 1 : 1;  // cache rows; the new token rides with the last split
     if (G == 8 && dtype == KF_BF16 && U >= kDecodeBigMinUnits) {
-        // one 1024-thread workgroup per CU, the unit's 2 x 8 logit rows in most of the CU's LDS
+        // one workgroup per unit, up to one per CU with the unit's 2 x 8 logit rows in most of the CU's LDS
         const int64_t chunk = (rows + rpb - 1) / rpb * rpb;
         if (decode_lds_bytes_big(G, chunk, d) <= kDecodeLdsWhole) {
             p.S = 1;
@@ -961,14 +1080,19 @@ template <typename T, int D, int G>
 static hipError_t launch_decode_g(const DecodeArgs& a, int64_t U, size_t lds, hipStream_t st, bool merge) {
     const dim3 grid((unsigned)(U * a.S)), block(kDecodeThreads);
     if constexpr (G == 8 && MfmaLogits<T, G>::value) {
-        if (a.S == 1) {  // one split with 8 query heads: a CU-filling workgroup per unit
+        // one split with 8 query heads: short units keep the 4-wave workgroup (three or more fit a CU), longer
+        // ones take 8 waves (two per CU up to ~1000 tokens, then one with most of the CU's LDS).  Measured at
+        // 2048 units, d = 128: 512 tokens 51 % (4 waves) vs 49 % (8) vs 36 % (16); 1024 tokens 49 / 62 / 49 %;
+        // 2048 tokens - / 62 / 58 %.
+        if (a.S == 1 && decode_lds_bytes(G, a.chunk, D) > kDecodeLdsThird) {
             const size_t lds_big = decode_lds_bytes_big(G, a.chunk, D);
             if (lds_big > kDecodeLdsWhole) return hipErrorInvalidValue;
             hipLaunchKernelGGL((decode_kernel<T, D, kDecodeThreadsBig, G>), grid, dim3(kDecodeThreadsBig), lds_big, st, a);
             return hipGetLastError();
         }
     }
-    if (lds > kDecodeLdsPair || lds < decode_lds_bytes(G, a.chunk, D)) return hipErrorInvalidValue;
+    lds = decode_lds_bytes(G, a.chunk, D);  // what this workgroup shape needs for the plan's chunk
+    if (lds > kDecodeLdsPair) return hipErrorInvalidValue;
     hipLaunchKernelGGL((decode_kernel<T, D, kDecodeThreads, G>), grid, block, lds, st, a);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess && a.S > 1 && merge) {

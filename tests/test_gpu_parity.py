@@ -1057,7 +1057,7 @@ def test_grouped_query_decode_at_the_largest_lds_footprint():
 @pytest.mark.parametrize("d,noise,new_pos", [(128, ko.NOISE_GUMBEL, False), (64, ko.NOISE_GAUSSIAN, True),
                                              (256, ko.NOISE_NONE, False)])
 def test_grouped_query_eight_heads_one_workgroup_per_unit(d, noise, new_pos):
-    """8 bf16 query heads per cached head and a unit per compute unit: one 16-wave workgroup streams a whole
+    """8 bf16 query heads per cached head and a unit per compute unit: one 8-wave workgroup streams a whole
     unit (logits on the matrix cores, adjusted in the K stream, partial outputs folded into the logit area)."""
     rng = np.random.default_rng(7400 + d)
     L, B, H, G = 2, 8, 16, 8

@@ -146,7 +146,7 @@ def test_decode_launch_shape_covers_the_rows_and_balances_the_chip():
     # logits of one unit beyond what two workgroups per compute unit can hold in LDS: splits of at most 4096 rows
     S, chunk = kf.kf_decode_launch_shape(fake_cache(L=32, B=1, H=32, d=128, cap=20000), 20000)
     assert S >= 5 and chunk <= 4096
-    # 8 bf16 query heads per cached head: one 16-wave workgroup per unit while 2 x 8 logit rows fit a compute
+    # 8 bf16 query heads per cached head: one workgroup per unit while 2 x 8 logit rows fit a compute
     # unit's LDS (about 2500 tokens) and there is a unit per compute unit; splits of at most 512 rows otherwise
     assert kf.kf_decode_launch_shape(fake_cache(L=32, B=8, H=8, d=128, cap=2049, q_per_kv=8), 2049) == (1, 2048)
     S, chunk = kf.kf_decode_launch_shape(fake_cache(L=32, B=8, H=8, d=128, cap=4097, q_per_kv=8), 4097)
