@@ -631,7 +631,22 @@ __device__ __forceinline__ void decode_block(const DecodeArgs& a) {
                 mxy[2 * g + 1] = fmaxf(mxy[2 * g + 1], y);
             }
         };
-        for (int t = tid; t < cnt; t += NT) adjust(t, (t == cnt_c) ? q_pos : pu[j0 + t]);
+        // the rows' positions come from memory: eight strides' worth are requested at once, so that a lane
+        // waits for one round trip per eight tokens instead of one per token
+        constexpr int PB = 8;
+        for (int t0 = tid; t0 < cnt; t0 += PB * NT) {
+            int pj[PB];
+#pragma unroll
+            for (int i = 0; i < PB; ++i) {
+                const int t = t0 + i * NT;
+                pj[i] = (t < cnt_c) ? pu[j0 + t] : q_pos;
+            }
+#pragma unroll
+            for (int i = 0; i < PB; ++i) {
+                const int t = t0 + i * NT;
+                if (t < cnt) adjust(t, pj[i]);
+            }
+        }
         block_max_n<NT, 2 * G>(mxy, red_s);
     }
     float spe[2 * G];
