@@ -9,9 +9,12 @@
 // Work decomposition: a unit's m tokens are cut into S contiguous splits, one
 // workgroup each.  A workgroup streams its K rows (16 bytes per lane, a row
 // spread over D*sizeof(T)/16 adjacent lanes so that every wave-wide load is one
-// contiguous kilobyte), keeps the logits in LDS, forms the two softmaxes'
-// local statistics while its first V tile is already in flight, then streams
-// its V rows.  With S == 1 it finishes the unit itself.  With S > 1 it leaves a
+// contiguous kilobyte), applies position bias and logit adjustment to the
+// logits as they come out of the dot products (the vector units have time to
+// spare while the next rows are in flight) and keeps both adjusted logit rows
+// in LDS; between the streams only the exponentials and the two softmaxes'
+// sums remain, formed while the first V tile is already in flight; then it
+// streams its V rows.  With S == 1 it finishes the unit itself.  With S > 1 it leaves a
 // partial record (un-normalised output, local max and sum of both softmaxes,
 // un-normalised score increments) and a second, tiny launch merges the records
 // of each unit.  (Merging inside the first launch, by the last split to arrive,
@@ -311,8 +314,8 @@ __device__ __forceinline__ void decode_block(const DecodeArgs& a) {
 
     // ---- phase 1: stream K (next tile in flight while this one is reduced), logits into LDS
     uint4 cur[UNR], nxt[UNR];
+    const bool rnd_l = (a.noise == kNoiseGumbel || a.noise == kNoiseGaussian);
     if constexpr (MfmaLogits<T, G>::value) {
-        const bool rnd_l = (a.noise == kNoiseGumbel || a.noise == kNoiseGaussian);
         if constexpr (D >= 128) {
             // Rows of 256 bytes and more.  An MFMA row slot holds a QUARTER of a cache row: slot i = 4*r + s
             // is row r of a group of four rows, pieces {s, 4+s, 8+s, 12+s} (16 bytes each) of every 256 bytes.
@@ -510,34 +513,34 @@ __device__ __forceinline__ void decode_block(const DecodeArgs& a) {
                 red_s[2 * G * wv + 2 * lane + 1] = my_l;
             }
         }
-        if (wv == 0) {
-            const uint4 kv = ((const uint4*)knew)[cl];
-#pragma unroll
-            for (int g = 0; g < G; ++g) {
-                QueryPiece<T> qg;
-                qg.load(((const uint4*)(qu + (size_t)g * D))[cl]);
-                const float p = group_sum<LPR>(qg.dot(kv));
-                if (lane == 0) {
-                    float x = -INFINITY, y = -INFINITY;
-                    if (owner) {
-                        const int hq = h * G + g;
-                        const uint32_t rk = rnd_l ? row_key(unit_key(a.seeds[b], (uint32_t)l, (uint32_t)hq), (uint32_t)q_pos) : 0u;
-                        x = (p * a.scale) * kLog2e;
-                        y = (x + zeta_log2e(a.noise, rk, (uint32_t)q_pos)) * inv_tau;
-                        xs[g * CS + cnt_c] = x;
-                        ys[g * CS + cnt_c] = y;
-                    }
-                    red_s[2 * G * NW + 2 * g] = x;
-                    red_s[2 * G * NW + 2 * g + 1] = y;
-                }
-            }
-        }
     } else {
         QueryPiece<T> qp[G];
 #pragma unroll
         for (int g = 0; g < G; ++g) qp[g].load(((const uint4*)(qu + (size_t)g * D))[cl]);
 
-        auto logits_of = [&](int base) {
+        // After the lane-group sums every lane of a row holds all G x UNR logits of its row group.  Lane cl
+        // keeps those numbered cl, cl + LPR, ...: number v is head v % G (always cl % G: one head per lane) of
+        // the tile's load v / G.  It applies position bias and logit adjustment to them right here, while the
+        // next tile is in flight -- the vector units have time to spare during the K stream, and the statistics
+        // pass after it (one more sweep over all logits with the memory pipeline empty, all workgroups of a
+        // small launch at the same time) shrinks to the two running maxima kept per lane.
+        constexpr int NV = G * UNR, VPL = (NV + LPR - 1) / LPR;
+        static_assert(LPR % G == 0, "a lane's logits belong to one head");
+        const int g_l = cl % G, i_l = cl / G;
+        const int hq_l = h * G + g_l;
+        const float slope_l = a.slopes ? a.slopes[hq_l] : 0.0f;
+        const uint32_t rkey_l = rnd_l ? row_key(unit_key(a.seeds[b], (uint32_t)l, (uint32_t)hq_l), (uint32_t)q_pos) : 0u;
+        float mx_l = -INFINITY, my_l = -INFINITY;
+        int pcur[VPL], pnxt[VPL];
+        // positions of this lane's rows of the tile at `base` (rows past the split: its last row, dropped later)
+        auto load_pos = [&](int base, int(&ps)[VPL]) {
+#pragma unroll
+            for (int r = 0; r < VPL; ++r) {
+                const int i = i_l + r * (LPR / G);
+                ps[r] = (i < UNR) ? pu[min(base + i * RPB + sub, j1 - 1)] : 0;
+            }
+        };
+        auto logits_of = [&](int base, const int(&ps)[VPL]) {
             float p[G][UNR];
 #pragma unroll
             for (int g = 0; g < G; ++g) {
@@ -550,40 +553,89 @@ __device__ __forceinline__ void decode_block(const DecodeArgs& a) {
                 for (int i = 0; i < UNR; ++i) p[g][i] = group_sum<LPR>(p[g][i]);
             }
 #pragma unroll
-            for (int i = 0; i < UNR; ++i) {
-                const int j = base + i * RPB + sub;
-                if (cl == 0 && j < j1) {
+            for (int r = 0; r < VPL; ++r) {
+                const int i_r = i_l + r * (LPR / G);
+                float v = 0.0f;
 #pragma unroll
-                    for (int g = 0; g < G; ++g) xs[g * CS + j - j0] = p[g][i] * a.scale;
+                for (int g = 0; g < G; ++g) {
+#pragma unroll
+                    for (int i = 0; i < UNR; ++i) v = (g == g_l && i == i_r) ? p[g][i] : v;
+                }
+                const int j = base + i_r * RPB + sub;
+                if (i_r < UNR && j < j1) {
+                    const int dist = a.new_pos ? (len0 - j) : (q_pos - ps[r]);
+                    // base-2 domain: x2 = log2(e)*x, y2 = log2(e)*(x + zeta)/tau
+                    const float x = (v * a.scale - slope_l * (float)dist) * kLog2e;
+                    const float y = (x + zeta_log2e(a.noise, rkey_l, (uint32_t)ps[r])) * inv_tau;
+                    xs[g_l * CS + j - j0] = x;
+                    ys[g_l * CS + j - j0] = y;
+                    mx_l = fmaxf(mx_l, x);
+                    my_l = fmaxf(my_l, y);
                 }
             }
         };
         {
             int base = base0;
-            if (base < j1) load_tile(Ku, base, cur);
+            if (base < j1) {
+                load_tile(Ku, base, cur);
+                load_pos(base, pcur);
+            }
             // steady state: the next tile needs no bounds checks, so the loop body is
             // branch-free and only the older tile's loads are waited for
             while (plain(base + TILE)) {
                 load_plain(Ku, base + TILE, nxt);
-                logits_of(base);
+                load_pos(base + TILE, pnxt);
+                logits_of(base, pcur);
 #pragma unroll
                 for (int i = 0; i < UNR; ++i) cur[i] = nxt[i];
+#pragma unroll
+                for (int r = 0; r < VPL; ++r) pcur[r] = pnxt[r];
                 base += TILE;
             }
             while (base < j1) {  // the last one or two tiles of the split
-                if (base + TILE < j1) load_edge(Ku, base + TILE, nxt);
-                logits_of(base);
+                if (base + TILE < j1) {
+                    load_edge(Ku, base + TILE, nxt);
+                    load_pos(base + TILE, pnxt);
+                }
+                logits_of(base, pcur);
 #pragma unroll
                 for (int i = 0; i < UNR; ++i) cur[i] = nxt[i];
+#pragma unroll
+                for (int r = 0; r < VPL; ++r) pcur[r] = pnxt[r];
                 base += TILE;
             }
         }
-        if (owner && wv == 0) {  // the new token's own logits (distance 0: no position bias)
-            const uint4 kv = ((const uint4*)knew)[cl];
+        // per head, the wave's maxima; row NW of the table takes the new token's own logits, or nothing
 #pragma unroll
-            for (int g = 0; g < G; ++g) {
-                const float p = group_sum<LPR>(qp[g].dot(kv));
-                if (lane == 0) xs[g * CS + cnt_c] = p * a.scale;
+        for (int g = 0; g < G; ++g) {
+            const float mx = wave_max_fast(g == g_l ? mx_l : -INFINITY);
+            const float my = wave_max_fast(g == g_l ? my_l : -INFINITY);
+            if (lane == 0) {
+                red_s[2 * G * wv + 2 * g] = mx;
+                red_s[2 * G * wv + 2 * g + 1] = my;
+            }
+        }
+    }
+    // the new token's own logits (distance 0: no position bias)
+    if (wv == 0) {
+        const uint4 kv = ((const uint4*)knew)[cl];
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            QueryPiece<T> qg;
+            qg.load(((const uint4*)(qu + (size_t)g * D))[cl]);
+            const float p = group_sum<LPR>(qg.dot(kv));
+            if (lane == 0) {
+                float x = -INFINITY, y = -INFINITY;
+                if (owner) {
+                    const int hq = h * G + g;
+                    const uint32_t rk = rnd_l ? row_key(unit_key(a.seeds[b], (uint32_t)l, (uint32_t)hq), (uint32_t)q_pos) : 0u;
+                    x = (p * a.scale) * kLog2e;
+                    y = (x + zeta_log2e(a.noise, rk, (uint32_t)q_pos)) * inv_tau;
+                    xs[g * CS + cnt_c] = x;
+                    ys[g * CS + cnt_c] = y;
+                }
+                red_s[2 * G * NW + 2 * g] = x;
+                red_s[2 * G * NW + 2 * g + 1] = y;
             }
         }
     }
@@ -593,7 +645,7 @@ __device__ __forceinline__ void decode_block(const DecodeArgs& a) {
 
     // ---- phase 1.5: position bias, logit adjustment, the two softmaxes' statistics
     float mxy[2 * G];
-    if constexpr (MfmaLogits<T, G>::value) {
+    {
         // adjusted in the K stream; the waves' maxima (and the new token's logits) wait in red_s
         float* res = red_s + 2 * G * (NW + 1);
         if (tid < 2 * G) {
@@ -605,49 +657,6 @@ __device__ __forceinline__ void decode_block(const DecodeArgs& a) {
         __syncthreads();
 #pragma unroll
         for (int i = 0; i < 2 * G; ++i) mxy[i] = res[i];
-    } else {
-        float slope[G];
-        uint32_t rkey[G];
-        const bool rnd = (a.noise == kNoiseGumbel || a.noise == kNoiseGaussian);
-#pragma unroll
-        for (int g = 0; g < G; ++g) {
-            const int hq = h * G + g;
-            slope[g] = a.slopes ? a.slopes[hq] : 0.0f;
-            rkey[g] = rnd ? row_key(unit_key(a.seeds[b], (uint32_t)l, (uint32_t)hq), (uint32_t)q_pos) : 0u;
-        }
-#pragma unroll
-        for (int i = 0; i < 2 * G; ++i) mxy[i] = -INFINITY;
-        auto adjust = [&](int t, int pj) {  // t == cnt_c: the new token
-            const int dist = a.new_pos ? (len0 - (j0 + t)) : (q_pos - pj);  // the new token: 0 either way
-            const float fdist = (float)((t == cnt_c) ? 0 : dist);
-#pragma unroll
-            for (int g = 0; g < G; ++g) {
-                // base-2 domain: x2 = log2(e)*x, y2 = log2(e)*(x + zeta)/tau
-                const float x = (xs[g * CS + t] - slope[g] * fdist) * kLog2e;
-                const float y = (x + zeta_log2e(a.noise, rkey[g], (uint32_t)pj)) * inv_tau;
-                xs[g * CS + t] = x;
-                ys[g * CS + t] = y;
-                mxy[2 * g] = fmaxf(mxy[2 * g], x);
-                mxy[2 * g + 1] = fmaxf(mxy[2 * g + 1], y);
-            }
-        };
-        // the rows' positions come from memory: eight strides' worth are requested at once, so that a lane
-        // waits for one round trip per eight tokens instead of one per token
-        constexpr int PB = 8;
-        for (int t0 = tid; t0 < cnt; t0 += PB * NT) {
-            int pj[PB];
-#pragma unroll
-            for (int i = 0; i < PB; ++i) {
-                const int t = t0 + i * NT;
-                pj[i] = (t < cnt_c) ? pu[j0 + t] : q_pos;
-            }
-#pragma unroll
-            for (int i = 0; i < PB; ++i) {
-                const int t = t0 + i * NT;
-                if (t < cnt) adjust(t, pj[i]);
-            }
-        }
-        block_max_n<NT, 2 * G>(mxy, red_s);
     }
     float spe[2 * G];
 #pragma unroll
