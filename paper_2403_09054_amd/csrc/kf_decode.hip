@@ -27,7 +27,7 @@
 namespace kf {
 
 constexpr int kDecodeThreads = 256;
-constexpr int kDecodeThreadsBig = 512;   // 8 query heads, one split: a workgroup with up to most of a CU's LDS
+constexpr int kDecodeThreadsBig = 512;   // 4 or 8 query heads, one split: a workgroup with up to most of a CU's LDS
 constexpr int kDecodeRedWaves = 4;       // rows of LDS in which a workgroup's waves fold their partial outputs
 constexpr int kDecodeMaxChunk = 4096;   // tokens per split the LDS arrays are sized for
 constexpr int kDecodeMinBlocks = 1024;  // workgroups wanted on the chip
@@ -38,7 +38,8 @@ constexpr size_t kDecodeLdsBudget = 65536 - 1024;       // dynamic LDS of a spli
 constexpr size_t kDecodeLdsPair = 81920 - 1024;         // ... of a single-split workgroup: two fit a CU's 160 KB
 constexpr int kDecodeSingleMinUnits = 320;              // units from which one workgroup per unit fills the chip
 constexpr size_t kDecodeLdsWhole = 163840 - 2048;       // ... of a workgroup that has a CU to itself
-constexpr size_t kDecodeLdsThird = 53248;               // three workgroups of at most this much fit a CU
+constexpr size_t kDecodeBigMinLogits8 = 36 * 1024;      // logit bytes from which 8 query heads take the 8-wave workgroup
+constexpr size_t kDecodeBigMinLogits4 = 24 * 1024;      // ... 4 query heads
 constexpr int kDecodeBigMinUnits = 256;                 // units from which one such workgroup per unit fills the chip
 
 constexpr int kDecodeUnroll = 4;  // 16-byte loads a lane keeps in flight per tile (2 and 8 measured within 2 %)
@@ -210,7 +211,7 @@ __device__ __forceinline__ void decode_block(const DecodeArgs& a) {
     constexpr int UNR = (G >= 8) ? 2 : kDecodeUnroll;
     constexpr int TILE = RPB * UNR;              // rows per tile of the workgroup
     constexpr int PW = D + 4;                    // floats in a partial record
-    constexpr bool BIG = NW > kDecodeRedWaves;  // the 8-wave workgroup: one split, 8 query heads, up to most of a CU's LDS
+    constexpr bool BIG = NW > kDecodeRedWaves;  // the 8-wave workgroup: one split, 4 or 8 query heads, up to most of a CU's LDS
     constexpr size_t ROWB = (size_t)D * sizeof(T);
     static_assert(LPR <= 32 && D <= NT, "row must fit half a wave, output a block");
 
@@ -734,14 +735,15 @@ __device__ __forceinline__ void decode_block(const DecodeArgs& a) {
         }
     }
     // Partial outputs of the waves meet in LDS.  Few accumulators per lane: the rows of one wave-wide load
-    // (RPW lane groups) are folded with exchanges, lane group 0 stores.  Many (8 query heads): the fold is a
+    // (RPW lane groups) are folded with exchanges, lane group 0 stores.  Many (4 or 8 query heads): the fold is a
     // reduce-scatter, every lane group ends up with 1/RPW of the sums and stores those.  The 8-wave
     // workgroup stores later, into the logit area, once nobody reads logits any more (see below).
     constexpr int HV = G * EPV / RPW;  // sums a lane holds after the reduce-scatter
-    float fin[G >= 8 ? HV : 1];
+    constexpr bool RS = G >= 4;        // many accumulators per lane: reduce-scatter fold
+    float fin[RS ? HV : 1];
     int off = 0;
     auto store_fin = [&](float* row) {  // this lane's sums -> its places in a [G][D] row of partial outputs
-        if constexpr (G >= 8) {
+        if constexpr (RS) {
 #pragma unroll
             for (int i4 = 0; i4 < HV / 4; ++i4) {
                 const int fi = off + 4 * i4;
@@ -750,9 +752,9 @@ __device__ __forceinline__ void decode_block(const DecodeArgs& a) {
             }
         }
     };
-    if constexpr (G >= 8) {
+    if constexpr (RS) {
         constexpr int N = G * EPV;
-        static_assert(HV % EPV == 0 && EPV % 4 == 0, "a lane group ends up with whole output-row pieces");
+        static_assert(HV % 4 == 0, "a lane group ends up with whole 16-byte pieces of output rows");
         float flat[N];
 #pragma unroll
         for (int i = 0; i < N; ++i) flat[i] = acc[i / EPV][i % EPV];
@@ -777,7 +779,7 @@ __device__ __forceinline__ void decode_block(const DecodeArgs& a) {
             __syncthreads();  // red_o and stat are complete
         }
     } else {
-        static_assert(!BIG, "the 8-wave workgroup is built for 8 query heads");
+        static_assert(!BIG, "the 8-wave workgroup is built for 4 and 8 query heads");
 #pragma unroll
         for (int o = LPR; o < kWave; o <<= 1) {
 #pragma unroll
@@ -1045,8 +1047,8 @@ DecodePlan plan_decode(int64_t U, int32_t m, int32_t d, int32_t dtype, int32_t G
     DecodePlan p;
     const int rpb = rows_per_block(d, dtype);
     const int64_t rows = m > 1 ? m - 1 : 1;  // cache rows; the new token rides with the last split
-    if (G == 8 && dtype == KF_BF16 && U >= kDecodeBigMinUnits) {
-        // one workgroup per unit, up to one per CU with the unit's 2 x 8 logit rows in most of the CU's LDS
+    if ((G == 4 || (G == 8 && dtype == KF_BF16)) && U >= kDecodeBigMinUnits) {
+        // one workgroup per unit, up to one per CU with the unit's 2 x G logit rows in most of the CU's LDS
         const int64_t chunk = (rows + rpb - 1) / rpb * rpb;
         if (decode_lds_bytes_big(G, chunk, d) <= kDecodeLdsWhole) {
             p.S = 1;
@@ -1103,12 +1105,14 @@ DecodePlan plan_decode(int64_t U, int32_t m, int32_t d, int32_t dtype, int32_t G
 template <typename T, int D, int G>
 static hipError_t launch_decode_g(const DecodeArgs& a, int64_t U, size_t lds, hipStream_t st, bool merge) {
     const dim3 grid((unsigned)(U * a.S)), block(kDecodeThreads);
-    if constexpr (G == 8 && MfmaLogits<T, G>::value) {
-        // one split with 8 query heads: short units keep the 4-wave workgroup (three or more fit a CU), longer
-        // ones take 8 waves (two per CU up to ~1000 tokens, then one with most of the CU's LDS).  Measured at
-        // 2048 units, d = 128: 512 tokens 51 % (4 waves) vs 49 % (8) vs 36 % (16); 1024 tokens 49 / 62 / 49 %;
-        // 2048 tokens - / 62 / 58 %.
-        if (a.S == 1 && decode_lds_bytes(G, a.chunk, D) > kDecodeLdsThird) {
+    if constexpr (G == 4 || (G == 8 && MfmaLogits<T, G>::value)) {
+        // One split with 4 or 8 query heads: short units keep the 4-wave workgroup (three or more fit a CU),
+        // longer ones take 8 waves (two per CU while the logits stay under ~75 KB, then one with most of the CU's
+        // LDS).  Measured at 2048 units, d = 128, 8 heads: 512 tokens 51 % (4 waves) vs 49 % (8) vs 36 % (16 waves);
+        // 1024 tokens 49 / 62 / 49 %; 2048 tokens - / 62 / 58 %.  4 heads: 512 tokens 67 % (4 waves) vs 63 % (8);
+        // 1024 tokens 71 / 74.5 %; 2048 tokens 73-78 / 80 %.
+        const size_t logits = (size_t)2 * G * (a.chunk + 1) * sizeof(float);
+        if (a.S == 1 && logits > (G == 8 ? kDecodeBigMinLogits8 : kDecodeBigMinLogits4)) {
             const size_t lds_big = decode_lds_bytes_big(G, a.chunk, D);
             if (lds_big > kDecodeLdsWhole) return hipErrorInvalidValue;
             hipLaunchKernelGGL((decode_kernel<T, D, kDecodeThreadsBig, G>), grid, dim3(kDecodeThreadsBig), lds_big, st, a);

@@ -1054,16 +1054,19 @@ def test_grouped_query_decode_at_the_largest_lds_footprint():
     assert_close_score(host(gc.score), oc.score, oc.len)
 
 
-@pytest.mark.parametrize("d,noise,new_pos", [(128, ko.NOISE_GUMBEL, False), (64, ko.NOISE_GAUSSIAN, True),
-                                             (256, ko.NOISE_NONE, False)])
-def test_grouped_query_eight_heads_one_workgroup_per_unit(d, noise, new_pos):
-    """8 bf16 query heads per cached head and a unit per compute unit: one 8-wave workgroup streams a whole
-    unit (logits on the matrix cores, adjusted in the K stream, partial outputs folded into the logit area)."""
-    rng = np.random.default_rng(7400 + d)
-    L, B, H, G = 2, 8, 16, 8
-    cap = 2049 if d == 128 else 1500
+@pytest.mark.parametrize("dtype,d,G,noise,new_pos,cap", [
+    (ko.BF16, 128, 8, ko.NOISE_GUMBEL, False, 2049), (ko.BF16, 64, 8, ko.NOISE_GAUSSIAN, True, 1500),
+    (ko.BF16, 256, 8, ko.NOISE_NONE, False, 1500), (ko.BF16, 128, 4, ko.NOISE_GUMBEL, False, 4097),
+    (ko.BF16, 64, 4, ko.NOISE_GUMBEL, True, 1500), (ko.BF16, 256, 4, ko.NOISE_CONSTANT, False, 900),
+    (ko.F32, 64, 4, ko.NOISE_GUMBEL, False, 1100)])
+def test_grouped_query_one_eight_wave_workgroup_per_unit(dtype, d, G, noise, new_pos, cap):
+    """4 or 8 query heads per cached head, a unit per compute unit and more than a few hundred tokens: one
+    8-wave workgroup streams a whole unit (8 bf16 heads: logits on the matrix cores; partial outputs folded as a
+    reduce-scatter into the logit area)."""
+    rng = np.random.default_rng(7400 + d + G)
+    L, B, H = 2, 8, 16
     c0 = kf.Cache(K=0x10000, V=0x20000, score=0x30000, pos=0x40000, len=0x50000, L=L, B=B, H=H, d=d, cap=cap,
-                  dtype=kf.BF16, q_per_kv=G)
+                  dtype=dtype, q_per_kv=G)
     S, chunk = kf.kf_decode_launch_shape(c0, cap)
     assert S == 1 and chunk >= cap - 1
     lens = rng.integers(cap - 300, cap, (L, B, H)).astype(np.int32)
@@ -1072,11 +1075,11 @@ def test_grouped_query_eight_heads_one_workgroup_per_unit(d, noise, new_pos):
     lens[0, 0, 2] = 15           # less than one 16-row tile of one wave
     lens[0, 0, 3] = 257          # one row into the second sweep of the 16 waves
     lens[1, 7, 15] = cap         # no room: skipped and reported
-    oc = random_cache(rng, L, B, H, d, cap, ko.BF16, lens)
+    oc = random_cache(rng, L, B, H, d, cap, dtype, lens)
     gc = upload(oc, G)
     ws = kf.new_workspace(gc)
-    q = rnd(rng, (L, B, H * G, d), ko.BF16)
-    kn, vn = (rnd(rng, (L, B, H, d), ko.BF16) for _ in range(2))
+    q = rnd(rng, (L, B, H * G, d), dtype)
+    kn, vn = (rnd(rng, (L, B, H, d), dtype) for _ in range(2))
     seeds = (np.arange(B) * 7 + 1).astype(np.uint64)
     slopes = (0.5 ** (np.arange(1, H * G + 1) / 16.0)).astype(np.float32) * 0.05
     q_pos = int(oc.pos.max()) + 1

@@ -151,6 +151,10 @@ def test_decode_launch_shape_covers_the_rows_and_balances_the_chip():
     assert kf.kf_decode_launch_shape(fake_cache(L=32, B=8, H=8, d=128, cap=2049, q_per_kv=8), 2049) == (1, 2048)
     S, chunk = kf.kf_decode_launch_shape(fake_cache(L=32, B=8, H=8, d=128, cap=4097, q_per_kv=8), 4097)
     assert S >= 8 and chunk <= 512
+    # 4 query heads: the same up to about 5000 tokens
+    assert kf.kf_decode_launch_shape(fake_cache(L=32, B=8, H=8, d=128, cap=4097, q_per_kv=4), 4097) == (1, 4096)
+    S, chunk = kf.kf_decode_launch_shape(fake_cache(L=32, B=8, H=8, d=128, cap=8193, q_per_kv=4), 8193)
+    assert S >= 8 and chunk <= 1024
     S, chunk = kf.kf_decode_launch_shape(fake_cache(L=2, B=8, H=8, d=128, cap=2049, q_per_kv=8), 2049)
     assert S >= 4 and chunk <= 512
     S, chunk = kf.kf_decode_launch_shape(fake_cache(L=32, B=8, H=8, d=128, cap=2049, q_per_kv=8, dtype=kf.F32), 2049)
