@@ -750,6 +750,12 @@ __device__ __forceinline__ void decode_block(const DecodeArgs& a) {
                 *(float4*)&row[(fi / EPV) * D + cl * EPV + (fi % EPV)] =
                     make_float4(fin[4 * i4], fin[4 * i4 + 1], fin[4 * i4 + 2], fin[4 * i4 + 3]);
             }
+        } else if (sub == 0) {  // folded over the lane groups with exchanges: group 0 has the sums
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+#pragma unroll
+                for (int e = 0; e < EPV; ++e) row[g * D + cl * EPV + e] = acc[g][e];
+            }
         }
     };
     if constexpr (RS) {
@@ -779,7 +785,6 @@ __device__ __forceinline__ void decode_block(const DecodeArgs& a) {
             __syncthreads();  // red_o and stat are complete
         }
     } else {
-        static_assert(!BIG, "the 8-wave workgroup is built for 4 and 8 query heads");
 #pragma unroll
         for (int o = LPR; o < kWave; o <<= 1) {
 #pragma unroll
@@ -788,14 +793,10 @@ __device__ __forceinline__ void decode_block(const DecodeArgs& a) {
                 for (int e = 0; e < EPV; ++e) acc[g][e] += __shfl_xor(acc[g][e], o, kWave);
             }
         }
-        if (sub == 0) {
-#pragma unroll
-            for (int g = 0; g < G; ++g) {
-#pragma unroll
-                for (int e = 0; e < EPV; ++e) red_o[(wv * G + g) * D + cl * EPV + e] = acc[g][e];
-            }
+        if constexpr (!BIG) {
+            store_fin(red_o + (size_t)wv * G * D);
+            __syncthreads();  // red_o and stat are complete
         }
-        __syncthreads();  // red_o and stat are complete
     }
     if (S == 1) {
         // the whole unit is here: accumulate the normalised score increment of all its query heads
@@ -1065,6 +1066,12 @@ DecodePlan plan_decode(int64_t U, int32_t m, int32_t d, int32_t dtype, int32_t G
             p.lds_bytes = decode_lds_bytes(G, chunk, d);
             return p;
         }
+        if (decode_lds_bytes_big(G, chunk, d) <= kDecodeLdsWhole) {  // one 8-wave workgroup per CU
+            p.S = 1;
+            p.chunk = (int32_t)chunk;
+            p.lds_bytes = decode_lds_bytes_big(G, chunk, d);
+            return p;
+        }
     }
     // LDS of a split workgroup: within 64 KB less the small static arrays
     const int lds_rows = (int)((kDecodeLdsBudget - 3 * sizeof(float) - (size_t)kDecodeRedWaves * G * d * sizeof(float)) /
@@ -1120,6 +1127,14 @@ static hipError_t launch_decode_g(const DecodeArgs& a, int64_t U, size_t lds, hi
         }
     }
     lds = decode_lds_bytes(G, a.chunk, D);  // what this workgroup shape needs for the plan's chunk
+    if constexpr (G <= 2) {
+        if (a.S == 1 && lds > kDecodeLdsPair) {  // a unit too long for two workgroups per CU: one of 8 waves
+            const size_t lds_big = decode_lds_bytes_big(G, a.chunk, D);
+            if (lds_big > kDecodeLdsWhole) return hipErrorInvalidValue;
+            hipLaunchKernelGGL((decode_kernel<T, D, kDecodeThreadsBig, G>), grid, dim3(kDecodeThreadsBig), lds_big, st, a);
+            return hipGetLastError();
+        }
+    }
     if (lds > kDecodeLdsPair) return hipErrorInvalidValue;
     hipLaunchKernelGGL((decode_kernel<T, D, kDecodeThreads, G>), grid, block, lds, st, a);
     hipError_t e = hipGetLastError();

@@ -1102,6 +1102,38 @@ def test_grouped_query_one_eight_wave_workgroup_per_unit(dtype, d, G, noise, new
     assert_close_score(g_score, oc.score, oc.len)
 
 
+@pytest.mark.parametrize("d,G,cap", [(128, 1, 12001), (128, 2, 6001)])
+def test_long_units_one_eight_wave_workgroup_per_unit(d, G, cap):
+    """Units whose logits no longer fit a compute unit's LDS twice (about 10 k tokens with one query head) but
+    still fit it once stay one workgroup's, of 8 waves: no increments through memory, no merge launch."""
+    rng = np.random.default_rng(7500 + d + G)
+    L, B, H = 1, 10, 32
+    c0 = kf.Cache(K=0x10000, V=0x20000, score=0x30000, pos=0x40000, len=0x50000, L=L, B=B, H=H, d=d, cap=cap,
+                  dtype=kf.BF16, q_per_kv=G)
+    S, chunk = kf.kf_decode_launch_shape(c0, cap)
+    assert S == 1 and chunk >= cap - 1
+    lens = rng.integers(cap - 2000, cap, (L, B, H)).astype(np.int32)
+    lens[0, 0, 0] = cap - 1
+    lens[0, 0, 1] = 3
+    oc = random_cache(rng, L, B, H, d, cap, ko.BF16, lens)
+    gc = upload(oc, G)
+    ws = kf.new_workspace(gc)
+    q = rnd(rng, (L, B, H * G, d), ko.BF16)
+    kn, vn = (rnd(rng, (L, B, H, d), ko.BF16) for _ in range(2))
+    seeds = (np.arange(B) * 11 + 5).astype(np.uint64)
+    slopes = (0.5 ** (np.arange(1, H * G + 1) / 8.0)).astype(np.float32) * 0.01
+    q_pos = int(oc.pos.max()) + 1
+    out = torch.zeros((L, B, H * G, d), dtype=torch.float32, device="cuda")
+    scale = float(1.0 / np.sqrt(np.float32(d)))
+    kf.kf_decode_step(gc, dev(q), dev(kn), dev(vn), q_pos, cap, 1.25, scale, kf.NOISE_GUMBEL, dev(seeds), dev(slopes), out, ws)
+    torch.cuda.synchronize()
+    assert error_word(ws) == 0
+    out_ref = oc.decode_step(q, kn, vn, q_pos, 1.25, scale, ko.NOISE_GUMBEL, seeds, slopes, q_per_kv=G)
+    assert_close_out(host(out), out_ref)
+    np.testing.assert_array_equal(host(gc.len), oc.len)
+    assert_close_score(host(gc.score), oc.score, oc.len)
+
+
 # ------------------------------------------------------------------ sequences at different steps
 @pytest.mark.parametrize("cap,layout", [(120, kf.LAYOUT_ORDERED), (1500, kf.LAYOUT_ORDERED), (300, kf.LAYOUT_SLOT)])
 def test_per_sequence_position_and_temperature(cap, layout):
@@ -1153,15 +1185,17 @@ def test_standalone_cpp_user_of_the_c_abi():
 
 
 # ------------------------------------------------------------------ whole step in one launch (slot layout, one split)
-@pytest.mark.parametrize("dtype,d,G,w", [(ko.BF16, 64, 1, 26), (ko.BF16, 128, 1, 0), (ko.F32, 64, 1, 26),
-                                         (ko.BF16, 128, 2, 26), (ko.BF16, 64, 4, 129), (ko.BF16, 128, 8, 26),
-                                         (ko.BF16, 64, 8, 0), (ko.BF16, 256, 8, 50)])
-def test_single_launch_slot_step_equals_the_two_calls(dtype, d, G, w):
+@pytest.mark.parametrize("dtype,d,G,w,k", [
+    (ko.BF16, 64, 1, 26, 129), (ko.BF16, 128, 1, 0, 129), (ko.F32, 64, 1, 26, 129), (ko.BF16, 128, 2, 26, 129),
+    (ko.BF16, 64, 4, 129, 129), (ko.BF16, 128, 8, 26, 129), (ko.BF16, 64, 8, 0, 129), (ko.BF16, 256, 8, 50, 129),
+    (ko.BF16, 128, 1, 2000, 10500),      # a unit too long for two workgroups per CU: one 8-wave workgroup
+    (ko.BF16, 128, 4, 300, 1500)])       # 4 query heads in the 8-wave workgroup
+def test_single_launch_slot_step_equals_the_two_calls(dtype, d, G, w, k):
     """With at least 320 units of a length that fits LDS, kf_decode_select_step in the slot layout is ONE
     launch: the workgroup that scored a unit evicts for it and stores the new token straight into the freed
     slot.  Same results, bit for bit, as kf_decode_step + kf_select_evict (which the oracle checks)."""
     rng = np.random.default_rng(9000 + d + G + w)
-    L, B, H, k = 4, 4, 20, 129
+    L, B, H = 4, 4, 20
     cap = k + 2
     c0 = kf.Cache(K=0x10000, V=0x20000, score=0x30000, pos=0x40000, len=0x50000, L=L, B=B, H=H, d=d, cap=cap,
                   dtype=dtype, q_per_kv=G)
@@ -1184,7 +1218,7 @@ def test_single_launch_slot_step_equals_the_two_calls(dtype, d, G, w):
     kept_a = torch.zeros((L, B, H, k), dtype=torch.int32, device="cuda")
     kept_b = torch.zeros_like(kept_a)
     seq_pos = torch.from_numpy(np.full(B, k, np.int32)).cuda()
-    for t in range(1, 4):
+    for t in range(1, 4 if k < 1000 else 3):
         q = dev(rnd(rng, (L, B, H * G, d), dtype))
         kn, vn = (dev(rnd(rng, (L, B, H, d), dtype)) for _ in range(2))
         q_pos = k + t - 1

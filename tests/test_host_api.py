@@ -134,7 +134,7 @@ def test_decode_launch_shape_covers_the_rows_and_balances_the_chip():
         c = fake_cache(L=L, B=B, H=H, d=d, cap=cap, dtype=dt)
         S, chunk = kf.kf_decode_launch_shape(c, hint)
         rows = (hint or cap) - 1
-        assert 1 <= S <= 256 and 1 <= chunk <= (10240 if S == 1 else 4096)     # LDS: 80 KB single, 64 KB split
+        assert 1 <= S <= 256 and 1 <= chunk <= (20480 if S == 1 else 4096)     # LDS: up to 158 KB single, 64 KB split
         assert S * chunk >= rows                      # every cache row belongs to a split
         assert (S - 1) * chunk < max(rows, 1) or S == 1   # no split is entirely beyond the rows
     # more than one unit per compute unit and the logits fit LDS: one workgroup per unit, nothing to merge
@@ -143,9 +143,12 @@ def test_decode_launch_shape_covers_the_rows_and_balances_the_chip():
     assert kf.kf_decode_launch_shape(fake_cache(L=32, B=1, H=32, d=128, cap=9831), 9831) == (1, 9840)
     # too few units to fill the chip that way: 256 units -> 4 splits of 256 rows = 1024 workgroups
     assert kf.kf_decode_launch_shape(fake_cache(L=16, B=1, H=16, d=256, cap=1025), 1025) == (4, 256)
-    # logits of one unit beyond what two workgroups per compute unit can hold in LDS: splits of at most 4096 rows
-    S, chunk = kf.kf_decode_launch_shape(fake_cache(L=32, B=1, H=32, d=128, cap=20000), 20000)
-    assert S >= 5 and chunk <= 4096
+    # logits beyond what two workgroups per compute unit can hold in LDS, but within one's reach: still one per unit
+    S, chunk = kf.kf_decode_launch_shape(fake_cache(L=32, B=1, H=32, d=128, cap=16385), 16385)
+    assert S == 1 and chunk >= 16384
+    # beyond that: splits of at most 4096 rows
+    S, chunk = kf.kf_decode_launch_shape(fake_cache(L=32, B=1, H=32, d=128, cap=24000), 24000)
+    assert S >= 6 and chunk <= 4096
     # 8 bf16 query heads per cached head: one workgroup per unit while 2 x 8 logit rows fit a compute
     # unit's LDS (about 2500 tokens) and there is a unit per compute unit; splits of at most 512 rows otherwise
     assert kf.kf_decode_launch_shape(fake_cache(L=32, B=8, H=8, d=128, cap=2049, q_per_kv=8), 2049) == (1, 2048)
