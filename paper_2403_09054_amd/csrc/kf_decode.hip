@@ -1031,10 +1031,11 @@ static size_t decode_lds_bytes_big(int32_t G, int64_t chunk, int32_t d) {
 // the unit is finished by the workgroup that streamed it -- no increments and
 // partial records through memory, no merge launch -- which measures 6-15 %
 // faster than any split (gptj 82 vs 89 us, long 790 vs 875 us).  It needs the
-// unit's logits in LDS twice (two workgroups must still fit a CU's 160 KB), and
-// enough units that a CU has more than one workgroup to overlap (at 256 units a
-// split wins again); with 8 query heads per unit the registers allow too few
-// waves for rows that long.
+// unit's 2*G logit rows in LDS -- twice per CU for the 4-wave workgroup, once
+// (up to most of a CU's 160 KB) for the 8-wave workgroup that takes the units
+// beyond that and the longer ones with 4 or 8 query heads (16 k tokens with one
+// head: 87 % of the HBM peak against 75 % in splits) -- and enough units to
+// fill the chip (at 256 units of one head a split wins again).
 //
 // Otherwise the launch is bandwidth bound and every workgroup does the same
 // amount of work, so what matters is how evenly U*S workgroups spread over the
