@@ -187,3 +187,27 @@ class OracleCache:
         if rc:
             raise ValueError("kfo_select_evict rc=%d" % rc)
         return kept
+
+    def beam_fork(self, parent):
+        """Beam search with one cache per beam (Sec. 4: every evaluation uses 4 beams; Sec. 6: tokens are
+        discarded across heads, layers and beams): row b of the batch continues the hypothesis that row
+        parent[b] held before this step.  Rows that continue themselves keep their state; every other
+        row receives a copy of its parent's live entries (K, V, score, pos, len).  A parent must continue
+        itself -- the caller numbers the new beams so -- because its row is read while others are written."""
+        parent = np.asarray(parent, np.int64)
+        assert parent.shape == (self.B,)
+        for b in range(self.B):
+            pb = int(parent[b])
+            if not (0 <= pb < self.B) or int(parent[pb]) != pb:
+                raise ValueError("beam %d: parent %d does not continue itself" % (b, pb))
+        for b in range(self.B):
+            pb = int(parent[b])
+            if pb == b:
+                continue
+            for l in range(self.L):
+                for h in range(self.H):
+                    m = int(self.len[l, pb, h])
+                    for nm in ("K", "V", "score", "pos"):
+                        getattr(self, nm)[l, b, h, :m] = getattr(self, nm)[l, pb, h, :m]
+                    self.len[l, b, h] = m
+

@@ -778,3 +778,46 @@ def test_select_random_shapes_against_stable_sort():
         np.testing.assert_array_equal(c.K[0, 0, 0, :k], before.K[0, 0, 0, want])
 
     check()
+
+
+# ----------------------------------------------------------------------------
+# Beam search: one cache per beam (Sec. 4 uses 4 beams everywhere)
+# ----------------------------------------------------------------------------
+def test_beam_fork_copies_the_parent_state():
+    rng = np.random.default_rng(31)
+    L, B, H, d, cap = 2, 4, 2, 16, 12
+    c = make_cache(rng, L, B, H, d, cap, cap, ko.BF16)
+    c.score[...] = rng.random(c.score.shape).astype(np.float32)
+    c.pos[...] = rng.integers(0, 1000, c.pos.shape)
+    c.len[...] = rng.integers(1, cap - 1, c.len.shape)
+    before = c.copy()
+    same = c.copy()
+    same.beam_fork([0, 1, 2, 3])                       # every beam continues itself: nothing moves
+    for nm in ("K", "V", "score", "pos", "len"):
+        np.testing.assert_array_equal(getattr(same, nm), getattr(before, nm))
+    c.beam_fork([0, 0, 2, 0])                          # beams 1 and 3 died; beam 0 has three continuations
+    for l, h in itertools.product(range(L), range(H)):
+        m = int(before.len[l, 0, h])
+        for b in (1, 3):
+            assert c.len[l, b, h] == m
+            for nm in ("K", "V", "score", "pos"):
+                np.testing.assert_array_equal(getattr(c, nm)[l, b, h, :m], getattr(before, nm)[l, 0, h, :m])
+                # beyond the parent's length the row keeps what it had
+                np.testing.assert_array_equal(getattr(c, nm)[l, b, h, m:], getattr(before, nm)[l, b, h, m:])
+        for b in (0, 2):
+            for nm in ("K", "V", "score", "pos"):
+                np.testing.assert_array_equal(getattr(c, nm)[l, b, h], getattr(before, nm)[l, b, h])
+    # a forked beam that is fed what its parent is fed (and draws its noise) answers like its parent
+    q = rand_vec(rng, (L, 1, H, d), ko.BF16).repeat(B, axis=1)
+    kn = rand_vec(rng, (L, 1, H, d), ko.BF16).repeat(B, axis=1)
+    vn = rand_vec(rng, (L, 1, H, d), ko.BF16).repeat(B, axis=1)
+    seeds = np.array([5, 5, 5, 5], np.uint64)
+    out = c.decode_step(q, kn, vn, 40, 1.5, 0.25, ko.NOISE_GUMBEL, seeds)
+    np.testing.assert_array_equal(out[:, 1], out[:, 0])
+    np.testing.assert_array_equal(out[:, 3], out[:, 0])
+    assert not np.array_equal(out[:, 2], out[:, 0])
+    with pytest.raises(ValueError):
+        c.beam_fork([1, 0, 2, 3])                      # 0 and 1 swap: neither continues itself
+    with pytest.raises(ValueError):
+        c.beam_fork([0, 4, 2, 3])
+
