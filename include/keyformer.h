@@ -229,6 +229,23 @@ kf_status kf_select_evict_into(const kf_cache *src, kf_cache *dst, int32_t dst_l
                                int32_t *kept_idx, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Beam search with one cache per beam (Sec. 4: every evaluation runs 4 beams;
+ * Sec. 6: tokens are discarded across heads, layers and beams).  Rows of the
+ * batch dimension are beams; after a search step row b continues the hypothesis
+ * that row parent[b] held.  For every b with parent[b] != b the live entries of
+ * all of row parent[b]'s units (K, V, score, pos rows [0, len), and len) are
+ * copied to row b's; rows with parent[b] == b are not touched.  A parent must
+ * continue itself (parent[parent[b]] == parent[b]: its row is read while others
+ * are written), which the caller arranges by numbering the new beams so that
+ * every surviving hypothesis keeps its row for one of its continuations and the
+ * others take the rows of hypotheses that died.  Only forked beams cost traffic.
+ * parent is DEVICE [B].  A row whose parent is out of range or does not continue
+ * itself is left as it is and each of its units counted in the error word.
+ * Errors: KF_EINVAL for null pointers.
+ */
+kf_status kf_beam_fork(kf_cache *c, const int32_t *parent, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * One whole generation step: kf_decode_step followed by kf_select_evict, with
  * the same arguments, results and error behaviour as the two calls in a row,
  * in as few kernel launches as the shape allows: one in the slot layout when

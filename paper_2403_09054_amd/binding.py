@@ -23,7 +23,7 @@ KF_OK, KF_EINVAL, KF_EUNSUPPORTED, KF_EWORKSPACE, KF_EDEVICE = 0, -1, -2, -3, -4
 # every symbol include/keyformer.h declares
 SYMBOLS = ("kf_version", "kf_last_error", "kf_tau", "kf_noise_bits", "kf_workspace_bytes",
            "kf_prefill_score", "kf_decode_step", "kf_select_evict", "kf_select_evict_into", "kf_decode_select_step",
-           "kf_decode_launch_shape", "kf_decode_select_step_at")
+           "kf_decode_launch_shape", "kf_decode_select_step_at", "kf_beam_fork")
 
 
 class KeyformerError(RuntimeError):
@@ -91,6 +91,8 @@ def lib():
         L.kf_select_evict_into.restype = C.c_int
         L.kf_select_evict_into.argtypes = [C.POINTER(kf_cache), C.POINTER(kf_cache), C.c_int32, C.c_int32, C.c_int32,
                                            vp, vp, C.c_size_t, vp]
+        L.kf_beam_fork.restype = C.c_int
+        L.kf_beam_fork.argtypes = [C.POINTER(kf_cache), vp, vp, C.c_size_t, vp]
         L.kf_decode_select_step.restype = C.c_int
         L.kf_decode_select_step.argtypes = [C.POINTER(kf_cache), vp, vp, vp, C.c_int32, C.c_int32,
                                             C.POINTER(kf_score_cfg), vp, C.c_int32, C.c_int32, C.c_int32, vp, vp,
@@ -215,6 +217,13 @@ def kf_prefill_score(cache: Cache, Q, n: int, tau: float, scale: float, noise: i
     cs, cfg = cache.c_struct(), _cfg(tau, scale, noise, seeds, slopes, 0, score_mode, seq_n=seq_n)
     wp, wb = _ws(workspace)
     _check(lib().kf_prefill_score(C.byref(cs), _ptr(Q), n, C.byref(cfg), wp, wb, _stream(stream)))
+
+
+def kf_beam_fork(cache: Cache, parent, workspace=None, stream=None) -> None:
+    """parent: int32 device tensor [B]; row b of the batch takes over the cache state of row parent[b]."""
+    cs = cache.c_struct()
+    wp, wb = _ws(workspace)
+    _check(lib().kf_beam_fork(C.byref(cs), _ptr(parent), wp, wb, _stream(stream)))
 
 
 def kf_decode_step(cache: Cache, q, k_new, v_new, q_pos: int, m_hint: int, tau: float, scale: float,

@@ -400,6 +400,34 @@ kf_status kf_select_evict(kf_cache* c, int32_t k, int32_t w, int32_t layout, int
     return KF_OK;
 }
 
+kf_status kf_beam_fork(kf_cache* c, const int32_t* parent, void* workspace, size_t workspace_bytes, void* stream) {
+    kf_status st = check_cache(c);
+    if (st != KF_OK) return st;
+    if (!parent) return fail(KF_EINVAL, "parent is NULL");
+    const WsLayout w = ws_layout(c, 0);
+    st = check_ws(workspace, workspace_bytes, w.total);
+    if (st != KF_OK) return st;
+    kf::ForkArgs f;
+    f.K = c->K;
+    f.V = c->V;
+    f.score = c->score;
+    f.pos = c->pos;
+    f.len = c->len;
+    f.parent = parent;
+    f.ws_err = (int32_t*)workspace + KF_WS_ERROR_WORD;
+    f.L = c->L;
+    f.B = c->B;
+    f.H = c->H;
+    f.cap = c->cap;
+    f.row_bytes = c->d * (c->dtype == KF_F32 ? 4 : 2);
+    const int64_t U = (int64_t)c->L * c->B * c->H;
+    if ((U + 32767) / 32768 > 65535) return fail(KF_EUNSUPPORTED, "%lld units exceed the largest launch", (long long)U);
+    const hipError_t e = kf::launch_fork(f, (hipStream_t)stream);
+    if (e != hipSuccess) return fail(KF_EDEVICE, "fork launch: %s", hipGetErrorString(e));
+    g_err[0] = 0;
+    return KF_OK;
+}
+
 kf_status kf_select_evict_into(const kf_cache* src, kf_cache* dst, int32_t dst_layer0, int32_t k, int32_t w,
                                int32_t* kept_idx, void* workspace, size_t workspace_bytes, void* stream) {
     kf_status st = check_cache(dst);

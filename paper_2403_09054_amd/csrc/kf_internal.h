@@ -124,6 +124,19 @@ struct GatherArgs {
     int32_t src_cap, dst_cap, k, row_bytes;
 };
 hipError_t launch_gather(const GatherArgs& g, hipStream_t stream);
+
+// Beam fork: row b of the batch takes over the state of row parent[b] (see kf_beam_fork).
+struct ForkArgs {
+    void* K;
+    void* V;
+    float* score;
+    int32_t* pos;
+    int32_t* len;
+    const int32_t* parent;  // [B]
+    int32_t* ws_err;
+    int32_t L, B, H, cap, row_bytes;
+};
+hipError_t launch_fork(const ForkArgs& f, hipStream_t stream);
 // decode merge + select + compact of every unit in one launch (after the split kernel of a fused step)
 hipError_t launch_step_tail(const DecodeArgs& d, const SelectArgs& a, int64_t U, int32_t hd, hipStream_t stream);
 // the split kernel alone (no merge launch): first half of a fused step

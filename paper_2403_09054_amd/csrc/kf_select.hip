@@ -769,6 +769,68 @@ hipError_t launch_gather(const GatherArgs& g, hipStream_t stream) {
     return hipGetLastError();
 }
 
+// Beam fork (beam search, one cache per beam): gridDim.x workgroups share the live rows of a destination unit
+// and copy them from the parent beam's unit -- a lane one 16-byte piece of K or V at a time, four in flight --
+// with their scores and positions.  The parent's row of the batch is only read in this launch (it continues
+// itself), so source and destination never meet.  Few, looping workgroups per unit rather than one per 64
+// rows: most calls fork few beams or none, and a workgroup that finds nothing to do still costs its launch.
+constexpr int kForkDepth = 4;
+__global__ void __launch_bounds__(kGatherThreads) fork_kernel(const ForkArgs f) {
+    const int64_t u = blockIdx.y + (int64_t)blockIdx.z * gridDim.y;  // destination unit
+    const int64_t units = (int64_t)f.L * f.B * f.H;
+    if (u >= units) return;
+    const int h = (int)(u % f.H), b = (int)((u / f.H) % f.B);
+    const int64_t l = u / ((int64_t)f.H * f.B);
+    const int pb = f.parent[b];
+    if (pb == b) return;
+    if (pb < 0 || pb >= f.B || f.parent[pb] != pb) {
+        if (blockIdx.x == 0 && threadIdx.x == 0) atomicAdd(f.ws_err, 1);
+        return;
+    }
+    const int64_t us = (l * f.B + pb) * f.H + h;  // source unit
+    const int n = min(max(f.len[us], 0), f.cap);
+    if (blockIdx.x == 0 && threadIdx.x == 0) f.len[u] = n;
+    const int per = (n + (int)gridDim.x - 1) / (int)gridDim.x;
+    const int row0 = (int)blockIdx.x * per, row1 = min(n, row0 + per);
+    if (row0 >= row1) return;
+    const int tid = threadIdx.x;
+    const int PPR = f.row_bytes >> 4;
+    const size_t so = (size_t)us * f.cap * PPR + (size_t)row0 * PPR, dof = (size_t)u * f.cap * PPR + (size_t)row0 * PPR;
+    const int pieces = (row1 - row0) * PPR;  // per tensor; the rows of a slice are contiguous
+    for (int p0 = tid; p0 < 2 * pieces; p0 += kForkDepth * kGatherThreads) {
+        uint4 v[kForkDepth];
+#pragma unroll
+        for (int i = 0; i < kForkDepth; ++i) {
+            const int p = p0 + i * kGatherThreads;
+            v[i] = make_uint4(0u, 0u, 0u, 0u);
+            if (p < 2 * pieces) v[i] = stream_load((p >= pieces ? (const uint4*)f.V + so + (p - pieces) : (const uint4*)f.K + so + p));
+        }
+#pragma unroll
+        for (int i = 0; i < kForkDepth; ++i) {
+            const int p = p0 + i * kGatherThreads;
+            if (p < 2 * pieces) stream_store((p >= pieces ? (uint4*)f.V + dof + (p - pieces) : (uint4*)f.K + dof + p), v[i]);
+        }
+    }
+    for (int r = row0 + tid; r < row1; r += kGatherThreads) {
+        f.score[(size_t)u * f.cap + r] = f.score[(size_t)us * f.cap + r];
+        f.pos[(size_t)u * f.cap + r] = f.pos[(size_t)us * f.cap + r];
+    }
+}
+
+hipError_t launch_fork(const ForkArgs& f, hipStream_t stream) {
+    const int64_t units = (int64_t)f.L * f.B * f.H;
+    const unsigned gy = (unsigned)(units < 32768 ? units : 32768);
+    const unsigned gz = (unsigned)((units + gy - 1) / gy);
+    // slices per unit: about 64 KB of rows each, at most 16, fewer when the units alone fill the chip
+    const int64_t unit_bytes = 2 * (int64_t)f.cap * f.row_bytes;
+    int64_t slices = (unit_bytes + 65535) / 65536;
+    if (slices > 16) slices = 16;
+    while (slices > 1 && units * slices > 4096) slices >>= 1;
+    const dim3 grid((unsigned)slices, gy, gz);
+    hipLaunchKernelGGL(fork_kernel, grid, dim3(kGatherThreads), 0, stream, f);
+    return hipGetLastError();
+}
+
 hipError_t launch_select(const SelectArgs& a, int64_t U, hipStream_t stream) {
     const dim3 grid((unsigned)U);
     if (a.presel) {

@@ -10,7 +10,7 @@ import kf_workloads as kw
 import paper_2403_09054_amd as kf
 from oracle import kf_oracle as ko
 from parity_harness import (LockStep, assert_close_out, assert_close_score, assert_set_equal, assert_state_equal,
-                            compare_kept, dev, error_word, host, upload)
+                            compare_kept, dev, error_word, host, upload, upload_into)
 
 pytestmark = pytest.mark.gpu
 
@@ -1167,6 +1167,82 @@ def test_per_sequence_position_and_temperature(cap, layout):
         assert_close_score(host(gc.score), oc.score, oc.len)
     else:
         assert_set_equal(gc, oc, kv=True, score_exact=False)
+
+
+# ------------------------------------------------------------------ beam search: one cache per beam
+@pytest.mark.parametrize("dtype,d,cap", [(ko.BF16, 128, 700), (ko.BF16, 256, 65), (ko.F32, 64, 130)])
+def test_beam_fork_matches_oracle(dtype, d, cap):
+    rng = np.random.default_rng(8100 + d)
+    L, B, H = 3, 6, 4
+    lens = rng.integers(0, cap + 1, (L, B, H)).astype(np.int32)
+    lens[0, 0, 0] = cap
+    lens[0, 0, 1] = 0
+    oc = random_cache(rng, L, B, H, d, cap, dtype, lens)
+    gc = upload(oc)
+    ws = kf.new_workspace(gc)
+    before = oc.copy()
+    parent = np.array([0, 0, 2, 0, 2, 5], np.int32)          # beams 1, 3 continue beam 0; beam 4 continues beam 2
+    kf.kf_beam_fork(gc, dev(parent), ws)
+    torch.cuda.synchronize()
+    assert error_word(ws) == 0
+    oc.beam_fork(parent)
+    assert_state_equal(gc, oc, kv=True, score_exact=True)
+    # beyond the copied entries a row keeps what it had
+    gK = host(gc.K)
+    for l, b, h in np.ndindex(L, B, H):
+        m = int(oc.len[l, b, h])
+        np.testing.assert_array_equal(gK[l, b, h, m:], before.K[l, b, h, m:])
+    # parents that do not continue themselves, or lie outside the batch: those rows are left alone and counted
+    bad = np.array([1, 0, 2, 7, -1, 5], np.int32)
+    ref = oc.copy()
+    kf.kf_beam_fork(gc, dev(bad), ws)
+    torch.cuda.synchronize()
+    assert error_word(ws) == 4 * L * H
+    assert_state_equal(gc, ref, kv=True, score_exact=True)
+
+
+def test_beam_search_steps_in_lockstep_with_the_oracle():
+    """Four beams of one prompt (Sec. 4): after every step some beams are replaced by continuations of
+    others; forked beams then answer exactly like a cache that had lived that hypothesis from the start."""
+    rng = np.random.default_rng(8200)
+    wl = kw.CONFIGS["tiny"].slice(B=1)
+    L, H, d, n, k, w = wl.L, wl.H, wl.d, wl.n, wl.k, wl.w
+    B = 4
+    dtype = ko.F32 if wl.dtype == "f32" else ko.BF16
+    oc = ko.OracleCache(L, B, H, d, n, dtype)
+    K1 = rnd(rng, (L, 1, H, n, d), dtype)
+    V1 = rnd(rng, (L, 1, H, n, d), dtype)
+    Q1 = rnd(rng, (L, 1, H, n, d), dtype)
+    oc.K[...] = np.repeat(K1, B, axis=1)                     # the beams share the prompt
+    oc.V[...] = np.repeat(V1, B, axis=1)
+    Q = np.repeat(Q1, B, axis=1)
+    seeds = np.full(B, 77, np.uint64)                        # one sequence: one noise stream for all its beams
+    T = 12
+    gc = upload(oc)
+    ws = kf.new_workspace(gc, n)
+    kf.kf_prefill_score(gc, dev(Q), n, kf.kf_tau(0, T), wl.scale, kf.NOISE_GUMBEL, dev(seeds), None, ws)
+    oc.prefill_score(Q, n, ko.tau(0, T), wl.scale, ko.NOISE_GUMBEL, seeds)
+    kf.kf_select_evict(gc, k, w, None, ws)
+    oc.select_evict(k, w)
+    out = torch.zeros((L, B, H, d), dtype=torch.float32, device="cuda")
+    parents = [[0, 0, 2, 3], [0, 1, 1, 1], [0, 1, 2, 3], [3, 3, 3, 3], [0, 0, 2, 2]]
+    for t in range(1, T + 1):
+        q, kn, vn = (rnd(rng, (L, B, H, d), dtype) for _ in range(3))   # every beam appends its own token
+        kf.kf_decode_select_step(gc, dev(q), dev(kn), dev(vn), n + t - 1, k + 1, kf.kf_tau(t, T), wl.scale,
+                                 kf.NOISE_GUMBEL, dev(seeds), None, out, k=k, w=w, layout=kf.LAYOUT_ORDERED, workspace=ws)
+        out_ref = oc.decode_step(q, kn, vn, n + t - 1, ko.tau(t, T), wl.scale, ko.NOISE_GUMBEL, seeds)
+        oc.select_evict(k, w)
+        torch.cuda.synchronize()
+        assert_close_out(host(out), out_ref, "out step %d" % t)
+        np.testing.assert_array_equal(host(gc.pos)[..., :k], oc.pos[..., :k])
+        parent = np.array(parents[t % len(parents)], np.int32)
+        kf.kf_beam_fork(gc, dev(parent), ws)
+        oc.beam_fork(parent)
+        torch.cuda.synchronize()
+        assert error_word(ws) == 0
+        assert_state_equal(gc, oc, kv=True, score_exact=False)
+        upload_into(gc, oc, kv=False)                        # scores: continue from the oracle's bits
+    assert_close_score(host(gc.score), oc.score, oc.len)
 
 
 # ------------------------------------------------------------------ the C ABI without Python

@@ -223,6 +223,12 @@ def test_launches_beyond_the_grid_limit_are_refused():
            (0x100000, 1 << 62), 0)
 
 
+def test_beam_fork_argument_validation():
+    expect(binding.KF_EINVAL, kf.kf_beam_fork, fake_cache(), None, WS)
+    expect(binding.KF_EWORKSPACE, kf.kf_beam_fork, fake_cache(), 0x60000, (0x100000, 4))
+    expect(binding.KF_EINVAL, kf.kf_beam_fork, fake_cache(K=None), 0x60000, WS)
+
+
 def test_bench_refuses_more_than_one_gpu():
     import os
     import subprocess
