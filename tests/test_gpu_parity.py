@@ -1134,6 +1134,60 @@ def test_long_units_one_eight_wave_workgroup_per_unit(d, G, cap):
     assert_close_score(host(gc.score), oc.score, oc.len)
 
 
+def test_decode_step_on_random_shapes_matches_oracle():
+    """Seeded sweep over the decode call's shape space: element types, head sizes, query heads per cached
+    head, few and many units (one workgroup per unit or splits, 4- and 8-wave workgroups), ragged lengths,
+    every logit adjustment, both position modes, with and without a position bias."""
+    rng = np.random.default_rng(20240309)
+    combos = [(ko.BF16, 64), (ko.BF16, 128), (ko.BF16, 256), (ko.F32, 64), (ko.F32, 128)]
+    seen = set()
+    for case in range(36):
+        dtype, d = combos[case % len(combos)]
+        G = int(rng.choice([1, 2, 4, 8]))
+        many = bool(rng.integers(0, 2))
+        if many:                                    # enough units for the one-workgroup-per-unit shapes
+            L, B, H = 2, int(rng.integers(5, 9)), 32
+            cap = int(rng.integers(40, 420)) if case % 3 else int(rng.integers(900, 1300))
+        else:
+            L, B, H = 1, int(rng.integers(1, 4)), int(rng.integers(1, 5))
+            cap = int(rng.integers(2, 3000))
+        lens = rng.integers(0, cap, (L, B, H)).astype(np.int32)
+        lens.flat[0] = cap - 1
+        lens.flat[-1] = 0
+        noise = int(rng.choice([ko.NOISE_GUMBEL, ko.NOISE_GUMBEL, ko.NOISE_NONE, ko.NOISE_GAUSSIAN, ko.NOISE_CONSTANT]))
+        new_pos = bool(rng.integers(0, 2))
+        slopes = (rng.random(H * G) * 0.05).astype(np.float32) if rng.integers(0, 2) else None
+        tau = float(np.float32(rng.uniform(0.7, 2.5)))
+        oc = random_cache(rng, L, B, H, d, cap, dtype, lens)
+        gc = upload(oc, G)
+        seen.add((G, kf.kf_decode_launch_shape(gc, cap)[0] == 1))
+        ws = kf.new_workspace(gc)
+        q = rnd(rng, (L, B, H * G, d), dtype)
+        kn, vn = (rnd(rng, (L, B, H, d), dtype) for _ in range(2))
+        seeds = rng.integers(0, 2 ** 63, B).astype(np.uint64)
+        q_pos = int(oc.pos.max()) + int(rng.integers(1, 5))
+        out = torch.full((L, B, H * G, d), 3.0, dtype=torch.float32, device="cuda")
+        scale = float(1.0 / np.sqrt(np.float32(d)))
+        what = "case %d: dtype=%d d=%d G=%d L,B,H=%d,%d,%d cap=%d noise=%d new_pos=%d slopes=%s" % (
+            case, dtype, d, G, L, B, H, cap, noise, new_pos, slopes is not None)
+        print(what, flush=True)
+        kf.kf_decode_step(gc, dev(q), dev(kn), dev(vn), q_pos, 0, tau, scale, noise, dev(seeds),
+                          None if slopes is None else dev(slopes), out, ws,
+                          pos_mode=kf.POS_NEW if new_pos else kf.POS_ORIGINAL)
+        torch.cuda.synchronize()
+        assert error_word(ws) == 0, what
+        out_ref = oc.decode_step(q, kn, vn, q_pos, tau, scale, noise, seeds, slopes, q_per_kv=G, new_pos=new_pos)
+        assert_close_out(host(out), out_ref, what)
+        np.testing.assert_array_equal(host(gc.len), oc.len)
+        assert_close_score(host(gc.score), oc.score, oc.len, what)
+        gpos = host(gc.pos)
+        for l, b, h in np.ndindex(L, B, H):
+            m = int(oc.len[l, b, h])
+            np.testing.assert_array_equal(gpos[l, b, h, :m], oc.pos[l, b, h, :m])
+        del gc, ws, out
+    assert len(seen) >= 7, seen                     # both launch shapes for (nearly) every group size
+
+
 # ------------------------------------------------------------------ sequences at different steps
 @pytest.mark.parametrize("cap,layout", [(120, kf.LAYOUT_ORDERED), (1500, kf.LAYOUT_ORDERED), (300, kf.LAYOUT_SLOT)])
 def test_per_sequence_position_and_temperature(cap, layout):
