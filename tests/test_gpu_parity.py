@@ -665,6 +665,71 @@ def test_fused_step_equals_the_two_calls(dtype, d, cap, layout):
     assert_close_out(results[0][0], out_ref)
 
 
+def test_fused_step_on_random_shapes_equals_the_two_calls():
+    """Seeded sweep: kf_decode_select_step against kf_decode_step + kf_select_evict, bit for bit, over element
+    types, head sizes, query heads per cached head, few and many units (every fused launch sequence: one
+    launch, split + tail, decode + select, with and without the shared score), both layouts, ragged lengths."""
+    rng = np.random.default_rng(20240310)
+    combos = [(ko.BF16, 64), (ko.BF16, 128), (ko.BF16, 256), (ko.F32, 64), (ko.F32, 128)]
+    for case in range(30):
+        dtype, d = combos[case % len(combos)]
+        G = int(rng.choice([1, 1, 2, 4, 8]))
+        layout = int(rng.integers(0, 2))
+        shared = bool(rng.integers(0, 4) == 0)
+        if rng.integers(0, 2):
+            L, B, H = 2, int(rng.integers(5, 9)), 32
+            k = int(rng.integers(30, 400)) if case % 3 else int(rng.integers(800, 1200))
+        else:
+            L, B, H = int(rng.integers(1, 3)), int(rng.integers(1, 4)), int(rng.integers(1, 5))
+            k = int(rng.integers(8, 5000))
+        cap, w = k + 1, int(rng.integers(0, k // 2 + 1))
+        lens = np.full((L, B, H), k, np.int32)
+        if not shared:                                   # layers of a shared score must agree in length
+            lens[0, 0, 0] = int(rng.integers(0, k))      # under budget after the step: not touched
+        oc = random_cache(rng, L, B, H, d, cap, dtype, lens)
+        oc.pos[...] = np.arange(cap)                     # consecutive positions (the slot layout's window rule)
+        if shared:
+            oc.score[...] = oc.score[0:1]
+        if layout == kf.LAYOUT_SLOT:                     # any slot order
+            for l, b, h in np.ndindex(L, B, H):
+                n_u = int(lens[l, b, h])
+                perm = rng.permutation(n_u)
+                if shared:
+                    perm = np.arange(n_u)
+                for nm in ("K", "V", "score", "pos"):
+                    getattr(oc, nm)[l, b, h, :n_u] = getattr(oc, nm)[l, b, h, :n_u][perm]
+        q = rnd(rng, (L, B, H * G, d), dtype)
+        kn, vn = (rnd(rng, (L, B, H, d), dtype) for _ in range(2))
+        seeds = rng.integers(0, 2 ** 63, B).astype(np.uint64)
+        what = "case %d: dtype=%d d=%d G=%d L,B,H=%d,%d,%d k=%d w=%d layout=%d shared=%d" % (
+            case, dtype, d, G, L, B, H, k, w, layout, shared)
+        print(what, flush=True)
+        mode = kf.SCORE_SHARED if shared else kf.SCORE_PER_LAYER
+        results = []
+        for fused in (False, True):
+            gc = upload(oc, G)
+            ws = kf.new_workspace(gc)
+            out = torch.zeros((L, B, H * G, d), dtype=torch.float32, device="cuda")
+            kept = torch.full((L, B, H, k), -7, dtype=torch.int32, device="cuda")
+            args = (dev(q), dev(kn), dev(vn), cap + 3, 0, 1.3, 0.09, kf.NOISE_GUMBEL, dev(seeds), None, out)
+            if fused:
+                kf.kf_decode_select_step(gc, *args, k=k, w=w, layout=layout, kept_idx=kept, workspace=ws, score_mode=mode)
+            else:
+                kf.kf_decode_step(gc, *args, ws, score_mode=mode)
+                kf.kf_select_evict(gc, k, w, kept, ws, layout=layout)
+            torch.cuda.synchronize()
+            assert error_word(ws) == 0, what
+            lens_now = host(gc.len)
+            live = [host(t).copy() for t in (gc.K, gc.V, gc.score, gc.pos)]
+            for l, b, h in np.ndindex(L, B, H):          # beyond a unit's length nothing is specified
+                for t in live:
+                    t[l, b, h, int(lens_now[l, b, h]):] = 0
+            results.append([host(out).copy(), host(kept).copy(), lens_now.copy()] + live)
+            del gc, ws, out, kept
+        for i, (a_, b_) in enumerate(zip(*results)):
+            np.testing.assert_array_equal(a_, b_, err_msg="%s tensor %d" % (what, i))
+
+
 def test_steps_captured_in_a_hip_graph_replay_exactly():
     """A run of fused steps captured in a HIP graph must reproduce the eager run bit for bit on every
     replay (the library records no memset nodes; eager work and synchronisation sit between replays)."""
