@@ -671,7 +671,7 @@ def test_fused_step_on_random_shapes_equals_the_two_calls():
     launch, split + tail, decode + select, with and without the shared score), both layouts, ragged lengths."""
     rng = np.random.default_rng(20240310)
     combos = [(ko.BF16, 64), (ko.BF16, 128), (ko.BF16, 256), (ko.F32, 64), (ko.F32, 128)]
-    for case in range(30):
+    for case in range(24):
         dtype, d = combos[case % len(combos)]
         G = int(rng.choice([1, 1, 2, 4, 8]))
         layout = int(rng.integers(0, 2))
@@ -1167,7 +1167,7 @@ def test_grouped_query_one_eight_wave_workgroup_per_unit(dtype, d, G, noise, new
     assert_close_score(g_score, oc.score, oc.len)
 
 
-@pytest.mark.parametrize("d,G,cap", [(128, 1, 12001), (128, 2, 6001)])
+@pytest.mark.parametrize("d,G,cap", [(64, 1, 10501), (128, 2, 5401)])
 def test_long_units_one_eight_wave_workgroup_per_unit(d, G, cap):
     """Units whose logits no longer fit a compute unit's LDS twice (about 10 k tokens with one query head) but
     still fit it once stay one workgroup's, of 8 waves: no increments through memory, no merge launch."""
@@ -1202,11 +1202,11 @@ def test_long_units_one_eight_wave_workgroup_per_unit(d, G, cap):
 def test_decode_step_on_random_shapes_matches_oracle():
     """Seeded sweep over the decode call's shape space: element types, head sizes, query heads per cached
     head, few and many units (one workgroup per unit or splits, 4- and 8-wave workgroups), ragged lengths,
-    every logit adjustment, both position modes, with and without a position bias."""
+    every logit adjustment, both position modes, with and without a position bias (30 shapes)."""
     rng = np.random.default_rng(20240309)
     combos = [(ko.BF16, 64), (ko.BF16, 128), (ko.BF16, 256), (ko.F32, 64), (ko.F32, 128)]
     seen = set()
-    for case in range(36):
+    for case in range(30):
         dtype, d = combos[case % len(combos)]
         G = int(rng.choice([1, 2, 4, 8]))
         many = bool(rng.integers(0, 2))
@@ -1383,7 +1383,7 @@ def test_standalone_cpp_user_of_the_c_abi():
 @pytest.mark.parametrize("dtype,d,G,w,k", [
     (ko.BF16, 64, 1, 26, 129), (ko.BF16, 128, 1, 0, 129), (ko.F32, 64, 1, 26, 129), (ko.BF16, 128, 2, 26, 129),
     (ko.BF16, 64, 4, 129, 129), (ko.BF16, 128, 8, 26, 129), (ko.BF16, 64, 8, 0, 129), (ko.BF16, 256, 8, 50, 129),
-    (ko.BF16, 128, 1, 2000, 10500),      # a unit too long for two workgroups per CU: one 8-wave workgroup
+    (ko.BF16, 64, 1, 2000, 10500),       # a unit too long for two workgroups per CU: one 8-wave workgroup
     (ko.BF16, 128, 4, 300, 1500)])       # 4 query heads in the 8-wave workgroup
 def test_single_launch_slot_step_equals_the_two_calls(dtype, d, G, w, k):
     """With at least 320 units of a length that fits LDS, kf_decode_select_step in the slot layout is ONE
@@ -1413,7 +1413,7 @@ def test_single_launch_slot_step_equals_the_two_calls(dtype, d, G, w, k):
     kept_a = torch.zeros((L, B, H, k), dtype=torch.int32, device="cuda")
     kept_b = torch.zeros_like(kept_a)
     seq_pos = torch.from_numpy(np.full(B, k, np.int32)).cuda()
-    for t in range(1, 4 if k < 1000 else 3):
+    for t in range(1, 4 if k < 1000 else 2):
         q = dev(rnd(rng, (L, B, H * G, d), dtype))
         kn, vn = (dev(rnd(rng, (L, B, H, d), dtype)) for _ in range(2))
         q_pos = k + t - 1
