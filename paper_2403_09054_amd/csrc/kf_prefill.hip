@@ -306,16 +306,20 @@ __global__ void __launch_bounds__(kPrefillThreads) prefill_colsum_kernel(const P
             rbuf[buf][threadIdx.x] = r_st;
         }
     };
-    Stage::fetch(Qu, it_first * kTile, n, stage);
-    fetch_stats(it_first);
+    // The query tiles are walked from the LAST one down: every column block of a unit then starts at the same
+    // tile and the blocks, which run at the same time on one XCD, ask its L2 for the same rows at about the
+    // same time (walking up, each block starts at its own diagonal and the L2 sees 16 unrelated streams:
+    // 2.7 GB instead of 1.0 GB fetched on the GPT-J-shaped workload).
+    Stage::fetch(Qu, it_end * kTile, n, stage);
+    fetch_stats(it_end);
     Stage::park(qbuf[0], stage);
     park_stats(0);
     __syncthreads();
-    for (int it = it_first; it <= it_end; ++it) {
-        const int cur = (it - it_first) & 1;
-        // the next tile (the last one again at the end: rows stay in range), in flight during this tile's work
-        Stage::fetch(Qu, min(it + 1, it_end) * kTile, n, stage);
-        fetch_stats(min(it + 1, it_end));
+    for (int it = it_end; it >= it_first; --it) {
+        const int cur = (it_end - it) & 1;
+        // the next tile (the first one again at the end: rows stay in range), in flight during this tile's work
+        Stage::fetch(Qu, max(it - 1, it_first) * kTile, n, stage);
+        fetch_stats(max(it - 1, it_first));
         if (active && it >= it_begin) {
             const char* qb = qbuf[cur];
             f32x16 acc;
@@ -352,7 +356,7 @@ __global__ void __launch_bounds__(kPrefillThreads) prefill_colsum_kernel(const P
 #pragma unroll
             for (int r = 0; r < 16; ++r) colsum += z[r];
         }
-        if (it < it_end) {
+        if (it > it_first) {
             Stage::park(qbuf[cur ^ 1], stage);
             park_stats(cur ^ 1);
         }
