@@ -40,6 +40,8 @@ constexpr int kDecodeSingleMinUnits = 320;              // units from which one 
 constexpr size_t kDecodeLdsWhole = 163840 - 2048;       // ... of a workgroup that has a CU to itself
 constexpr size_t kDecodeBigMinLogits8 = 36 * 1024;      // logit bytes from which 8 query heads take the 8-wave workgroup
 constexpr size_t kDecodeBigMinLogits4 = 24 * 1024;      // ... 4 query heads
+constexpr size_t kDecodeBigMinLogitsSplit = 16 * 1024;  // ... a split of either (few units: few, large workgroups)
+constexpr int kDecodeMinBlocksGrouped = 256;            // workgroups wanted on the chip with 4 or 8 query heads
 constexpr int kDecodeBigMinUnits = 256;                 // units from which one such workgroup per unit fills the chip
 
 constexpr int kDecodeUnroll = 4;  // 16-byte loads a lane keeps in flight per tile (2 and 8 measured within 2 %)
@@ -913,7 +915,6 @@ __device__ __forceinline__ void decode_block(const DecodeArgs& a) {
         return;
     }
     // ---- S > 1: leave the un-normalised increments and a partial record per query head for the merge
-    if constexpr (BIG) return;  // never launched that way: the 8-wave workgroup takes a whole unit
     {
         float* we = a.ws_e + (size_t)u * G * a.cap;
         for (int t = tid; t < cnt; t += NT) {
@@ -923,11 +924,18 @@ __device__ __forceinline__ void decode_block(const DecodeArgs& a) {
         }
     }
     if (owner && tid == 0) a.ws_m[u] = m;  // tokens scored in this unit: the merge reads the length from here
+    const float* orows = red_o;
+    if constexpr (BIG) {  // as above: the waves' partial outputs take the place of the logits
+        __syncthreads();
+        store_fin(smem + (size_t)wv * G * D);
+        __syncthreads();
+        orows = smem;
+    }
     float* part = a.ws_part + ((size_t)u * S + s) * G * PW;
     for (int c = tid; c < G * D; c += NT) {
         float o_c = 0.0f;
 #pragma unroll
-        for (int w2 = 0; w2 < NW; ++w2) o_c += red_o[w2 * G * D + c];
+        for (int w2 = 0; w2 < NW; ++w2) o_c += orows[w2 * G * D + c];
         part[(c / D) * PW + (c % D)] = o_c;
     }
     if (tid < 4 * G) part[(tid >> 2) * PW + D + (tid & 3)] = stat[tid];
@@ -1081,10 +1089,14 @@ DecodePlan plan_decode(int64_t U, int32_t m, int32_t d, int32_t dtype, int32_t G
     if (lds_rows < max_chunk) max_chunk = lds_rows / rpb * rpb;
     const int min_chunk = kDecodeMinChunk < max_chunk ? kDecodeMinChunk : max_chunk;
     int64_t s_hi = (m + min_chunk - 1) / min_chunk;
-    int64_t s_lo = (m + max_chunk - 1) / max_chunk;
+    int64_t s_lo = (rows + max_chunk - 1) / max_chunk;  // the new token takes no cache row
     if (s_hi > kDecodeMaxSplits) s_hi = kDecodeMaxSplits;
     if (s_lo < 1) s_lo = 1;
     if (s_hi < s_lo) s_hi = s_lo;
+    // 4 and 8 query heads: a workgroup's fixed work (statistics and folds of G heads, G partial records) is
+    // large, so few units are cut into few, long splits for 8-wave workgroups, one per CU (8 cached heads x
+    // 8 sequences x 2048 tokens, 8 query heads each: 16 splits of 128 rows 73 us, 4 of 512 rows 52 us)
+    const int64_t min_blocks = (G >= 4) ? kDecodeMinBlocksGrouped : kDecodeMinBlocks;
     int64_t best_S = s_lo;
     double best_cost = 0.0;
     bool best_filled = false;
@@ -1095,7 +1107,7 @@ DecodePlan plan_decode(int64_t U, int32_t m, int32_t d, int32_t dtype, int32_t G
         const int64_t blocks = U * S;
         const int64_t per_cu = (blocks + kComputeUnits - 1) / kComputeUnits;
         const double cost = (double)per_cu * (double)(chunk + kDecodeBlockOverheadTokens);
-        const bool filled = blocks >= kDecodeMinBlocks;
+        const bool filled = blocks >= min_blocks;
         if (best_cost == 0.0 || (filled && !best_filled) || (filled == best_filled && cost < best_cost)) {
             best_S = S;
             best_cost = cost;
@@ -1118,13 +1130,24 @@ static hipError_t launch_decode_g(const DecodeArgs& a, int64_t U, size_t lds, hi
         // longer ones take 8 waves (two per CU while the logits stay under ~75 KB, then one with most of the CU's
         // LDS).  Measured at 2048 units, d = 128, 8 heads: 512 tokens 51 % (4 waves) vs 49 % (8) vs 36 % (16 waves);
         // 1024 tokens 49 / 62 / 49 %; 2048 tokens - / 62 / 58 %.  4 heads: 512 tokens 67 % (4 waves) vs 63 % (8);
-        // 1024 tokens 71 / 74.5 %; 2048 tokens 73-78 / 80 %.
+        // 1024 tokens 71 / 74.5 %; 2048 tokens 73-78 / 80 %.  Splits (few units) take the 8 waves from 16 KB
+        // of logits on: 64 units x 4 splits of 512 rows, 8 heads 61 -> 52 us, 4 heads 43 -> 39 us.
         const size_t logits = (size_t)2 * G * (a.chunk + 1) * sizeof(float);
-        if (a.S == 1 && logits > (G == 8 ? kDecodeBigMinLogits8 : kDecodeBigMinLogits4)) {
+        const size_t big_from = a.S > 1 ? kDecodeBigMinLogitsSplit : (G == 8 ? kDecodeBigMinLogits8 : kDecodeBigMinLogits4);
+        if (logits > big_from) {
             const size_t lds_big = decode_lds_bytes_big(G, a.chunk, D);
             if (lds_big > kDecodeLdsWhole) return hipErrorInvalidValue;
             hipLaunchKernelGGL((decode_kernel<T, D, kDecodeThreadsBig, G>), grid, dim3(kDecodeThreadsBig), lds_big, st, a);
-            return hipGetLastError();
+            hipError_t e2 = hipGetLastError();
+            if (e2 == hipSuccess && a.S > 1 && merge) {
+                const int64_t tokens = (int64_t)a.S * a.chunk;
+                int64_t slices = (tokens + 8 * kDecodeThreads - 1) / (8 * kDecodeThreads);
+                if (slices > 16) slices = 16;
+                if (slices < 1) slices = 1;
+                hipLaunchKernelGGL((decode_merge_kernel<D, kDecodeThreads, G>), dim3((unsigned)U, (unsigned)slices), block, 0, st, a);
+                e2 = hipGetLastError();
+            }
+            return e2;
         }
     }
     lds = decode_lds_bytes(G, a.chunk, D);  // what this workgroup shape needs for the plan's chunk
