@@ -132,16 +132,15 @@ __device__ __forceinline__ float wave_sum_fast(float v) {
     return v + __shfl_xor(v, 32, kWave);
 }
 
-// Block-wide max / sum of N values at once.  `red` holds N*NT/64 + N floats.  With few values and waves
-// every thread folds the waves' results itself (one pair of barriers); with many (8 query heads, 8 waves:
-// 128 LDS reads per thread that way) N threads fold them once and publish the N results.
-template <int NT, int N, bool IS_MAX>
-__device__ __forceinline__ void block_reduce_n(float (&v)[N], float* red) {
+// Block-wide sums of N values at once.  `red` holds N*NT/64 + N floats.  With few values and waves every
+// thread folds the waves' results itself (one pair of barriers); with many (8 query heads, 8 waves: 128 LDS
+// reads per thread that way) N threads fold them once and publish the N results.
+template <int NT, int N>
+__device__ __forceinline__ void block_sum_n(float (&v)[N], float* red) {
     constexpr int NW = NT / 64;
     constexpr bool kTwoLevel = N * NW > 32;
 #pragma unroll
-    for (int i = 0; i < N; ++i) v[i] = kTwoLevel ? (IS_MAX ? wave_max_fast(v[i]) : wave_sum_fast(v[i]))
-                                                 : (IS_MAX ? wave_max(v[i]) : wave_sum(v[i]));
+    for (int i = 0; i < N; ++i) v[i] = kTwoLevel ? wave_sum_fast(v[i]) : wave_sum(v[i]);
     __syncthreads();
     if ((threadIdx.x & 63) == 0) {
 #pragma unroll
@@ -153,7 +152,7 @@ __device__ __forceinline__ void block_reduce_n(float (&v)[N], float* red) {
         if (threadIdx.x < N) {
             float r = red[threadIdx.x];
 #pragma unroll
-            for (int w = 1; w < NW; ++w) r = IS_MAX ? fmaxf(r, red[N * w + threadIdx.x]) : r + red[N * w + threadIdx.x];
+            for (int w = 1; w < NW; ++w) r += red[N * w + threadIdx.x];
             res[threadIdx.x] = r;
         }
         __syncthreads();
@@ -164,18 +163,10 @@ __device__ __forceinline__ void block_reduce_n(float (&v)[N], float* red) {
         for (int i = 0; i < N; ++i) {
             float r = red[i];
 #pragma unroll
-            for (int w = 1; w < NW; ++w) r = IS_MAX ? fmaxf(r, red[N * w + i]) : r + red[N * w + i];
+            for (int w = 1; w < NW; ++w) r += red[N * w + i];
             v[i] = r;
         }
     }
-}
-template <int NT, int N>
-__device__ __forceinline__ void block_max_n(float (&v)[N], float* red) {
-    block_reduce_n<NT, N, true>(v, red);
-}
-template <int NT, int N>
-__device__ __forceinline__ void block_sum_n(float (&v)[N], float* red) {
-    block_reduce_n<NT, N, false>(v, red);
 }
 
 // Logits of a query group on the matrix cores.  With 8 bf16 query heads per
