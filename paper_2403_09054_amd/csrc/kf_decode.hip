@@ -932,8 +932,10 @@ __device__ __forceinline__ void decode_block(const DecodeArgs& a) {
     if (tid < 4 * G) part[(tid >> 2) * PW + D + (tid & 3)] = stat[tid];
 }
 
+// (The 8-wave workgroup is compiled for four waves per SIMD, i.e. two per CU -- at most 128 registers per lane: with a few more its
+// medium-length units lose the second workgroup that overlaps their statistics and folds, 67 -> 48 % of peak.)
 template <typename T, int D, int NT, int G>
-__global__ void __launch_bounds__(NT) decode_kernel(const DecodeArgs a) {
+__global__ void __launch_bounds__(NT, NT >= 512 ? 4 : 1) decode_kernel(const DecodeArgs a) {
     decode_block<T, D, NT, G>(a);
     // Whole-step launch with the step number in device memory: every workgroup read the number when it
     // started, so the one that finishes last may move it on (and clears the ticket counter for the next launch).
