@@ -26,9 +26,10 @@
  *    the paper says the method applies to unchanged -- G query heads read one
  *    cached head and its f takes the sum of their increments)               [Sec. 6]
  *
- * All arithmetic is done in double on the exact input bits (fp32, or bf16
- * given as uint16).  State that persists between steps (the accumulated score
- * f) is stored as fp32, the new value being (float)((double)f + delta).
+ * All arithmetic is done in double on the exact input bits (fp32, or bf16 /
+ * IEEE half given as 16-bit words).  State that persists between steps (the
+ * accumulated score f) is stored as fp32, the new value being
+ * (float)((double)f + delta).
  *
  * Pins: every function here is pinned by tests/test_oracle_*.py against
  * closed forms, limits, invariants and brute force.  The specific noise VALUES
@@ -52,6 +53,7 @@
 
 #define KFO_F32 0
 #define KFO_BF16 1
+#define KFO_F16 2
 
 #define KFO_NOISE_NONE 0
 #define KFO_NOISE_GUMBEL 1
@@ -70,6 +72,16 @@ static double load_elem(const void *base, int dtype, size_t idx)
 {
     if (dtype == KFO_F32)
         return (double)((const float *)base)[idx];
+    if (dtype == KFO_F16) {
+        /* IEEE binary16: 1 sign, 5 exponent (bias 15), 10 fraction bits */
+        uint16_t hbits = ((const uint16_t *)base)[idx];
+        int sign = hbits >> 15, e = (hbits >> 10) & 31, frac = hbits & 1023;
+        double v;
+        if (e == 0) v = ldexp((double)frac, -24);                   /* zero and subnormals */
+        else if (e == 31) v = frac ? NAN : INFINITY;
+        else v = ldexp(1.0 + (double)frac / 1024.0, e - 15);
+        return sign ? -v : v;
+    }
     /* bf16: the upper 16 bits of an fp32 */
     uint32_t w = (uint32_t)((const uint16_t *)base)[idx] << 16;
     float f;

@@ -6,7 +6,7 @@ library and never calls it.
 
 All state lives in numpy arrays laid out as the paper's per-layer, per-head
 caches (Fig. 5 caption: the score accumulates "for each layer and head"):
-K, V [L,B,H,cap,d] (float32, or uint16 holding bf16 bits), score [L,B,H,cap]
+K, V [L,B,H,cap,d] (float32, float16, or uint16 holding bf16 bits), score [L,B,H,cap]
 float32, pos [L,B,H,cap] int32, len [L,B,H] int32.
 """
 from __future__ import annotations
@@ -21,7 +21,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "kf_oracle.c")
 _LIB = os.path.join(_HERE, "libkf_oracle.so")
 
-F32, BF16 = 0, 1
+F32, BF16, F16 = 0, 1, 2
 NOISE_NONE, NOISE_GUMBEL, NOISE_GAUSSIAN, NOISE_CONSTANT = 0, 1, 2, 3
 
 
@@ -88,7 +88,9 @@ def _dtype_code(a: np.ndarray) -> int:
         return F32
     if a.dtype == np.uint16:
         return BF16
-    raise TypeError("K/V must be float32 or uint16 (bf16 bits), got %s" % a.dtype)
+    if a.dtype == np.float16:
+        return F16
+    raise TypeError("K/V must be float32, float16 or uint16 (bf16 bits), got %s" % a.dtype)
 
 
 class OracleCache:
@@ -97,7 +99,7 @@ class OracleCache:
     def __init__(self, L, B, H, d, cap, dtype=F32, layer0=0):
         self.L, self.B, self.H, self.d, self.cap, self.dtype = L, B, H, d, cap, dtype
         self.layer0 = layer0
-        et = np.float32 if dtype == F32 else np.uint16
+        et = {F32: np.float32, BF16: np.uint16, F16: np.float16}[dtype]
         self.K = np.zeros((L, B, H, cap, d), et)
         self.V = np.zeros((L, B, H, cap, d), et)
         self.score = np.zeros((L, B, H, cap), np.float32)

@@ -821,3 +821,45 @@ def test_beam_fork_copies_the_parent_state():
     with pytest.raises(ValueError):
         c.beam_fork([0, 4, 2, 3])
 
+
+# ----------------------------------------------------------------------------
+# Element types: the oracle reads fp32, bf16 and IEEE half; all arithmetic is in double
+# ----------------------------------------------------------------------------
+def test_sixteen_bit_inputs_are_read_exactly():
+    # every bf16 / half value is an fp32 value: a cache holding the same numbers as fp32 must give the
+    # same bits at every output (prompt scores, attention output, score increments, survivors)
+    rng = np.random.default_rng(41)
+    L, B, H, d, n, cap = 1, 2, 2, 16, 19, 24
+    for dt in (ko.BF16, ko.F16):
+        vals = rng.standard_normal((L, B, H, cap, d)).astype(np.float32)
+        vals[0, 0, 0, 0, :4] = [0.0, -0.0, 6.1e-5, 65504.0 if dt == ko.F16 else 3.0e38]   # zero, smallest normal half, largest
+        vals[0, 0, 0, 1, :2] = [5.96e-8, -3.0e-6]                                         # half subnormals
+        if dt == ko.F16:
+            k16 = vals.astype(np.float16)
+            back = k16.astype(np.float32)
+        else:
+            k16 = bf16_round(vals)
+            back = (k16.astype(np.uint32) << 16).view(np.float32)
+        lo, hi = ko.OracleCache(L, B, H, d, cap, dt), ko.OracleCache(L, B, H, d, cap, ko.F32)
+        lo.K[...], hi.K[...] = k16, back
+        v = rng.standard_normal((L, B, H, cap, d)).astype(np.float32)
+        if dt == ko.F16:
+            lo.V[...], hi.V[...] = v.astype(np.float16), v.astype(np.float16).astype(np.float32)
+        else:
+            lo.V[...], hi.V[...] = bf16_round(v), (bf16_round(v).astype(np.uint32) << 16).view(np.float32)
+        q = rng.standard_normal((L, B, H, n, d)).astype(np.float32) * 0.25
+        q16 = q.astype(np.float16) if dt == ko.F16 else bf16_round(q)
+        q32 = q16.astype(np.float32) if dt == ko.F16 else (q16.astype(np.uint32) << 16).view(np.float32)
+        seeds = np.array([3, 4], np.uint64)
+        lo.prefill_score(q16, n, 1.0, 0.01, ko.NOISE_GUMBEL, seeds)
+        hi.prefill_score(q32, n, 1.0, 0.01, ko.NOISE_GUMBEL, seeds)
+        np.testing.assert_array_equal(lo.score, hi.score)
+        o16 = lo.decode_step(q16[:, :, :, 0], k16[:, :, :, cap - 1], lo.V[:, :, :, cap - 1].copy(), n, 1.5, 0.01, ko.NOISE_GUMBEL, seeds)
+        o32 = hi.decode_step(q32[:, :, :, 0], back[:, :, :, cap - 1], hi.V[:, :, :, cap - 1].copy(), n, 1.5, 0.01, ko.NOISE_GUMBEL, seeds)
+        np.testing.assert_array_equal(o16, o32)
+        np.testing.assert_array_equal(lo.score, hi.score)
+        np.testing.assert_array_equal(lo.select_evict(10, 3), hi.select_evict(10, 3))
+        np.testing.assert_array_equal(lo.pos, hi.pos)
+        got = lo.K.astype(np.float32) if dt == ko.F16 else (lo.K.astype(np.uint32) << 16).view(np.float32)
+        np.testing.assert_array_equal(got[..., :10, :], hi.K[..., :10, :])                # rows moved as 16-bit words
+
