@@ -22,8 +22,9 @@
  *    16-byte aligned, zero-filled once by the caller before its first use; the
  *    library leaves it reusable after every call.  Calls that share a workspace
  *    must be ordered on one stream.
- *  - Supported element type / head dimension pairs: bf16 with d in {64,128,256},
- *    fp32 with d in {64,128}; query heads per cached head: 1, 2, 4 or 8.
+ *  - Supported element type / head dimension pairs: bf16 and IEEE half with d in
+ *    {64,128,256}, fp32 with d in {64,128}; query heads per cached head: 1, 2, 4
+ *    or 8.  Q, K, V, k_new and v_new share the cache's element type.
  */
 #ifndef KEYFORMER_H
 #define KEYFORMER_H
@@ -43,7 +44,7 @@ typedef enum {
     KF_EDEVICE = -4       /* the HIP runtime refused a launch */
 } kf_status;
 
-typedef enum { KF_F32 = 0, KF_BF16 = 1 } kf_dtype;
+typedef enum { KF_F32 = 0, KF_BF16 = 1, KF_F16 = 2 /* IEEE half */ } kf_dtype;
 
 /* Logit adjustment zeta of Eq. 4.  GUMBEL is the method (Eq. 7); NONE is the
  * accumulated-attention score of prior work; GAUSSIAN (Eq. 5, mean 0.5772,

@@ -33,7 +33,7 @@ class Workload:
     B: int
     H: int
     d: int
-    dtype: str  # "f32" | "bf16"
+    dtype: str  # "f32" | "bf16" | "f16"
     n: int      # prompt length
     k: int      # KV budget
     w: int      # recent window
@@ -52,7 +52,7 @@ class Workload:
 
     @property
     def torch_dtype(self):
-        return torch.float32 if self.dtype == "f32" else torch.bfloat16
+        return {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[self.dtype]
 
     @property
     def elem_bytes(self) -> int:

@@ -13,7 +13,7 @@ from dataclasses import dataclass
 HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(HERE, "libkeyformer.so")
 
-F32, BF16 = 0, 1
+F32, BF16, F16 = 0, 1, 2
 NOISE_NONE, NOISE_GUMBEL, NOISE_GAUSSIAN, NOISE_CONSTANT = 0, 1, 2, 3
 LAYOUT_ORDERED, LAYOUT_SLOT = 0, 1
 POS_ORIGINAL, POS_NEW = 0, 1
@@ -133,8 +133,8 @@ def _ptr(t):
 
 @dataclass
 class Cache:
-    """Torch tensors that back a kf_cache.  K, V: [L,B,H,cap,d] (float32 or
-    bfloat16); score [L,B,H,cap] float32; pos [L,B,H,cap] int32; len [L,B,H] int32."""
+    """Torch tensors that back a kf_cache.  K, V: [L,B,H,cap,d] (float32, bfloat16 or
+    float16); score [L,B,H,cap] float32; pos [L,B,H,cap] int32; len [L,B,H] int32."""
     K: object
     V: object
     score: object
@@ -152,7 +152,7 @@ class Cache:
     @staticmethod
     def allocate(L, B, H, d, cap, dtype=BF16, device="cuda", layer0=0, q_per_kv=1):
         import torch
-        et = torch.float32 if dtype == F32 else torch.bfloat16
+        et = {F32: torch.float32, BF16: torch.bfloat16, F16: torch.float16}[dtype]
         return Cache(K=torch.zeros((L, B, H, cap, d), dtype=et, device=device),
                      V=torch.zeros((L, B, H, cap, d), dtype=et, device=device),
                      score=torch.zeros((L, B, H, cap), dtype=torch.float32, device=device),

@@ -31,7 +31,7 @@ constexpr int64_t kWideMaxUnits = 256;
 constexpr int32_t kPreselMinTokens = 4096;
 
 bool supported(int32_t dtype, int32_t d) {
-    if (dtype == KF_BF16) return d == 64 || d == 128 || d == 256;
+    if (dtype == KF_BF16 || dtype == KF_F16) return d == 64 || d == 128 || d == 256;
     if (dtype == KF_F32) return d == 64 || d == 128;
     return false;
 }
@@ -47,7 +47,7 @@ kf_status check_cache(const kf_cache* c) {
                     c->d, c->cap);
     if ((int64_t)c->L * c->B * c->H > (int64_t)1 << 24) return fail(KF_EINVAL, "too many units");
     if (c->layer0 < 0) return fail(KF_EINVAL, "layer0 must be non-negative");
-    if (c->dtype != KF_F32 && c->dtype != KF_BF16) return fail(KF_EINVAL, "unknown dtype %d", c->dtype);
+    if (c->dtype != KF_F32 && c->dtype != KF_BF16 && c->dtype != KF_F16) return fail(KF_EINVAL, "unknown dtype %d", c->dtype);
     if (!supported(c->dtype, c->d))
         return fail(KF_EUNSUPPORTED, "dtype %d with head dimension %d is not built", c->dtype, c->d);
     if (((uintptr_t)c->K | (uintptr_t)c->V) & 15) return fail(KF_EINVAL, "K and V must be 16-byte aligned");

@@ -132,6 +132,21 @@ __device__ __forceinline__ float wave_sum_fast(float v) {
     return v + __shfl_xor(v, 32, kWave);
 }
 
+typedef _Float16 f16x2_t __attribute__((ext_vector_type(2)));
+template <>
+struct QueryPiece<f16_t> {
+    uint4 q;  // eight halves, kept packed: products of half pairs are accumulated in fp32
+    __device__ __forceinline__ void load(const uint4& r) { q = r; }
+    __device__ __forceinline__ float dot(const uint4& k) const {
+        float p = 0.0f;
+        p = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2_t, k.x), __builtin_bit_cast(f16x2_t, q.x), p, false);
+        p = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2_t, k.y), __builtin_bit_cast(f16x2_t, q.y), p, false);
+        p = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2_t, k.z), __builtin_bit_cast(f16x2_t, q.z), p, false);
+        p = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2_t, k.w), __builtin_bit_cast(f16x2_t, q.w), p, false);
+        return p;
+    }
+};
+
 // Block-wide sums of N values at once.  `red` holds N*NT/64 + N floats.  With few values and waves every
 // thread folds the waves' results itself (one pair of barriers); with many (8 query heads, 8 waves: 128 LDS
 // reads per thread that way) N threads fold them once and publish the N results.
@@ -188,6 +203,22 @@ template <int G>
 struct MfmaLogits<bf16_t, G> {
     static constexpr bool value = (G >= 8);
 };
+template <int G>
+struct MfmaLogits<f16_t, G> {
+    static constexpr bool value = (G >= 8);
+};
+// acc += A (16 rows x 32) * B (32 x 16 columns), eight 16-bit elements of each per lane
+typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
+template <typename T>
+__device__ __forceinline__ f32x4_t mfma_16x16x32(const uint4& a, const uint4& b, f32x4_t acc);
+template <>
+__device__ __forceinline__ f32x4_t mfma_16x16x32<bf16_t>(const uint4& a, const uint4& b, f32x4_t acc) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), acc, 0, 0, 0);
+}
+template <>
+__device__ __forceinline__ f32x4_t mfma_16x16x32<f16_t>(const uint4& a, const uint4& b, f32x4_t acc) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), acc, 0, 0, 0);
+}
 
 // One workgroup streams the cache rows [j0, j1) of one cached head ("unit") once
 // and serves the G query heads that read it (G = 1: ordinary multi-head
@@ -366,8 +397,7 @@ __device__ __forceinline__ void decode_block(const DecodeArgs& a) {
                         f32x4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
                         for (int ks = 0; ks < KS; ++ks)
-                            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, raw[rg][ks]),
-                                                                          __builtin_bit_cast(bf16x8_t, bq[hh][ks]), acc, 0, 0, 0);
+                            acc = mfma_16x16x32<T>(raw[rg][ks], bq[hh][ks], acc);
                         float t = s4 == 0 ? acc[0] : s4 == 1 ? acc[1] : s4 == 2 ? acc[2] : acc[3];
                         t += dpp_move<0xB1>(t);  // the quad's four classes
                         t += dpp_move<0x4E>(t);
@@ -459,8 +489,7 @@ __device__ __forceinline__ void decode_block(const DecodeArgs& a) {
                 f32x4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
                 for (int kk = 0; kk < KK; ++kk)
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, raw[kk]),
-                                                                  __builtin_bit_cast(bf16x8_t, bq[kk]), acc, 0, 0, 0);
+                    acc = mfma_16x16x32<T>(raw[kk], bq[kk], acc);
                 const float from2 = dpp_move<0x118>(acc[2]), from3 = dpp_move<0x118>(acc[3]);  // row_shr:8
                 const float v[2] = {mrow >= G ? from2 : acc[0], mrow >= G ? from3 : acc[1]};
 #pragma unroll
@@ -1050,7 +1079,7 @@ DecodePlan plan_decode(int64_t U, int32_t m, int32_t d, int32_t dtype, int32_t G
     DecodePlan p;
     const int rpb = rows_per_block(d, dtype);
     const int64_t rows = m > 1 ? m - 1 : 1;  // cache rows; the new token rides with the last split
-    if ((G == 4 || (G == 8 && dtype == KF_BF16)) && U >= kDecodeBigMinUnits) {
+    if ((G == 4 || (G == 8 && dtype != KF_F32)) && U >= kDecodeBigMinUnits) {
         // one workgroup per unit, up to one per CU with the unit's 2 x G logit rows in most of the CU's LDS
         const int64_t chunk = (rows + rpb - 1) / rpb * rpb;
         if (decode_lds_bytes_big(G, chunk, d) <= kDecodeLdsWhole) {
@@ -1185,6 +1214,10 @@ static hipError_t launch_decode_any(const DecodeArgs& a, int64_t U, int32_t d, i
         if (d == 64) return launch_decode_t<bf16_t, 64>(a, U, lds_bytes, stream, merge);
         if (d == 128) return launch_decode_t<bf16_t, 128>(a, U, lds_bytes, stream, merge);
         if (d == 256) return launch_decode_t<bf16_t, 256>(a, U, lds_bytes, stream, merge);
+    } else if (dtype == KF_F16) {
+        if (d == 64) return launch_decode_t<f16_t, 64>(a, U, lds_bytes, stream, merge);
+        if (d == 128) return launch_decode_t<f16_t, 128>(a, U, lds_bytes, stream, merge);
+        if (d == 256) return launch_decode_t<f16_t, 256>(a, U, lds_bytes, stream, merge);
     } else {
         if (d == 64) return launch_decode_t<float, 64>(a, U, lds_bytes, stream, merge);
         if (d == 128) return launch_decode_t<float, 128>(a, U, lds_bytes, stream, merge);

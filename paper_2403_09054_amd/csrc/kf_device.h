@@ -10,6 +10,11 @@ struct bf16_t {
     uint16_t bits;
 };
 
+// IEEE half storage type.
+struct f16_t {
+    uint16_t bits;
+};
+
 constexpr int kWave = 64;
 
 // Mean and standard deviation of the standard Gumbel pdf as the paper prints
@@ -28,6 +33,10 @@ struct ElemTraits<float> {
 };
 template <>
 struct ElemTraits<bf16_t> {
+    static constexpr int kPerVec = 8;
+};
+template <>
+struct ElemTraits<f16_t> {
     static constexpr int kPerVec = 8;
 };
 
@@ -54,6 +63,20 @@ __device__ __forceinline__ void unpack16<bf16_t>(const uint4& r, float* f) {
     f[5] = bf16_hi(r.z);
     f[6] = bf16_lo(r.w);
     f[7] = bf16_hi(r.w);
+}
+
+__device__ __forceinline__ float f16_lo(uint32_t w) { return (float)__builtin_bit_cast(_Float16, (uint16_t)(w & 0xFFFFu)); }
+__device__ __forceinline__ float f16_hi(uint32_t w) { return (float)__builtin_bit_cast(_Float16, (uint16_t)(w >> 16)); }
+template <>
+__device__ __forceinline__ void unpack16<f16_t>(const uint4& r, float* f) {
+    f[0] = f16_lo(r.x);
+    f[1] = f16_hi(r.x);
+    f[2] = f16_lo(r.y);
+    f[3] = f16_hi(r.y);
+    f[4] = f16_lo(r.z);
+    f[5] = f16_hi(r.z);
+    f[6] = f16_lo(r.w);
+    f[7] = f16_hi(r.w);
 }
 
 // ---------------------------------------------------------------- streaming access

@@ -41,6 +41,13 @@ struct Mma<bf16_t> {
                                                        __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
     }
 };
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+template <>
+struct Mma<f16_t> {
+    static __device__ __forceinline__ f32x16 group(const uint4& a, const uint4& b, f32x16 c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+    }
+};
 template <>
 struct Mma<float> {
     static __device__ __forceinline__ f32x16 group(const uint4& a, const uint4& b, f32x16 c) {
@@ -408,6 +415,10 @@ hipError_t launch_prefill(const PrefillArgs& a, int64_t U, int32_t d, int32_t dt
         if (d == 64) return launch_prefill_t<bf16_t, 64>(a, U, stream);
         if (d == 128) return launch_prefill_t<bf16_t, 128>(a, U, stream);
         if (d == 256) return launch_prefill_t<bf16_t, 256>(a, U, stream);
+    } else if (dtype == KF_F16) {
+        if (d == 64) return launch_prefill_t<f16_t, 64>(a, U, stream);
+        if (d == 128) return launch_prefill_t<f16_t, 128>(a, U, stream);
+        if (d == 256) return launch_prefill_t<f16_t, 256>(a, U, stream);
     } else {
         if (d == 64) return launch_prefill_t<float, 64>(a, U, stream);
         if (d == 128) return launch_prefill_t<float, 128>(a, U, stream);

@@ -175,7 +175,7 @@ class LockStep:
         self.shared = shared            # one score function for all layers (the paper's "Shared" ablation)
         self.score_mode = kf.SCORE_SHARED if shared else kf.SCORE_PER_LAYER
         self.cap = cap or wl.n
-        dt = ko.F32 if wl.dtype == "f32" else ko.BF16
+        dt = {"f32": ko.F32, "bf16": ko.BF16, "f16": ko.F16}[wl.dtype]
         assert wl.H % G == 0
         self.oc = ko.OracleCache(wl.L, wl.B, wl.H // G, wl.d, self.cap, dt)
         self.Q = np.zeros((wl.L, wl.B, wl.H, wl.n, wl.d), self.oc.K.dtype)

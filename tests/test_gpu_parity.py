@@ -14,7 +14,8 @@ from parity_harness import (LockStep, assert_close_out, assert_close_score, asse
 
 pytestmark = pytest.mark.gpu
 
-DTYPES = [(ko.BF16, 64), (ko.BF16, 128), (ko.BF16, 256), (ko.F32, 64), (ko.F32, 128)]
+DTYPES = [(ko.BF16, 64), (ko.BF16, 128), (ko.BF16, 256), (ko.F32, 64), (ko.F32, 128), (ko.F16, 64), (ko.F16, 128),
+          (ko.F16, 256)]
 
 
 def bf16_round(a):
@@ -24,6 +25,8 @@ def bf16_round(a):
 
 def rnd(rng, shape, dtype):
     a = rng.standard_normal(shape).astype(np.float32)
+    if dtype == ko.F16:
+        return a.astype(np.float16)
     return bf16_round(a) if dtype == ko.BF16 else a
 
 
@@ -670,7 +673,8 @@ def test_fused_step_on_random_shapes_equals_the_two_calls():
     types, head sizes, query heads per cached head, few and many units (every fused launch sequence: one
     launch, split + tail, decode + select, with and without the shared score), both layouts, ragged lengths."""
     rng = np.random.default_rng(20240310)
-    combos = [(ko.BF16, 64), (ko.BF16, 128), (ko.BF16, 256), (ko.F32, 64), (ko.F32, 128)]
+    combos = [(ko.BF16, 64), (ko.BF16, 128), (ko.BF16, 256), (ko.F32, 64), (ko.F32, 128), (ko.F16, 128), (ko.F16, 64),
+              (ko.F16, 256)]
     for case in range(24):
         dtype, d = combos[case % len(combos)]
         G = int(rng.choice([1, 1, 2, 4, 8]))
@@ -1123,7 +1127,8 @@ def test_grouped_query_decode_at_the_largest_lds_footprint():
     (ko.BF16, 128, 8, ko.NOISE_GUMBEL, False, 2049), (ko.BF16, 64, 8, ko.NOISE_GAUSSIAN, True, 1500),
     (ko.BF16, 256, 8, ko.NOISE_NONE, False, 1500), (ko.BF16, 128, 4, ko.NOISE_GUMBEL, False, 4097),
     (ko.BF16, 64, 4, ko.NOISE_GUMBEL, True, 1500), (ko.BF16, 256, 4, ko.NOISE_CONSTANT, False, 900),
-    (ko.F32, 64, 4, ko.NOISE_GUMBEL, False, 1100)])
+    (ko.F32, 64, 4, ko.NOISE_GUMBEL, False, 1100), (ko.F16, 128, 8, ko.NOISE_GUMBEL, False, 2049),
+    (ko.F16, 64, 8, ko.NOISE_GUMBEL, True, 700), (ko.F16, 256, 4, ko.NOISE_GAUSSIAN, False, 1200)])
 def test_grouped_query_one_eight_wave_workgroup_per_unit(dtype, d, G, noise, new_pos, cap):
     """4 or 8 query heads per cached head, a unit per compute unit and more than a few hundred tokens: one
     8-wave workgroup streams a whole unit (8 bf16 heads: logits on the matrix cores; partial outputs folded as a
@@ -1204,7 +1209,8 @@ def test_decode_step_on_random_shapes_matches_oracle():
     head, few and many units (one workgroup per unit or splits, 4- and 8-wave workgroups), ragged lengths,
     every logit adjustment, both position modes, with and without a position bias (30 shapes)."""
     rng = np.random.default_rng(20240309)
-    combos = [(ko.BF16, 64), (ko.BF16, 128), (ko.BF16, 256), (ko.F32, 64), (ko.F32, 128)]
+    combos = [(ko.BF16, 64), (ko.BF16, 128), (ko.BF16, 256), (ko.F32, 64), (ko.F32, 128), (ko.F16, 128), (ko.F16, 64),
+              (ko.F16, 256)]
     seen = set()
     for case in range(30):
         dtype, d = combos[case % len(combos)]
@@ -1362,6 +1368,21 @@ def test_beam_search_steps_in_lockstep_with_the_oracle():
         assert_state_equal(gc, oc, kv=True, score_exact=False)
         upload_into(gc, oc, kv=False)                        # scores: continue from the oracle's bits
     assert_close_score(host(gc.score), oc.score, oc.len)
+
+
+# ------------------------------------------------------------------ IEEE half caches
+@pytest.mark.parametrize("name,layout", [("gptj", kf.LAYOUT_ORDERED), ("mpt", kf.LAYOUT_SLOT)])
+def test_half_precision_cache_lockstep(name, layout):
+    """The gptj- and mpt-shaped slices with K, V and Q held as IEEE half instead of bf16: prompt scoring,
+    first eviction and generation steps in lock-step with the oracle."""
+    import dataclasses
+    wl = dataclasses.replace(kw.CONFIGS[name].slice(L=1, B=1 if name == "gptj" else 2, H=4, n=512, k=256, w=51, T=64),
+                             dtype="f16")
+    ls = LockStep(wl, layout=layout)
+    ls.prefill()
+    for t in range(1, 17):
+        ls.step(t, check_kv=(t == 16))
+    print("half lockstep", name, ls.stats)
 
 
 # ------------------------------------------------------------------ the C ABI without Python
