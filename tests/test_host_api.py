@@ -234,7 +234,8 @@ def test_element_types_and_head_sizes():
         for d in ds:
             assert kf.kf_decode_launch_shape(fake_cache(dtype=dt, d=d), 0)[0] >= 1
     expect(binding.KF_EUNSUPPORTED, kf.kf_decode_launch_shape, fake_cache(dtype=kf.F32, d=256), 0)
-    expect(binding.KF_EINVAL, kf.kf_decode_launch_shape, fake_cache(dtype=3), 0)
+    expect(binding.KF_EUNSUPPORTED, kf.kf_decode_launch_shape, fake_cache(dtype=3), 0)
+    expect(binding.KF_EINVAL, kf.kf_beam_fork, fake_cache(dtype=3), 0x60000, WS)
 
 
 def test_bench_refuses_more_than_one_gpu():
