@@ -150,16 +150,16 @@ def test_decode_launch_shape_covers_the_rows_and_balances_the_chip():
     S, chunk = kf.kf_decode_launch_shape(fake_cache(L=32, B=1, H=32, d=128, cap=24000), 24000)
     assert S >= 6 and chunk <= 4096
     # 8 bf16 query heads per cached head: one workgroup per unit while 2 x 8 logit rows fit a compute
-    # unit's LDS (about 2500 tokens) and there is a unit per compute unit; splits of at most 512 rows otherwise
+    # unit's LDS (about 2500 tokens) and there is a unit per compute unit; splits of at most 1024 rows otherwise
     assert kf.kf_decode_launch_shape(fake_cache(L=32, B=8, H=8, d=128, cap=2049, q_per_kv=8), 2049) == (1, 2048)
     S, chunk = kf.kf_decode_launch_shape(fake_cache(L=32, B=8, H=8, d=128, cap=4097, q_per_kv=8), 4097)
-    assert S >= 8 and chunk <= 512
+    assert S >= 4 and chunk <= 1024
     # 4 query heads: the same up to about 5000 tokens
     assert kf.kf_decode_launch_shape(fake_cache(L=32, B=8, H=8, d=128, cap=4097, q_per_kv=4), 4097) == (1, 4096)
     S, chunk = kf.kf_decode_launch_shape(fake_cache(L=32, B=8, H=8, d=128, cap=8193, q_per_kv=4), 8193)
-    assert S >= 8 and chunk <= 1024
+    assert S >= 4 and chunk <= 2048
     S, chunk = kf.kf_decode_launch_shape(fake_cache(L=2, B=8, H=8, d=128, cap=2049, q_per_kv=8), 2049)
-    assert S >= 4 and chunk <= 512
+    assert S >= 2 and chunk <= 1024
     S, chunk = kf.kf_decode_launch_shape(fake_cache(L=32, B=8, H=8, d=128, cap=2049, q_per_kv=8, dtype=kf.F32), 2049)
     assert S >= 4 and chunk <= 512
     expect(binding.KF_EINVAL, kf.kf_decode_launch_shape, fake_cache(), 2000)
@@ -211,7 +211,8 @@ def test_query_group_validation_and_sizes():
     for g in (1, 2, 4, 8):
         for cap in (1025, 9831, 40000):
             S, chunk = kf.kf_decode_launch_shape(fake_cache(L=4, B=2, H=8, cap=cap, q_per_kv=g), cap)
-            assert (chunk * g <= 4096 or S == 1) and S * chunk >= cap - 1 and 1 <= S <= 256, (g, cap, S, chunk)
+            lim = 8192 if g >= 4 else 4096            # 4 and 8 heads: splits for 8-wave workgroups
+            assert (chunk * g <= lim or S == 1) and S * chunk >= cap - 1 and 1 <= S <= 256, (g, cap, S, chunk)
 
 
 def test_launches_beyond_the_grid_limit_are_refused():
