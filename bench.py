@@ -57,8 +57,8 @@ def decode_bytes(wl, m):
 def main():
     args = parse()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (units are independent; see DESIGN.md for how the "
-              "path would shard); --gpus %d is not supported" % args.gpus, file=sys.stderr)
+        print("bench.py: this build runs on ONE GPU (units are independent: the path would shard by head, batch "
+              "or layer without any exchange); --gpus %d is not supported" % args.gpus, file=sys.stderr)
         sys.exit(2)
     import numpy as np
     import torch

@@ -1143,7 +1143,7 @@ def test_grouped_query_one_eight_wave_workgroup_per_unit(dtype, d, G, noise, new
     lens[0, 0, 0] = 0            # the new token alone
     lens[0, 0, 1] = cap - 1      # fills the cache exactly
     lens[0, 0, 2] = 15           # less than one 16-row tile of one wave
-    lens[0, 0, 3] = 257          # one row into the second sweep of the 16 waves
+    lens[0, 0, 3] = 129          # one row into the second sweep of the 8 waves
     lens[1, 7, 15] = cap         # no room: skipped and reported
     oc = random_cache(rng, L, B, H, d, cap, dtype, lens)
     gc = upload(oc, G)
