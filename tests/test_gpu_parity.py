@@ -1508,24 +1508,27 @@ def test_single_launch_slot_step_from_the_device_counter_and_in_a_graph():
 
 
 # ------------------------------------------------------------------ temperature away from the schedule's range
+@pytest.mark.parametrize("G", [1, 8])
 @pytest.mark.parametrize("tau", [0.05, 0.5, 8.0, 1000.0])
-def test_decode_at_extreme_temperatures(tau):
+def test_decode_at_extreme_temperatures(tau, G):
     """Sec. 3.3.1: small tau sharpens the score distribution towards one-hot, large tau flattens it towards
     uniform; the kernels keep everything in the base-2 domain with running maxima, so neither end overflows."""
     rng = np.random.default_rng(int(tau * 100))
     L, B, H, d, cap = 1, 2, 3, 128, 900
     lens = rng.integers(600, cap, (L, B, H)).astype(np.int32)
     oc = random_cache(rng, L, B, H, d, cap, ko.BF16, lens)
-    q, kn, vn = (rnd(rng, (L, B, H, d), ko.BF16) for _ in range(3))
+    q = rnd(rng, (L, B, H * G, d), ko.BF16)
+    kn, vn = (rnd(rng, (L, B, H, d), ko.BF16) for _ in range(2))
     seeds = np.array([21, 22], np.uint64)
-    gc = upload(oc)
+    gc = upload(oc, G)
     ws = kf.new_workspace(gc)
-    out = torch.zeros((L, B, H, d), dtype=torch.float32, device="cuda")
+    out = torch.zeros((L, B, H * G, d), dtype=torch.float32, device="cuda")
     q_pos = int(oc.pos.max()) + 1
     before = oc.score.copy()
     kf.kf_decode_step(gc, dev(q), dev(kn), dev(vn), q_pos, 0, tau, 0.0884, kf.NOISE_GUMBEL, dev(seeds), None, out, ws)
     torch.cuda.synchronize()
-    out_ref, _, df = oc.decode_step(q, kn, vn, q_pos, tau, 0.0884, ko.NOISE_GUMBEL, seeds, None, debug=True)
+    out_ref, _, df = oc.decode_step(q, kn, vn, q_pos, tau, 0.0884, ko.NOISE_GUMBEL, seeds, None, debug=True, q_per_kv=G)
+    df = df.reshape(L, B, H, G, cap).sum(axis=3)      # a cached head's score takes the sum of its query heads' increments
     assert_close_out(host(out), out_ref)
     # increments: 2e-3 relative where they matter, plus an absolute floor of 1e-7 of the step's unit mass
     # (at tau = 0.05 most increments are far below fp32's resolution next to the scores they are added to)
@@ -1534,11 +1537,11 @@ def test_decode_at_extreme_temperatures(tau):
         m = int(lens[l, b, h]) + 1
         g, r = got[l, b, h, :m], df[l, b, h, :m]
         assert np.all(np.abs(g - r) <= 2e-3 * np.abs(r) + 2e-7 * (1.0 + np.abs(before[l, b, h, :m]))), (tau, l, b, h)
-        assert abs(g.sum() - 1.0) < 1e-3
+        assert abs(g.sum() - G) < 1e-3 * G
     if tau <= 0.05:
-        assert df.max(axis=-1).min() > 0.5          # nearly one-hot
+        assert df.max(axis=-1).min() > 0.5 / (G ** 0.5)    # nearly one-hot (per query head)
     if tau >= 1000.0:
-        assert df[0, 0, 0, : lens[0, 0, 0] + 1].max() < 2.0 / lens[0, 0, 0]   # nearly uniform
+        assert df[0, 0, 0, : lens[0, 0, 0] + 1].max() < 2.0 * G / lens[0, 0, 0]   # nearly uniform
 
 
 # ------------------------------------------------------------------ free-running on a bf16 slice (informational)
