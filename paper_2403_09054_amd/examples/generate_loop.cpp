@@ -182,6 +182,29 @@ int main() {
             }
         }
     }
+    // ---- beam search bookkeeping: sequence 1 is replaced by a continuation of sequence 0
+    {
+        const int32_t parent[2] = {0, 0};
+        int32_t* dparent;
+        HIP_OK(hipMalloc((void**)&dparent, sizeof(parent)));
+        HIP_OK(hipMemcpy(dparent, parent, sizeof(parent), hipMemcpyHostToDevice));
+        KF_OK_(kf_beam_fork(&gen, dparent, ws, ws_bytes, stream));
+        HIP_OK(hipStreamSynchronize(stream));
+        if (read_state()) return 2;
+        for (int l = 0; l < L; ++l) {
+            for (int h = 0; h < H; ++h) {
+                const size_t u0 = ((size_t)l * B + 0) * H + h, u1 = ((size_t)l * B + 1) * H + h;
+                bool ok = hlen[u0] == hlen[u1];
+                for (int j = 0; ok && j < hlen[u0]; ++j)
+                    ok = hpos[u0 * gen.cap + j] == hpos[u1 * gen.cap + j] && hscore[u0 * gen.cap + j] == hscore[u1 * gen.cap + j];
+                if (!ok) {
+                    ++failures;
+                    fprintf(stderr, "beam fork: layer %d head %d differs from its parent\n", l, h);
+                }
+            }
+        }
+        HIP_OK(hipFree(dparent));
+    }
     int32_t hstep = 0, herr = 0;
     HIP_OK(hipMemcpy(&hstep, dstep, 4, hipMemcpyDeviceToHost));
     HIP_OK(hipMemcpy(&herr, (int32_t*)ws + KF_WS_ERROR_WORD, 4, hipMemcpyDeviceToHost));
