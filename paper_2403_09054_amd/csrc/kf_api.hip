@@ -510,9 +510,10 @@ static kf_status fused_step(kf_cache* c, const void* q, const void* k_new, const
         e = kf::launch_decode(da, U, c->d, c->dtype, p.lds_bytes, (hipStream_t)stream);
         if (e == hipSuccess && da.shared) e = share_after_decode(c, da, (hipStream_t)stream);
         if (e == hipSuccess) e = kf::launch_select(sa, U, (hipStream_t)stream);
-    } else if (da.S > 1 && (int64_t)da.S * da.chunk <= kTailMergeMaxTokens && !sa.wide && !sa.presel) {
+    } else if (da.S > 1 && (int64_t)da.S * da.chunk <= kTailMergeMaxTokens && !sa.presel) {
         e = kf::launch_decode_split(da, U, c->d, c->dtype, p.lds_bytes, (hipStream_t)stream);
         if (e == hipSuccess) e = kf::launch_step_tail(da, sa, U, c->d, (hipStream_t)stream);
+        if (e == hipSuccess && sa.wide) e = kf::launch_shift(sa, U, (hipStream_t)stream);  // few units: rows move in a launch of their own
     } else {  // one workgroup per unit (nothing to merge), or units too long to merge inside the selection
         e = kf::launch_decode(da, U, c->d, c->dtype, p.lds_bytes, (hipStream_t)stream);
         if (e == hipSuccess) e = kf::launch_select(sa, U, (hipStream_t)stream);

@@ -139,6 +139,8 @@ struct ForkArgs {
 hipError_t launch_fork(const ForkArgs& f, hipStream_t stream);
 // decode merge + select + compact of every unit in one launch (after the split kernel of a fused step)
 hipError_t launch_step_tail(const DecodeArgs& d, const SelectArgs& a, int64_t U, int32_t hd, hipStream_t stream);
+// the row-shifting launch of the two-launch eviction (after a selection launch that ran with a.wide set)
+hipError_t launch_shift(const SelectArgs& a, int64_t U, hipStream_t stream);
 // the split kernel alone (no merge launch): first half of a fused step
 hipError_t launch_decode_split(const DecodeArgs& a, int64_t U, int32_t d, int32_t dtype, size_t lds_bytes,
                                hipStream_t stream);

@@ -843,12 +843,15 @@ hipError_t launch_select(const SelectArgs& a, int64_t U, hipStream_t stream) {
     else
         hipLaunchKernelGGL((select_kernel<kSelectThreads>), grid, dim3(kSelectThreads), 0, stream, a);
     hipError_t e = hipGetLastError();
-    if (e == hipSuccess && a.wide) {
-        const int nchunks = (a.k + a.chunk_rows - 1) / a.chunk_rows;
-        hipLaunchKernelGGL(shift_chunk_kernel, dim3((unsigned)(U * nchunks)), dim3(kWideThreads), 0, stream, a, nchunks, U);
-        e = hipGetLastError();
-    }
+    if (e == hipSuccess && a.wide) e = launch_shift(a, U, stream);
     return e;
+}
+
+// Second launch of the two-launch eviction: every chunk of rows behind the evicted slot moves down by one.
+hipError_t launch_shift(const SelectArgs& a, int64_t U, hipStream_t stream) {
+    const int nchunks = (a.k + a.chunk_rows - 1) / a.chunk_rows;
+    hipLaunchKernelGGL(shift_chunk_kernel, dim3((unsigned)(U * nchunks)), dim3(kWideThreads), 0, stream, a, nchunks, U);
+    return hipGetLastError();
 }
 
 }  // namespace kf
