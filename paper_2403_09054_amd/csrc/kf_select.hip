@@ -686,29 +686,41 @@ __global__ void __launch_bounds__(NT) select_kernel(const SelectArgs a) {
 // Tail of a fused generation step: merge the decode kernel's split records of
 // the unit (attention output, score accumulation, new length), then select and
 // compact -- one launch instead of two.
-template <int D, int NT>
+template <int D, int NT, int G>
 __global__ void __launch_bounds__(NT) step_tail_kernel(const DecodeArgs d, const SelectArgs a) {
     __shared__ float red_s[NT / kWave];
-    __shared__ float w_p[kDecodeMaxSplits], w_e[kDecodeMaxSplits];
+    __shared__ float w_p[G * kDecodeMaxSplits], w_e[G * kDecodeMaxSplits];
     const int64_t u = blockIdx.x;
     const int len0 = d.len[u];
     if (len0 >= 0 && len0 < d.cap && len0 <= d.S * d.chunk) {  // else: skipped by the split kernel too
-        merge_unit<D, NT, 1>(d, u, len0, red_s, w_p, w_e, 0, len0 + 1, true);  // one query head per unit only
+        merge_unit<D, NT, G>(d, u, len0, red_s, w_p, w_e, 0, len0 + 1, true);
         __syncthreads();  // the merged scores and the new length are visible to the whole workgroup
     }
     select_unit<NT>(a, u);
     advance_step(a);
 }
 
+template <int NT, int G>
+static hipError_t launch_step_tail_g(const DecodeArgs& d, const SelectArgs& a, int64_t U, int32_t hd,
+                                     hipStream_t stream) {
+    const dim3 grid((unsigned)U), block(NT);
+    if (hd == 64) hipLaunchKernelGGL((step_tail_kernel<64, NT, G>), grid, block, 0, stream, d, a);
+    else if (hd == 128) hipLaunchKernelGGL((step_tail_kernel<128, NT, G>), grid, block, 0, stream, d, a);
+    else if (hd == 256) hipLaunchKernelGGL((step_tail_kernel<256, NT, G>), grid, block, 0, stream, d, a);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
 template <int NT>
 static hipError_t launch_step_tail_nt(const DecodeArgs& d, const SelectArgs& a, int64_t U, int32_t hd,
                                       hipStream_t stream) {
-    const dim3 grid((unsigned)U), block(NT);
-    if (hd == 64) hipLaunchKernelGGL((step_tail_kernel<64, NT>), grid, block, 0, stream, d, a);
-    else if (hd == 128) hipLaunchKernelGGL((step_tail_kernel<128, NT>), grid, block, 0, stream, d, a);
-    else if (hd == 256) hipLaunchKernelGGL((step_tail_kernel<256, NT>), grid, block, 0, stream, d, a);
-    else return hipErrorInvalidValue;
-    return hipGetLastError();
+    switch (d.G) {
+        case 1: return launch_step_tail_g<NT, 1>(d, a, U, hd, stream);
+        case 2: return launch_step_tail_g<NT, 2>(d, a, U, hd, stream);
+        case 4: return launch_step_tail_g<NT, 4>(d, a, U, hd, stream);
+        case 8: return launch_step_tail_g<NT, 8>(d, a, U, hd, stream);
+        default: return hipErrorInvalidValue;
+    }
 }
 
 hipError_t launch_step_tail(const DecodeArgs& d, const SelectArgs& a, int64_t U, int32_t hd, hipStream_t stream) {
