@@ -509,10 +509,8 @@ static kf_status fused_step(kf_cache* c, const void* q, const void* k_new, const
         e = kf::launch_decode(da, U, c->d, c->dtype, p.lds_bytes, (hipStream_t)stream);
         if (e == hipSuccess) e = share_after_decode(c, da, (hipStream_t)stream);
         if (e == hipSuccess) e = kf::launch_select(sa, U, (hipStream_t)stream);
-    } else if (da.S > 1 && (int64_t)da.S * da.chunk <= kTailMergeMaxTokens && !sa.presel && (da.G == 1 || !sa.wide)) {
-        // (few units with several query heads each keep the merge launch: it spreads a unit over several
-        // workgroups, which one selection workgroup merging G heads does not make up for -- 68 vs 79 us per step
-        // on 64 units x 8 heads x 2048 tokens)
+    } else if (da.S > 1 && (int64_t)da.S * da.chunk <= kTailMergeMaxTokens && !sa.presel) {
+        // few units in splits: the merge rides in the selection launch, whatever the number of query heads
         e = kf::launch_decode_split(da, U, c->d, c->dtype, p.lds_bytes, (hipStream_t)stream);
         if (e == hipSuccess) e = kf::launch_step_tail(da, sa, U, c->d, (hipStream_t)stream);
         if (e == hipSuccess && sa.wide) e = kf::launch_shift(sa, U, (hipStream_t)stream);  // few units: rows move in a launch of their own
