@@ -1204,6 +1204,51 @@ def test_long_units_one_eight_wave_workgroup_per_unit(d, G, cap):
     assert_close_score(host(gc.score), oc.score, oc.len)
 
 
+@pytest.mark.parametrize("H,G,cap", [(1, 1, 20001), (2, 2, 12001)])
+def test_one_long_unit_in_more_than_64_splits(H, G, cap):
+    """One or two long units are cut into more splits than a wave has lanes: the merge then holds two
+    partial records per lane.  Decode call, and the whole step against the two calls."""
+    rng = np.random.default_rng(9100 + G)
+    L, B, d = 1, 1, 128
+    c0 = kf.Cache(K=0x10000, V=0x20000, score=0x30000, pos=0x40000, len=0x50000, L=L, B=B, H=H, d=d, cap=cap,
+                  dtype=kf.BF16, q_per_kv=G)
+    S, chunk = kf.kf_decode_launch_shape(c0, cap)
+    assert S > 64
+    lens = np.full((L, B, H), cap - 1, np.int32)
+    lens[0, 0, H - 1] = cap - 1 - 3 * chunk - 5  # the last splits of this unit are empty
+    oc = random_cache(rng, L, B, H, d, cap, ko.BF16, lens)
+    gc, g2 = upload(oc, G), upload(oc, G)
+    ws, ws2 = kf.new_workspace(gc), kf.new_workspace(g2)
+    q = rnd(rng, (L, B, H * G, d), ko.BF16)
+    kn, vn = (rnd(rng, (L, B, H, d), ko.BF16) for _ in range(2))
+    seeds = np.array([77], np.uint64)
+    q_pos = int(oc.pos.max()) + 1
+    out = torch.zeros((L, B, H * G, d), dtype=torch.float32, device="cuda")
+    scale = float(1.0 / np.sqrt(np.float32(d)))
+    kf.kf_decode_step(gc, dev(q), dev(kn), dev(vn), q_pos, cap, 1.5, scale, kf.NOISE_GUMBEL, dev(seeds), None, out, ws)
+    torch.cuda.synchronize()
+    assert error_word(ws) == 0
+    out_ref = oc.decode_step(q, kn, vn, q_pos, 1.5, scale, ko.NOISE_GUMBEL, seeds, None, q_per_kv=G)
+    assert_close_out(host(out), out_ref)
+    np.testing.assert_array_equal(host(gc.len), oc.len)
+    assert_close_score(host(gc.score), oc.score, oc.len)
+    # the whole step on a second copy equals the two calls on the first
+    k, w = cap - 1, (cap - 1) // 5
+    out2 = torch.zeros_like(out)
+    kf.kf_select_evict(gc, k, w, None, ws, layout=kf.LAYOUT_ORDERED)
+    kf.kf_decode_select_step(g2, dev(q), dev(kn), dev(vn), q_pos, cap, 1.5, scale, kf.NOISE_GUMBEL, dev(seeds), None, out2,
+                             k=k, w=w, layout=kf.LAYOUT_ORDERED, workspace=ws2)
+    torch.cuda.synchronize()
+    assert error_word(ws) == 0 and error_word(ws2) == 0
+    np.testing.assert_array_equal(host(out2), host(out))
+    ln = host(gc.len)
+    np.testing.assert_array_equal(host(g2.len), ln)
+    for h in range(H):
+        n = int(ln[0, 0, h])
+        np.testing.assert_array_equal(host(g2.pos)[0, 0, h, :n], host(gc.pos)[0, 0, h, :n])
+        np.testing.assert_array_equal(host(g2.score)[0, 0, h, :n], host(gc.score)[0, 0, h, :n])
+
+
 def test_decode_step_on_random_shapes_matches_oracle():
     """Seeded sweep over the decode call's shape space: element types, head sizes, query heads per cached
     head, few and many units (one workgroup per unit or splits, 4- and 8-wave workgroups), ragged lengths,
