@@ -217,6 +217,21 @@ def main():
             roofline["traffic"] = tj.get("decode_kernel_bytes_per_launch", 0) + tj.get(
                 "decode_merge_kernel_bytes_per_launch", 0)
 
+    # ---------------- what a plain device-to-device copy reaches on this machine (read + write bytes): the
+    # practical ceiling beside the published 8 TB/s
+    src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")   # 1 GiB
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    c_ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    c_ev[0].record()
+    for _ in range(5):
+        dst.copy_(src)
+    c_ev[1].record()
+    torch.cuda.synchronize()
+    copy_gbs = 5 * 2 * src.numel() * 4 / (c_ev[0].elapsed_time(c_ev[1]) * 1e-3) / 1e9
+    copy_ceiling = {"value": round(copy_gbs, 1), "unit": "GB/s", "kind": "device copy of 1 GiB, bytes read + written"}
+    del src, dst
+
     # ---------------- variants of the same step (not the headline): one fused call per step, in the
     # ordered layout and in the slot-replacement layout (one row moves per unit instead of ~0.2*k)
     def timed_variant(layout):
@@ -412,7 +427,7 @@ def main():
             "units": wl.units, "noise": "gumbel", "tau": [wl.tau_init, wl.tau_end],
             "layout": "ordered (in-place order-preserving compaction)"},
         "roofline": roofline, "select_compact": select_info, "prefill_score": prefill, "variants": variants,
-        "cpu_baseline": cpu,
+        "copy_ceiling": copy_ceiling, "cpu_baseline": cpu,
     }
     print(json.dumps(line))
 
