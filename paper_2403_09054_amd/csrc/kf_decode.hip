@@ -981,14 +981,13 @@ __global__ void __launch_bounds__(NT, NT >= 512 ? 4 : 1) decode_kernel(const Dec
 // unit's token count comes from the split kernel's record, not from len, which the first workgroup updates.
 template <int D, int NT, int G>
 __global__ void __launch_bounds__(NT) decode_merge_kernel(const DecodeArgs a) {
-    __shared__ float red_s[NT / kWave];
     __shared__ float w_p[G * kDecodeMaxSplits], w_e[G * kDecodeMaxSplits];
     const int64_t u = blockIdx.x;
     const int m = a.ws_m[u];
     if (m <= 0) return;  // skipped by the split kernel
     const int per = ((m + (int)gridDim.y - 1) / (int)gridDim.y + NT - 1) / NT * NT;
     const int j_begin = (int)blockIdx.y * per;
-    merge_unit<D, NT, G>(a, u, m - 1, red_s, w_p, w_e, j_begin, j_begin + per, blockIdx.y == 0);
+    merge_unit<D, NT, G>(a, u, m - 1, w_p, w_e, j_begin, j_begin + per, blockIdx.y == 0);
 }
 
 // Shared score function (the paper's ablation of one score for all layers,

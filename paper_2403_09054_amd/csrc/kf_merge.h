@@ -6,7 +6,7 @@
 
 namespace kf {
 
-constexpr int kDecodeMaxSplits = 256;  // one thread per split in the merge: <= threads of the merging workgroup
+constexpr int kDecodeMaxSplits = 256;  // a wave merges one head's records: this many / 64 per lane, in registers
 
 // Merges the S partial records of unit u (one per split and query head):
 // rescales every split's un-normalised output and score increments to the
@@ -16,8 +16,8 @@ constexpr int kDecodeMaxSplits = 256;  // one thread per split in the merge: <= 
 // The workgroup handles tokens [j_begin, j_end) of the score update; the `lead`
 // workgroup of a unit also writes the attention outputs and the new length.
 template <int D, int NT, int G>
-__device__ __forceinline__ void merge_unit(const DecodeArgs& a, int64_t u, int len0, float* red_s, float* w_p,
-                                           float* w_e, int j_begin, int j_end, bool lead) {
+__device__ __forceinline__ void merge_unit(const DecodeArgs& a, int64_t u, int len0, float* w_p, float* w_e, int j_begin,
+                                           int j_end, bool lead) {
     constexpr int PW = D + 4;
     const int tid = threadIdx.x, S = a.S, m = len0 + 1;
     const float* parts = a.ws_part + (size_t)u * S * G * PW;
@@ -28,7 +28,6 @@ __device__ __forceinline__ void merge_unit(const DecodeArgs& a, int64_t u, int l
     constexpr int NW = NT / kWave, SP = kDecodeMaxSplits / kWave;
     __shared__ float inv_p[G];
     const int wave = tid / kWave, lane = tid % kWave;
-    (void)red_s;
     for (int g = wave; g < G; g += NW) {
         float pmx[SP], psp[SP], pmy[SP], pse[SP];
 #pragma unroll

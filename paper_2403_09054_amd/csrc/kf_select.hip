@@ -688,12 +688,11 @@ __global__ void __launch_bounds__(NT) select_kernel(const SelectArgs a) {
 // compact -- one launch instead of two.
 template <int D, int NT, int G>
 __global__ void __launch_bounds__(NT) step_tail_kernel(const DecodeArgs d, const SelectArgs a) {
-    __shared__ float red_s[NT / kWave];
     __shared__ float w_p[G * kDecodeMaxSplits], w_e[G * kDecodeMaxSplits];
     const int64_t u = blockIdx.x;
     const int len0 = d.len[u];
     if (len0 >= 0 && len0 < d.cap && len0 <= d.S * d.chunk) {  // else: skipped by the split kernel too
-        merge_unit<D, NT, G>(d, u, len0, red_s, w_p, w_e, 0, len0 + 1, true);
+        merge_unit<D, NT, G>(d, u, len0, w_p, w_e, 0, len0 + 1, true);
         __syncthreads();  // the merged scores and the new length are visible to the whole workgroup
     }
     select_unit<NT>(a, u);
