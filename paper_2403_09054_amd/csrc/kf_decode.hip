@@ -984,10 +984,28 @@ __global__ void __launch_bounds__(NT) decode_merge_kernel(const DecodeArgs a) {
     __shared__ float w_p[G * kDecodeMaxSplits], w_e[G * kDecodeMaxSplits];
     const int64_t u = blockIdx.x;
     const int m = a.ws_m[u];
-    if (m <= 0) return;  // skipped by the split kernel
+    if (m <= 0) {  // skipped by the split kernel
+        // the selection may still evict from this unit (it is full): its slices' minima come from the scores as they are
+        const int n = a.len[u];
+        if (a.pre_slices > 0 && !a.shared && n == a.pre_k + 1) {
+            const int per = ((n + (int)gridDim.y - 1) / (int)gridDim.y + NT - 1) / NT * NT;
+            const int j_begin = (int)blockIdx.y * per;
+            const bool by_pos = a.pre_layout == KF_LAYOUT_SLOT;
+            const float* fu = a.score + (size_t)u * a.cap;
+            const int32_t* pu = a.pos + (size_t)u * a.cap;
+            const int newest = by_pos ? pu[n - 1] : 0;
+            SliceMin smin;
+            for (int j = j_begin + (int)threadIdx.x; j < min(j_begin + per, n); j += NT) {
+                const int pj = by_pos ? pu[j] : 0;
+                if (by_pos ? (pj <= newest - a.pre_w) : (j < n - a.pre_w)) smin.take(fu[j], j, by_pos ? pj : j);
+            }
+            publish_slice_min<NT>(a, u, (int)blockIdx.y, smin);
+        }
+        return;
+    }
     const int per = ((m + (int)gridDim.y - 1) / (int)gridDim.y + NT - 1) / NT * NT;
     const int j_begin = (int)blockIdx.y * per;
-    merge_unit<D, NT, G>(a, u, m - 1, w_p, w_e, j_begin, j_begin + per, blockIdx.y == 0);
+    merge_unit<D, NT, G>(a, u, m - 1, w_p, w_e, j_begin, j_begin + per, blockIdx.y == 0, (int)blockIdx.y);
 }
 
 // Shared score function (the paper's ablation of one score for all layers,
@@ -1074,6 +1092,15 @@ static size_t decode_lds_bytes_big(int32_t G, int64_t chunk, int32_t d) {
 // hide memory latency are skipped when a better filled one exists.  With G
 // query heads per unit a split workgroup keeps G logit rows in LDS, so its
 // chunk is at most 1/G of the single-head maximum.
+// Enough workgroups per unit that each walks at most ~8 strides of the token range.
+int32_t decode_merge_slices(int32_t S, int32_t chunk) {
+    const int64_t tokens = (int64_t)S * chunk;
+    int64_t slices = (tokens + 8 * kDecodeThreads - 1) / (8 * kDecodeThreads);
+    if (slices > 16) slices = 16;
+    if (slices < 1) slices = 1;
+    return (int32_t)slices;
+}
+
 DecodePlan plan_decode(int64_t U, int32_t m, int32_t d, int32_t dtype, int32_t G) {
     DecodePlan p;
     const int rpb = rows_per_block(d, dtype);
@@ -1167,10 +1194,7 @@ static hipError_t launch_decode_g(const DecodeArgs& a, int64_t U, size_t lds, hi
             hipLaunchKernelGGL((decode_kernel<T, D, kDecodeThreadsBig, G>), grid, dim3(kDecodeThreadsBig), lds_big, st, a);
             hipError_t e2 = hipGetLastError();
             if (e2 == hipSuccess && a.S > 1 && merge) {
-                const int64_t tokens = (int64_t)a.S * a.chunk;
-                int64_t slices = (tokens + 8 * kDecodeThreads - 1) / (8 * kDecodeThreads);
-                if (slices > 16) slices = 16;
-                if (slices < 1) slices = 1;
+                const int32_t slices = decode_merge_slices(a.S, a.chunk);
                 hipLaunchKernelGGL((decode_merge_kernel<D, kDecodeThreads, G>), dim3((unsigned)U, (unsigned)slices), block, 0, st, a);
                 e2 = hipGetLastError();
             }
@@ -1190,11 +1214,7 @@ static hipError_t launch_decode_g(const DecodeArgs& a, int64_t U, size_t lds, hi
     hipLaunchKernelGGL((decode_kernel<T, D, kDecodeThreads, G>), grid, block, lds, st, a);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess && a.S > 1 && merge) {
-        // enough workgroups per unit that each walks at most ~8 strides of the token range, and the chip is filled
-        const int64_t tokens = (int64_t)a.S * a.chunk;
-        int64_t slices = (tokens + 8 * kDecodeThreads - 1) / (8 * kDecodeThreads);
-        if (slices > 16) slices = 16;
-        if (slices < 1) slices = 1;
+        const int32_t slices = decode_merge_slices(a.S, a.chunk);
         hipLaunchKernelGGL((decode_merge_kernel<D, kDecodeThreads, G>), dim3((unsigned)U, (unsigned)slices), block, 0, st, a);
         e = hipGetLastError();
     }

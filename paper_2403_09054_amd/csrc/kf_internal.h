@@ -47,6 +47,12 @@ struct DecodeArgs {
     int32_t* fuse_idx;  // NULL, or [U][k] survivor list as the selection kernel writes it
     int32_t* step_inc;   // NULL, or the device step counter the launch's last workgroup advances (whole-step launch)
     int32_t* ws_ticket;  // [1] workgroups of this launch that are done (zero between launches)
+    // Fused step of few, long units: the merge launch (pre_slices workgroups per unit) also leaves, per
+    // workgroup, the smallest eviction candidate among the tokens it updated -- what the selection's own
+    // candidate scan launch would compute from the finished scores.  pre_slices = 0: off.
+    int32_t pre_slices, pre_k, pre_w, pre_layout;
+    unsigned long long* pre_min;  // [U][pre_slices] (score key, tie-break) pack, ~0 if the slice has no candidate
+    int32_t* pre_slot;            // [U][pre_slices] its slot
     float inv_tau;
     float scale;
 };
@@ -59,6 +65,8 @@ struct DecodePlan {
 DecodePlan plan_decode(int64_t U, int32_t m, int32_t d, int32_t dtype, int32_t G);
 hipError_t launch_decode(const DecodeArgs& a, int64_t U, int32_t d, int32_t dtype, size_t lds_bytes,
                          hipStream_t stream);
+// Workgroups per unit of the merge launch that follows a split decode launch.
+int32_t decode_merge_slices(int32_t S, int32_t chunk);
 
 // Shared score function: adds up the layers' contributions and gives every layer the same score.
 //   inc != NULL (decode): score[l][bh][j] += sum_l' inc[l'][bh][j] for the m[.][bh] tokens just scored
@@ -100,6 +108,7 @@ struct SelectArgs {
     // Long units in the decode shape: a launch ahead of the selection cuts the candidate scan of a unit
     // into `presel` slices, one workgroup each, and leaves every slice's smallest candidate here.
     int32_t presel;             // 0: the selection workgroup scans the candidates itself
+    int32_t presel_done;        // the slices' minima are there already (left by the decode merge launch)
     unsigned long long* ws_pmin;  // [U][presel] smallest (score key, tie-break) pack of the slice, ~0 if none
     int32_t* ws_pslot;          // [U][presel] its slot
 };

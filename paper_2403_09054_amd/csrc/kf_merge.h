@@ -15,9 +15,57 @@ constexpr int kDecodeMaxSplits = 256;  // a wave merges one head's records: this
 // w_p, w_e: LDS, G*S floats each.
 // The workgroup handles tokens [j_begin, j_end) of the score update; the `lead`
 // workgroup of a unit also writes the attention outputs and the new length.
+// Smallest eviction candidate of a slice of tokens, as the selection's candidate scan forms it: the pack
+// orders by score, then (equal scores) the higher slot -- ordered layout -- or the higher position -- slot
+// layout -- leaves first.
+struct SliceMin {
+    unsigned long long best = ~0ull;
+    int slot = -1;
+    __device__ __forceinline__ void take(float f, int j, int tie) {
+        const unsigned long long pack = ((unsigned long long)float_key(f) << 32) | (uint32_t)(~(uint32_t)tie);
+        if (pack < best) {
+            best = pack;
+            slot = j;
+        }
+    }
+};
+
+// The workgroup's smallest candidate goes to entry `slice` of the unit's table.  Called by a whole workgroup.
+template <int NT>
+__device__ __forceinline__ void publish_slice_min(const DecodeArgs& a, int64_t u, int slice, SliceMin mine) {
+    __shared__ unsigned long long wmin_s[NT / kWave];
+    __shared__ int wslot_s[NT / kWave];
+    const int tid = threadIdx.x, lane = tid % kWave, wv = tid / kWave;
+    unsigned long long best = mine.best;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const unsigned long long t = __shfl_xor(best, o, kWave);
+        best = t < best ? t : best;
+    }
+    // slots and positions are unique: one lane of the wave owns the wave's minimum
+    const unsigned long long owner = __ballot(mine.best == best && best != ~0ull);
+    const int wslot = __shfl(mine.slot, owner ? __ffsll((long long)owner) - 1 : 0, kWave);
+    if (lane == 0) {
+        wmin_s[wv] = best;
+        wslot_s[wv] = owner ? wslot : -1;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        unsigned long long g = wmin_s[0];
+        int gs = wslot_s[0];
+        for (int i = 1; i < NT / kWave; ++i)
+            if (wmin_s[i] < g) {
+                g = wmin_s[i];
+                gs = wslot_s[i];
+            }
+        a.pre_min[(size_t)u * a.pre_slices + slice] = g;
+        a.pre_slot[(size_t)u * a.pre_slices + slice] = gs;
+    }
+}
+
 template <int D, int NT, int G>
 __device__ __forceinline__ void merge_unit(const DecodeArgs& a, int64_t u, int len0, float* w_p, float* w_e, int j_begin,
-                                           int j_end, bool lead) {
+                                           int j_end, bool lead, int slice = 0) {
     constexpr int PW = D + 4;
     const int tid = threadIdx.x, S = a.S, m = len0 + 1;
     const float* parts = a.ws_part + (size_t)u * S * G * PW;
@@ -73,15 +121,28 @@ __device__ __forceinline__ void merge_unit(const DecodeArgs& a, int64_t u, int l
         }
     }
     float* we = a.ws_e + (size_t)u * G * a.cap;
+    // with pre_slices the finished scores are also searched for the slice's smallest eviction candidate
+    // (only a unit exactly one token over the budget is looked at by the selection launch)
+    const bool pre = a.pre_slices > 0 && m == a.pre_k + 1;
+    const bool by_pos = a.pre_layout == KF_LAYOUT_SLOT;
+    const int32_t* pu = a.pos + (size_t)u * a.cap;
+    const int newest = (pre && by_pos) ? pu[len0] : 0;
+    SliceMin smin;
     for (int j = j_begin + tid; j < min(j_end, m); j += NT) {
         const int split = (j == len0) ? S - 1 : j / a.chunk;  // the new token belongs to the last split
         float df = 0.0f;
 #pragma unroll
         for (int g = 0; g < G; ++g) df = fmaf(we[(size_t)g * a.cap + j], w_e[g * S + split], df);
         if (a.shared) we[j] = df;  // summed over the layers by the launch that follows
-        else if (j == len0) fu[j] = df;
+        else if (pre) {
+            const float f_new = (j == len0) ? df : fu[j] + df;  // one add per address, as below
+            fu[j] = f_new;
+            const int pj = by_pos ? pu[j] : 0;
+            if (by_pos ? (pj <= newest - a.pre_w) : (j < m - a.pre_w)) smin.take(f_new, j, by_pos ? pj : j);
+        } else if (j == len0) fu[j] = df;
         else unsafeAtomicAdd(&fu[j], df);  // fire-and-forget add at the L2 (one per address: the plain fp32 sum)
     }
+    if (pre) publish_slice_min<NT>(a, u, slice, smin);
     if (lead && tid == 0) a.len[u] = m;
 }
 

@@ -844,7 +844,7 @@ hipError_t launch_fork(const ForkArgs& f, hipStream_t stream) {
 
 hipError_t launch_select(const SelectArgs& a, int64_t U, hipStream_t stream) {
     const dim3 grid((unsigned)U);
-    if (a.presel) {
+    if (a.presel && !a.presel_done) {
         hipLaunchKernelGGL(presel_kernel, dim3((unsigned)(U * a.presel)), dim3(kPreselThreads), 0, stream, a, U);
         const hipError_t e0 = hipGetLastError();
         if (e0 != hipSuccess) return e0;

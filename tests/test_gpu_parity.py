@@ -1249,6 +1249,61 @@ def test_one_long_unit_in_more_than_64_splits(H, G, cap):
         np.testing.assert_array_equal(host(g2.score)[0, 0, h, :n], host(gc.score)[0, 0, h, :n])
 
 
+@pytest.mark.parametrize("G,layout", [(1, 0), (1, 1), (2, 1), (4, 0)])
+def test_fused_step_of_few_long_units_equals_the_two_calls(G, layout):
+    """Few units of several thousand tokens: in the fused step the merge launch also leaves the candidate
+    minima the selection needs (the selection's own scan launch is skipped).  One unit is under budget, one
+    is full: the decode refuses it and reports it, the selection still evicts from it -- in both forms."""
+    rng = np.random.default_rng(4400 + 10 * G + layout)
+    L, B, H, d, k = 1, 2, 3, 128, 6000
+    cap, w = k + 1, 700
+    lens = np.full((L, B, H), k, np.int32)
+    lens[0, 0, 1] = k - 5
+    lens[0, 1, 2] = cap
+    oc = random_cache(rng, L, B, H, d, cap, ko.BF16, lens)
+    oc.pos[...] = np.arange(cap)
+    oc.score[0, 1, 0, 17] = oc.score[0, 1, 0, 4000] = -1.0      # two far-apart slices hold the smallest scores
+    if layout == kf.LAYOUT_SLOT:
+        for l, b, h in np.ndindex(L, B, H):
+            n_u = int(lens[l, b, h])
+            perm = rng.permutation(n_u)
+            if n_u == cap:
+                perm[n_u - 1:] = n_u - 1                   # the newest entry of a unit over budget sits in the last slot
+                perm[:n_u - 1] = rng.permutation(n_u - 1)
+            for nm in ("K", "V", "score", "pos"):
+                getattr(oc, nm)[l, b, h, :n_u] = getattr(oc, nm)[l, b, h, :n_u][perm]
+    q = rnd(rng, (L, B, H * G, d), ko.BF16)
+    kn, vn = (rnd(rng, (L, B, H, d), ko.BF16) for _ in range(2))
+    seeds = rng.integers(0, 2 ** 63, B).astype(np.uint64)
+    results = []
+    for fused in (False, True):
+        gc = upload(oc, G)
+        S, _ = kf.kf_decode_launch_shape(gc, cap)
+        assert S > 1
+        ws = kf.new_workspace(gc)
+        out = torch.zeros((L, B, H * G, d), dtype=torch.float32, device="cuda")
+        kept = torch.full((L, B, H, k), -7, dtype=torch.int32, device="cuda")
+        args = (dev(q), dev(kn), dev(vn), cap + 3, 0, 1.3, 0.09, kf.NOISE_GUMBEL, dev(seeds), None, out)
+        if fused:
+            kf.kf_decode_select_step(gc, *args, k=k, w=w, layout=layout, kept_idx=kept, workspace=ws)
+        else:
+            kf.kf_decode_step(gc, *args, ws)
+            kf.kf_select_evict(gc, k, w, kept, ws, layout=layout)
+        torch.cuda.synchronize()
+        assert error_word(ws) == 1                      # the full unit
+        lens_now = host(gc.len)
+        assert lens_now[0, 0, 1] == k - 4 and lens_now[0, 1, 2] == k and lens_now[0, 0, 0] == k
+        live = [host(t).copy() for t in (gc.K, gc.V, gc.score, gc.pos)]
+        for l, b, h in np.ndindex(L, B, H):
+            for t in live:
+                t[l, b, h, int(lens_now[l, b, h]):] = 0
+        kept_h = host(kept).copy()
+        kept_h[0, 0, 1] = 0                             # under budget: no survivor list
+        results.append([host(out).copy(), kept_h, lens_now.copy()] + live)
+    for i, (a_, b_) in enumerate(zip(*results)):
+        np.testing.assert_array_equal(a_, b_, err_msg="tensor %d" % i)
+
+
 def test_decode_step_on_random_shapes_matches_oracle():
     """Seeded sweep over the decode call's shape space: element types, head sizes, query heads per cached
     head, few and many units (one workgroup per unit or splits, 4- and 8-wave workgroups), ragged lengths,
