@@ -517,6 +517,17 @@ static kf_status fused_step(kf_cache* c, const void* q, const void* k_new, const
         if (e == hipSuccess) e = kf::launch_select(sa, U, (hipStream_t)stream);
     } else if (da.S > 1 && (int64_t)da.S * da.chunk <= kTailMergeMaxTokens && !sa.presel) {
         // few units in splits: the merge rides in the selection launch, whatever the number of query heads
+        if (layout == KF_LAYOUT_SLOT || sa.wide) {
+            // the merge has every final score in a register once: it also finds the smallest candidate, and the
+            // selection part of the launch takes the evicted slot from there instead of reading the scores again
+            da.pre_slices = sa.presel = 1;
+            da.pre_k = k;
+            da.pre_w = w;
+            da.pre_layout = layout;
+            da.pre_min = sa.ws_pmin;
+            da.pre_slot = sa.ws_pslot;
+            sa.presel_done = 1;
+        }
         e = kf::launch_decode_split(da, U, c->d, c->dtype, p.lds_bytes, (hipStream_t)stream);
         if (e == hipSuccess) e = kf::launch_step_tail(da, sa, U, c->d, (hipStream_t)stream);
         if (e == hipSuccess && sa.wide) e = kf::launch_shift(sa, U, (hipStream_t)stream);  // few units: rows move in a launch of their own

@@ -990,16 +990,7 @@ __global__ void __launch_bounds__(NT) decode_merge_kernel(const DecodeArgs a) {
         if (a.pre_slices > 0 && !a.shared && n == a.pre_k + 1) {
             const int per = ((n + (int)gridDim.y - 1) / (int)gridDim.y + NT - 1) / NT * NT;
             const int j_begin = (int)blockIdx.y * per;
-            const bool by_pos = a.pre_layout == KF_LAYOUT_SLOT;
-            const float* fu = a.score + (size_t)u * a.cap;
-            const int32_t* pu = a.pos + (size_t)u * a.cap;
-            const int newest = by_pos ? pu[n - 1] : 0;
-            SliceMin smin;
-            for (int j = j_begin + (int)threadIdx.x; j < min(j_begin + per, n); j += NT) {
-                const int pj = by_pos ? pu[j] : 0;
-                if (by_pos ? (pj <= newest - a.pre_w) : (j < n - a.pre_w)) smin.take(fu[j], j, by_pos ? pj : j);
-            }
-            publish_slice_min<NT>(a, u, (int)blockIdx.y, smin);
+            scan_slice_min<NT>(a, u, n, j_begin, j_begin + per, (int)blockIdx.y);
         }
         return;
     }

@@ -63,6 +63,22 @@ __device__ __forceinline__ void publish_slice_min(const DecodeArgs& a, int64_t u
     }
 }
 
+// The same table entry for a unit the decode launch skipped (it is full; the selection may still evict
+// from it): the candidates among slots [j_begin, j_end) of its n entries, from the scores as they are.
+template <int NT>
+__device__ __forceinline__ void scan_slice_min(const DecodeArgs& a, int64_t u, int n, int j_begin, int j_end, int slice) {
+    const bool by_pos = a.pre_layout == KF_LAYOUT_SLOT;
+    const float* fu = a.score + (size_t)u * a.cap;
+    const int32_t* pu = a.pos + (size_t)u * a.cap;
+    const int newest = by_pos ? pu[n - 1] : 0;
+    SliceMin smin;
+    for (int j = j_begin + (int)threadIdx.x; j < min(j_end, n); j += NT) {
+        const int pj = by_pos ? pu[j] : 0;
+        if (by_pos ? (pj <= newest - a.pre_w) : (j < n - a.pre_w)) smin.take(fu[j], j, by_pos ? pj : j);
+    }
+    publish_slice_min<NT>(a, u, slice, smin);
+}
+
 template <int D, int NT, int G>
 __device__ __forceinline__ void merge_unit(const DecodeArgs& a, int64_t u, int len0, float* w_p, float* w_e, int j_begin,
                                            int j_end, bool lead, int slice = 0) {

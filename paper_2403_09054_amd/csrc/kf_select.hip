@@ -694,6 +694,9 @@ __global__ void __launch_bounds__(NT) step_tail_kernel(const DecodeArgs d, const
     if (len0 >= 0 && len0 < d.cap && len0 <= d.S * d.chunk) {  // else: skipped by the split kernel too
         merge_unit<D, NT, G>(d, u, len0, w_p, w_e, 0, len0 + 1, true);
         __syncthreads();  // the merged scores and the new length are visible to the whole workgroup
+    } else if (d.pre_slices > 0 && len0 == d.pre_k + 1) {
+        scan_slice_min<NT>(d, u, len0, 0, len0, 0);  // the selection below takes the evicted slot from the table
+        __syncthreads();
     }
     select_unit<NT>(a, u);
     advance_step(a);

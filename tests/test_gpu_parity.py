@@ -1249,20 +1249,23 @@ def test_one_long_unit_in_more_than_64_splits(H, G, cap):
         np.testing.assert_array_equal(host(g2.score)[0, 0, h, :n], host(gc.score)[0, 0, h, :n])
 
 
-@pytest.mark.parametrize("G,layout", [(1, 0), (1, 1), (2, 1), (4, 0)])
-def test_fused_step_of_few_long_units_equals_the_two_calls(G, layout):
-    """Few units of several thousand tokens: in the fused step the merge launch also leaves the candidate
-    minima the selection needs (the selection's own scan launch is skipped).  One unit is under budget, one
-    is full: the decode refuses it and reports it, the selection still evicts from it -- in both forms."""
-    rng = np.random.default_rng(4400 + 10 * G + layout)
-    L, B, H, d, k = 1, 2, 3, 128, 6000
-    cap, w = k + 1, 700
+@pytest.mark.parametrize("G,layout,k", [(1, 0, 6000), (1, 1, 6000), (2, 1, 6000), (4, 0, 6000),
+                                        (1, 0, 1500), (1, 1, 1500), (8, 1, 1500), (2, 0, 1500)])
+def test_fused_step_of_few_split_units_equals_the_two_calls(G, layout, k):
+    """Few units in splits: in the fused step the merge, which has every final score in a register once,
+    also finds the smallest eviction candidate -- per slice in the merge launch of units of several
+    thousand tokens (the selection's own scan launch is skipped), for the whole unit where the merge rides
+    in the selection launch.  One unit is under budget, one is full: the decode refuses it and reports it,
+    the selection still evicts from it -- in both forms."""
+    rng = np.random.default_rng(4400 + 10 * G + layout + k)
+    L, B, H, d = 1, 2, 3, 128
+    cap, w = k + 1, k // 8
     lens = np.full((L, B, H), k, np.int32)
     lens[0, 0, 1] = k - 5
     lens[0, 1, 2] = cap
     oc = random_cache(rng, L, B, H, d, cap, ko.BF16, lens)
     oc.pos[...] = np.arange(cap)
-    oc.score[0, 1, 0, 17] = oc.score[0, 1, 0, 4000] = -1.0      # two far-apart slices hold the smallest scores
+    oc.score[0, 1, 0, 17] = oc.score[0, 1, 0, 2 * k // 3] = -1.0  # two far-apart slices hold the smallest scores
     if layout == kf.LAYOUT_SLOT:
         for l, b, h in np.ndindex(L, B, H):
             n_u = int(lens[l, b, h])
