@@ -917,6 +917,7 @@ def test_shared_score_fused_step_and_disagreeing_layers():
 # ------------------------------------------------------------------ step number in device memory
 @pytest.mark.parametrize("name,kwargs,shared", [("gptj", dict(L=2, H=8, T=12), False),   # splits + fused tail
                                                 ("tiny", dict(T=12), False),             # one split per unit
+                                                ("long", dict(L=1, H=2, T=6), False),    # splits, merge launch with the candidate minima
                                                 ("tiny", dict(L=2, T=12), True)])
 def test_one_captured_step_replays_as_successive_steps(name, kwargs, shared):
     """kf_decode_select_step_at reads t from device memory (q_pos = n+t-1, tau = tau_t) and advances it: ONE
