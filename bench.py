@@ -365,6 +365,41 @@ def main():
                 "frac_of_peak": round(byt / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                 "query_head_rows_per_s": round(wl.L * B2 * wl.H * m / (ms * 1e-3), 0)}
 
+    def one_layer_variant(layout):
+        """The fused step on ONE layer's cache per call -- the shape an integration launches, a model running
+        its layers one after the other: layer 0's units copied into a cache of their own, 32 calls captured
+        in a HIP graph (step number in device memory) and replayed."""
+        c1 = kf.Cache.allocate(1, wl.B, wl.H, wl.d, wl.k + 1, dt)
+        for nm in ("K", "V", "score", "pos", "len"):
+            getattr(c1, nm).copy_(getattr(cache, nm)[0:1])
+        ws1 = kf.new_workspace(c1)
+        out1 = torch.zeros((1, wl.B, wl.H, wl.d), dtype=torch.float32, device="cuda")
+        ins = [tuple(t[0:1].contiguous() for t in steps_in[i % n_distinct]) for i in range(32)]
+        step = torch.full((1,), W_steps + K_steps + 8, dtype=torch.int32, device="cuda")
+
+        def calls():
+            for q, kn, vn in ins:
+                kf.kf_decode_select_step_at(c1, q, kn, vn, wl.n, wl.T, wl.tau_init, wl.tau_end, step, m, wl.scale,
+                                            noise, seeds, slopes, out1, k=wl.k, w=wl.w, layout=layout, workspace=ws1)
+        calls()                         # eager warm-up
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            calls()
+        g.replay()
+        torch.cuda.synchronize()
+        c0 = time.perf_counter()
+        for _ in range(8):
+            g.replay()
+        torch.cuda.synchronize()
+        us = (time.perf_counter() - c0) / (8 * len(ins)) * 1e6
+        assert int(ws1[:4].view(torch.int32)[0].item()) == 0
+        assert int(c1.len.min()) == wl.k and int(c1.len.max()) == wl.k
+        splits, chunk = kf.kf_decode_launch_shape(c1, m)
+        byt = decode_bytes(wl, m) / wl.L
+        return {"us_per_step": round(us, 2), "units": wl.B * wl.H, "splits_per_unit": splits, "rows_per_split": chunk,
+                "GB_per_s": round(byt / us / 1e3, 1)}
+
     variants = None
     if not args.no_variants:
         variants = {"fused_step_ordered_layout": timed_variant(kf.LAYOUT_ORDERED),
@@ -375,9 +410,11 @@ def main():
                     "noise_gaussian": noise_variant(kf.NOISE_GAUSSIAN)}
         if Ls >= wl.L:   # every layer in one cache: the shared score function can be timed
             variants["shared_score_fused_step_ordered_layout"] = shared_variant()
+        variants["one_layer_graph_fused_step_ordered_layout"] = one_layer_variant(kf.LAYOUT_ORDERED)
         # slot layout last: it unsorts the cache
         variants["fused_step_slot_layout"] = timed_variant(kf.LAYOUT_SLOT)
         variants["graph_fused_step_slot_layout"] = graph_variant(kf.LAYOUT_SLOT)
+        variants["one_layer_graph_fused_step_slot_layout"] = one_layer_variant(kf.LAYOUT_SLOT)
         for G in (2, 4, 8):
             if wl.H % G == 0:
                 variants["grouped_query_decode_G%d" % G] = gqa_variant(G)
