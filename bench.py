@@ -331,11 +331,12 @@ def main():
 
     def gqa_variant(G):
         """Decode call with G query heads per cached head (grouped-query attention): the workload's query
-        heads on H/G cached heads, same per-unit shape, the batch raised until at least 1024 cached heads
-        fill the chip (the workload's own batch would leave a launch of a few dozen units); K+V
+        heads on H/G cached heads, same per-unit shape, the batch raised to the largest with at most 1024
+        cached heads (the workload's own batch would leave a launch of a few dozen units; a few more than
+        the ~1024 workgroups the chip holds at once would time a nearly empty second round); K+V
         algorithmic bytes over the call's duration."""
         Hk = wl.H // G
-        B2 = max(wl.B, -(-1024 // (wl.L * Hk)))
+        B2 = max(wl.B, 1024 // (wl.L * Hk))
         c2 = kf.Cache.allocate(wl.L, B2, Hk, wl.d, wl.k + 1, dt, q_per_kv=G)
         c2.K.normal_()
         c2.V.normal_()
