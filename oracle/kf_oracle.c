@@ -44,7 +44,10 @@
  *   len    [U]           int32
  * layer0 is the model-wide index of the cache's first layer (it only enters
  * the noise key), so that a cache holding a subset of the layers draws the
- * same noise as the full one.
+ * same noise as the full one.  head0 is the same for heads: cached head hk of
+ * the cache is the model's cached head head0 + hk (noise key and slope index),
+ * so that one (layer, sequence, head) unit of a large model can be computed
+ * by itself.
  */
 #include <math.h>
 #include <stdint.h>
@@ -209,7 +212,7 @@ static void softmax_inplace(double *v, int m)
 /* ------------------------------------------------------------------ */
 int kfo_prefill_score(const void *Q, const void *K, float *score, int32_t *pos,
                       int32_t *len, int L, int B, int H, int d, int cap,
-                      int dtype, int layer0, int n, float tau, float scale, int noise,
+                      int dtype, int layer0, int head0, int n, float tau, float scale, int noise,
                       const uint64_t *seeds, const float *slopes, int shared, int G)
 {
     if (n < 1 || n > cap || !(tau > 0.0f) || G < 1) return -1;
@@ -232,7 +235,7 @@ int kfo_prefill_score(const void *Q, const void *K, float *score, int32_t *pos,
             kk[e] = load_elem(K, dtype, (size_t)u * cap * d + e);
         int failed = 0;
         for (int g = 0; g < G; ++g) {
-            int h = hk * G + g;                        /* the query head */
+            int h = (head0 + hk) * G + g;              /* the query head */
             double slope = slopes ? (double)slopes[h] : 0.0;
             for (size_t e = 0; e < (size_t)n * d; ++e)
                 q[e] = load_elem(Q, dtype, ((size_t)u * G + g) * n * d + e);
@@ -315,7 +318,7 @@ int kfo_prefill_score(const void *Q, const void *K, float *score, int32_t *pos,
 /* Optional debug outputs (may be NULL): dbg_p, dbg_df [U*G][cap] doubles. */
 /* ------------------------------------------------------------------ */
 int kfo_decode_step(void *K, void *V, float *score, int32_t *pos, int32_t *len,
-                    int L, int B, int H, int d, int cap, int dtype, int layer0,
+                    int L, int B, int H, int d, int cap, int dtype, int layer0, int head0,
                     const void *q, const void *k_new, const void *v_new,
                     int32_t q_pos, float tau, float scale, int noise,
                     const uint64_t *seeds, const float *slopes, int new_pos, int shared,
@@ -377,7 +380,7 @@ int kfo_decode_step(void *K, void *V, float *score, int32_t *pos, int32_t *len,
             continue;
         }
         for (int g = 0; g < G; ++g) {
-            int h = hk * G + g;                        /* the query head */
+            int h = (head0 + hk) * G + g;              /* the query head */
             size_t uq = (size_t)u * G + g;
             double slope = slopes ? (double)slopes[h] : 0.0;
             for (int j = 0; j < m; ++j) {

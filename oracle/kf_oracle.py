@@ -52,10 +52,10 @@ def lib():
         L.kfo_zeta.argtypes = [C.c_int, C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32]
         vp = C.c_void_p
         L.kfo_prefill_score.restype = C.c_int
-        L.kfo_prefill_score.argtypes = [vp, vp, vp, vp, vp] + [C.c_int] * 8 + [
+        L.kfo_prefill_score.argtypes = [vp, vp, vp, vp, vp] + [C.c_int] * 9 + [
             C.c_float, C.c_float, C.c_int, vp, vp, C.c_int, C.c_int]
         L.kfo_decode_step.restype = C.c_int
-        L.kfo_decode_step.argtypes = [vp, vp, vp, vp, vp] + [C.c_int] * 7 + [
+        L.kfo_decode_step.argtypes = [vp, vp, vp, vp, vp] + [C.c_int] * 8 + [
             vp, vp, vp, C.c_int32, C.c_float, C.c_float, C.c_int, vp, vp, C.c_int, C.c_int, C.c_int, vp, vp, vp, vp, vp]
         L.kfo_select_evict.restype = C.c_int
         L.kfo_select_evict.argtypes = [vp, vp, vp, vp, vp] + [C.c_int] * 8 + [vp]
@@ -96,9 +96,10 @@ def _dtype_code(a: np.ndarray) -> int:
 class OracleCache:
     """Per-unit KV caches + accumulated scores, on the host."""
 
-    def __init__(self, L, B, H, d, cap, dtype=F32, layer0=0):
+    def __init__(self, L, B, H, d, cap, dtype=F32, layer0=0, head0=0):
         self.L, self.B, self.H, self.d, self.cap, self.dtype = L, B, H, d, cap, dtype
-        self.layer0 = layer0
+        self.layer0 = layer0    # model-wide index of the first layer held (noise key)
+        self.head0 = head0      # ... and of the first cached head (noise key, and index into `slopes`)
         et = {F32: np.float32, BF16: np.uint16, F16: np.float16}[dtype]
         self.K = np.zeros((L, B, H, cap, d), et)
         self.V = np.zeros((L, B, H, cap, d), et)
@@ -109,7 +110,7 @@ class OracleCache:
     def copy(self):
         o = OracleCache.__new__(OracleCache)
         o.L, o.B, o.H, o.d, o.cap, o.dtype = self.L, self.B, self.H, self.d, self.cap, self.dtype
-        o.layer0 = self.layer0
+        o.layer0, o.head0 = self.layer0, self.head0
         for nm in ("K", "V", "score", "pos", "len"):
             setattr(o, nm, getattr(self, nm).copy())
         return o
@@ -135,7 +136,7 @@ class OracleCache:
             for b in range(self.B):
                 nb = int(n_seq[b])
                 assert 1 <= nb <= n
-                one = OracleCache(self.L, 1, self.H, self.d, self.cap, self.dtype, self.layer0)
+                one = OracleCache(self.L, 1, self.H, self.d, self.cap, self.dtype, self.layer0, self.head0)
                 for nm in ("K", "V", "score", "pos", "len"):
                     setattr(one, nm, np.ascontiguousarray(getattr(self, nm)[:, b:b + 1]))
                 one.prefill_score(np.ascontiguousarray(Q[:, b:b + 1, :, :nb]), nb, tau_, scale, noise,
@@ -147,7 +148,7 @@ class OracleCache:
         slopes = None if slopes is None else np.ascontiguousarray(slopes, np.float32)
         Q = np.ascontiguousarray(Q)
         rc = lib().kfo_prefill_score(_p(Q), _p(self.K), _p(self.score), _p(self.pos), _p(self.len),
-                                     *self._dims(), self.layer0, n, tau_, scale, noise, _p(seeds), _p(slopes),
+                                     *self._dims(), self.layer0, self.head0, n, tau_, scale, noise, _p(seeds), _p(slopes),
                                      int(shared), int(q_per_kv))
         if rc:
             raise ValueError("kfo_prefill_score rc=%d" % rc)
@@ -175,7 +176,7 @@ class OracleCache:
         dp = np.zeros(dshape, np.float64) if debug else None
         df = np.zeros(dshape, np.float64) if debug else None
         rc = lib().kfo_decode_step(_p(self.K), _p(self.V), _p(self.score), _p(self.pos), _p(self.len),
-                                   *self._dims(), self.layer0, _p(q), _p(k_new), _p(v_new), q_pos, tau_, scale,
+                                   *self._dims(), self.layer0, self.head0, _p(q), _p(k_new), _p(v_new), q_pos, tau_, scale,
                                    noise, _p(seeds), _p(slopes), int(new_pos), int(shared), int(q_per_kv), _p(q_pos_seq), _p(tau_seq),
                                    _p(out), _p(dp), _p(df))
         if rc:

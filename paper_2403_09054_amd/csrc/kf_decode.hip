@@ -822,6 +822,9 @@ __device__ __forceinline__ void decode_block(const DecodeArgs& a) {
     }
     if (S == 1) {
         // the whole unit is here: accumulate the normalised score increment of all its query heads
+        // The 8-wave workgroup has had no barrier since thread 0 published stat[]: a wave that found no V rows
+        // of its own (a launch shaped for many more tokens than the unit holds) would read it too early.
+        if constexpr (BIG && G >= 8) __syncthreads();
         float inv[G];
 #pragma unroll
         for (int g = 0; g < G; ++g) inv[g] = 1.0f / (G >= 8 ? stat[4 * g + 3] : spe[2 * g + 1]);  // many heads: not kept in registers across the V stream

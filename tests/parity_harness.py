@@ -2,10 +2,25 @@
 caches and the library's torch caches, compare with the tolerances the build
 target states, and run the lock-step protocol.
 
-Tolerances (from the build target): attention outputs and accumulated scores
+Tolerances.  The build target states: attention outputs and accumulated scores
 within 2e-3 relative (fp32 accumulation over bf16 K/V); retained index sets
 bit-exact except at tokens whose oracle score lies within 1e-5 relative of the
-(k-w)-th largest candidate score.
+(k-w)-th largest candidate score.  As tested here:
+
+* attention output: |got-ref| <= 2e-3*|ref| + 1e-5*max|ref| element by element, the
+  maximum taken over the unit's head dimension.  The second term is this
+  build's reading of "relative" for a vector whose components are signed sums
+  sum_j p_j V_j: a component can cancel to (almost) zero while the rounding error
+  of its fp32 accumulation stays proportional to the magnitudes that were added
+  up, i.e. to max|ref|, not to the component.  Every run also reports the worst
+  PURELY relative error over the components with |ref| >= 1e-2*max|ref| (which must
+  itself stay within 2e-3) and the fraction of components that needed the floor.
+* accumulated score: purely relative, element by element; the contract is 2e-3
+  but the tests hold the path to what it delivers, with headroom of about one
+  order of magnitude: 2e-5 after a decode step, 1e-4 after prompt scoring (a
+  column sum over up to 32768 rows).  Tests that leave these bounds for a stated
+  reason (temperatures far below 1) pass their own.
+* retained sets: as stated above, on the GPU's OWN scores.
 """
 from __future__ import annotations
 
@@ -16,7 +31,11 @@ import kf_workloads as kw
 import paper_2403_09054_amd as kf
 from oracle import kf_oracle as ko
 
-RTOL = 2e-3
+RTOL = 2e-3                 # the contract
+OUT_FLOOR = 1e-5            # absolute term of the output comparison, in units of the unit's max|ref|
+OUT_REL_FROM = 1e-2         # components at least this large (relative to max|ref|) are also held to RTOL purely relatively
+SCORE_RTOL_DECODE = 2e-5    # what the tests hold the scores to after a decode step ...
+SCORE_RTOL_PREFILL = 1e-4   # ... and after prompt scoring
 TIE_BAND = 1e-5
 
 
@@ -48,19 +67,37 @@ def host(t):
     return kw.to_oracle(t)
 
 
-def assert_close_out(got, ref, what="out"):
-    """|got-ref| <= 2e-3*|ref| + 1e-5*max|ref| per unit (last axis = head dim)."""
+def out_errors(got, ref):
+    """(normalised worst error, worst purely relative error over the large components, fraction of
+    components outside RTOL*|ref| that the absolute floor admitted)."""
     got = got.astype(np.float64)
     ref = ref.astype(np.float64)
-    atol = 1e-5 * np.abs(ref).max(axis=-1, keepdims=True) + 1e-30
-    bad = np.abs(got - ref) > RTOL * np.abs(ref) + atol
+    top = np.abs(ref).max(axis=-1, keepdims=True)
+    atol = OUT_FLOOR * top + 1e-30
+    err = np.abs(got - ref)
+    bad = err > RTOL * np.abs(ref) + atol
+    large = np.abs(ref) >= OUT_REL_FROM * top
+    rel = float((err[large] / np.abs(ref[large])).max()) if large.any() else 0.0
+    floor_frac = float((err > RTOL * np.abs(ref)).mean()) if err.size else 0.0
+    return bad, float((err / (np.abs(ref) + atol)).max()) if err.size else 0.0, rel, floor_frac
+
+
+def assert_close_out(got, ref, what="out", stats=None):
+    """|got-ref| <= 2e-3*|ref| + 1e-5*max|ref| per unit (last axis = head dim); components of at least
+    1e-2*max|ref| must also be within 2e-3 purely relatively."""
+    bad, worst, rel, floor_frac = out_errors(got, ref)
     assert not bad.any(), "%s: %d elements off, worst abs err %g" % (
-        what, bad.sum(), np.abs(got - ref).max())
-    return float((np.abs(got - ref) / (np.abs(ref) + atol)).max())
+        what, bad.sum(), np.abs(got.astype(np.float64) - ref.astype(np.float64)).max())
+    assert rel <= RTOL, "%s: worst purely relative error %g over the large components" % (what, rel)
+    if stats is not None:
+        stats["out_err"] = max(stats.get("out_err", 0.0), worst)
+        stats["out_rel"] = max(stats.get("out_rel", 0.0), rel)
+        stats["out_floor_frac"] = max(stats.get("out_floor_frac", 0.0), floor_frac)
+    return worst
 
 
-def assert_close_score(got, ref, lens, what="score"):
-    """Accumulated scores of the live slots, relative 2e-3 element by element."""
+def assert_close_score(got, ref, lens, what="score", rtol=SCORE_RTOL_DECODE):
+    """Accumulated scores of the live slots, purely relative, element by element."""
     worst = 0.0
     L, B, H = lens.shape
     for l in range(L):
@@ -70,8 +107,8 @@ def assert_close_score(got, ref, lens, what="score"):
                 g = got[l, b, h, :m].astype(np.float64)
                 r = ref[l, b, h, :m].astype(np.float64)
                 err = np.abs(g - r) / (np.abs(r) + 1e-30)
-                assert (err <= RTOL).all(), "%s unit (%d,%d,%d): worst rel err %g at slot %d" % (
-                    what, l, b, h, err.max(), int(err.argmax()))
+                assert (err <= rtol).all(), "%s unit (%d,%d,%d): worst rel err %g at slot %d (bound %g)" % (
+                    what, l, b, h, err.max(), int(err.argmax()), rtol)
                 worst = max(worst, float(err.max()) if m else 0.0)
     return worst
 
@@ -163,10 +200,22 @@ def error_word(ws) -> int:
     return int(ws[:4].view(torch.int32)[0].item())
 
 
+def pos_order(gc: kf.Cache):
+    """order[l,b,h,:m] = slot of the i-th live entry in position order (positions and lengths only)."""
+    pos, lens = host(gc.pos), host(gc.len)
+    order = np.zeros(pos.shape, np.int64)
+    for l, b, h in np.ndindex(*lens.shape):
+        m = int(lens[l, b, h])
+        order[l, b, h, :m] = np.argsort(pos[l, b, h, :m], kind="stable")
+    return order, lens
+
+
 class LockStep:
-    """Oracle and GPU advance together over a workload; before every call both
-    hold the same state (scores are re-uploaded from the oracle after each
-    decode step, everything after a tie-band event)."""
+    """Oracle and GPU advance together over a workload.  Within an iteration the GPU runs on its OWN
+    results: the scores its scoring call produced drive its selection, and the retained set is compared
+    with the oracle's (exact, or inside the tie band around the oracle's threshold score).  Only after
+    the selection are the GPU's scores overwritten with the oracle's (everything, after a tie-band event),
+    so that the next iteration starts from identical state and one borderline eviction cannot snowball."""
 
     def __init__(self, wl: kw.Workload, noise=ko.NOISE_GUMBEL, cap=None, layout=kf.LAYOUT_ORDERED,
                  shared=False, q_per_kv=1):
@@ -191,7 +240,7 @@ class LockStep:
         self.d_seeds, self.d_slopes = dev(self.seeds), dev(self.slopes)
         self.out = torch.zeros((wl.L, wl.B, wl.H, wl.d), dtype=torch.float32, device="cuda")
         self.kept = torch.zeros((wl.L, wl.B, wl.H // G, wl.k), dtype=torch.int32, device="cuda")
-        self.stats = dict(out_err=0.0, score_err=0.0, tie_events=0, steps=0)
+        self.stats = dict(out_err=0.0, out_rel=0.0, out_floor_frac=0.0, score_err=0.0, tie_events=0, steps=0)
 
     def prefill(self):
         wl = self.wl
@@ -205,18 +254,20 @@ class LockStep:
         lens = host(self.gc.len)
         np.testing.assert_array_equal(lens, self.oc.len)
         np.testing.assert_array_equal(host(self.gc.pos)[..., : wl.n], self.oc.pos[..., : wl.n])
-        e = assert_close_score(host(self.gc.score), self.oc.score, lens, "prefill score")
+        e = assert_close_score(host(self.gc.score), self.oc.score, lens, "prefill score", rtol=SCORE_RTOL_PREFILL)
         self.stats["prefill_err"] = e
-        self.gc.score.copy_(dev(self.oc.score))
-        self.select()
+        self.select(check_kv=True)
 
-    def select(self):
+    def select(self, check_kv=False):
+        """Both sides select on their own scores; the retained sets are compared (tie band on the oracle's
+        scores), then the GPU takes the oracle's scores (its whole state after a tie-band event) and the
+        live state is compared bit for bit."""
         wl = self.wl
         before_score, before_len = self.oc.score.copy(), self.oc.len.copy()
         kept_ref = self.oc.select_evict(wl.k, wl.w)
         slot = self.layout == kf.LAYOUT_SLOT and int(before_len.max()) <= wl.k + 1
         if slot:
-            order_before = sort_by_pos(self.gc)[5]
+            order_before = pos_order(self.gc)[0]
         kf.kf_select_evict(self.gc, wl.k, wl.w, self.kept, self.ws,
                            layout=kf.LAYOUT_SLOT if slot else kf.LAYOUT_ORDERED)
         torch.cuda.synchronize()
@@ -236,8 +287,32 @@ class LockStep:
             kept_g = host(self.kept)
         ev = compare_kept(kept_g, kept_ref, before_score, before_len, wl.k, wl.w)
         self.stats["tie_events"] += ev
+        unordered = self.layout == kf.LAYOUT_SLOT
         if ev:
             upload_into(self.gc, self.oc)       # adopt the oracle's choice and go on
+        else:
+            # same survivors: the GPU's compacted scores are its own, still within tolerance of the oracle's
+            lens = host(self.gc.len)
+            np.testing.assert_array_equal(lens, self.oc.len)
+            if unordered:
+                order, _ = pos_order(self.gc)
+                g_score = host(self.gc.score).copy()
+                new_score = g_score.copy()
+                for l, b, h in np.ndindex(*lens.shape):
+                    m = int(lens[l, b, h])
+                    o = order[l, b, h, :m]
+                    g_score[l, b, h, :m] = g_score[l, b, h, o]
+                    new_score[l, b, h, o] = self.oc.score[l, b, h, :m]     # oracle scores, scattered to the GPU's slots
+                assert_close_score(g_score, self.oc.score, lens, "score after selection", rtol=SCORE_RTOL_PREFILL)
+                self.gc.score.copy_(dev(new_score))
+            else:
+                assert_close_score(host(self.gc.score), self.oc.score, lens, "score after selection",
+                                   rtol=SCORE_RTOL_PREFILL)
+                self.gc.score.copy_(dev(self.oc.score))
+        if unordered:
+            assert_set_equal(self.gc, self.oc, kv=check_kv)
+        else:
+            assert_state_equal(self.gc, self.oc, kv=check_kv)
         return ev
 
     def step(self, t, check_kv=False):
@@ -257,31 +332,22 @@ class LockStep:
         assert error_word(self.ws) == 0
         lens = host(self.gc.len)
         np.testing.assert_array_equal(lens, self.oc.len)
+        g_all = host(self.gc.score)
         if self.shared:                 # one function: every layer holds the same copy, bit for bit
-            g = host(self.gc.score)
             for l in range(1, wl.L):
                 for b, h in np.ndindex(wl.B, wl.H // self.G):
-                    np.testing.assert_array_equal(g[l, b, h, : lens[l, b, h]], g[0, b, h, : lens[0, b, h]])
-        self.stats["out_err"] = max(self.stats["out_err"], assert_close_out(host(self.out), out_ref))
+                    np.testing.assert_array_equal(g_all[l, b, h, : lens[l, b, h]], g_all[0, b, h, : lens[0, b, h]])
+        assert_close_out(host(self.out), out_ref, stats=self.stats)
         if self.layout == kf.LAYOUT_SLOT:
-            _, _, g_score, g_pos, _, order = sort_by_pos(self.gc)
-            for l, b, h in np.ndindex(*lens.shape):
-                np.testing.assert_array_equal(g_pos[l, b, h, : lens[l, b, h]], self.oc.pos[l, b, h, : lens[l, b, h]])
-            self.stats["score_err"] = max(self.stats["score_err"], assert_close_score(g_score, self.oc.score, lens))
-            new_score = host(self.gc.score).copy()       # oracle scores, scattered to the GPU's slots
+            order, _ = pos_order(self.gc)
+            g_pos, g_score = host(self.gc.pos), g_all.copy()
             for l, b, h in np.ndindex(*lens.shape):
                 m = int(lens[l, b, h])
-                new_score[l, b, h, order[l, b, h, :m]] = self.oc.score[l, b, h, :m]
-            self.gc.score.copy_(dev(new_score))
+                o = order[l, b, h, :m]
+                np.testing.assert_array_equal(g_pos[l, b, h, o], self.oc.pos[l, b, h, :m])
+                g_score[l, b, h, :m] = g_all[l, b, h, o]
+            self.stats["score_err"] = max(self.stats["score_err"], assert_close_score(g_score, self.oc.score, lens))
         else:
-            self.stats["score_err"] = max(self.stats["score_err"],
-                                          assert_close_score(host(self.gc.score), self.oc.score, lens))
-            self.gc.score.copy_(dev(self.oc.score))     # lock-step: same scores before selection
-        ev = self.select()
-        if self.layout == kf.LAYOUT_SLOT:
-            if ev:    # the oracle's (ordered) state was adopted: it is a valid unordered state as well
-                pass
-            assert_set_equal(self.gc, self.oc, kv=check_kv)
-        else:
-            assert_state_equal(self.gc, self.oc, kv=check_kv)
+            self.stats["score_err"] = max(self.stats["score_err"], assert_close_score(g_all, self.oc.score, lens))
+        self.select(check_kv=check_kv)      # on the GPU's own scores; resynchronised afterwards
         self.stats["steps"] += 1

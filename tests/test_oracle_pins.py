@@ -132,8 +132,52 @@ def test_noise_independence_across_positions_heads_seeds():
     other = np.array([[ko.noise_bits(20240308, 3, 5, qp, kp) for kp in range(300)]
                       for qp in range(1000, 1300)], dtype=np.uint64)
     assert abs(c(u, (other >> np.uint64(9)).astype(np.float64))) < lim   # neighbouring seed
+    # the layer enters the key: neighbouring layers (and layers far apart) draw unrelated streams at the
+    # same seed, head and positions -- per-layer scores (Sec. 4.4.1) rest on per-layer noise
+    for other_layer in (4, 2, 27):
+        other = np.array([[ko.noise_bits(20240309, other_layer, 5, qp, kp) for kp in range(300)]
+                          for qp in range(1000, 1300)], dtype=np.uint64)
+        assert abs(c(u, (other >> np.uint64(9)).astype(np.float64))) < lim, other_layer
+        assert (other != bits).mean() > 0.999, other_layer
+    # layer and head are separate coordinates: (layer 3, head 5) is not (layer 5, head 3)
+    other = np.array([[ko.noise_bits(20240309, 5, 3, qp, kp) for kp in range(300)]
+                      for qp in range(1000, 1300)], dtype=np.uint64)
+    assert abs(c(u, (other >> np.uint64(9)).astype(np.float64))) < lim
     # no duplicated streams: all 32-bit words of one row distinct from the next row's
     assert (bits[0] != bits[1]).mean() > 0.999
+
+
+def test_gaussian_adjustment_draws_two_unrelated_uniforms():
+    """Eq. 5 needs a normal variate, i.e. (Box-Muller) two independent uniforms per logit.  The second one
+    is the generator's word at the key position with its top bit flipped: it must be unrelated to the
+    first, and the variate must be the Box-Muller combination of exactly these two words."""
+    pc = paper_constants()
+    seed, layer, head = 424242, 2, 7
+    qps, kps = range(500, 700), range(0, 300)
+    b1 = np.array([[ko.noise_bits(seed, layer, head, qp, kp) for kp in kps] for qp in qps], dtype=np.uint64)
+    b2 = np.array([[ko.noise_bits(seed, layer, head, qp, kp ^ 0x80000000) for kp in kps] for qp in qps],
+                  dtype=np.uint64)
+    u1 = (2.0 * (b1 >> np.uint64(9)).astype(np.float64) + 1.0) / 2.0 ** 24
+    u2 = (2.0 * (b2 >> np.uint64(9)).astype(np.float64) + 1.0) / 2.0 ** 24
+    N = u1.size
+    lim = 4.5 / math.sqrt(N)
+    corr = lambda a, b: np.corrcoef(a.ravel(), b.ravel())[0, 1]
+    assert (b1 != b2).mean() > 0.999
+    assert abs(corr(u1, u2)) < lim                                  # linear
+    assert abs(corr(np.log(u1), np.cos(2 * np.pi * u2))) < lim      # radius against angle
+    assert abs(corr((u1 - 0.5) ** 2, (u2 - 0.5) ** 2)) < lim        # second order
+    # joint uniformity on an 8x8 grid (chi-square, 63 degrees of freedom)
+    cells = np.histogram2d(u1.ravel(), u2.ravel(), bins=8, range=[[0, 1], [0, 1]])[0]
+    chi2 = ((cells - N / 64.0) ** 2 / (N / 64.0)).sum()
+    assert chi2 < scipy.stats.chi2.ppf(0.9995, 63), chi2
+    # the variate itself, from these two words (textbook Box-Muller, mean and std as printed in Sec. 4.4.3)
+    g = np.array([[ko.zeta(ko.NOISE_GAUSSIAN, seed, layer, head, qp, kp) for kp in kps] for qp in qps])
+    want = pc["gumbel_mean"] + pc["gumbel_std"] * np.sqrt(-2.0 * np.log(u1)) * np.cos(2.0 * np.pi * u2)
+    np.testing.assert_allclose(g, want, rtol=0, atol=1e-9)
+    # and its radial and angular parts are independent: the squared distance from the mean is exponential
+    # whatever the sign of the variate
+    r2 = ((g - pc["gumbel_mean"]) / pc["gumbel_std"]) ** 2
+    assert abs(corr(r2, np.sign(g - pc["gumbel_mean"]))) < lim
 
 
 def test_noise_golden_file_matches_oracle():
@@ -692,6 +736,93 @@ def test_decode_shape_drops_the_single_minimum():
     drop = [30, int(np.argmin(before.score[0, 0, 1, :n - w])), 0, n - w - 1]
     for h in range(4):
         assert kept[0, 0, h].tolist() == [i for i in range(n) if i != drop[h]]
+
+
+def test_layer_and_head_offsets_reproduce_the_units_of_the_full_cache():
+    """A cache that holds one layer / one head of a model (layer0, head0) computes exactly what the full
+    cache computes for that unit: the offsets enter the noise key and the slope index, nothing else."""
+    rng = np.random.default_rng(61)
+    L, B, H, d, n, cap = 3, 2, 4, 16, 21, 24
+    full = make_cache(rng, L, B, H, d, cap, n, ko.BF16)
+    Q = rand_vec(rng, (L, B, H, n, d), ko.BF16)
+    q, kn, vn = (rand_vec(rng, (L, B, H, d), ko.BF16) for _ in range(3))
+    seeds = np.array([5, 6], np.uint64)
+    slopes = np.array([0.5, 0.25, 0.125, 0.0625], np.float32)
+    ref = full.copy()
+    ref.prefill_score(Q, n, 1.0, 0.25, ko.NOISE_GUMBEL, seeds, slopes)
+    ref_pre = ref.score.copy()
+    out_ref = ref.decode_step(q, kn, vn, n, 1.25, 0.25, ko.NOISE_GUMBEL, seeds, slopes)
+    for l, b, h in [(0, 0, 0), (1, 1, 2), (2, 0, 3)]:
+        one = ko.OracleCache(1, 1, 1, d, cap, ko.BF16, layer0=l, head0=h)
+        one.K[0, 0, 0], one.V[0, 0, 0] = full.K[l, b, h], full.V[l, b, h]
+        one.prefill_score(np.ascontiguousarray(Q[l:l + 1, b:b + 1, h:h + 1]), n, 1.0, 0.25, ko.NOISE_GUMBEL,
+                          seeds[b:b + 1], slopes)
+        np.testing.assert_array_equal(one.score[0, 0, 0], ref_pre[l, b, h])
+        o = one.decode_step(q[l:l + 1, b:b + 1, h:h + 1], kn[l:l + 1, b:b + 1, h:h + 1], vn[l:l + 1, b:b + 1, h:h + 1],
+                            n, 1.25, 0.25, ko.NOISE_GUMBEL, seeds[b:b + 1], slopes)
+        np.testing.assert_array_equal(o[0, 0, 0], out_ref[l, b, h])
+        np.testing.assert_array_equal(one.score[0, 0, 0], ref.score[l, b, h])
+    # the offsets matter: the same data under another head index draws other noise
+    other = ko.OracleCache(1, 1, 1, d, cap, ko.BF16, layer0=1, head0=1)
+    other.K[0, 0, 0], other.V[0, 0, 0] = full.K[1, 1, 2], full.V[1, 1, 2]
+    other.prefill_score(np.ascontiguousarray(Q[1:2, 1:2, 2:3]), n, 1.0, 0.25, ko.NOISE_GUMBEL, seeds[1:2], None)
+    assert (other.score[0, 0, 0, :n] != ref_pre[1, 1, 2, :n]).mean() > 0.9
+
+
+def test_hand_worked_window_plus_key_tokens_scenario():
+    """Fig. 2(d): a recent window of 2 plus 2 key tokens over three consecutive iterations.  The expected
+    retained positions and scores were worked out by hand (tests/golden/fig2d_scenario.txt): the two key
+    tokens persist while the window slides."""
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "fig2d_scenario.txt")) if l.strip() and not l.startswith("#")]
+    k, w, d = 4, 2, 4
+    c = ko.OracleCache(1, 1, 1, d, k + 1, ko.F32)
+    assert rows[0][0] == "start"
+    c.pos[0, 0, 0, :k] = [int(v) for v in rows[0][1:1 + k]]
+    c.score[0, 0, 0, :k] = [int(v) / 10.0 for v in rows[0][1 + k:1 + 2 * k]]
+    c.len[...] = k
+    zero = np.zeros((1, 1, 1, d), np.float32)
+    q = np.ones((1, 1, 1, d), np.float32)
+    for step, row in enumerate(rows[1:]):
+        new_pos = k + step
+        out = c.decode_step(q, zero, np.full((1, 1, 1, d), float(new_pos), np.float32), new_pos, 1.0 + 0.5 * step, 0.5,
+                            ko.NOISE_NONE)
+        assert int(c.len[0, 0, 0]) == k + 1
+        c.select_evict(k, w)
+        assert int(c.len[0, 0, 0]) == k
+        assert c.pos[0, 0, 0, :k].tolist() == [int(v) for v in row[1:1 + k]], row[0]
+        np.testing.assert_allclose(c.score[0, 0, 0, :k], [int(v) / 10.0 for v in row[1 + k:1 + 2 * k]], rtol=3e-7)
+        # equal logits: the attention output is the plain mean of the 5 cached value rows
+        np.testing.assert_allclose(out[0, 0, 0], np.full(d, int(row[1 + 2 * k]) / 10.0), rtol=3e-7)
+
+
+def test_gumbel_adjustment_spreads_the_expected_score():
+    """Eq. 9-10: the expectation (over the logit adjustment) of the normalised, Gumbel-adjusted logits is more
+    uniform than the plain softmax: H(E[z_Gumbel]) > H(E[z]).  Averaged here over 600 query positions, i.e.
+    600 independent draws of the adjustment on the same logits; the new token's key equals an old one, so
+    the logits do not depend on the query position."""
+    rng = np.random.default_rng(77)
+    H_, d, n = 2, 16, 24
+    base = make_cache(rng, 1, 1, H_, d, n + 1, n)
+    base.K[..., :n, :] *= 2.0                      # a peaked softmax
+    q = rng.standard_normal((1, 1, H_, d)).astype(np.float32)
+    kn, vn = base.K[..., 0, :].copy(), base.V[..., 0, :].copy()
+    seeds = np.array([31337], np.uint64)
+
+    def increments(noise, q_pos):
+        c = base.copy()
+        c.score[...] = 0.0
+        c.decode_step(q, kn, vn, q_pos, 1.0, 0.25, noise, seeds)
+        return c.score[0, 0, :, : n + 1].astype(np.float64)
+
+    entropy = lambda p: float(-(p * np.log(p)).sum())
+    plain = increments(ko.NOISE_NONE, 100)
+    mean_g = np.mean([increments(ko.NOISE_GUMBEL, 100 + t) for t in range(600)], axis=0)
+    for h in range(H_):
+        assert abs(mean_g[h].sum() - 1.0) < 1e-5
+        assert entropy(mean_g[h]) > entropy(plain[h]) + 0.05, (h, entropy(mean_g[h]), entropy(plain[h]))
+        # ... while the ranking by expected score still follows the logits (the adjustment regularises,
+        # it does not reorder): the top token stays on top
+        assert int(np.argmax(mean_g[h])) == int(np.argmax(plain[h]))
 
 
 def test_select_boundaries():
