@@ -83,6 +83,13 @@ CONFIGS = {
 }
 
 
+def staging_layers(wl: Workload, budget_bytes: float = 12e9) -> int:
+    """Layers of the prompt (Q, K and V of n tokens each) staged per prompt-scoring call: as many as fit
+    the byte budget, so that the n-token prompts of all layers never have to be resident at once."""
+    layer_bytes = 3 * wl.B * wl.H * wl.n * wl.d * wl.elem_bytes
+    return max(1, min(wl.L, int(budget_bytes // layer_bytes)))
+
+
 def alibi_slopes(wl: Workload):
     """Per-head slopes 2^(-8h/H), h = 1..H (first wl.H of them), or None."""
     if not wl.alibi:

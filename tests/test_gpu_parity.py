@@ -400,21 +400,32 @@ def test_tiny_config_full_lockstep_and_free_running():
 
 
 SLICES = {
-    # name: (slice kwargs, decode steps checked)
-    "gptj": (dict(L=2, H=16, T=512), 512),           # the whole generation: tau runs from tau_init to tau_end
-    "mpt": (dict(L=1, B=2, H=8, T=1024), 256),
-    "batched": (dict(L=1, B=4, H=8, T=1024), 256),
+    # name: (slice kwargs, decode steps checked from t = 1, steps checked at the end of the schedule)
+    "gptj": (dict(L=2, H=16, T=512), 512, 0),        # the whole generation: tau runs from tau_init to tau_end
+    "mpt": (dict(L=1, B=2, H=8, T=1024), 256, 8),
+    "batched": (dict(L=1, B=4, H=8, T=1024), 256, 8),
 }
+
+
+def late_steps(ls, late):
+    """The last `late` iterations of the schedule (t = T-late+1 .. T, tau -> tau_end of Eq. 12) on the state
+    the slice has reached: the generation in between is skipped, the query position jumps with t."""
+    wl = ls.wl
+    for t in range(wl.T - late + 1, wl.T + 1):
+        ls.step(t, check_kv=(t == wl.T))
+    assert kf.kf_tau(wl.T, wl.T, wl.tau_init, wl.tau_end) == wl.tau_end
 
 
 @pytest.mark.parametrize("name", list(SLICES))
 def test_config_slice_lockstep(name):
-    kwargs, steps = SLICES[name]
+    kwargs, steps, late = SLICES[name]
     wl = kw.CONFIGS[name].slice(**kwargs)
     ls = LockStep(wl)
     ls.prefill()
     for t in range(1, steps + 1):
         ls.step(t, check_kv=(t == steps))
+    late_steps(ls, late)
+    assert ls.stats["steps"] == steps + late
     print(name, "slice lockstep", ls.stats)
 
 
@@ -425,7 +436,41 @@ def test_long_config_slice_lockstep():
     ls.prefill()
     for t in range(1, 129):
         ls.step(t, check_kv=(t == 128))
+    late_steps(ls, 8)
     print("long slice lockstep", ls.stats)
+
+
+def test_mpt_slice_free_running_with_position_bias():
+    """No resynchronisation at all on an MPT-shaped slice (ALiBi, k = 2048): prompt scoring, first eviction and
+    96 generation steps, each side following its own scores.  While the retained sets agree the GPU's
+    self-accumulated scores are compared element by element; the step of the first difference, if any, is
+    printed (a near-tie at the threshold may send the two apart for good)."""
+    wl = kw.CONFIGS["mpt"].slice(L=1, B=2, H=4, T=1024)
+    fr = LockStep(wl)
+    fr.oc.prefill_score(fr.Q, wl.n, ko.tau(0, wl.T), wl.scale, fr.noise, fr.seeds, fr.slopes)
+    kf.kf_prefill_score(fr.gc, dev(fr.Q), wl.n, kf.kf_tau(0, wl.T), wl.scale, fr.noise, fr.d_seeds, fr.d_slopes, fr.ws)
+    fr.oc.select_evict(wl.k, wl.w)
+    kf.kf_select_evict(fr.gc, wl.k, wl.w, None, fr.ws)
+    torch.cuda.synchronize()
+    first_div, steps, worst = None, 96, 0.0
+    for t in range(1, steps + 1):
+        q, kn, vn = kw.decode_inputs(wl, t)
+        out_ref = fr.oc.decode_step(kw.to_oracle(q), kw.to_oracle(kn), kw.to_oracle(vn), wl.n + t - 1, ko.tau(t, wl.T),
+                                    wl.scale, fr.noise, fr.seeds, fr.slopes)
+        kf.kf_decode_select_step(fr.gc, q.cuda(), kn.cuda(), vn.cuda(), wl.n + t - 1, wl.k + 1, kf.kf_tau(t, wl.T), wl.scale,
+                                 fr.noise, fr.d_seeds, fr.d_slopes, fr.out, k=wl.k, w=wl.w, workspace=fr.ws)
+        fr.oc.select_evict(wl.k, wl.w)
+        torch.cuda.synchronize()
+        assert error_word(fr.ws) == 0
+        if first_div is None:
+            if (host(fr.gc.pos)[..., : wl.k] == fr.oc.pos[..., : wl.k]).all():
+                assert_close_out(host(fr.out), out_ref, "free-running out step %d" % t)
+                worst = max(worst, assert_close_score(host(fr.gc.score), fr.oc.score, fr.oc.len,
+                                                      "free-running score step %d" % t, rtol=SCORE_RTOL_PREFILL))
+            else:
+                first_div = t
+    print("mpt slice free-running: first divergence step:", first_div, "of", steps, "; worst score error", worst)
+    assert first_div is None or first_div > 16
 
 
 def test_gptj_full_size_in_bench_launch_shape_sampled_layers():
@@ -509,6 +554,67 @@ def test_gptj_full_size_in_bench_launch_shape_sampled_layers():
                            len=cache.len[l:l + 1], L=1, B=wl.B, H=wl.H, d=wl.d, cap=wl.k + 1, dtype=kf.BF16)
             assert_state_equal(sub, dec[l], kv=(t == steps))
     assert int(cache.len.min()) == wl.k and int(cache.len.max()) == wl.k
+
+
+@pytest.mark.parametrize("name", ["mpt", "long", "batched"])
+def test_full_size_prompt_phase_in_bench_staging_shape_sampled_units(name):
+    """Prompt scoring and the first eviction of the large configurations in the launch shapes bench.py
+    stages them in (as many layers per call as kf_workloads.staging_layers allows, every sequence and head),
+    for the first group of layers and for the last, smaller one.  Inputs are generated on the device; the
+    oracle recomputes three single units per call -- first, middle, last -- from the rows copied back."""
+    wl = kw.CONFIGS[name]
+    Ls = kw.staging_layers(wl)
+    assert Ls == {"mpt": 14, "long": 14, "batched": 3}[name]
+    stage = kf.Cache.allocate(Ls, wl.B, wl.H, wl.d, wl.n, kf.BF16)
+    Qs = torch.empty((Ls, wl.B, wl.H, wl.n, wl.d), dtype=torch.bfloat16, device="cuda")
+    ws = kf.new_workspace(stage, wl.n)
+    seeds, slopes = kw.noise_seeds(wl), kw.alibi_slopes(wl)
+    d_seeds, d_slopes = dev(seeds), dev(slopes)
+    tau0 = kf.kf_tau(0, wl.T, wl.tau_init, wl.tau_end)
+    groups = [0] + ([wl.L // Ls * Ls] if wl.L % Ls else [])
+    ties = 0
+    for l0 in groups:
+        nl = min(Ls, wl.L - l0)
+        for i in range(nl):
+            Q, K, V = kw.prompt_layer(wl, l0 + i, device="cuda")
+            Qs[i].copy_(Q)
+            stage.K[i].copy_(K)
+            stage.V[i].copy_(V)
+            del Q, K, V
+        sub = stage if nl == Ls else kf.Cache(K=stage.K[:nl], V=stage.V[:nl], score=stage.score[:nl], pos=stage.pos[:nl],
+                                              len=stage.len[:nl], L=nl, B=wl.B, H=wl.H, d=wl.d, cap=wl.n, dtype=kf.BF16)
+        sub.layer0 = l0
+        sub.score.fill_(-1.0)
+        sub.len.fill_(0)
+        gen = kf.Cache.allocate(nl, wl.B, wl.H, wl.d, wl.k + 1, kf.BF16)
+        kept = torch.full((nl, wl.B, wl.H, wl.k), -7, dtype=torch.int32, device="cuda")
+        kf.kf_prefill_score(sub, Qs[:nl], wl.n, tau0, wl.scale, kf.NOISE_GUMBEL, d_seeds, d_slopes, ws)
+        kf.kf_select_evict_into(sub, gen, 0, wl.k, wl.w, kept, ws)
+        torch.cuda.synchronize()
+        assert error_word(ws) == 0
+        assert int(sub.len.min()) == wl.n and int(sub.len.max()) == wl.n
+        assert int(gen.len.min()) == wl.k and int(gen.len.max()) == wl.k
+        assert bool((sub.score[..., : wl.n] > 0).all())          # every unit of the launch was scored
+        for l, b, h in [(0, 0, 0), (nl // 2, wl.B // 2, wl.H // 2), (nl - 1, wl.B - 1, wl.H - 1)]:
+            oc = ko.OracleCache(1, 1, 1, wl.d, wl.n, ko.BF16, layer0=l0 + l, head0=h)
+            oc.K[0, 0, 0], oc.V[0, 0, 0] = host(stage.K[l, b, h]), host(stage.V[l, b, h])
+            oc.prefill_score(host(Qs[l, b, h])[None, None, None], wl.n, ko.tau(0, wl.T, wl.tau_init, wl.tau_end), wl.scale,
+                             ko.NOISE_GUMBEL, seeds[b:b + 1], slopes)
+            what = "%s layers %d+%d unit (%d,%d,%d)" % (name, l0, nl, l, b, h)
+            np.testing.assert_array_equal(host(sub.pos[l, b, h]), oc.pos[0, 0, 0])
+            assert_close_score(host(sub.score[l, b, h])[None, None, None], oc.score, oc.len, what, rtol=SCORE_RTOL_PREFILL)
+            before = (oc.score.copy(), oc.len.copy())
+            kept_ref = oc.select_evict(wl.k, wl.w)
+            ev = compare_kept(host(kept[l, b, h])[None, None, None], kept_ref, before[0], before[1], wl.k, wl.w)
+            ties += ev
+            if not ev:                                   # same survivors: rows gathered bit for bit
+                np.testing.assert_array_equal(host(gen.pos[l, b, h, : wl.k]), oc.pos[0, 0, 0, : wl.k])
+                np.testing.assert_array_equal(host(gen.K[l, b, h, : wl.k]), oc.K[0, 0, 0, : wl.k])
+                np.testing.assert_array_equal(host(gen.V[l, b, h, : wl.k]), oc.V[0, 0, 0, : wl.k])
+                assert_close_score(host(gen.score[l, b, h])[None, None, None], oc.score, oc.len, what + " after eviction",
+                                   rtol=SCORE_RTOL_PREFILL)
+        del gen, kept
+    print(name, "full-size prompt phase: tie-band events", ties)
 
 
 @pytest.mark.parametrize("name", ["mpt", "long", "batched"])
@@ -1171,6 +1277,41 @@ def test_grouped_query_one_eight_wave_workgroup_per_unit(dtype, d, G, noise, new
     g_score = host(gc.score)
     g_score[1, 7, 15] = oc.score[1, 7, 15]
     assert_close_score(g_score, oc.score, oc.len)
+
+
+@pytest.mark.parametrize("d,layout", [(128, kf.LAYOUT_ORDERED), (64, kf.LAYOUT_SLOT)])
+def test_eight_wave_workgroup_on_units_of_a_few_tokens(d, layout):
+    """8 query heads, a launch shaped for a 2048-token budget (one 8-wave workgroup per unit) on units that
+    hold a few tokens only, as early in a generation or with a ragged batch: most waves of a workgroup find
+    no rows of their own and must still wait for the softmax sums before they normalise the increments."""
+    rng = np.random.default_rng(8800 + d)
+    L, B, H, G, cap = 2, 8, 16, 8, 2049
+    c0 = kf.Cache(K=0x10000, V=0x20000, score=0x30000, pos=0x40000, len=0x50000, L=L, B=B, H=H, d=d, cap=cap,
+                  dtype=ko.BF16, q_per_kv=G)
+    S, chunk = kf.kf_decode_launch_shape(c0, cap)
+    assert S == 1 and chunk >= cap - 1
+    lens = rng.integers(0, 40, (L, B, H)).astype(np.int32)
+    lens[0, 0, :4] = [0, 1, 15, 17]
+    oc = random_cache(rng, L, B, H, d, cap, ko.BF16, lens)
+    oc.pos[...] = np.arange(cap, dtype=np.int32) + 100          # consecutive: what the slot layout's window test expects
+    gc = upload(oc, G)
+    ws = kf.new_workspace(gc)
+    seeds = (np.arange(B) * 5 + 3).astype(np.uint64)
+    out = torch.zeros((L, B, H * G, d), dtype=torch.float32, device="cuda")
+    scale = float(1.0 / np.sqrt(np.float32(d)))
+    for t in range(3):
+        q = rnd(rng, (L, B, H * G, d), ko.BF16)
+        kn, vn = (rnd(rng, (L, B, H, d), ko.BF16) for _ in range(2))
+        q_pos = 100 + cap + t
+        kf.kf_decode_select_step(gc, dev(q), dev(kn), dev(vn), q_pos, cap, 1.25, scale, kf.NOISE_GUMBEL, dev(seeds), None,
+                                 out, k=cap - 1, w=16, layout=layout, workspace=ws)
+        torch.cuda.synchronize()
+        assert error_word(ws) == 0
+        out_ref = oc.decode_step(q, kn, vn, q_pos, 1.25, scale, ko.NOISE_GUMBEL, seeds, None, q_per_kv=G)
+        assert_close_out(host(out), out_ref, "step %d" % t)
+        np.testing.assert_array_equal(host(gc.len), oc.len)        # far under budget: nothing is evicted
+        assert_close_score(host(gc.score), oc.score, oc.len, "step %d" % t)
+        np.testing.assert_array_equal(host(gc.pos)[..., :40], oc.pos[..., :40])
 
 
 @pytest.mark.parametrize("d,G,cap", [(64, 1, 10501), (128, 2, 5401)])
