@@ -289,6 +289,34 @@ kf_status kf_decode_select_step_at(kf_cache *c, const void *q, const void *k_new
                                    const kf_score_cfg *cfg, float *out, int32_t k, int32_t w, int32_t layout,
                                    int32_t *kept_idx, void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * kf_decode_select_step for callers that cannot allocate device memory and have
+ * no workspace to hand over: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same step, same kernels, same results as
+ * kf_decode_select_step; the scratch the kernels need (split-wise partial
+ * results, score increments, survivor lists, counters) lives in a buffer of
+ * KF_NOALLOC_SCRATCH_BYTES built into the library's device code, one per GPU,
+ * held from the library's load until the process ends.  The call allocates and
+ * frees nothing, and clears the buffer's counters itself by a kernel (no memset
+ * node), so it can be captured.
+ *  - `skipped`, DEVICE [1] or NULL, plays the workspace error word: it is
+ *    incremented by one for every unit the kernels had to skip.  The caller
+ *    zeroes it; with NULL the count is dropped.
+ *  - Every call on a GPU uses that GPU's one buffer: calls on the same GPU
+ *    must not overlap (order them on one stream, or by events); overlapping
+ *    calls race.
+ *  - The first call on a device looks up the buffer's device address
+ *    (hipGetSymbolAddress); make that call outside a stream capture.
+ * Errors: as kf_decode_select_step; KF_EWORKSPACE if the cache's shape needs
+ * more than KF_NOALLOC_SCRATCH_BYTES of scratch (kf_workspace_bytes(c, 0) tells);
+ * KF_EDEVICE if the buffer's address cannot be resolved.
+ */
+#define KF_NOALLOC_SCRATCH_BYTES (32u << 20)
+kf_status kf_decode_select_step_noalloc(kf_cache *c, const void *q, const void *k_new, const void *v_new,
+                                        int32_t q_pos, int32_t m_hint, const kf_score_cfg *cfg, float *out,
+                                        int32_t k, int32_t w, int32_t layout, int32_t *kept_idx,
+                                        int32_t *skipped, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

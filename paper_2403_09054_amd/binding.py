@@ -23,7 +23,8 @@ KF_OK, KF_EINVAL, KF_EUNSUPPORTED, KF_EWORKSPACE, KF_EDEVICE = 0, -1, -2, -3, -4
 # every symbol include/keyformer.h declares
 SYMBOLS = ("kf_version", "kf_last_error", "kf_tau", "kf_noise_bits", "kf_workspace_bytes",
            "kf_prefill_score", "kf_decode_step", "kf_select_evict", "kf_select_evict_into", "kf_decode_select_step",
-           "kf_decode_launch_shape", "kf_decode_select_step_at", "kf_beam_fork")
+           "kf_decode_launch_shape", "kf_decode_select_step_at", "kf_beam_fork", "kf_decode_select_step_noalloc")
+NOALLOC_SCRATCH_BYTES = 32 << 20
 
 
 class KeyformerError(RuntimeError):
@@ -101,6 +102,10 @@ def lib():
         L.kf_decode_select_step_at.argtypes = [C.POINTER(kf_cache), vp, vp, vp, C.POINTER(kf_schedule), vp, C.c_int32,
                                                C.POINTER(kf_score_cfg), vp, C.c_int32, C.c_int32, C.c_int32, vp, vp,
                                                C.c_size_t, vp]
+        L.kf_decode_select_step_noalloc.restype = C.c_int
+        L.kf_decode_select_step_noalloc.argtypes = [C.POINTER(kf_cache), vp, vp, vp, C.c_int32, C.c_int32,
+                                                    C.POINTER(kf_score_cfg), vp, C.c_int32, C.c_int32, C.c_int32, vp,
+                                                    vp, vp]
         _lib = L
     return _lib
 
@@ -275,3 +280,16 @@ def kf_decode_select_step_at(cache: Cache, q, k_new, v_new, n: int, T: int, tau_
     _check(lib().kf_decode_select_step_at(C.byref(cs), _ptr(q), _ptr(k_new), _ptr(v_new), C.byref(sched),
                                           _ptr(step), m_hint, C.byref(cfg), _ptr(out), k, w, layout,
                                           _ptr(kept_idx), wp, wb, _stream(stream)))
+
+
+def kf_decode_select_step_noalloc(cache: Cache, q, k_new, v_new, q_pos: int, m_hint: int, tau: float, scale: float,
+                                  noise: int = NOISE_GUMBEL, seeds=None, slopes=None, out=None, k: int = 0, w: int = 0,
+                                  layout: int = LAYOUT_ORDERED, kept_idx=None, skipped=None, stream=None,
+                                  pos_mode: int = POS_ORIGINAL, score_mode: int = SCORE_PER_LAYER,
+                                  seq_q_pos=None, seq_tau=None) -> None:
+    """kf_decode_select_step on the library's built-in scratch (no workspace argument).  `skipped`: int32
+    device tensor of one element that counts skipped units, or None."""
+    cs, cfg = cache.c_struct(), _cfg(tau, scale, noise, seeds, slopes, pos_mode, score_mode, seq_q_pos, seq_tau)
+    _check(lib().kf_decode_select_step_noalloc(C.byref(cs), _ptr(q), _ptr(k_new), _ptr(v_new), q_pos, m_hint,
+                                               C.byref(cfg), _ptr(out), k, w, layout, _ptr(kept_idx),
+                                               _ptr(skipped), _stream(stream)))

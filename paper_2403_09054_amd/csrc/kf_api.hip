@@ -5,8 +5,16 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "kf_device.h"
 #include "kf_internal.h"
+
+// Built-in scratch of the allocation-free entry point (kf_decode_select_step_noalloc): one array per GPU
+// the library runs on, held until the process ends.  In host code the name is only a handle: it is never
+// passed to a kernel or a copy; the runtime is asked once per device for the array's device address
+// (scratch_of_current_device below) and that address is used from then on.
+static __device__ __align__(256) unsigned char scratch[KF_NOALLOC_SCRATCH_BYTES];
 
 namespace {
 
@@ -133,6 +141,33 @@ kf_status check_ws(const void* ws, size_t have, size_t need) {
     if (have < need) return fail(KF_EWORKSPACE, "workspace has %zu bytes, %zu needed", have, need);
     return KF_OK;
 }
+
+// ---- built-in scratch of the allocation-free entry point (kf_decode_select_step_noalloc) ----
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices];  // device address of `scratch` on each device, once resolved
+std::mutex g_scratch_mutex;
+
+// Device address of the current device's copy of `scratch`.
+kf_status scratch_of_current_device(void** ptr) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(KF_EDEVICE, "hipGetDevice: %s", hipGetErrorString(e));
+    if (dev < 0 || dev >= kMaxDevices) return fail(KF_EDEVICE, "device index %d outside [0, %d)", dev, kMaxDevices);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p)
+            return fail(KF_EDEVICE, "address of the built-in scratch on device %d: %s", dev, hipGetErrorString(e));
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return KF_OK;
+}
+
+// The words of a workspace that must start a call as zero (error word, ticket word): a fill kernel, not a
+// memset node, so that the call can be captured in a HIP graph.
+__global__ void clear_header_kernel(int32_t* head) { head[threadIdx.x] = 0; }
 
 }  // namespace
 
@@ -483,10 +518,13 @@ kf_status kf_select_evict_into(const kf_cache* src, kf_cache* dst, int32_t dst_l
 }
 
 // One generation step in one call.  With a schedule, the step number comes from device memory.
+// `skipped`, if not NULL, takes the place of the workspace's error word; `clear_header` zeroes the
+// workspace's first words by a kernel ahead of the step (a workspace whose contents are unknown).
 static kf_status fused_step(kf_cache* c, const void* q, const void* k_new, const void* v_new, int32_t q_pos,
                             const kf_schedule* sched, int32_t* step, int32_t m_hint, const kf_score_cfg* cfg,
                             float* out, int32_t k, int32_t w, int32_t layout, int32_t* kept_idx, void* workspace,
-                            size_t workspace_bytes, void* stream) {
+                            size_t workspace_bytes, void* stream, int32_t* skipped = nullptr,
+                            bool clear_header = false) {
     kf::DecodeArgs da;
     kf::DecodePlan p;
     kf_status st = prepare_decode(c, q, k_new, v_new, q_pos, m_hint, cfg, out, workspace, workspace_bytes, &da, &p);
@@ -494,6 +532,12 @@ static kf_status fused_step(kf_cache* c, const void* q, const void* k_new, const
     kf::SelectArgs sa;
     st = prepare_select(c, k, w, layout, kept_idx, workspace, workspace_bytes, true, &sa);
     if (st != KF_OK) return st;
+    if (skipped) da.ws_err = sa.ws_err = skipped;
+    if (clear_header) {
+        hipLaunchKernelGGL(clear_header_kernel, dim3(1), dim3(64), 0, (hipStream_t)stream, (int32_t*)workspace);
+        const hipError_t e0 = hipGetLastError();
+        if (e0 != hipSuccess) return fail(KF_EDEVICE, "step launch: %s", hipGetErrorString(e0));
+    }
     if (sched) {
         da.step = step;
         da.n0 = sched->n;
@@ -557,6 +601,24 @@ kf_status kf_decode_select_step(kf_cache* c, const void* q, const void* k_new, c
                                 void* stream) {
     return fused_step(c, q, k_new, v_new, q_pos, nullptr, nullptr, m_hint, cfg, out, k, w, layout, kept_idx,
                       workspace, workspace_bytes, stream);
+}
+
+kf_status kf_decode_select_step_noalloc(kf_cache* c, const void* q, const void* k_new, const void* v_new,
+                                        int32_t q_pos, int32_t m_hint, const kf_score_cfg* cfg, float* out, int32_t k,
+                                        int32_t w, int32_t layout, int32_t* kept_idx, int32_t* skipped, void* stream) {
+    kf_status st = check_cache(c);
+    if (st != KF_OK) return st;
+    const size_t need = ws_layout(c, 0).total;
+    if (need > (size_t)KF_NOALLOC_SCRATCH_BYTES)
+        return fail(KF_EWORKSPACE,
+                    "a step on this cache needs %zu bytes of scratch, the built-in buffer holds %zu: use "
+                    "kf_decode_select_step with a workspace of the caller's",
+                    need, (size_t)KF_NOALLOC_SCRATCH_BYTES);
+    void* ptr = nullptr;
+    st = scratch_of_current_device(&ptr);
+    if (st != KF_OK) return st;
+    return fused_step(c, q, k_new, v_new, q_pos, nullptr, nullptr, m_hint, cfg, out, k, w, layout, kept_idx, ptr,
+                      (size_t)KF_NOALLOC_SCRATCH_BYTES, stream, skipped, true);
 }
 
 kf_status kf_decode_select_step_at(kf_cache* c, const void* q, const void* k_new, const void* v_new,

@@ -247,3 +247,15 @@ def test_bench_refuses_more_than_one_gpu():
     r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
                        timeout=120)
     assert r.returncode != 0 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_built_in_scratch_rejects_shapes_it_cannot_hold():
+    # the allocation-free step refuses, on the host and before any device call, a cache whose scratch
+    # does not fit the buffer built into the library
+    big = fake_cache(L=32, B=8, H=32, cap=2049)
+    assert kf.kf_workspace_bytes(big) > kf.NOALLOC_SCRATCH_BYTES
+    with pytest.raises(kf.KeyformerError) as e:
+        kf.kf_decode_select_step_noalloc(big, 0x1000, 0x2000, 0x3000, 5000, 0, 1.5, 0.09, kf.NOISE_NONE, None, None,
+                                         0x4000, k=2048, w=410)
+    assert e.value.status == binding.KF_EWORKSPACE and "built-in" in str(e.value)
+    assert kf.kf_workspace_bytes(fake_cache()) <= kf.NOALLOC_SCRATCH_BYTES
