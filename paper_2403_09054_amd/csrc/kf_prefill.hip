@@ -16,7 +16,15 @@
 //           key and sees 16 of the tile's 32 queries: z_ij = 2^(y2_ij - c_i) is
 //           added into the lane's column sum.
 // Per logit the work is one 32-bit hash, two logarithms and one exponential;
-// that, not the MFMA rate, bounds the kernel.
+// that, not the MFMA rate, bounds the kernel, so the per-logit instruction count
+// is what is trimmed.  With the Gumbel adjustment (the method; the other
+// adjustments keep the plain form): pass 1 sums every term against a reference
+// exponent instead of searching each tile's maximum first -- the reference
+// starts at the row's own diagonal term (so the sum cannot vanish), follows the
+// sum's exponent upwards tile by tile, and a tile whose sum overflows is summed
+// again against a higher reference; pass 1 leaves the row normaliser already
+// combined with the adjustment's constant part; kernels built for "no position
+// bias" drop that term.
 #include "kf_device.h"
 #include "kf_internal.h"
 
@@ -137,7 +145,40 @@ struct TileStage {
 };
 
 // ------------------------------------------------------------------ pass 1
-template <typename T, int D>
+// <q, k> over the elements of the 16-byte pieces a and b
+template <typename T>
+__device__ __forceinline__ float dot_piece(const uint4& x, const uint4& y) {
+    constexpr int EPV = ElemTraits<T>::kPerVec;
+    float xf[EPV], yf[EPV];
+    unpack16<T>(x, xf);
+    unpack16<T>(y, yf);
+    float d = 0.0f;
+#pragma unroll
+    for (int e = 0; e < EPV; ++e) d = fmaf(xf[e], yf[e], d);
+    return d;
+}
+
+// Sum over this lane's 16 logits of a tile of 2^(y2 - reference), Gumbel adjustment; `base` is the
+// adjustment's constant part less the reference (and the position bias of the lane's first key).  MASK: keep only the keys up to `room` places behind the
+// lane's first one (the tile crosses the diagonal).
+template <bool BIAS, bool MASK>
+__device__ __forceinline__ float tile_sum(const LogitParams& lp, const f32x16& acc, float base, uint32_t rkey,
+                                          uint32_t kmul, int room) {
+    float ssum = 0.0f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int ro = (r >> 2) * 8 + (r & 3);
+        const float l2t = hw_log2(neg_log2_uniform(mix32(rkey ^ (kmul + (uint32_t)ro * kKposMul))));
+        // position bias -slope*(dist0 - ro): its dist0 part rides in `base`, the ro part is a literal multiple
+        const float t = fmaf(l2t, -lp.inv_tau, BIAS ? fmaf(lp.slope1, (float)ro, base) : base);
+        const float e = hw_exp2(fmaf(acc[r], lp.sc1, t));
+        ssum += (!MASK || ro <= room) ? e : 0.0f;
+    }
+    return ssum;
+}
+
+// GUMBEL: the method's adjustment, trimmed form; otherwise any adjustment, plain form.  BIAS: slopes given.
+template <typename T, int D, bool GUMBEL, bool BIAS>
 __global__ void __launch_bounds__(kPrefillThreads) prefill_rowstats_kernel(const PrefillArgs a, int nblk, int64_t units) {
     constexpr int EPV = ElemTraits<T>::kPerVec;
     constexpr int NG = D / (2 * EPV);
@@ -171,7 +212,7 @@ __global__ void __launch_bounds__(kPrefillThreads) prefill_rowstats_kernel(const
     LogitParams lp;
     lp.c1 = a.inv_tau * kLog2e;
     lp.sc1 = a.scale * lp.c1;
-    lp.slope1 = (a.slopes ? a.slopes[h] : 0.0f) * lp.c1;
+    lp.slope1 = (BIAS ? a.slopes[h] : 0.0f) * lp.c1;
     lp.inv_tau = a.inv_tau;
     lp.gz = -kLog2Ln2 * a.inv_tau;
     lp.noise = a.noise;
@@ -180,6 +221,17 @@ __global__ void __launch_bounds__(kPrefillThreads) prefill_rowstats_kernel(const
     const uint32_t kmul_lane = (uint32_t)(half * 4) * kKposMul;
 
     float M = -INFINITY, Ssum = 0.0f;
+    if constexpr (GUMBEL) {
+        // Reference exponent of the row's sum: its own diagonal term y2_ii, formed here from the query's and the
+        // key's elements this lane holds (both halves of the wave added up).  It is a term of the sum, so the
+        // sum against it cannot vanish however far below it the others lie.
+        const T* krow = Ku + (size_t)min(i, n - 1) * D + half * EPV;
+        float dot = 0.0f;
+#pragma unroll
+        for (int g = 0; g < NG; ++g) dot += dot_piece<T>(bq[g], *(const uint4*)(krow + g * 2 * EPV));
+        dot += __shfl_xor(dot, 32, kWave);
+        M = logit2_gumbel(lp, dot, 0.0f, rkey ^ ((uint32_t)i * kKposMul));
+    }
     const int jt_end = min(i0 + kTile - 1, n - 1) / kTile;                      // this wave's last key tile
     const int jt_last = min(rb * (4 * kTile) + 4 * kTile - 1, n - 1) / kTile;   // the workgroup's
     uint4 stage[Stage::NP];
@@ -200,19 +252,37 @@ __global__ void __launch_bounds__(kPrefillThreads) prefill_rowstats_kernel(const
             const int jl = jb + half * 4;                       // first key of this lane in the tile
             const uint32_t kmul = (uint32_t)jb * kKposMul + kmul_lane;
             const float dist0 = (float)(i - jl);
-            float y2[16];
-            if (a.noise == kNoiseGumbel) {
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int ro = (r >> 2) * 8 + (r & 3);
-                    y2[r] = logit2_gumbel(lp, acc[r], dist0 - (float)ro, rkey ^ (kmul + (uint32_t)ro * kKposMul));
+            if constexpr (GUMBEL) {
+                // every term against the reference as it stands, (gz - M) folded into the chain: no search for the
+                // tile's maximum, no subtraction per logit.  A later, larger logit just gives a term above one.
+                const bool diag = jb + kTile - 1 > i0;  // the tile crosses the diagonal for some lane: causal mask
+                for (int attempt = 0;; ++attempt) {
+                    const float base = BIAS ? fmaf(dist0, -lp.slope1, lp.gz - M) : lp.gz - M;
+                    const float ssum = diag ? tile_sum<BIAS, true>(lp, acc, base, rkey, kmul, i - jl)
+                                            : tile_sum<BIAS, false>(lp, acc, base, rkey, kmul, 0);
+                    const float Snew = Ssum + ssum;
+                    // a sum beyond fp32 in some lane (a logit 2^120 above its row's reference): every lane of the
+                    // wave raises its reference and sums the tile again; bounded, so that NaN inputs end as NaN
+                    if (__any(!(Snew < 0x1p120f)) && attempt < 64) {
+                        M += 100.0f;
+                        Ssum *= 0x1p-100f;
+                        continue;
+                    }
+                    Ssum = Snew;
+                    break;
+                }
+                // the reference follows the sum's exponent (exact: a power of two)
+                if (Ssum > 0x1p40f) {
+                    const int sh = (int)(__float_as_uint(Ssum) >> 23) - 127;
+                    M += (float)sh;
+                    Ssum = __uint_as_float(__float_as_uint(Ssum) - ((uint32_t)sh << 23));
                 }
             } else {
+            float y2[16];
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int ro = (r >> 2) * 8 + (r & 3);
-                    y2[r] = logit2_other(lp, acc[r], dist0 - (float)ro, rkey, (uint32_t)(jl + ro));
-                }
+            for (int r = 0; r < 16; ++r) {
+                const int ro = (r >> 2) * 8 + (r & 3);
+                y2[r] = logit2_other(lp, acc[r], dist0 - (float)ro, rkey, (uint32_t)(jl + ro));
             }
             if (jb + kTile - 1 > i0) {  // the tile crosses the diagonal for some lane: causal mask
 #pragma unroll
@@ -232,6 +302,7 @@ __global__ void __launch_bounds__(kPrefillThreads) prefill_rowstats_kernel(const
                 Ssum = Ssum * hw_exp2(M - Mn) + ssum;
                 M = Mn;
             }
+            }
         }
         if (jt < jt_last) Stage::park(kbuf[(jt + 1) & 1], stage);
         __syncthreads();
@@ -242,13 +313,16 @@ __global__ void __launch_bounds__(kPrefillThreads) prefill_rowstats_kernel(const
     const float Mt = fmaxf(M, M2);
     const float St = (M > -INFINITY ? Ssum * hw_exp2(M - Mt) : 0.0f) + (M2 > -INFINITY ? S2 * hw_exp2(M2 - Mt) : 0.0f);
     if (half == 0 && i < n) {
-        a.ws_c[(size_t)u * a.n_pad + i] = Mt + hw_log2(St);
+        // log2 of the row's normaliser; the trimmed second pass wants it subtracted from the adjustment's
+        // constant part, so that is what is left for it
+        const float c = Mt + hw_log2(St);
+        a.ws_c[(size_t)u * a.n_pad + i] = GUMBEL ? lp.gz - c : c;
         a.ws_r[(size_t)u * a.n_pad + i] = rkey;
     }
 }
 
 // ------------------------------------------------------------------ pass 2
-template <typename T, int D>
+template <typename T, int D, bool GUMBEL, bool BIAS>
 __global__ void __launch_bounds__(kPrefillThreads) prefill_colsum_kernel(const PrefillArgs a, int nblk, int64_t units) {
     constexpr int EPV = ElemTraits<T>::kPerVec;
     constexpr int NG = D / (2 * EPV);
@@ -286,7 +360,7 @@ __global__ void __launch_bounds__(kPrefillThreads) prefill_colsum_kernel(const P
     LogitParams lp;
     lp.c1 = a.inv_tau * kLog2e;
     lp.sc1 = a.scale * lp.c1;
-    lp.slope1 = (a.slopes ? a.slopes[h] : 0.0f) * lp.c1;
+    lp.slope1 = (BIAS ? a.slopes[h] : 0.0f) * lp.c1;
     lp.inv_tau = a.inv_tau;
     lp.gz = -kLog2Ln2 * a.inv_tau;
     lp.noise = a.noise;
@@ -345,12 +419,21 @@ __global__ void __launch_bounds__(kPrefillThreads) prefill_colsum_kernel(const P
                 const float cs[4] = {c4.x, c4.y, c4.z, c4.w};
                 const uint32_t rs[4] = {r4.x, r4.y, r4.z, r4.w};
                 const float dist0 = (float)(ir - j);
+                if constexpr (GUMBEL) {
+                    // cs holds (adjustment's constant part - row normaliser): z = 2^(x2 - log2(t)/tau + cs)
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float y = (a.noise == kNoiseGumbel)
-                                        ? logit2_gumbel(lp, acc[q4 * 4 + e], dist0 + (float)e, rs[e] ^ kmul)
-                                        : logit2_other(lp, acc[q4 * 4 + e], dist0 + (float)e, rs[e], (uint32_t)j);
-                    z[q4 * 4 + e] = hw_exp2(y - cs[e]);
+                    for (int e = 0; e < 4; ++e) {
+                        const float l2t = hw_log2(neg_log2_uniform(mix32(rs[e] ^ kmul)));
+                        float t = fmaf(l2t, -lp.inv_tau, cs[e]);
+                        if (BIAS) t = fmaf(dist0 + (float)e, -lp.slope1, t);
+                        z[q4 * 4 + e] = hw_exp2(fmaf(acc[q4 * 4 + e], lp.sc1, t));
+                    }
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float y = logit2_other(lp, acc[q4 * 4 + e], dist0 + (float)e, rs[e], (uint32_t)j);
+                        z[q4 * 4 + e] = hw_exp2(y - cs[e]);
+                    }
                 }
             }
             if (edge) {
@@ -399,10 +482,19 @@ static hipError_t launch_prefill_t(const PrefillArgs& a, int64_t U, hipStream_t 
     const int nblk = (a.n + 4 * kTile - 1) / (4 * kTile);
     const int64_t groups = (U + kXcds - 1) / kXcds;  // units are dealt to XCDs in groups of 8
     const dim3 grid((unsigned)(groups * kXcds * nblk)), block(kPrefillThreads);
-    hipLaunchKernelGGL((prefill_rowstats_kernel<T, D>), grid, block, 0, st, a, nblk, U);
+    // four builds of each pass: the Gumbel adjustment in the trimmed form or any adjustment in the plain form,
+    // with or without the position-bias term
+    const bool gum = a.noise == kNoiseGumbel, bias = a.slopes != nullptr;
+    if (gum && bias) hipLaunchKernelGGL((prefill_rowstats_kernel<T, D, true, true>), grid, block, 0, st, a, nblk, U);
+    else if (gum) hipLaunchKernelGGL((prefill_rowstats_kernel<T, D, true, false>), grid, block, 0, st, a, nblk, U);
+    else if (bias) hipLaunchKernelGGL((prefill_rowstats_kernel<T, D, false, true>), grid, block, 0, st, a, nblk, U);
+    else hipLaunchKernelGGL((prefill_rowstats_kernel<T, D, false, false>), grid, block, 0, st, a, nblk, U);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((prefill_colsum_kernel<T, D>), grid, block, 0, st, a, nblk, U);
+    if (gum && bias) hipLaunchKernelGGL((prefill_colsum_kernel<T, D, true, true>), grid, block, 0, st, a, nblk, U);
+    else if (gum) hipLaunchKernelGGL((prefill_colsum_kernel<T, D, true, false>), grid, block, 0, st, a, nblk, U);
+    else if (bias) hipLaunchKernelGGL((prefill_colsum_kernel<T, D, false, true>), grid, block, 0, st, a, nblk, U);
+    else hipLaunchKernelGGL((prefill_colsum_kernel<T, D, false, false>), grid, block, 0, st, a, nblk, U);
     e = hipGetLastError();
     if (e != hipSuccess || a.G == 1) return e;
     hipLaunchKernelGGL(prefill_group_sum_kernel, dim3((unsigned)(U / a.G), (unsigned)((a.n + 255) / 256)), dim3(256), 0,

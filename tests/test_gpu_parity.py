@@ -765,7 +765,12 @@ def test_fused_step_equals_the_two_calls(dtype, d, cap, layout):
             kf.kf_select_evict(gc, k, w, kept, ws, layout=layout)
         torch.cuda.synchronize()
         assert error_word(ws) == 0
-        results.append([host(t).copy() for t in (out, kept, gc.K, gc.V, gc.score, gc.pos, gc.len)])
+        lens_now = host(gc.len)
+        live = [host(t).copy() for t in (gc.K, gc.V, gc.score, gc.pos)]
+        for l, b, h in np.ndindex(L, B, H):          # beyond a unit's length nothing is specified (a whole-step
+            for t in live:                           # launch never appends the token it places directly)
+                t[l, b, h, int(lens_now[l, b, h]):] = 0
+        results.append([host(out).copy(), host(kept).copy(), lens_now.copy()] + live)
     for a, b in zip(*results):
         np.testing.assert_array_equal(a, b)
     # and the two-call path is the one checked against the oracle
@@ -1705,7 +1710,8 @@ def test_single_launch_slot_step_equals_the_two_calls(dtype, d, G, w, k):
     assert int(a.len[1, 1, 1]) == k
 
 
-def test_single_launch_slot_step_from_the_device_counter_and_in_a_graph():
+@pytest.mark.parametrize("layout", [kf.LAYOUT_SLOT, kf.LAYOUT_ORDERED])
+def test_single_launch_step_from_the_device_counter_and_in_a_graph(layout):
     rng = np.random.default_rng(9100)
     L, B, H, d, k, w = 4, 4, 20, 64, 129, 26
     cap = k + 1
@@ -1722,7 +1728,7 @@ def test_single_launch_slot_step_from_the_device_counter_and_in_a_graph():
     for t in range(1, steps + 1):
         q, kn, vn = inputs[t - 1]
         kf.kf_decode_select_step(a, q, kn, vn, n + t - 1, cap, kf.kf_tau(min(t, T), T), 0.125, kf.NOISE_GUMBEL, seeds, None,
-                                 out_a, k=k, w=w, layout=kf.LAYOUT_SLOT, workspace=ws_a)
+                                 out_a, k=k, w=w, layout=layout, workspace=ws_a)
         torch.cuda.synchronize()
         ref.append([host(x).copy() for x in (out_a, a.score[..., :k], a.pos[..., :k], a.len)])
     step = torch.ones(1, dtype=torch.int32, device="cuda")
@@ -1730,7 +1736,7 @@ def test_single_launch_slot_step_from_the_device_counter_and_in_a_graph():
 
     def one():
         kf.kf_decode_select_step_at(b_, qb, kb, vb, n, T, 1.0, 2.0, step, cap, 0.125, kf.NOISE_GUMBEL, seeds, None, out_b,
-                                    k=k, w=w, layout=kf.LAYOUT_SLOT, workspace=ws_b)
+                                    k=k, w=w, layout=layout, workspace=ws_b)
 
     for src, dst in zip(inputs[0], (qb, kb, vb)):
         dst.copy_(src)
