@@ -261,6 +261,32 @@ def test_prefill_score_matches_oracle(dtype, d, n):
         assert_close_score(host(gc.score), oc.score, oc.len, "prefill noise=%d" % noise, rtol=SCORE_RTOL_PREFILL)
 
 
+@pytest.mark.parametrize("dtype,d,scale", [(ko.BF16, 128, 6.0), (ko.F32, 64, 9.0), (ko.BF16, 256, 0.0)])
+def test_prefill_with_logits_far_from_the_rows_reference(dtype, d, scale):
+    """Logits spread over hundreds of powers of two (a logit scale far above 1/sqrt(d)): the row sums are
+    formed against a reference exponent that starts at the diagonal term, so terms 2^120 and more above it
+    must send the reference up (the tile is summed again) instead of overflowing, and rows whose other terms
+    all vanish against it keep their diagonal term.  Scale 0: every logit is pure adjustment."""
+    rng = np.random.default_rng(int(scale * 10) + d)
+    L, B, H, n = 1, 2, 2, 200
+    oc = random_cache(rng, L, B, H, d, n, dtype, 0)
+    Q = rnd(rng, (L, B, H, n, d), dtype)
+    seeds = np.array([3, 4], np.uint64)
+    slopes = np.array([0.0, 0.7], np.float32)
+    gc = upload(oc)
+    ws = kf.new_workspace(gc, n)
+    oc.prefill_score(Q, n, 1.0, scale, ko.NOISE_GUMBEL, seeds, slopes)
+    kf.kf_prefill_score(gc, dev(Q), n, 1.0, scale, ko.NOISE_GUMBEL, dev(seeds), dev(slopes), ws)
+    torch.cuda.synchronize()
+    got, ref = host(gc.score).astype(np.float64), oc.score.astype(np.float64)
+    assert np.isfinite(got).all()
+    np.testing.assert_allclose(got.sum(axis=-1), n, rtol=1e-5)          # every row of the softmax sums to one
+    big = ref > 1e-12                                                    # below that the sums are lost in fp32
+    assert big.sum() > n                                                 # (near one-hot rows: few columns carry the mass)
+    assert (np.abs(got - ref)[big] <= SCORE_RTOL_PREFILL * ref[big] + 1e-12).all()
+    assert (got[~big] <= 1e-11).all()
+
+
 @pytest.mark.parametrize("dtype,d,G,shared", [(ko.BF16, 128, 1, False), (ko.BF16, 256, 1, False), (ko.F32, 64, 1, False),
                                               (ko.BF16, 64, 4, False), (ko.BF16, 128, 1, True)])
 def test_prefill_of_a_padded_batch_matches_oracle(dtype, d, G, shared):
