@@ -261,11 +261,15 @@ __global__ void __launch_bounds__(kPrefillThreads) prefill_rowstats_kernel(const
                     const float ssum = diag ? tile_sum<BIAS, true>(lp, acc, base, rkey, kmul, i - jl)
                                             : tile_sum<BIAS, false>(lp, acc, base, rkey, kmul, 0);
                     const float Snew = Ssum + ssum;
-                    // a sum beyond fp32 in some lane (a logit 2^120 above its row's reference): every lane of the
-                    // wave raises its reference and sums the tile again; bounded, so that NaN inputs end as NaN
-                    if (__any(!(Snew < 0x1p120f)) && attempt < 64) {
-                        M += 100.0f;
-                        Ssum *= 0x1p-100f;
+                    // a sum beyond fp32 in some lane (a logit 2^120 above its row's reference): that lane raises its
+                    // reference and the wave sums the tile again (the other lanes arrive at the same sums as
+                    // before); bounded, so that NaN inputs end as NaN
+                    const bool over = !(Snew < 0x1p120f);
+                    if (__any(over) && attempt < 64) {
+                        if (over) {
+                            M += 100.0f;
+                            Ssum *= 0x1p-100f;
+                        }
                         continue;
                     }
                     Ssum = Snew;
