@@ -220,6 +220,41 @@ __device__ __forceinline__ f32x4_t mfma_16x16x32<f16_t>(const uint4& a, const ui
     return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), acc, 0, 0, 0);
 }
 
+// Attention output of a query group on the matrix cores.  The contraction of out[g][c] = sum_j p[g][j]*V[j][c]
+// runs over the tokens, and an MFMA lane must hold eight consecutive contraction elements -- but a coalesced
+// load gives a lane eight consecutive COLUMNS of one token.  So the contraction index is widened to the pair
+// (token, column within the lane's eight): with rows of 256 bytes a wave-wide load is four tokens x 16 lanes,
+// which read as the B operand of a 16x16x32 MFMA is B[k = (token, e)][n = lane's piece] = V[token][8n + e] --
+// the loaded registers as they are, no transposition.  The A operand carries the weights with a Kronecker
+// delta, A[m = (head, e')][k = (token, e)] = p[head][token] * (e == e'), so that C[(head, e')][n] =
+// sum_token p[head][token] * V[token][8n + e']: 16 rows of A are two heads x eight column offsets, four MFMAs
+// cover the eight heads, and a lane's A operand is one weight in one fixed 16-bit slot, zeros elsewhere.
+// Seven eighths of the matrix work multiply zeros, on units that idle otherwise; against 64 multiply-adds
+// per 16 bytes on the vector units it leaves them eight byte-permutes per MFMA pair.  Weights enter as
+// bf16, so each is split in two terms (the upper 16 bits and the upper 16 bits of the rest: 2^-16
+// relative), one MFMA each; they wait in LDS already split and packed.
+template <typename T, int D, int G>
+struct MfmaPV {
+    static constexpr bool value = false;
+};
+template <>
+struct MfmaPV<bf16_t, 128, 8> {
+    static constexpr bool value = true;
+};
+// weight p in [0, 1] -> (p rounded to bf16) | (the rest, rounded to bf16) >> 16: the two terms add up to p within
+// 2^-18 relative (round to nearest even on the bit patterns; the rest is exact in fp32 and may be negative)
+__device__ __forceinline__ uint32_t bf16_bits_rne(float x) {
+    const uint32_t b = __float_as_uint(x);
+    return (b + 0x7FFFu + ((b >> 16) & 1u)) & 0xFFFF0000u;
+}
+__device__ __forceinline__ uint32_t split_weight(float p) {
+    const uint32_t hi = bf16_bits_rne(p);
+    return hi | (bf16_bits_rne(p - __uint_as_float(hi)) >> 16);
+}
+__device__ __forceinline__ float joined_weight(uint32_t w) {
+    return __uint_as_float(w & 0xFFFF0000u) + __uint_as_float(w << 16);
+}
+
 // One workgroup streams the cache rows [j0, j1) of one cached head ("unit") once
 // and serves the G query heads that read it (G = 1: ordinary multi-head
 // attention; G > 1: grouped-query attention, query head hq = h*G + g).
@@ -232,10 +267,11 @@ __device__ __forceinline__ void decode_block(const DecodeArgs& a) {
     constexpr int RPB = RPW * NW;                // rows per block-wide load
     // independent loads in flight per lane (8 query heads: registers are short; one instead of two costs the
     // 8-wave workgroup 15-20 %, four do not fit)
-    constexpr int UNR = (G >= 8) ? 2 : kDecodeUnroll;
+    constexpr int UNR = (G >= 8 && !MfmaPV<T, D, G>::value) ? 2 : kDecodeUnroll;
     constexpr int TILE = RPB * UNR;              // rows per tile of the workgroup
     constexpr int PW = D + 4;                    // floats in a partial record
     constexpr bool BIG = NW > kDecodeRedWaves;  // the 8-wave workgroup: one split, 4 or 8 query heads, up to most of a CU's LDS
+    constexpr bool PVM = MfmaPV<T, D, G>::value;  // attention output on the matrix cores
     constexpr size_t ROWB = (size_t)D * sizeof(T);
     static_assert(LPR <= 32 && D <= NT, "row must fit half a wave, output a block");
 
@@ -689,7 +725,7 @@ __device__ __forceinline__ void decode_block(const DecodeArgs& a) {
         for (int g = 0; g < G; ++g) {
             const float p = hw_exp2(xs[g * CS + t] - mxy[2 * g]);
             const float e = hw_exp2(ys[g * CS + t] - mxy[2 * g + 1]);
-            xs[g * CS + t] = p;
+            xs[g * CS + t] = PVM ? __uint_as_float(split_weight(p)) : p;
             ys[g * CS + t] = e;
             spe[2 * g] += p;
             spe[2 * g + 1] += e;
@@ -715,7 +751,50 @@ __device__ __forceinline__ void decode_block(const DecodeArgs& a) {
 #pragma unroll
         for (int e = 0; e < EPV; ++e) acc[g][e] = 0.0f;
     }
+    // matrix-core form: lane (piece cl, row sub) feeds A row cl = (head 2*mf + cl/8, column offset cl%8) and
+    // receives C rows 4*sub .. +3 = (head 2*mf + sub/2, column offsets 4*(sub%2) .. +3) of column piece cl
+    f32x4_t cacc[PVM ? 4 : 1];
+    uint32_t sel_hi[4], sel_lo[4];  // byte selectors that put a weight's term into this lane's slot of A
+#pragma unroll
+    for (int q = 0; q < (PVM ? 4 : 1); ++q) cacc[q] = f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const bool mine = q == ((cl & 7) >> 1), upper = (cl & 1) != 0;
+        sel_hi[q] = !mine ? 0x0C0C0C0Cu : upper ? 0x03020C0Cu : 0x0C0C0302u;
+        sel_lo[q] = !mine ? 0x0C0C0C0Cu : upper ? 0x01000C0Cu : 0x0C0C0100u;
+    }
     auto weigh = [&](int base) {
+        if constexpr (PVM) {
+            const uint32_t* xw = (const uint32_t*)xs + (cl >> 3) * CS - j0;
+            // The matrix cores do not round their fp32 accumulation to nearest: over the hundreds of dependent
+            // MFMAs of a long unit that grows into a bias of 1e-4 of the sum.  So a tile's eight MFMAs start
+            // from zero and the tile's sums are added to the running ones on the vector units.
+            f32x4_t tacc[4];
+#pragma unroll
+            for (int mf = 0; mf < 4; ++mf) tacc[mf] = f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+            for (int i = 0; i < UNR; ++i) {
+                const int j = base + i * RPB + sub;
+#pragma unroll
+                for (int mf = 0; mf < 4; ++mf) {
+                    const uint32_t w = (j < j1) ? xw[2 * mf * CS + j] : 0u;
+                    uint4 ah, al;
+                    ah.x = __builtin_amdgcn_perm(w, w, sel_hi[0]);
+                    ah.y = __builtin_amdgcn_perm(w, w, sel_hi[1]);
+                    ah.z = __builtin_amdgcn_perm(w, w, sel_hi[2]);
+                    ah.w = __builtin_amdgcn_perm(w, w, sel_hi[3]);
+                    al.x = __builtin_amdgcn_perm(w, w, sel_lo[0]);
+                    al.y = __builtin_amdgcn_perm(w, w, sel_lo[1]);
+                    al.z = __builtin_amdgcn_perm(w, w, sel_lo[2]);
+                    al.w = __builtin_amdgcn_perm(w, w, sel_lo[3]);
+                    tacc[mf] = mfma_16x16x32<T>(ah, cur[i], tacc[mf]);
+                    tacc[mf] = mfma_16x16x32<T>(al, cur[i], tacc[mf]);
+                }
+            }
+#pragma unroll
+            for (int mf = 0; mf < 4; ++mf) cacc[mf] += tacc[mf];
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < UNR; ++i) {
             const int j = base + i * RPB + sub;
@@ -746,7 +825,19 @@ __device__ __forceinline__ void decode_block(const DecodeArgs& a) {
             base += TILE;
         }
     }
-    if (owner && wv == 0 && sub == 0) {  // the new token's value row
+    if constexpr (PVM) {
+        if (owner && wv == 0) {  // the new token's value row, into the accumulators as the MFMAs lay them out
+            static_assert(!PVM || sizeof(T) == 2, "four 16-bit columns per accumulator register group");
+            const uint2 hv = ((const uint2*)vnew)[2 * cl + (sub & 1)];  // columns 8*cl + 4*(sub%2) .. +3
+            const float v4[4] = {bf16_lo(hv.x), bf16_hi(hv.x), bf16_lo(hv.y), bf16_hi(hv.y)};
+#pragma unroll
+            for (int mf = 0; mf < 4; ++mf) {
+                const float p = joined_weight(((const uint32_t*)xs)[(2 * mf + (sub >> 1)) * CS + cnt_c]);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) cacc[mf][r] = fmaf(p, v4[r], cacc[mf][r]);
+            }
+        }
+    } else if (owner && wv == 0 && sub == 0) {  // the new token's value row
         float vvals[EPV];
         unpack16<T>(((const uint4*)vnew)[cl], vvals);
 #pragma unroll
@@ -765,7 +856,12 @@ __device__ __forceinline__ void decode_block(const DecodeArgs& a) {
     float fin[RS ? HV : 1];
     int off = 0;
     auto store_fin = [&](float* row) {  // this lane's sums -> its places in a [G][D] row of partial outputs
-        if constexpr (RS) {
+        if constexpr (PVM) {  // the MFMAs summed over the lane groups already: 16 sums per lane, each (head, column) once
+#pragma unroll
+            for (int mf = 0; mf < 4; ++mf)
+                *(float4*)&row[(2 * mf + (sub >> 1)) * D + cl * EPV + 4 * (sub & 1)] =
+                    make_float4(cacc[mf][0], cacc[mf][1], cacc[mf][2], cacc[mf][3]);
+        } else if constexpr (RS) {
 #pragma unroll
             for (int i4 = 0; i4 < HV / 4; ++i4) {
                 const int fi = off + 4 * i4;
@@ -780,7 +876,12 @@ __device__ __forceinline__ void decode_block(const DecodeArgs& a) {
             }
         }
     };
-    if constexpr (RS) {
+    if constexpr (PVM) {
+        if constexpr (!BIG) {
+            store_fin(red_o + (size_t)wv * G * D);
+            __syncthreads();  // red_o and stat are complete
+        }
+    } else if constexpr (RS) {
         constexpr int N = G * EPV;
         static_assert(HV % 4 == 0, "a lane group ends up with whole 16-byte pieces of output rows");
         float flat[N];
