@@ -349,18 +349,15 @@ def bench_config(wl, args, headline):
         out2 = torch.zeros((wl.L, B2, wl.H, wl.d), dtype=torch.float32, device="cuda")
         seeds2 = torch.arange(B2, device="cuda", dtype=torch.int64) + 20240309
         n_v = 20
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        tot = 0.0
-        for i in range(n_v + 3):
+        ev2 = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_v + 3)]
+        for e0, e1 in ev2:              # back to back, no synchronisation in between: the chip stays busy
             c2.len.fill_(wl.k)
             e0.record()
             kf.kf_decode_step(c2, q2, kn2, vn2, wl.n + 7, m, 1.5, wl.scale, noise, seeds2, slopes, out2, ws2)
             e1.record()
-            torch.cuda.synchronize()
-            if i >= 3:
-                tot += e0.elapsed_time(e1)
+        torch.cuda.synchronize()
         assert int(ws2[:4].view(torch.int32)[0].item()) == 0
-        ms = tot / n_v
+        ms = sum(e0.elapsed_time(e1) for e0, e1 in ev2[3:]) / n_v
         byt = wl.L * B2 * Hk * (m * (2 * wl.d * wl.elem_bytes + 12))
         return {"batch": B2, "cached_heads": Hk, "decode_us": round(ms * 1e3, 2),
                 "frac_of_peak": round(byt / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
