@@ -287,6 +287,34 @@ def test_prefill_with_logits_far_from_the_rows_reference(dtype, d, scale):
     assert (got[~big] <= 1e-11).all()
 
 
+def test_prefill_with_a_nan_query_row_stays_confined_to_it():
+    """A query row of NaNs makes that row's terms NaN (its sum can never be brought into range: the retry of
+    the row sum is bounded), which reaches the columns it contributes to (keys up to its own position) of its
+    own unit and nothing else."""
+    rng = np.random.default_rng(404)
+    L, B, H, d, n, bad = 1, 1, 2, 64, 150, 70
+    oc = random_cache(rng, L, B, H, d, n, ko.F32, 0)
+    Q = rnd(rng, (L, B, H, n, d), ko.F32)
+    Q[0, 0, 0, bad] = np.nan
+    seeds = np.array([8], np.uint64)
+    gc = upload(oc)
+    ws = kf.new_workspace(gc, n)
+    scale = float(1.0 / np.sqrt(np.float32(d)))
+    kf.kf_prefill_score(gc, dev(Q), n, 1.0, scale, kf.NOISE_GUMBEL, dev(seeds), None, ws)
+    torch.cuda.synchronize()
+    clean = Q.copy()
+    clean[0, 0, 0, bad] = 0.0
+    oc.prefill_score(clean, n, 1.0, scale, ko.NOISE_GUMBEL, seeds, None)
+    got = host(gc.score)
+    assert np.isnan(got[0, 0, 0, : bad + 1]).all()                   # the columns row `bad` contributes to
+    sel = np.zeros((L, B, H), np.int32)
+    sel[0, 0, 1] = n                                                   # the other unit: untouched by it
+    assert_close_score(got, oc.score, sel, rtol=SCORE_RTOL_PREFILL)
+    # columns behind the bad row receive nothing from it: the same sums as with that row replaced (rows after it
+    # are unchanged, and a zero query row only matters to the columns up to its own position)
+    np.testing.assert_allclose(got[0, 0, 0, bad + 1:n], oc.score[0, 0, 0, bad + 1:n], rtol=SCORE_RTOL_PREFILL)
+
+
 @pytest.mark.parametrize("dtype,d,G,shared", [(ko.BF16, 128, 1, False), (ko.BF16, 256, 1, False), (ko.F32, 64, 1, False),
                                               (ko.BF16, 64, 4, False), (ko.BF16, 128, 1, True)])
 def test_prefill_of_a_padded_batch_matches_oracle(dtype, d, G, shared):
