@@ -128,14 +128,6 @@ __device__ __forceinline__ void merge_unit(const DecodeArgs& a, int64_t u, int l
         if (lane == 0) inv_p[g] = 1.0f / sumP;
     }
     __syncthreads();
-    if (lead) {
-        for (int idx = tid; idx < G * D; idx += NT) {
-            const int g = idx / D, t = idx % D;
-            float o = 0.0f;
-            for (int ss = 0; ss < S; ++ss) o = fmaf(w_p[g * S + ss], parts[((size_t)ss * G + g) * PW + t], o);
-            a.out[(u * G + g) * D + t] = o * inv_p[g];
-        }
-    }
     float* we = a.ws_e + (size_t)u * G * a.cap;
     // with pre_slices the finished scores are also searched for the slice's smallest eviction candidate
     // (only a unit exactly one token over the budget is looked at by the selection launch)
@@ -143,20 +135,62 @@ __device__ __forceinline__ void merge_unit(const DecodeArgs& a, int64_t u, int l
     const bool by_pos = a.pre_layout == KF_LAYOUT_SLOT;
     const int32_t* pu = a.pos + (size_t)u * a.cap;
     const int newest = (pre && by_pos) ? pu[len0] : 0;
-    SliceMin smin;
-    for (int j = j_begin + tid; j < min(j_end, m); j += NT) {
-        const int split = (j == len0) ? S - 1 : j / a.chunk;  // the new token belongs to the last split
-        float df = 0.0f;
+    // Loads first, arithmetic after: a loop that waits for each of its loads in turn costs a trip to memory per
+    // split and per token stride (32 splits: the output alone took 11 us).  A thread has kMergeTok tokens of the
+    // score update and kMergeRec split records of an output element in flight at a time, and the first tokens
+    // are asked for before the outputs are formed.  The order of every sum is the sequential one.
+    constexpr int kMergeTok = 4, kMergeRec = 8;
+    const int jmax = min(j_end, m);
+    float tw[kMergeTok][G], tf[kMergeTok];
+    int tp[kMergeTok];
+    auto load_tokens = [&](int jb) {
 #pragma unroll
-        for (int g = 0; g < G; ++g) df = fmaf(we[(size_t)g * a.cap + j], w_e[g * S + split], df);
-        if (a.shared) we[j] = df;  // summed over the layers by the launch that follows
-        else if (pre) {
-            const float f_new = (j == len0) ? df : fu[j] + df;  // one add per address, as below
-            fu[j] = f_new;
-            const int pj = by_pos ? pu[j] : 0;
-            if (by_pos ? (pj <= newest - a.pre_w) : (j < m - a.pre_w)) smin.take(f_new, j, by_pos ? pj : j);
-        } else if (j == len0) fu[j] = df;
-        else unsafeAtomicAdd(&fu[j], df);  // fire-and-forget add at the L2 (one per address: the plain fp32 sum)
+        for (int i = 0; i < kMergeTok; ++i) {
+            const int j = jb + i * NT;
+            const bool ok = j < jmax;
+#pragma unroll
+            for (int g = 0; g < G; ++g) tw[i][g] = ok ? we[(size_t)g * a.cap + j] : 0.0f;
+            tf[i] = (ok && pre && j != len0) ? fu[j] : 0.0f;
+            tp[i] = (ok && pre && by_pos) ? pu[j] : 0;
+        }
+    };
+    int jb = j_begin + tid;
+    if (jb < jmax) load_tokens(jb);
+    if (lead) {
+        for (int idx = tid; idx < G * D; idx += NT) {
+            const int g = idx / D, t = idx % D;
+            const float* pr = parts + (size_t)g * PW + t;
+            float o = 0.0f;
+            for (int s0 = 0; s0 < S; s0 += kMergeRec) {
+                float v[kMergeRec];
+#pragma unroll
+                for (int i = 0; i < kMergeRec; ++i) v[i] = (s0 + i < S) ? pr[(size_t)(s0 + i) * G * PW] : 0.0f;
+#pragma unroll
+                for (int i = 0; i < kMergeRec; ++i) o = fmaf((s0 + i < S) ? w_p[g * S + s0 + i] : 0.0f, v[i], o);
+            }
+            a.out[(u * G + g) * D + t] = o * inv_p[g];
+        }
+    }
+    SliceMin smin;
+    while (jb < jmax) {
+#pragma unroll
+        for (int i = 0; i < kMergeTok; ++i) {
+            const int j = jb + i * NT;
+            if (j >= jmax) break;
+            const int split = (j == len0) ? S - 1 : j / a.chunk;  // the new token belongs to the last split
+            float df = 0.0f;
+#pragma unroll
+            for (int g = 0; g < G; ++g) df = fmaf(tw[i][g], w_e[g * S + split], df);
+            if (a.shared) we[j] = df;  // summed over the layers by the launch that follows
+            else if (pre) {
+                const float f_new = (j == len0) ? df : tf[i] + df;  // one add per address, as below
+                fu[j] = f_new;
+                if (by_pos ? (tp[i] <= newest - a.pre_w) : (j < m - a.pre_w)) smin.take(f_new, j, by_pos ? tp[i] : j);
+            } else if (j == len0) fu[j] = df;
+            else unsafeAtomicAdd(&fu[j], df);  // fire-and-forget add at the L2 (one per address: the plain fp32 sum)
+        }
+        jb += kMergeTok * NT;
+        if (jb < jmax) load_tokens(jb);
     }
     if (pre) publish_slice_min<NT>(a, u, slice, smin);
     if (lead && tid == 0) a.len[u] = m;
