@@ -1,6 +1,7 @@
 """GPU-vs-oracle parity of the three hot calls, element by element, through the
 C ABI (python binding -> libkeyformer.so).  Needs a real MI355X: -m gpu."""
 import itertools
+import os
 
 import numpy as np
 import pytest
@@ -13,6 +14,15 @@ from parity_harness import (SCORE_RTOL_PREFILL, LockStep, assert_close_out, asse
                             assert_state_equal, compare_kept, dev, error_word, host, upload, upload_into)
 
 pytestmark = pytest.mark.gpu
+
+
+def _extra_seeds():
+    """More seeds for the seeded shape sweeps, from the environment (KF_TEST_SEEDS="1,2,3"): the committed
+    seeds are what every run covers; anybody hunting a rare case can widen the sweeps without editing them."""
+    return [int(x) for x in os.environ.get("KF_TEST_SEEDS", "").replace(",", " ").split()]
+
+
+SWEEP_SEEDS = [None] + _extra_seeds()   # None: the committed seed
 
 DTYPES = [(ko.BF16, 64), (ko.BF16, 128), (ko.BF16, 256), (ko.F32, 64), (ko.F32, 128), (ko.F16, 64), (ko.F16, 128),
           (ko.F16, 256)]
@@ -162,12 +172,12 @@ def test_select_evict_matches_oracle(dtype, d, n, k, w):
     assert_state_equal(gc2, oc)
 
 
-@pytest.mark.parametrize("seed", range(6))
+@pytest.mark.parametrize("seed", list(range(6)) + [1000 + x for x in _extra_seeds()])
 def test_select_random_ragged_units(seed):
     """Units of every length in one call (empty, under budget, one over, far over, full), random budget and
     window, scores with many exact ties: survivor lists and compacted state bit-exact against the oracle."""
     rng = np.random.default_rng(400 + seed)
-    d, dtype = [(64, ko.BF16), (128, ko.F32), (256, ko.BF16), (128, ko.BF16), (64, ko.F32), (256, ko.BF16)][seed]
+    d, dtype = [(64, ko.BF16), (128, ko.F32), (256, ko.BF16), (128, ko.BF16), (64, ko.F32), (256, ko.BF16)][seed % 6]
     cap = int(rng.integers(40, 700))
     k = int(rng.integers(1, cap + 1))
     w = int(rng.integers(0, k + 1))
@@ -833,11 +843,12 @@ def test_fused_step_equals_the_two_calls(dtype, d, cap, layout):
     assert_close_out(results[0][0], out_ref)
 
 
-def test_fused_step_on_random_shapes_equals_the_two_calls():
+@pytest.mark.parametrize("sweep_seed", SWEEP_SEEDS)
+def test_fused_step_on_random_shapes_equals_the_two_calls(sweep_seed):
     """Seeded sweep: kf_decode_select_step against kf_decode_step + kf_select_evict, bit for bit, over element
     types, head sizes, query heads per cached head, few and many units (every fused launch sequence: one
     launch, split + tail, decode + select, with and without the shared score), both layouts, ragged lengths."""
-    rng = np.random.default_rng(20240310)
+    rng = np.random.default_rng(20240310 if sweep_seed is None else 888000 + sweep_seed)
     combos = [(ko.BF16, 64), (ko.BF16, 128), (ko.BF16, 256), (ko.F32, 64), (ko.F32, 128), (ko.F16, 128), (ko.F16, 64),
               (ko.F16, 256)]
     for case in range(24):
@@ -1508,11 +1519,12 @@ def test_fused_step_of_few_split_units_equals_the_two_calls(G, layout, k):
         np.testing.assert_array_equal(a_, b_, err_msg="tensor %d" % i)
 
 
-def test_decode_step_on_random_shapes_matches_oracle():
+@pytest.mark.parametrize("sweep_seed", SWEEP_SEEDS)
+def test_decode_step_on_random_shapes_matches_oracle(sweep_seed):
     """Seeded sweep over the decode call's shape space: element types, head sizes, query heads per cached
     head, few and many units (one workgroup per unit or splits, 4- and 8-wave workgroups), ragged lengths,
     every logit adjustment, both position modes, with and without a position bias (30 shapes)."""
-    rng = np.random.default_rng(20240309)
+    rng = np.random.default_rng(20240309 if sweep_seed is None else 777000 + sweep_seed)
     combos = [(ko.BF16, 64), (ko.BF16, 128), (ko.BF16, 256), (ko.F32, 64), (ko.F32, 128), (ko.F16, 128), (ko.F16, 64),
               (ko.F16, 256)]
     seen = set()
@@ -1560,7 +1572,8 @@ def test_decode_step_on_random_shapes_matches_oracle():
             m = int(oc.len[l, b, h])
             np.testing.assert_array_equal(gpos[l, b, h, :m], oc.pos[l, b, h, :m])
         del gc, ws, out
-    assert len(seen) >= 7, seen                     # both launch shapes for (nearly) every group size
+    if sweep_seed is None:
+        assert len(seen) >= 7, seen                 # both launch shapes for (nearly) every group size
 
 
 # ------------------------------------------------------------------ sequences at different steps
