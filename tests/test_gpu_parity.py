@@ -271,6 +271,39 @@ def test_prefill_score_matches_oracle(dtype, d, n):
         assert_close_score(host(gc.score), oc.score, oc.len, "prefill noise=%d" % noise, rtol=SCORE_RTOL_PREFILL)
 
 
+@pytest.mark.parametrize("sweep_seed", SWEEP_SEEDS)
+def test_prefill_on_random_shapes_matches_oracle(sweep_seed):
+    """Seeded sweep over the prompt-scoring call: element types, head sizes, prompt lengths around the tile
+    edges and in between, query heads per cached head, every logit adjustment at temperatures on both sides
+    of 1, logit scales from flat to peaked, with and without a position bias (each has kernels of its own)."""
+    rng = np.random.default_rng(20240311 if sweep_seed is None else 999000 + sweep_seed)
+    for case in range(12):
+        dtype, d = DTYPES[int(rng.integers(0, len(DTYPES)))]
+        n = int(rng.choice([1, 2, 31, 32, 33, 127, 128, 129, int(rng.integers(130, 900))]))
+        L, B, H = 1, int(rng.integers(1, 3)), int(rng.integers(1, 4))
+        G = int(rng.choice([1, 1, 2, 4]))
+        noise = int(rng.choice([ko.NOISE_GUMBEL, ko.NOISE_GUMBEL, ko.NOISE_NONE, ko.NOISE_GAUSSIAN, ko.NOISE_CONSTANT]))
+        tau = float(rng.choice([1.0, 1.0, 1.3, 0.6, 2.0]))
+        scale = float(rng.choice([1.0, 1.0, 3.0, 0.2])) / float(np.sqrt(np.float32(d)))
+        slopes = (rng.random(H * G) * 0.5).astype(np.float32) if rng.integers(0, 2) else None
+        oc = random_cache(rng, L, B, H, d, n + int(rng.integers(0, 5)), dtype, 0)
+        Q = rnd(rng, (L, B, H * G, n, d), dtype)
+        seeds = rng.integers(0, 2 ** 63, B).astype(np.uint64)
+        what = "case %d: dtype=%d d=%d n=%d B,H=%d,%d G=%d noise=%d tau=%g scale*sqrt(d)=%g slopes=%s" % (
+            case, dtype, d, n, B, H, G, noise, tau, scale * np.sqrt(d), slopes is not None)
+        print(what, flush=True)
+        gc = upload(oc, G)
+        ws = kf.new_workspace(gc, n)
+        oc.prefill_score(Q, n, tau, scale, noise, seeds, slopes, q_per_kv=G)
+        kf.kf_prefill_score(gc, dev(Q), n, tau, scale, noise, dev(seeds), None if slopes is None else dev(slopes), ws)
+        torch.cuda.synchronize()
+        assert error_word(ws) == 0, what
+        np.testing.assert_array_equal(host(gc.len), oc.len)
+        np.testing.assert_array_equal(host(gc.pos)[..., :n], oc.pos[..., :n])
+        assert_close_score(host(gc.score), oc.score, oc.len, what, rtol=SCORE_RTOL_PREFILL)
+        del gc, ws
+
+
 @pytest.mark.parametrize("dtype,d,scale", [(ko.BF16, 128, 6.0), (ko.F32, 64, 9.0), (ko.BF16, 256, 0.0)])
 def test_prefill_with_logits_far_from_the_rows_reference(dtype, d, scale):
     """Logits spread over hundreds of powers of two (a logit scale far above 1/sqrt(d)): the row sums are
